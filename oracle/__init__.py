@@ -1,0 +1,136 @@
+"""fp64 CPU oracle for segment attention (LSS Transformer, Section 3, Eq. 2).
+
+TEST INFRASTRUCTURE ONLY.  This package is the checker for the HIP library:
+it may be imported by the tests, by the smoke entry and by the benchmark's
+``cpu_baseline`` leg, and by nothing else.  It imports nothing from the HIP
+package and shares no code with it.
+
+The arithmetic lives in ``lss_oracle.c`` (plain loops in double precision);
+this module only compiles that file with gcc, loads it with ctypes and
+marshals numpy arrays.  Activations are ``[B, L, H, d]`` float64, C-contiguous;
+``lse`` is ``[B, H, l_s]``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "lss_oracle.c"
+_LIB = _HERE / "liblss_oracle.so"
+_lib = None
+
+
+def build(force: bool = False) -> Path:
+    """Compile the oracle with gcc (-O2, OpenMP).  Returns the library path."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".so.tmp{os.getpid()}")
+        subprocess.run(
+            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+             "-o", str(tmp), str(_SRC), "-lm"],
+            check=True,
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(str(build()))
+        i64, dp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        lib.lss_oracle_segment_fwd.argtypes = [dp, dp, dp, i64, i64, i64, i64, i64, i64, ci, dp, dp]
+        lib.lss_oracle_segment_bwd.argtypes = [dp, dp, dp, i64, i64, i64, i64, i64, i64, ci, dp, dp, dp, dp]
+        lib.lss_oracle_segment_weights.argtypes = [dp, dp, i64, i64, i64, i64, i64, i64, ci, dp]
+        lib.lss_oracle_reduce_partials.argtypes = [dp, ci, i64, dp]
+        for f in (lib.lss_oracle_segment_fwd, lib.lss_oracle_segment_bwd,
+                  lib.lss_oracle_segment_weights, lib.lss_oracle_reduce_partials,
+                  lib.lss_oracle_threads):
+            f.restype = ci
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    """Number of OpenMP threads the oracle will use."""
+    return int(_load().lss_oracle_threads())
+
+
+def _f64(a, shape=None):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {tuple(a.shape)}")
+    return a
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dims(q_seg, k, v):
+    if q_seg.ndim != 4 or k.ndim != 4 or k.shape != v.shape:
+        raise ValueError("q_seg, k, v must be [B, L, H, d] with k.shape == v.shape")
+    B, l_s, H, d = q_seg.shape
+    if k.shape[0] != B or k.shape[2] != H or k.shape[3] != d:
+        raise ValueError("q_seg and k disagree on B, H or d")
+    return B, l_s, k.shape[1], H, d
+
+
+def segment_fwd(q_seg, k, v, seg_offset: int, causal: bool = True):
+    """Eq. 2 for one segment.  Returns (out [B,l_s,H,d], lse [B,H,l_s])."""
+    q_seg, k, v = _f64(q_seg), _f64(k), _f64(v)
+    B, l_s, l_x, H, d = _dims(q_seg, k, v)
+    out = np.empty((B, l_s, H, d), dtype=np.float64)
+    lse = np.empty((B, H, l_s), dtype=np.float64)
+    rc = _load().lss_oracle_segment_fwd(_p(q_seg), _p(k), _p(v), seg_offset, l_s, l_x, B, H, d,
+                                        int(bool(causal)), _p(out), _p(lse))
+    if rc != 0:
+        raise ValueError(f"lss_oracle_segment_fwd rejected the shape (rc={rc})")
+    return out, lse
+
+
+def segment_bwd(q_seg, k, v, d_out, seg_offset: int, causal: bool = True):
+    """Gradient of Eq. 2 for one segment.
+
+    Returns (dq [B,l_s,H,d], dk_partial [B,l_x,H,d], dv_partial [B,l_x,H,d]).
+    """
+    q_seg, k, v = _f64(q_seg), _f64(k), _f64(v)
+    B, l_s, l_x, H, d = _dims(q_seg, k, v)
+    d_out = _f64(d_out, q_seg.shape)
+    dq = np.empty_like(q_seg)
+    dk = np.empty_like(k)
+    dv = np.empty_like(k)
+    rc = _load().lss_oracle_segment_bwd(_p(q_seg), _p(k), _p(v), seg_offset, l_s, l_x, B, H, d,
+                                        int(bool(causal)), _p(d_out), _p(dq), _p(dk), _p(dv))
+    if rc != 0:
+        raise ValueError(f"lss_oracle_segment_bwd failed (rc={rc})")
+    return dq, dk, dv
+
+
+def segment_weights(q_seg, k, seg_offset: int, causal: bool = True):
+    """The segment's softmax rows (partial A_w): [B, H, l_s, l_x], masked entries 0."""
+    q_seg, k = _f64(q_seg), _f64(k)
+    B, l_s, l_x, H, d = _dims(q_seg, k, k)
+    P = np.empty((B, H, l_s, l_x), dtype=np.float64)
+    rc = _load().lss_oracle_segment_weights(_p(q_seg), _p(k), seg_offset, l_s, l_x, B, H, d,
+                                            int(bool(causal)), _p(P))
+    if rc != 0:
+        raise ValueError(f"lss_oracle_segment_weights rejected the shape (rc={rc})")
+    return P
+
+
+def reduce_partials(parts):
+    """Segment sum of per-segment partials, in list order (Fig. 2(v) reduce-scatter arithmetic)."""
+    parts = [_f64(p) for p in parts]
+    if not parts:
+        raise ValueError("need at least one partial")
+    out = np.empty_like(parts[0])
+    arr = (ctypes.c_void_p * len(parts))(*[p.ctypes.data for p in parts])
+    rc = _load().lss_oracle_reduce_partials(arr, len(parts), out.size, _p(out))
+    if rc != 0:
+        raise ValueError("lss_oracle_reduce_partials failed")
+    return out

@@ -1,0 +1,221 @@
+/*
+ * fp64 CPU oracle for the partial self-attention of one sequence segment
+ * (LSS Transformer, Section 3 "Principle 3", Eq. 2; the full-sequence case
+ * s0 = 0, l_s = l_x is Eq. 1 of Section 2.2).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is the checker for the HIP library, not a
+ * fallback for it: only tests, the smoke entry and the benchmark's
+ * cpu_baseline leg may call it.  It shares no code with the HIP path.
+ *
+ * The method is exact (Section 3, Principle 3: concatenating per-segment
+ * outputs equals the sequential result), so the oracle is the definition
+ * written out: plain loops, two-pass softmax (max, then sum), nothing tiled,
+ * nothing fused, nothing online.  Everything is double precision.
+ *
+ * Layout of every activation: [B, L, H, d] contiguous, d fastest (token-major
+ * rows of E_m = H*d columns, the paper's l x E_m matrices; one head is a
+ * column slice of width d = E_m / H).  lse is [B, H, l_s].
+ *
+ * Readings of points the paper leaves open:
+ *   - d_k of Eq. 1 is the per-head width d; scores are divided by sqrt(d).
+ *   - "decoder-only (GPT)" (Section 5.1) means a causal mask: the query at
+ *     global position g = s0 + r sees keys j <= g.  Masked pairs have weight
+ *     exactly 0 (they are simply left out of the sums).
+ *   - no dropout on the attention weights.
+ *   - the backward pass is the textbook gradient of Eq. 2; a segment's
+ *     dK/dV "partial" is the contribution of its own query rows only, and the
+ *     sum over segments (the arithmetic of the reduce-scatter in Fig. 2(v))
+ *     is the full-sequence gradient.
+ *
+ * Threads: OpenMP over query rows, and over key rows for dK/dV.  Every sum
+ * is taken by one thread in increasing index order, so results do not depend
+ * on the thread count.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define IDX4(b, l, h, c, L, H, d) ((((int64_t)(b) * (L) + (l)) * (H) + (h)) * (d) + (c))
+
+int lss_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* number of keys visible to local row r of segment (s0, .): Eq. 2 with the
+ * causal reading above; all l_x keys when not causal. */
+static int64_t visible(int64_t s0, int64_t r, int64_t l_x, int causal)
+{
+    if (!causal) return l_x;
+    int64_t n = s0 + r + 1;
+    return n < l_x ? n : l_x;
+}
+
+/* One row of Eq. 2: scores S[j], their softmax P[j] and lse.  P must hold nj. */
+static double row_softmax(const double *q_row, const double *k, int64_t b, int64_t h,
+                          int64_t l_x, int64_t H, int64_t d, int64_t nj, double *P)
+{
+    const double inv_sqrt_d = 1.0 / sqrt((double)d);
+    double m = -INFINITY;
+    for (int64_t j = 0; j < nj; ++j) {
+        const double *k_row = k + IDX4(b, j, h, 0, l_x, H, d);
+        double s = 0.0;
+        for (int64_t c = 0; c < d; ++c) s += q_row[c] * k_row[c];
+        s *= inv_sqrt_d;
+        P[j] = s;
+        if (s > m) m = s;
+    }
+    double ell = 0.0;
+    for (int64_t j = 0; j < nj; ++j) ell += exp(P[j] - m);
+    const double lse = m + log(ell);
+    for (int64_t j = 0; j < nj; ++j) P[j] = exp(P[j] - lse);
+    return lse;
+}
+
+/*
+ * Forward of Eq. 2 for one segment.
+ *   q_seg [B, l_s, H, d], k, v [B, l_x, H, d]  ->  out [B, l_s, H, d], lse [B, H, l_s]
+ * returns 0, or -1 on a bad shape.
+ */
+int lss_oracle_segment_fwd(const double *q_seg, const double *k, const double *v,
+                           int64_t s0, int64_t l_s, int64_t l_x, int64_t B, int64_t H,
+                           int64_t d, int causal, double *out, double *lse)
+{
+    if (l_s < 0 || l_x < 1 || s0 < 0 || s0 + l_s > l_x || B < 0 || H < 1 || d < 1) return -1;
+    const int64_t rows = B * H * l_s;
+#pragma omp parallel
+    {
+        double *P = (double *)malloc(sizeof(double) * (size_t)l_x);
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t t = 0; t < rows; ++t) {
+            const int64_t r = t % l_s, h = (t / l_s) % H, b = t / (l_s * H);
+            const int64_t nj = visible(s0, r, l_x, causal);
+            const double *q_row = q_seg + IDX4(b, r, h, 0, l_s, H, d);
+            lse[(b * H + h) * l_s + r] = row_softmax(q_row, k, b, h, l_x, H, d, nj, P);
+            double *o_row = out + IDX4(b, r, h, 0, l_s, H, d);
+            for (int64_t c = 0; c < d; ++c) o_row[c] = 0.0;
+            for (int64_t j = 0; j < nj; ++j) {
+                const double *v_row = v + IDX4(b, j, h, 0, l_x, H, d);
+                for (int64_t c = 0; c < d; ++c) o_row[c] += P[j] * v_row[c];
+            }
+        }
+        free(P);
+    }
+    return 0;
+}
+
+/*
+ * Backward of Eq. 2 for one segment, given dO = d(loss)/d(out).
+ *   -> dq [B, l_s, H, d]; dk_part, dv_part [B, l_x, H, d] (all l_x rows
+ *      written; rows no query of this segment sees are 0).
+ * With P the softmax row and dP[j] = dO[r].v[j]:
+ *   D = sum_j P[j] dP[j];  dS[j] = P[j] (dP[j] - D);
+ *   dq[r] = sum_j dS[j] k[j] / sqrt(d);
+ *   dk_part[j] = sum_r dS[r][j] q[r] / sqrt(d);  dv_part[j] = sum_r P[r][j] dO[r].
+ * Like the paper's own implementation (Section 2.2) the l_s x l_x weight
+ * matrix of one head is materialised: first all rows (P, dS, dq), then all
+ * key columns (dk_part, dv_part), each sum taken in increasing index order.
+ */
+int lss_oracle_segment_bwd(const double *q_seg, const double *k, const double *v,
+                           int64_t s0, int64_t l_s, int64_t l_x, int64_t B, int64_t H,
+                           int64_t d, int causal, const double *dO,
+                           double *dq, double *dk_part, double *dv_part)
+{
+    if (l_s < 0 || l_x < 1 || s0 < 0 || s0 + l_s > l_x || B < 0 || H < 1 || d < 1) return -1;
+    const double inv_sqrt_d = 1.0 / sqrt((double)d);
+    const size_t w_elems = (size_t)(l_s > 0 ? l_s : 1) * (size_t)l_x;
+    double *Pm = (double *)malloc(sizeof(double) * w_elems);
+    double *dSm = (double *)malloc(sizeof(double) * w_elems);
+    if (!Pm || !dSm) { free(Pm); free(dSm); return -2; }
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h = 0; h < H; ++h) {
+#pragma omp parallel for schedule(dynamic, 4)
+            for (int64_t r = 0; r < l_s; ++r) {
+                const int64_t nj = visible(s0, r, l_x, causal);
+                double *P = Pm + r * l_x, *dS = dSm + r * l_x;
+                const double *q_row = q_seg + IDX4(b, r, h, 0, l_s, H, d);
+                const double *do_row = dO + IDX4(b, r, h, 0, l_s, H, d);
+                row_softmax(q_row, k, b, h, l_x, H, d, nj, P);
+                double D = 0.0;
+                for (int64_t j = 0; j < nj; ++j) {
+                    const double *v_row = v + IDX4(b, j, h, 0, l_x, H, d);
+                    double dp = 0.0;
+                    for (int64_t c = 0; c < d; ++c) dp += do_row[c] * v_row[c];
+                    dS[j] = dp;
+                    D += P[j] * dp;
+                }
+                for (int64_t j = 0; j < nj; ++j) dS[j] = P[j] * (dS[j] - D);
+                for (int64_t j = nj; j < l_x; ++j) { P[j] = 0.0; dS[j] = 0.0; }
+                double *dq_row = dq + IDX4(b, r, h, 0, l_s, H, d);
+                for (int64_t c = 0; c < d; ++c) dq_row[c] = 0.0;
+                for (int64_t j = 0; j < nj; ++j) {
+                    const double *k_row = k + IDX4(b, j, h, 0, l_x, H, d);
+                    for (int64_t c = 0; c < d; ++c) dq_row[c] += dS[j] * k_row[c];
+                }
+                for (int64_t c = 0; c < d; ++c) dq_row[c] *= inv_sqrt_d;
+            }
+#pragma omp parallel for schedule(static)
+            for (int64_t j = 0; j < l_x; ++j) {
+                double *dk_row = dk_part + IDX4(b, j, h, 0, l_x, H, d);
+                double *dv_row = dv_part + IDX4(b, j, h, 0, l_x, H, d);
+                for (int64_t c = 0; c < d; ++c) { dk_row[c] = 0.0; dv_row[c] = 0.0; }
+                for (int64_t r = 0; r < l_s; ++r) {
+                    const double ds = dSm[r * l_x + j], p = Pm[r * l_x + j];
+                    if (ds == 0.0 && p == 0.0) continue; /* masked pair */
+                    const double *q_row = q_seg + IDX4(b, r, h, 0, l_s, H, d);
+                    const double *do_row = dO + IDX4(b, r, h, 0, l_s, H, d);
+                    for (int64_t c = 0; c < d; ++c) {
+                        dk_row[c] += ds * q_row[c];
+                        dv_row[c] += p * do_row[c];
+                    }
+                }
+                for (int64_t c = 0; c < d; ++c) dk_row[c] *= inv_sqrt_d;
+            }
+        }
+    free(Pm);
+    free(dSm);
+    return 0;
+}
+
+/*
+ * Softmax rows themselves (the partial score matrix A_w of Section 2.2 for one
+ * segment), for tests that look at the weights: P [B, H, l_s, l_x], masked
+ * entries 0.
+ */
+int lss_oracle_segment_weights(const double *q_seg, const double *k, int64_t s0, int64_t l_s,
+                               int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, double *P)
+{
+    if (l_s < 0 || l_x < 1 || s0 < 0 || s0 + l_s > l_x || B < 0 || H < 1 || d < 1) return -1;
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h = 0; h < H; ++h)
+            for (int64_t r = 0; r < l_s; ++r) {
+                const int64_t nj = visible(s0, r, l_x, causal);
+                double *row = P + ((b * H + h) * l_s + r) * l_x;
+                for (int64_t j = 0; j < l_x; ++j) row[j] = 0.0;
+                row_softmax(q_seg + IDX4(b, r, h, 0, l_s, H, d), k, b, h, l_x, H, d, nj, row);
+            }
+    return 0;
+}
+
+/*
+ * Segment sum (the arithmetic of the reduce-scatter of Fig. 2(v)):
+ * out = parts[0] + parts[1] + ... in that order, elementwise, n_elems each.
+ */
+int lss_oracle_reduce_partials(const double *const *parts, int n, int64_t n_elems, double *out)
+{
+    if (n < 0 || n_elems < 0) return -1;
+    for (int64_t e = 0; e < n_elems; ++e) {
+        double s = 0.0;
+        for (int i = 0; i < n; ++i) s += parts[i][e];
+        out[e] = s;
+    }
+    return 0;
+}
