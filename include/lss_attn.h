@@ -1,0 +1,138 @@
+/*
+ * lss_attn.h -- C ABI of the MI355X (gfx950) segment-attention library.
+ *
+ * The operation is one GPU's share of the distributed self-attention of the
+ * LSS Transformer (Section 3, Principle 3): a contiguous segment Q_i of
+ * l_s = l_x / N query rows attends to the full, replicated K and V of l_x rows,
+ *     E_i = softmax(Q_i K^T / sqrt(d_k)) V                      (Eq. 2)
+ * whose row-concatenation over segments is Eq. 1.  d_k is read as the per-head
+ * width d; heads are independent column slices of the E_m = H*d columns.  The
+ * models are decoder-only (Section 5.1), so with causal != 0 the query at global
+ * position g = seg_offset + r sees keys j <= g; masked pairs have weight 0.
+ * There is no dropout on the weights.
+ *
+ * The backward pass is the gradient of Eq. 2.  Each segment produces dQ_i and
+ * its own contribution ("partial") to dK and dV; the sum of the partials over
+ * segments is the full gradient -- the arithmetic of the reduce-scatter that is
+ * the backward of the all-gather (Section 3, Principle 4, Fig. 2(v)).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library
+ *     neither frees nor retains them.  They must be 16-byte aligned.
+ *   - Activations are [B, L, H, d] contiguous, d fastest (token-major rows of
+ *     E_m columns); L = l_s for q_seg/out/dO/dq and l_x for k/v/partials.
+ *     lse is [B, H, l_s] float: natural log of the sum of exp(scaled score)
+ *     over the visible keys.
+ *   - d must be 64 or 128.  0 <= seg_offset, seg_offset + l_s <= l_x, l_x >= 1.
+ *     Segments need not be equal.  l_s == 0 or B == 0 is a valid empty call.
+ *     B*H <= 65535.  seg_offset does not enter the arithmetic when causal == 0.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work
+ *     is enqueued on it; no call synchronises with the host.
+ *   - Return value: LSS_OK (0) or a negative lss_status.  On error nothing has
+ *     been launched and no output was touched; lss_last_error() describes it.
+ *   - Scratch memory comes from the caller through lss_set_workspace(); kernels
+ *     launched by one call use it until they finish, so calls that overlap in
+ *     time (different streams) must not share one workspace.
+ *   - Results are bit-reproducible run to run: no atomics, every reduction has a
+ *     fixed order.
+ */
+#ifndef LSS_ATTN_H
+#define LSS_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum lss_status {
+    LSS_OK = 0,
+    LSS_ERR_NULL = -1,          /* a required pointer is NULL */
+    LSS_ERR_SHAPE = -2,         /* negative size, l_x < 1, B*H too large */
+    LSS_ERR_UNSUPPORTED_D = -3, /* d is not 64 or 128 */
+    LSS_ERR_ALIGN = -4,         /* a pointer is not 16-byte aligned */
+    LSS_ERR_RANGE = -5,         /* seg_offset < 0 or seg_offset + l_s > l_x */
+    LSS_ERR_WORKSPACE = -6,     /* workspace missing or smaller than lss_workspace_bytes() */
+    LSS_ERR_LAUNCH = -7         /* the HIP runtime refused a launch */
+} lss_status;
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int lss_version(void);
+
+/* Message for the last error returned on the calling thread ("" if none). Host pointer, static storage. */
+const char *lss_last_error(void);
+
+/*
+ * Bytes of device scratch that one forward or backward call of this shape may use
+ * (split-KV partial outputs, the row terms D = rowsum(dO * out), partial dQ).
+ * Depends on the shape only, not on seg_offset or causal.  Returns 0 for an
+ * empty or invalid shape.  `elem_bytes` is 2 (bf16 entry points) or 4 (f32).
+ */
+size_t lss_workspace_bytes(int64_t l_s, int64_t l_x, int64_t B, int64_t H, int64_t d, int elem_bytes);
+
+/*
+ * Hands the library a device buffer (16-byte aligned) to use as scratch from now
+ * on, for calls from any thread.  The caller keeps ownership and must keep it
+ * alive until the last call that uses it has finished on the GPU.  (NULL, 0)
+ * clears it.
+ */
+int lss_set_workspace(void *device_ptr, size_t bytes);
+
+/*
+ * Forward of Eq. 2 for one segment, bf16 storage, fp32 accumulation.
+ *   q_seg [B, l_s, H, d] bf16; k, v [B, l_x, H, d] bf16
+ *   out   [B, l_s, H, d] bf16 (written); lse [B, H, l_s] float (written)
+ * Scores and P*V products run on bf16 matrix cores; softmax is online over key
+ * tiles in fp32; key tiles that the causal mask hides entirely are skipped.
+ */
+int lss_segment_attn_fwd(const void *q_seg, const void *k, const void *v,
+                         int64_t seg_offset, int64_t l_s, int64_t l_x,
+                         int64_t B, int64_t H, int64_t d, int causal,
+                         void *out, float *lse, void *stream);
+
+/*
+ * Backward of Eq. 2 for one segment (gradient described above), bf16 storage.
+ *   out, lse: what the forward call wrote;  dO [B, l_s, H, d] bf16
+ *   dq [B, l_s, H, d] bf16 (written)
+ *   dk_partial, dv_partial [B, l_x, H, d] float (every row written; with
+ *   causal != 0 the rows >= seg_offset + l_s are exactly 0)
+ */
+int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v,
+                         int64_t seg_offset, int64_t l_s, int64_t l_x,
+                         int64_t B, int64_t H, int64_t d, int causal,
+                         const void *out, const float *lse, const void *dO,
+                         void *dq, float *dk_partial, float *dv_partial, void *stream);
+
+/*
+ * Single-precision twins (the paper's runs are single precision, Section 5.2):
+ * q_seg, k, v, out, dO, dq are float; products run on fp32 matrix cores.
+ */
+int lss_segment_attn_fwd_f32(const void *q_seg, const void *k, const void *v,
+                             int64_t seg_offset, int64_t l_s, int64_t l_x,
+                             int64_t B, int64_t H, int64_t d, int causal,
+                             void *out, float *lse, void *stream);
+int lss_segment_attn_bwd_f32(const void *q_seg, const void *k, const void *v,
+                             int64_t seg_offset, int64_t l_s, int64_t l_x,
+                             int64_t B, int64_t H, int64_t d, int causal,
+                             const void *out, const float *lse, const void *dO,
+                             void *dq, float *dk_partial, float *dv_partial, void *stream);
+
+/*
+ * Segment sum of partials (Fig. 2(v): what the reduce-scatter adds up):
+ *     out = parts[0] + parts[1] + ... + parts[n-1]   elementwise, in that order.
+ *   parts       HOST array of n DEVICE pointers, each [B, l_x, H, d] float
+ *   rows_valid  HOST array of n row counts, or NULL.  Rows >= rows_valid[i] of
+ *               parts[i] are taken as 0 without being read (for a causal
+ *               segment, seg_offset + l_s).  NULL means l_x for every part.
+ *   out         DEVICE [B, l_x, H, d] float (written); may alias parts[0] only.
+ * 1 <= n; the host arrays are read before the call returns.
+ */
+int lss_reduce_partials(const float *const *parts, int n, const int64_t *rows_valid,
+                        int64_t l_x, int64_t B, int64_t H, int64_t d,
+                        float *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSS_ATTN_H */

@@ -1,0 +1,218 @@
+// C ABI of the segment-attention library: argument checks, workspace, dispatch.
+// Every entry point is documented in include/lss_attn.h.
+#include "lss_attn.h"
+#include "lss_common.h"
+#include "lss_kernels.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <mutex>
+
+namespace lss {
+
+int choose_splits(int l_s, int l_x, int B, int H)
+{
+    // aim for >= 2 workgroups per compute unit (256 of them); a split needs >= 4 key tiles
+    const int64_t wgs = (int64_t)((l_s + 127) / 128) * B * H;
+    if (wgs <= 0) return 1;
+    int64_t want = (512 + wgs - 1) / wgs;
+    const int64_t tiles = (l_x + 63) / 64;
+    if (want > tiles / 4) want = tiles / 4;
+    if (want > 16) want = 16;
+    if (want < 1) want = 1;
+    return (int)want;
+}
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct WsLayout { size_t o_part, lse_part, D, dq_part, total; };
+static WsLayout ws_layout(int l_s, int l_x, int B, int H, int d)
+{
+    const size_t sp = (size_t)choose_splits(l_s, l_x, B, H);
+    const size_t rows = (size_t)B * H * l_s;
+    WsLayout w;
+    size_t off = 0;
+    w.o_part = off;   off += align256(sp > 1 ? sp * rows * d * sizeof(float) : 0);
+    w.lse_part = off; off += align256(sp > 1 ? sp * rows * sizeof(float) : 0);
+    w.D = off;        off += align256(rows * sizeof(float));
+    w.dq_part = off;  off += align256(sp > 1 ? sp * rows * d * sizeof(float) : 0);
+    w.total = off;
+    return w;
+}
+size_t workspace_bytes(int l_s, int l_x, int B, int H, int d) { return ws_layout(l_s, l_x, B, H, d).total; }
+Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d)
+{
+    const WsLayout w = ws_layout(l_s, l_x, B, H, d);
+    char *p = static_cast<char *>(base);
+    Workspace ws;
+    ws.o_part = reinterpret_cast<float *>(p + w.o_part);
+    ws.lse_part = reinterpret_cast<float *>(p + w.lse_part);
+    ws.D = reinterpret_cast<float *>(p + w.D);
+    ws.dq_part = reinterpret_cast<float *>(p + w.dq_part);
+    return ws;
+}
+
+} // namespace lss
+
+namespace {
+
+thread_local char g_err[256] = "";
+std::mutex g_ws_mutex;
+void *g_ws_ptr = nullptr;
+size_t g_ws_bytes = 0;
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_shape(int64_t s0, int64_t l_s, int64_t l_x, int64_t B, int64_t H, int64_t d)
+{
+    if (d != 64 && d != 128) return fail(LSS_ERR_UNSUPPORTED_D, "d = %lld: only 64 and 128 are supported", (long long)d);
+    if (l_s < 0 || B < 0 || H < 1 || l_x < 1) return fail(LSS_ERR_SHAPE, "bad shape: l_s=%lld l_x=%lld B=%lld H=%lld", (long long)l_s, (long long)l_x, (long long)B, (long long)H);
+    if (B * H > 65535) return fail(LSS_ERR_SHAPE, "B*H = %lld exceeds 65535", (long long)(B * H));
+    if (l_x > (int64_t)1 << 30) return fail(LSS_ERR_SHAPE, "l_x = %lld exceeds 2^30", (long long)l_x);
+    if (s0 < 0 || s0 + l_s > l_x) return fail(LSS_ERR_RANGE, "segment [%lld, %lld) is outside [0, %lld)", (long long)s0, (long long)(s0 + l_s), (long long)l_x);
+    return LSS_OK;
+}
+
+int get_workspace(int l_s, int l_x, int B, int H, int d, lss::Workspace *ws)
+{
+    const size_t need = lss::workspace_bytes(l_s, l_x, B, H, d);
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (need > 0 && (g_ws_ptr == nullptr || g_ws_bytes < need))
+        return fail(LSS_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu set (lss_set_workspace)", need, g_ws_bytes);
+    *ws = lss::carve_workspace(g_ws_ptr, l_s, l_x, B, H, d);
+    return LSS_OK;
+}
+
+template <typename T>
+int fwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_s, int64_t l_x, int64_t B,
+             int64_t H, int64_t d, int causal, void *out, float *lse, void *stream)
+{
+    if (int rc = check_shape(s0, l_s, l_x, B, H, d)) return rc;
+    if (l_s == 0 || B == 0) return LSS_OK;
+    if (!q || !k || !v || !out || !lse) return fail(LSS_ERR_NULL, "forward: NULL tensor pointer");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
+        return fail(LSS_ERR_ALIGN, "forward: tensor pointers must be 16-byte aligned");
+    lss::Workspace ws;
+    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, &ws)) return rc;
+    const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0};
+    const hipError_t e = lss::launch_fwd<T>(s, static_cast<const T *>(q), static_cast<const T *>(k),
+                                            static_cast<const T *>(v), static_cast<T *>(out), lse, ws,
+                                            static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "forward launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+template <typename T>
+int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_s, int64_t l_x, int64_t B,
+             int64_t H, int64_t d, int causal, const void *out, const float *lse, const void *dO, void *dq,
+             float *dk_part, float *dv_part, void *stream)
+{
+    if (int rc = check_shape(s0, l_s, l_x, B, H, d)) return rc;
+    if (B == 0) return LSS_OK;
+    if (!k || !v || !dk_part || !dv_part) return fail(LSS_ERR_NULL, "backward: NULL tensor pointer");
+    if (l_s > 0 && (!q || !out || !lse || !dO || !dq)) return fail(LSS_ERR_NULL, "backward: NULL tensor pointer");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse) || misaligned(dO) ||
+        misaligned(dq) || misaligned(dk_part) || misaligned(dv_part))
+        return fail(LSS_ERR_ALIGN, "backward: tensor pointers must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (l_s == 0) {     // an empty segment contributes nothing: the partials are all zero
+        const size_t bytes = (size_t)B * l_x * H * d * sizeof(float);
+        hipError_t e = hipMemsetAsync(dk_part, 0, bytes, st);
+        if (e == hipSuccess) e = hipMemsetAsync(dv_part, 0, bytes, st);
+        if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "backward memset failed: %s", hipGetErrorString(e));
+        return LSS_OK;
+    }
+    lss::Workspace ws;
+    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, &ws)) return rc;
+    const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0};
+    const hipError_t e = lss::launch_bwd<T>(s, static_cast<const T *>(q), static_cast<const T *>(k),
+                                            static_cast<const T *>(v), static_cast<const T *>(out), lse,
+                                            static_cast<const T *>(dO), static_cast<T *>(dq), dk_part, dv_part, ws, st);
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "backward launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int lss_version(void) { return 100; }
+
+const char *lss_last_error(void) { return g_err; }
+
+size_t lss_workspace_bytes(int64_t l_s, int64_t l_x, int64_t B, int64_t H, int64_t d, int elem_bytes)
+{
+    if ((elem_bytes != 2 && elem_bytes != 4) || (d != 64 && d != 128)) return 0;
+    if (l_s <= 0 || l_x < 1 || B <= 0 || H < 1 || l_s > l_x || l_x > (int64_t)1 << 30 || B * H > 65535) return 0;
+    return lss::workspace_bytes((int)l_s, (int)l_x, (int)B, (int)H, (int)d);
+}
+
+int lss_set_workspace(void *device_ptr, size_t bytes)
+{
+    if (device_ptr == nullptr && bytes != 0) return fail(LSS_ERR_NULL, "workspace pointer is NULL but bytes = %zu", bytes);
+    if (misaligned(device_ptr)) return fail(LSS_ERR_ALIGN, "workspace must be 16-byte aligned");
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    g_ws_ptr = device_ptr;
+    g_ws_bytes = device_ptr ? bytes : 0;
+    return LSS_OK;
+}
+
+int lss_segment_attn_fwd(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
+                         int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, void *out, float *lse,
+                         void *stream)
+{
+    return fwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, out, lse, stream);
+}
+
+int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
+                         int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, const void *out,
+                         const float *lse, const void *dO, void *dq, float *dk_partial, float *dv_partial,
+                         void *stream)
+{
+    return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, out, lse, dO, dq, dk_partial,
+                                 dv_partial, stream);
+}
+
+int lss_segment_attn_fwd_f32(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
+                             int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, void *out, float *lse,
+                             void *stream)
+{
+    return fwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, out, lse, stream);
+}
+
+int lss_segment_attn_bwd_f32(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
+                             int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, const void *out,
+                             const float *lse, const void *dO, void *dq, float *dk_partial, float *dv_partial,
+                             void *stream)
+{
+    return bwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, out, lse, dO, dq, dk_partial,
+                           dv_partial, stream);
+}
+
+int lss_reduce_partials(const float *const *parts, int n, const int64_t *rows_valid, int64_t l_x, int64_t B,
+                        int64_t H, int64_t d, float *out, void *stream)
+{
+    if (n < 1) return fail(LSS_ERR_SHAPE, "reduce: n = %d, need at least one part", n);
+    if (l_x < 1 || B < 0 || H < 1 || d < 4 || d % 4 != 0) return fail(LSS_ERR_SHAPE, "reduce: bad shape");
+    if (!parts || !out) return fail(LSS_ERR_NULL, "reduce: NULL pointer");
+    if (misaligned(out)) return fail(LSS_ERR_ALIGN, "reduce: out must be 16-byte aligned");
+    for (int i = 0; i < n; ++i) {
+        if (!parts[i]) return fail(LSS_ERR_NULL, "reduce: parts[%d] is NULL", i);
+        if (misaligned(parts[i])) return fail(LSS_ERR_ALIGN, "reduce: parts[%d] must be 16-byte aligned", i);
+        if (i > 0 && parts[i] == out) return fail(LSS_ERR_RANGE, "reduce: out may alias parts[0] only");
+    }
+    const hipError_t e = lss::launch_reduce(parts, n, rows_valid, l_x, B, H, d, out, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "reduce launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,45 @@
+// Host-side launchers of the segment-attention kernels; called by the C ABI only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lss {
+
+// One segment's problem, as the kernels see it (Eq. 2 of Section 3; device pointers).
+struct SegShape {
+    int64_t s0;      // global index of the segment's first query row
+    int l_s, l_x;    // query rows of the segment, key/value rows of the sequence
+    int B, H, d;
+    int causal;
+};
+
+// How many key ranges ("splits") a query tile's keys are divided into so that a
+// skinny segment (l_s << l_x) still fills the chip.  Shape-only, deterministic.
+int choose_splits(int l_s, int l_x, int B, int H);
+
+struct Workspace {
+    // forward
+    float *o_part;    // [splits, B*H, l_s, d]
+    float *lse_part;  // [splits, B*H, l_s]
+    // backward
+    float *D;         // [B*H, l_s]      rowsum(dO * out)
+    float *dq_part;   // [splits, B, l_s, H, d]
+};
+size_t workspace_bytes(int l_s, int l_x, int B, int H, int d);
+Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d);
+
+template <typename T>
+hipError_t launch_fwd(const SegShape &s, const T *q, const T *k, const T *v, T *out, float *lse,
+                      const Workspace &ws, hipStream_t st);
+
+template <typename T>
+hipError_t launch_bwd(const SegShape &s, const T *q, const T *k, const T *v, const T *out,
+                      const float *lse, const T *dO, T *dq, float *dk_part, float *dv_part,
+                      const Workspace &ws, hipStream_t st);
+
+constexpr int kMaxReduceParts = 64;
+hipError_t launch_reduce(const float *const *parts, int n, const int64_t *rows_valid, int64_t l_x,
+                         int64_t B, int64_t H, int64_t d, float *out, hipStream_t st);
+
+} // namespace lss

@@ -1,0 +1,186 @@
+"""Thin binding over liblss_attn.so: same names as the C ABI (include/lss_attn.h).
+
+Argument marshalling only -- every step of the path runs in the HIP kernels.  torch
+supplies device memory and the stream; nothing here computes.  If the library has
+not been built, the first call raises (there is no fallback path).
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "liblss_attn.so"
+_lib = None
+
+LSS_OK = 0
+STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_ERR_UNSUPPORTED_D",
+                -4: "LSS_ERR_ALIGN", -5: "LSS_ERR_RANGE", -6: "LSS_ERR_WORKSPACE", -7: "LSS_ERR_LAUNCH"}
+
+EXPORTS = ["lss_version", "lss_last_error", "lss_workspace_bytes", "lss_set_workspace",
+           "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
+           "lss_segment_attn_bwd_f32", "lss_reduce_partials"]
+
+
+class LssError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{STATUS_NAMES.get(code, code)}: {msg}")
+        self.code = code
+
+
+def load():
+    """Load the built library (once).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not LIB_PATH.exists():
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2311_02382_amd.build` "
+                           "(there is no fallback implementation)")
+    lib = ctypes.CDLL(str(LIB_PATH))
+    i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.lss_version.restype = ci
+    lib.lss_last_error.restype = ctypes.c_char_p
+    lib.lss_workspace_bytes.argtypes = [i64, i64, i64, i64, i64, ci]
+    lib.lss_workspace_bytes.restype = sz
+    lib.lss_set_workspace.argtypes = [vp, sz]
+    lib.lss_set_workspace.restype = ci
+    fwd = [vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, vp, vp, vp]
+    bwd = [vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, vp, vp, vp, vp, vp, vp, vp]
+    for name, args in (("lss_segment_attn_fwd", fwd), ("lss_segment_attn_fwd_f32", fwd),
+                       ("lss_segment_attn_bwd", bwd), ("lss_segment_attn_bwd_f32", bwd)):
+        getattr(lib, name).argtypes = args
+        getattr(lib, name).restype = ci
+    lib.lss_reduce_partials.argtypes = [vp, ci, vp, i64, i64, i64, i64, vp, vp]
+    lib.lss_reduce_partials.restype = ci
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != LSS_OK:
+        raise LssError(rc, load().lss_last_error().decode())
+
+
+def lss_version() -> int:
+    return int(load().lss_version())
+
+
+def lss_last_error() -> str:
+    return load().lss_last_error().decode()
+
+
+def lss_workspace_bytes(l_s, l_x, B, H, d, elem_bytes=2) -> int:
+    return int(load().lss_workspace_bytes(l_s, l_x, B, H, d, elem_bytes))
+
+
+_ws = {}        # device index -> uint8 tensor currently handed to the library
+_ws_retired = []  # older buffers, kept alive: kernels in flight may still use them
+
+
+def lss_set_workspace(buf) -> None:
+    """Hand the library a device buffer (a uint8 torch tensor) as scratch; None clears it."""
+    if buf is None:
+        _check(load().lss_set_workspace(None, 0))
+        return
+    _check(load().lss_set_workspace(buf.data_ptr(), buf.numel() * buf.element_size()))
+
+
+def _ensure_workspace(l_s, l_x, B, H, d, elem_bytes, device):
+    need = lss_workspace_bytes(l_s, l_x, B, H, d, elem_bytes)
+    idx = device.index if device.index is not None else torch.cuda.current_device()
+    cur = _ws.get(idx)
+    if cur is None or cur.numel() < need:
+        if cur is not None:
+            _ws_retired.append(cur)
+        cur = torch.empty(max(need, 1 << 20), dtype=torch.uint8, device=device)
+        _ws[idx] = cur
+    lss_set_workspace(cur)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _dims(q_seg, k, v):
+    if q_seg.dim() != 4 or k.dim() != 4 or k.shape != v.shape:
+        raise ValueError("q_seg, k, v must be [B, L, H, d] with k.shape == v.shape")
+    B, l_s, H, d = q_seg.shape
+    if k.shape[0] != B or k.shape[2] != H or k.shape[3] != d:
+        raise ValueError("q_seg and k disagree on B, H or d")
+    for t in (q_seg, k, v):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous device tensors")
+    if not (q_seg.dtype == k.dtype == v.dtype) or q_seg.dtype not in (torch.bfloat16, torch.float32):
+        raise ValueError("q_seg, k, v must share dtype bfloat16 or float32")
+    return B, l_s, k.shape[1], H, d
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def lss_segment_attn_fwd(q_seg, k, v, seg_offset, causal=True, out=None, lse=None, stream=None):
+    """Forward of one segment; dispatches on dtype (bf16 -> lss_segment_attn_fwd, f32 -> _f32).
+
+    Returns (out [B,l_s,H,d] in the input dtype, lse [B,H,l_s] float32).
+    """
+    B, l_s, l_x, H, d = _dims(q_seg, k, v)
+    if out is None:
+        out = torch.empty_like(q_seg)
+    if lse is None:
+        lse = torch.empty((B, H, l_s), dtype=torch.float32, device=q_seg.device)
+    f32 = q_seg.dtype == torch.float32
+    _ensure_workspace(l_s, l_x, B, H, d, 4 if f32 else 2, q_seg.device)
+    fn = load().lss_segment_attn_fwd_f32 if f32 else load().lss_segment_attn_fwd
+    _check(fn(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d, int(bool(causal)),
+              _ptr(out), _ptr(lse), _stream_ptr(stream)))
+    return out, lse
+
+
+def lss_segment_attn_bwd(q_seg, k, v, seg_offset, out, lse, d_out, causal=True,
+                         dq=None, dk_partial=None, dv_partial=None, stream=None):
+    """Backward of one segment.  Returns (dq, dk_partial, dv_partial); partials are float32 [B,l_x,H,d]."""
+    B, l_s, l_x, H, d = _dims(q_seg, k, v)
+    for t in (out, d_out):
+        if t.shape != q_seg.shape or t.dtype != q_seg.dtype or not t.is_contiguous():
+            raise ValueError("out and d_out must match q_seg in shape and dtype and be contiguous")
+    if lse.shape != (B, H, l_s) or lse.dtype != torch.float32 or not lse.is_contiguous():
+        raise ValueError("lse must be contiguous float32 [B, H, l_s]")
+    if dq is None:
+        dq = torch.empty_like(q_seg)
+    if dk_partial is None:
+        dk_partial = torch.empty(k.shape, dtype=torch.float32, device=k.device)
+    if dv_partial is None:
+        dv_partial = torch.empty(k.shape, dtype=torch.float32, device=k.device)
+    f32 = q_seg.dtype == torch.float32
+    _ensure_workspace(l_s, l_x, B, H, d, 4 if f32 else 2, q_seg.device)
+    fn = load().lss_segment_attn_bwd_f32 if f32 else load().lss_segment_attn_bwd
+    _check(fn(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d, int(bool(causal)),
+              _ptr(out), _ptr(lse), _ptr(d_out), _ptr(dq), _ptr(dk_partial), _ptr(dv_partial),
+              _stream_ptr(stream)))
+    return dq, dk_partial, dv_partial
+
+
+def lss_reduce_partials(parts, rows_valid=None, out=None, stream=None):
+    """out = parts[0] + parts[1] + ... in list order; rows >= rows_valid[i] of parts[i] count as 0."""
+    parts = list(parts)
+    if not parts:
+        raise ValueError("need at least one partial")
+    B, l_x, H, d = parts[0].shape
+    for p in parts:
+        if p.shape != parts[0].shape or p.dtype != torch.float32 or not p.is_cuda or not p.is_contiguous():
+            raise ValueError("partials must be contiguous float32 device tensors of one shape")
+    if out is None:
+        out = torch.empty_like(parts[0])
+    arr = (ctypes.c_void_p * len(parts))(*[p.data_ptr() for p in parts])
+    rv = None
+    if rows_valid is not None:
+        if len(rows_valid) != len(parts):
+            raise ValueError("rows_valid must have one entry per partial")
+        rv = (ctypes.c_int64 * len(parts))(*[int(x) for x in rows_valid])
+    _check(load().lss_reduce_partials(arr, len(parts), rv, l_x, B, H, d, _ptr(out), _stream_ptr(stream)))
+    return out

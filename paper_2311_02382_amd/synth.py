@@ -33,21 +33,35 @@ def _splitmix64(x: np.ndarray) -> np.ndarray:
     return z ^ (z >> np.uint64(31))
 
 
-def normal_f32(seed: int, n: int, std: float = 1.0, chunk: int = 1 << 22) -> np.ndarray:
-    """``n`` samples of N(0, std^2) as float32; element i depends on (seed, i) only."""
-    out = np.empty(n, dtype=np.float32)
-    base = _splitmix64(np.array([seed], dtype=np.uint64))[0]
+def _normal_chunk(base, lo, hi, std, out):
     with np.errstate(over="ignore"):
-        for lo in range(0, n, chunk):
-            hi = min(n, lo + chunk)
-            ctr = np.arange(lo, hi, dtype=np.uint64)
-            a = _splitmix64(base ^ (ctr * np.uint64(2)))
-            b = _splitmix64(base ^ (ctr * np.uint64(2) + np.uint64(1)))
-            # 53-bit uniforms; u1 in (0, 1], u2 in [0, 1)
-            u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
-            u2 = (b >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
-            z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
-            out[lo:hi] = (z * std).astype(np.float32)
+        ctr = np.arange(lo, hi, dtype=np.uint64)
+        a = _splitmix64(base ^ (ctr * np.uint64(2)))
+        b = _splitmix64(base ^ (ctr * np.uint64(2) + np.uint64(1)))
+        # 53-bit uniforms; u1 in (0, 1], u2 in [0, 1)
+        u1 = ((a >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)
+        u2 = (b >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)
+        z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+        out[lo:hi] = (z * std).astype(np.float32)
+
+
+def normal_f32(seed: int, n: int, std: float = 1.0, chunk: int = 1 << 20, workers: int = 8) -> np.ndarray:
+    """``n`` samples of N(0, std^2) as float32; element i depends on (seed, i) only.
+
+    Chunks are drawn by a small thread pool (numpy releases the GIL); the values do
+    not depend on the chunking.
+    """
+    out = np.empty(n, dtype=np.float32)
+    with np.errstate(over="ignore"):
+        base = _splitmix64(np.array([seed], dtype=np.uint64))[0]
+    spans = [(lo, min(n, lo + chunk)) for lo in range(0, n, chunk)]
+    if len(spans) <= 1 or workers <= 1:
+        for lo, hi in spans:
+            _normal_chunk(base, lo, hi, std, out)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            list(pool.map(lambda sp: _normal_chunk(base, sp[0], sp[1], std, out), spans))
     return out
 
 

@@ -1,0 +1,95 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2311_02382_amd import lss
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not lss.LIB_PATH.exists():
+        from paper_2311_02382_amd.build import build_library
+        build_library(verbose=False)
+    return lss.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = (ROOT / "include" / "lss_attn.h").read_text()
+    declared = set(re.findall(r"\b(lss_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(lss.EXPORTS), declared ^ set(lss.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.lss_version() >= 100
+
+
+def _fwd(lib, q=0x1000, k=0x2000, v=0x3000, s0=0, l_s=128, l_x=256, B=1, H=1, d=64, causal=1, out=0x4000,
+         lse=0x5000, f32=False):
+    fn = lib.lss_segment_attn_fwd_f32 if f32 else lib.lss_segment_attn_fwd
+    return fn(q, k, v, s0, l_s, l_x, B, H, d, causal, out, lse, None)
+
+
+def test_bad_arguments_are_rejected_without_launching(lib):
+    # fake (never dereferenced) device addresses: every call below must fail in the host checks
+    assert _fwd(lib, d=32) == -3 and "64 and 128" in lib.lss_last_error().decode()
+    assert _fwd(lib, d=96, f32=True) == -3
+    assert _fwd(lib, s0=200) == -5            # 200 + 128 > 256
+    assert _fwd(lib, s0=-1) == -5
+    assert _fwd(lib, l_s=-1) == -2
+    assert _fwd(lib, l_x=0, l_s=0) == -2
+    assert _fwd(lib, B=70000) == -2
+    assert _fwd(lib, q=0) == -1
+    assert _fwd(lib, lse=0) == -1
+    assert _fwd(lib, k=0x2008) == -4
+    assert _fwd(lib, out=0x4004, f32=True) == -4
+    # empty calls succeed and touch nothing
+    assert _fwd(lib, l_s=0) == 0
+    assert _fwd(lib, B=0) == 0
+
+
+def test_workspace_is_required_and_sized(lib):
+    need = lib.lss_workspace_bytes(128, 256, 1, 1, 64, 2)
+    assert need > 0
+    assert lib.lss_workspace_bytes(128, 256, 1, 1, 32, 2) == 0     # unsupported d
+    assert lib.lss_workspace_bytes(128, 256, 1, 1, 64, 3) == 0     # unsupported element size
+    assert lib.lss_set_workspace(None, 0) == 0
+    assert _fwd(lib) == -6 and "workspace" in lib.lss_last_error().decode()
+    assert lib.lss_set_workspace(0x10000, need - 1) == 0
+    assert _fwd(lib) == -6
+    assert lib.lss_set_workspace(0x10008, need) == -4
+    assert lib.lss_set_workspace(None, 64) == -1
+    assert lib.lss_set_workspace(None, 0) == 0
+    # a skinny segment needs room for its split partial results
+    assert lib.lss_workspace_bytes(128, 8192, 1, 1, 64, 2) > 4 * 128 * 64 * 4
+
+
+def test_backward_and_reduce_argument_checks(lib):
+    bwd = lib.lss_segment_attn_bwd
+    a = dict(q=0x1000, k=0x2000, v=0x3000, out=0x4000, lse=0x5000, dO=0x6000, dq=0x7000, dk=0x8000, dv=0x9000)
+
+    def call(s0=0, l_s=128, l_x=256, B=1, H=1, d=64, **kw):
+        p = dict(a, **kw)
+        return bwd(p["q"], p["k"], p["v"], s0, l_s, l_x, B, H, d, 1, p["out"], p["lse"], p["dO"], p["dq"],
+                   p["dk"], p["dv"], None)
+
+    assert call(d=80) == -3
+    assert call(s0=129) == -5
+    assert call(dk=0) == -1
+    assert call(dO=0) == -1
+    assert call(dv=0x9004) == -4
+    assert call() == -6        # no workspace set
+    red = lib.lss_reduce_partials
+    parts = (ctypes.c_void_p * 2)(0x1000, 0x2000)
+    assert red(parts, 0, None, 256, 1, 1, 64, 0x3000, None) == -2
+    assert red(None, 2, None, 256, 1, 1, 64, 0x3000, None) == -1
+    assert red(parts, 2, None, 256, 1, 1, 64, 0, None) == -1
+    assert red(parts, 2, None, 256, 1, 1, 64, 0x2000, None) == -5   # out aliases parts[1]
+    bad = (ctypes.c_void_p * 2)(0x1000, 0x2004)
+    assert red(bad, 2, None, 256, 1, 1, 64, 0x3000, None) == -4
+    nul = (ctypes.c_void_p * 2)(0x1000, None)
+    assert red(nul, 2, None, 256, 1, 1, 64, 0x3000, None) == -1
