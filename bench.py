@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the segment-attention hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch: for each of the N
+segments of the sequence, forward then backward (Eq. 2 of Section 3 and its gradient),
+followed by the segment sum of the dK and dV partials (the arithmetic of the
+reduce-scatter of Fig. 2(v)).  Inputs are resident in HBM before the timed region.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lx8k]
+
+Prints ONE JSON line.  `value` is the strict-count rate: 12*d flops per unmasked
+(query, key) pair and head (six matrix products: S, PV, dV, dP, dQ, dK), recomputation not
+counted.  The line also carries the dominant kernel's roofline figures (timed with HIP
+events on the launch stream, inside the timed region) and the fp64 oracle's rate on the
+host cores for a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak (published)
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak (published)
+
+# Matrix products each kernel contributes to the strict count (per pair: 2*d flops each).
+# fwd: S and PV.  dq kernel: dP and dQ (it also recomputes S).  dkv kernel: dV and dK (it also
+# recomputes S and dP).  Together the six products of the 12*d count.
+ALGO_PRODUCTS = {"fwd_kernel": 2, "bwd_dq_kernel": 2, "bwd_dkv_kernel": 2}
+EXEC_PRODUCTS = {"fwd_kernel": 2, "bwd_dq_kernel": 3, "bwd_dkv_kernel": 4}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="lx8k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="leave the per-kernel HIP events out of the timed region (roofline becomes null)")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print(f"bench.py: this build is one GPU's share of the path; --gpus {args.gpus} is not supported "
+              "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2311_02382_amd import lss, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    lss.load()      # fails loudly if the HIP library has not been built
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    w = synth.WORKLOADS[args.workload]
+    q, k, v, do = synth.workload_inputs(w)
+
+    def stage(x):
+        bits = synth.f32_to_bf16_bits(x)
+        return torch.from_numpy(bits.view(np.int16).reshape(x.shape)).to(dev).view(torch.bfloat16), bits
+
+    (qd, qb), (kd, kb), (vd, vb), (dod, dob) = map(stage, (q, k, v, do))
+    del q, k, v, do
+    offs, l_s = w.offsets(), w.l_s
+    q_seg = [qd[:, s0:s0 + l_s].contiguous() for s0 in offs]
+    do_seg = [dod[:, s0:s0 + l_s].contiguous() for s0 in offs]
+    out = [torch.empty_like(t) for t in q_seg]
+    dq = [torch.empty_like(t) for t in q_seg]
+    lse = [torch.empty((w.B, w.H, l_s), dtype=torch.float32, device=dev) for _ in offs]
+    dk_part = [torch.empty(kd.shape, dtype=torch.float32, device=dev) for _ in offs]
+    dv_part = [torch.empty(kd.shape, dtype=torch.float32, device=dev) for _ in offs]
+    dK = torch.empty(kd.shape, dtype=torch.float32, device=dev)
+    dV = torch.empty(kd.shape, dtype=torch.float32, device=dev)
+    rows_valid = [s0 + l_s if w.causal else w.l_x for s0 in offs]
+
+    def step():
+        for i, s0 in enumerate(offs):
+            lss.lss_segment_attn_fwd(q_seg[i], kd, vd, s0, w.causal, out=out[i], lse=lse[i])
+            lss.lss_segment_attn_bwd(q_seg[i], kd, vd, s0, out[i], lse[i], do_seg[i], w.causal,
+                                     dq=dq[i], dk_partial=dk_part[i], dv_partial=dv_part[i])
+        lss.lss_reduce_partials(dk_part, rows_valid, out=dK)
+        lss.lss_reduce_partials(dv_part, rows_valid, out=dV)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    timing = not args.no_kernel_timing
+    lss.lss_timing_reset()
+    lss.lss_timing_enable(timing)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    lss.lss_timing_enable(False)
+    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+
+    pairs = w.pairs()                       # unmasked (query, key) pairs x B x H, whole sequence
+    flops_strict = 12.0 * pairs * w.d
+    flops_fa = 14.0 * pairs * w.d
+    value = flops_strict / (ms_per_step * 1e-3) / 1e12
+
+    kernels, roofline = {}, None
+    if timing:
+        kid = 0
+        while (name := lss.lss_timing_kernel_name(kid)) is not None:
+            ms, n = lss.lss_timing_read(kid)
+            if n:
+                kernels[name] = {"launches_per_step": n / args.steps, "avg_us": 1e3 * ms / n,
+                                 "ms_per_step": ms / args.steps}
+            kid += 1
+        mfma = {n_: k_ for n_, k_ in kernels.items() if n_ in ALGO_PRODUCTS}
+        if mfma:
+            dom = max(mfma, key=lambda n_: mfma[n_]["ms_per_step"])
+            per_launch = ALGO_PRODUCTS[dom] * 2.0 * w.d * pairs / mfma[dom]["launches_per_step"]
+            achieved = per_launch / (mfma[dom]["avg_us"] * 1e-6) / 1e12
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                        "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                        "avg_launch_us": round(mfma[dom]["avg_us"], 2),
+                        "algorithmic_flops_per_launch": per_launch,
+                        "executed_over_algorithmic": EXEC_PRODUCTS[dom] / ALGO_PRODUCTS[dom]}
+        for name, kk in kernels.items():
+            if name in ALGO_PRODUCTS:
+                kk["algorithmic_tflops"] = round(ALGO_PRODUCTS[name] * 2.0 * w.d * pairs / (kk["ms_per_step"] * 1e-3) / 1e12, 2)
+            kk["avg_us"] = round(kk["avg_us"], 2)
+            kk["ms_per_step"] = round(kk["ms_per_step"], 4)
+        if "reduce_partials_kernel" in kernels:
+            # algorithmic bytes of the segment sum: valid rows of every part read once, l_x rows written
+            row_bytes = w.B * w.H * w.d * 4
+            byts = 2 * (sum(rows_valid) + w.l_x) * row_bytes
+            kernels["reduce_partials_kernel"]["algorithmic_GBps"] = round(
+                byts / (kernels["reduce_partials_kernel"]["ms_per_step"] * 1e-3) / 1e9, 1)
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = list(range(w.N)) if w.pairs() * w.d < 3e10 else sorted({w.N // 2 - 1, w.N - 1})
+        kh, vh = synth.bf16_bits_to_f64(kb).reshape(kb.shape), synth.bf16_bits_to_f64(vb).reshape(vb.shape)
+        t_cpu, p_cpu = 0.0, 0
+        for i in sample:
+            s0 = offs[i]
+            qh = synth.bf16_bits_to_f64(qb[:, s0:s0 + l_s]).reshape(w.B, l_s, w.H, w.d)
+            doh = synth.bf16_bits_to_f64(dob[:, s0:s0 + l_s]).reshape(w.B, l_s, w.H, w.d)
+            t = time.perf_counter()
+            oracle.segment_fwd(qh, kh, vh, s0, w.causal)
+            oracle.segment_bwd(qh, kh, vh, doh, s0, w.causal)
+            t_cpu += time.perf_counter() - t
+            p_cpu += w.segment_pairs(i)
+        cpu_baseline = {"value": round(12.0 * p_cpu * w.d / t_cpu / 1e12, 6), "unit": "TFLOP/s",
+                        "cores": oracle.threads(), "kind": "oracle",
+                        "sample": f"segments {sample} of {w.N} (fwd+bwd, all batches and heads), "
+                                  f"{t_cpu:.1f} s of fp64 CPU work, same strict flop count"}
+
+    line = {
+        "metric": "segment-attention fwd+bwd TFLOP/s on 1 MI355X; % of bf16 MFMA peak",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "l_x": w.l_x, "N": w.N, "l_s": l_s, "H": w.H, "d": w.d,
+                   "causal": w.causal, "step": "fwd+bwd of all N segments, then segment sum of dK and dV"},
+        "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "tflops_with_recompute_count_14Pd": round(flops_fa / (ms_per_step * 1e-3) / 1e12, 2),
+        "gpu_ms_per_step_events": round(gpu_ms / args.steps, 4),
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -205,13 +205,19 @@ static hipError_t launch_fwd_d(const SegShape &s, const T *q, const T *k, const 
     using C = FwdCfg<T, D>;
     const int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H);
     dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
-    hipLaunchKernelGGL((fwd_kernel<T, D>), grid, dim3(C::NT), 0, st, s, q, k, v, out, lse, ws.o_part,
-                       ws.lse_part, n_splits);
+    {
+        TimedLaunch tl(K_FWD, st);
+        hipLaunchKernelGGL((fwd_kernel<T, D>), grid, dim3(C::NT), 0, st, s, q, k, v, out, lse, ws.o_part,
+                           ws.lse_part, n_splits);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_splits == 1) return e;
     const int64_t items = (int64_t)s.B * s.H * s.l_s * (D / 4);
-    hipLaunchKernelGGL((fwd_merge_kernel<T, D>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, s,
-                       ws.o_part, ws.lse_part, n_splits, out, lse);
+    {
+        TimedLaunch tl(K_FWD_MERGE, st);
+        hipLaunchKernelGGL((fwd_merge_kernel<T, D>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, s,
+                           ws.o_part, ws.lse_part, n_splits, out, lse);
+    }
     return hipGetLastError();
 }
 

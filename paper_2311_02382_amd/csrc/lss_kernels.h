@@ -38,6 +38,17 @@ hipError_t launch_bwd(const SegShape &s, const T *q, const T *k, const T *v, con
                       const float *lse, const T *dO, T *dq, float *dk_part, float *dv_part,
                       const Workspace &ws, hipStream_t st);
 
+// Optional per-kernel timing for benchmarks: when enabled, every launch site brackets its
+// kernel with a pair of HIP events on the launch stream.
+enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_COUNT };
+void timing_begin(int id, hipStream_t st);
+void timing_end(int id, hipStream_t st);
+struct TimedLaunch {    // RAII bracket around one kernel launch
+    int id; hipStream_t st;
+    TimedLaunch(int id_, hipStream_t st_) : id(id_), st(st_) { timing_begin(id, st); }
+    ~TimedLaunch() { timing_end(id, st); }
+};
+
 constexpr int kMaxReduceParts = 64;
 hipError_t launch_reduce(const float *const *parts, int n, const int64_t *rows_valid, int64_t l_x,
                          int64_t B, int64_t H, int64_t d, float *out, hipStream_t st);

@@ -45,6 +45,7 @@ hipError_t launch_reduce(const float *const *parts, int n, const int64_t *rows_v
             const int64_t rv = rows_valid ? rows_valid[first + p] : l_x;
             a.rows_valid[p] = (int)(rv < 0 ? 0 : (rv > l_x ? l_x : rv));
         }
+        TimedLaunch tl(K_REDUCE, st);
         hipLaunchKernelGGL(reduce_partials_kernel, dim3(blocks), dim3(256), 0, st, a, n4, (int)l_x, row_f4, out);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

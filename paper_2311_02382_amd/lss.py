@@ -21,7 +21,8 @@ STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_E
 
 EXPORTS = ["lss_version", "lss_last_error", "lss_workspace_bytes", "lss_set_workspace",
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
-           "lss_segment_attn_bwd_f32", "lss_reduce_partials"]
+           "lss_segment_attn_bwd_f32", "lss_reduce_partials", "lss_timing_enable", "lss_timing_reset",
+           "lss_timing_read", "lss_timing_kernel_name"]
 
 
 class LssError(RuntimeError):
@@ -54,6 +55,12 @@ def load():
         getattr(lib, name).restype = ci
     lib.lss_reduce_partials.argtypes = [vp, ci, vp, i64, i64, i64, i64, vp, vp]
     lib.lss_reduce_partials.restype = ci
+    lib.lss_timing_enable.argtypes = [ci]
+    lib.lss_timing_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    lib.lss_timing_kernel_name.argtypes = [ci]
+    lib.lss_timing_kernel_name.restype = ctypes.c_char_p
+    for name in ("lss_timing_enable", "lss_timing_reset", "lss_timing_read"):
+        getattr(lib, name).restype = ci
     _lib = lib
     return lib
 
@@ -184,3 +191,23 @@ def lss_reduce_partials(parts, rows_valid=None, out=None, stream=None):
         rv = (ctypes.c_int64 * len(parts))(*[int(x) for x in rows_valid])
     _check(load().lss_reduce_partials(arr, len(parts), rv, l_x, B, H, d, _ptr(out), _stream_ptr(stream)))
     return out
+
+
+def lss_timing_enable(on: bool) -> None:
+    _check(load().lss_timing_enable(int(bool(on))))
+
+
+def lss_timing_reset() -> None:
+    _check(load().lss_timing_reset())
+
+
+def lss_timing_kernel_name(kernel_id: int):
+    name = load().lss_timing_kernel_name(kernel_id)
+    return name.decode() if name else None
+
+
+def lss_timing_read(kernel_id: int):
+    """(total milliseconds, launches) of kernel `kernel_id` since the last reset."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(load().lss_timing_read(kernel_id, ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
