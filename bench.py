@@ -152,7 +152,7 @@ def main() -> int:
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
-        sample = list(range(w.N)) if w.pairs() * w.d < 3e10 else sorted({w.N // 2 - 1, w.N - 1})
+        sample = list(range(w.N)) if w.pairs() * w.d < 4e10 else sorted({w.N // 2 - 1, w.N - 1})
         kh, vh = synth.bf16_bits_to_f64(kb).reshape(kb.shape), synth.bf16_bits_to_f64(vb).reshape(vb.shape)
         t_cpu, p_cpu = 0.0, 0
         for i in sample:

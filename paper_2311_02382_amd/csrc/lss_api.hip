@@ -10,10 +10,13 @@
 
 namespace lss {
 
-int choose_splits(int l_s, int l_x, int B, int H)
+int fwd_rows_per_wg(int elem_bytes, int d) { return elem_bytes == 2 ? fwd_bf16_rows_per_workgroup(d) : 128; }
+int dq_rows_per_wg(int elem_bytes, int d) { return elem_bytes == 2 ? dq_bf16_rows_per_workgroup(d) : 128; }
+
+int choose_splits(int l_s, int l_x, int B, int H, int rows_per_wg)
 {
     // aim for >= 2 workgroups per compute unit (256 of them); a split needs >= 4 key tiles
-    const int64_t wgs = (int64_t)((l_s + 127) / 128) * B * H;
+    const int64_t wgs = (int64_t)((l_s + rows_per_wg - 1) / rows_per_wg) * B * H;
     if (wgs <= 0) return 1;
     int64_t want = (512 + wgs - 1) / wgs;
     const int64_t tiles = (l_x + 63) / 64;
@@ -26,9 +29,12 @@ int choose_splits(int l_s, int l_x, int B, int H)
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout { size_t o_part, lse_part, D, dq_part, total; };
-static WsLayout ws_layout(int l_s, int l_x, int B, int H, int d)
+static WsLayout ws_layout(int l_s, int l_x, int B, int H, int d, int elem_bytes)
 {
-    const size_t sp = (size_t)choose_splits(l_s, l_x, B, H);
+    // forward and dQ kernels may use different tile heights, hence different split counts
+    const size_t sp_f = (size_t)choose_splits(l_s, l_x, B, H, fwd_rows_per_wg(elem_bytes, d));
+    const size_t sp_q = (size_t)choose_splits(l_s, l_x, B, H, dq_rows_per_wg(elem_bytes, d));
+    const size_t sp = sp_f > sp_q ? sp_f : sp_q;
     const size_t rows = (size_t)B * H * l_s;
     WsLayout w;
     size_t off = 0;
@@ -39,10 +45,13 @@ static WsLayout ws_layout(int l_s, int l_x, int B, int H, int d)
     w.total = off;
     return w;
 }
-size_t workspace_bytes(int l_s, int l_x, int B, int H, int d) { return ws_layout(l_s, l_x, B, H, d).total; }
-Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d)
+size_t workspace_bytes(int l_s, int l_x, int B, int H, int d, int elem_bytes)
 {
-    const WsLayout w = ws_layout(l_s, l_x, B, H, d);
+    return ws_layout(l_s, l_x, B, H, d, elem_bytes).total;
+}
+Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d, int elem_bytes)
+{
+    const WsLayout w = ws_layout(l_s, l_x, B, H, d, elem_bytes);
     char *p = static_cast<char *>(base);
     Workspace ws;
     ws.o_part = reinterpret_cast<float *>(p + w.o_part);
@@ -82,13 +91,13 @@ int check_shape(int64_t s0, int64_t l_s, int64_t l_x, int64_t B, int64_t H, int6
     return LSS_OK;
 }
 
-int get_workspace(int l_s, int l_x, int B, int H, int d, lss::Workspace *ws)
+int get_workspace(int l_s, int l_x, int B, int H, int d, int elem_bytes, lss::Workspace *ws)
 {
-    const size_t need = lss::workspace_bytes(l_s, l_x, B, H, d);
+    const size_t need = lss::workspace_bytes(l_s, l_x, B, H, d, elem_bytes);
     std::lock_guard<std::mutex> lock(g_ws_mutex);
     if (need > 0 && (g_ws_ptr == nullptr || g_ws_bytes < need))
         return fail(LSS_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu set (lss_set_workspace)", need, g_ws_bytes);
-    *ws = lss::carve_workspace(g_ws_ptr, l_s, l_x, B, H, d);
+    *ws = lss::carve_workspace(g_ws_ptr, l_s, l_x, B, H, d, elem_bytes);
     return LSS_OK;
 }
 
@@ -102,7 +111,7 @@ int fwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
         return fail(LSS_ERR_ALIGN, "forward: tensor pointers must be 16-byte aligned");
     lss::Workspace ws;
-    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, &ws)) return rc;
+    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), &ws)) return rc;
     const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0};
     const hipError_t e = lss::launch_fwd<T>(s, static_cast<const T *>(q), static_cast<const T *>(k),
                                             static_cast<const T *>(v), static_cast<T *>(out), lse, ws,
@@ -132,7 +141,7 @@ int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
         return LSS_OK;
     }
     lss::Workspace ws;
-    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, &ws)) return rc;
+    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), &ws)) return rc;
     const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0};
     const hipError_t e = lss::launch_bwd<T>(s, static_cast<const T *>(q), static_cast<const T *>(k),
                                             static_cast<const T *>(v), static_cast<const T *>(out), lse,
@@ -153,7 +162,7 @@ size_t lss_workspace_bytes(int64_t l_s, int64_t l_x, int64_t B, int64_t H, int64
 {
     if ((elem_bytes != 2 && elem_bytes != 4) || (d != 64 && d != 128)) return 0;
     if (l_s <= 0 || l_x < 1 || B <= 0 || H < 1 || l_s > l_x || l_x > (int64_t)1 << 30 || B * H > 65535) return 0;
-    return lss::workspace_bytes((int)l_s, (int)l_x, (int)B, (int)H, (int)d);
+    return lss::workspace_bytes((int)l_s, (int)l_x, (int)B, (int)H, (int)d, elem_bytes);
 }
 
 int lss_set_workspace(void *device_ptr, size_t bytes)

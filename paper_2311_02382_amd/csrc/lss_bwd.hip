@@ -318,37 +318,40 @@ static hipError_t launch_bwd_d(const SegShape &s, const T *q, const T *k, const 
                                const Workspace &ws, hipStream_t st)
 {
     hipError_t e;
-    {
-        const int64_t threads = (int64_t)s.B * s.l_s * s.H * 16;
-        TimedLaunch tl(K_ROWDOT, st);
-        hipLaunchKernelGGL((bwd_rowdot_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                           s, out, dO, ws.D);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
-    {
-        using C = DqCfg<T, D>;
-        const int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H);
-        dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
+    const int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H, dq_rows_per_wg((int)sizeof(T), D));
+    if constexpr (sizeof(T) == 2) {
+        if ((e = launch_bwd_bf16_main(s, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st)) != hipSuccess)
+            return e;
+    } else {
         {
+            const int64_t threads = (int64_t)s.B * s.l_s * s.H * 16;
+            TimedLaunch tl(K_ROWDOT, st);
+            hipLaunchKernelGGL((bwd_rowdot_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                               s, out, dO, ws.D);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
+        {
+            using C = DqCfg<T, D>;
+            dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
             TimedLaunch tl(K_DQ, st);
             hipLaunchKernelGGL((bwd_dq_kernel<T, D>), grid, dim3(C::NT), 0, st, s, q, k, v, dO, lse, ws.D, dq,
                                ws.dq_part, n_splits);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
         }
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-        if (n_splits > 1) {
-            const int64_t n4 = (int64_t)s.B * s.l_s * s.H * D / 4;
-            TimedLaunch tl(K_DQ_MERGE, st);
-            hipLaunchKernelGGL((bwd_dq_merge_kernel<T>), dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st,
-                               ws.dq_part, n_splits, n4, dq);
+        {
+            using C = DkvCfg<T, D>;
+            dim3 grid((s.l_x + C::BKV - 1) / C::BKV, s.B * s.H);
+            TimedLaunch tl(K_DKV, st);
+            hipLaunchKernelGGL((bwd_dkv_kernel<T, D>), grid, dim3(C::NT), 0, st, s, q, k, v, dO, lse, ws.D, dk_part,
+                               dv_part);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
     }
-    {
-        using C = DkvCfg<T, D>;
-        dim3 grid((s.l_x + C::BKV - 1) / C::BKV, s.B * s.H);
-        TimedLaunch tl(K_DKV, st);
-        hipLaunchKernelGGL((bwd_dkv_kernel<T, D>), grid, dim3(C::NT), 0, st, s, q, k, v, dO, lse, ws.D, dk_part,
-                           dv_part);
+    if (n_splits > 1) {
+        const int64_t n4 = (int64_t)s.B * s.l_s * s.H * D / 4;
+        TimedLaunch tl(K_DQ_MERGE, st);
+        hipLaunchKernelGGL((bwd_dq_merge_kernel<T>), dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st,
+                           ws.dq_part, n_splits, n4, dq);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;

@@ -203,14 +203,17 @@ static hipError_t launch_fwd_d(const SegShape &s, const T *q, const T *k, const 
                                const Workspace &ws, hipStream_t st)
 {
     using C = FwdCfg<T, D>;
-    const int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H);
-    dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
-    {
+    const int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H, fwd_rows_per_wg((int)sizeof(T), D));
+    hipError_t e;
+    if constexpr (sizeof(T) == 2) {
+        e = launch_fwd_bf16_main(s, q, k, v, out, lse, ws, n_splits, st);
+    } else {
+        dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
         TimedLaunch tl(K_FWD, st);
         hipLaunchKernelGGL((fwd_kernel<T, D>), grid, dim3(C::NT), 0, st, s, q, k, v, out, lse, ws.o_part,
                            ws.lse_part, n_splits);
+        e = hipGetLastError();
     }
-    hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_splits == 1) return e;
     const int64_t items = (int64_t)s.B * s.H * s.l_s * (D / 4);
     {

@@ -6,6 +6,8 @@
 
 namespace lss {
 
+typedef __bf16 bf16_t;
+
 // One segment's problem, as the kernels see it (Eq. 2 of Section 3; device pointers).
 struct SegShape {
     int64_t s0;      // global index of the segment's first query row
@@ -16,7 +18,10 @@ struct SegShape {
 
 // How many key ranges ("splits") a query tile's keys are divided into so that a
 // skinny segment (l_s << l_x) still fills the chip.  Shape-only, deterministic.
-int choose_splits(int l_s, int l_x, int B, int H);
+// `rows_per_wg` is the query-tile height of the kernel that will run (it differs per dtype).
+int choose_splits(int l_s, int l_x, int B, int H, int rows_per_wg);
+int fwd_rows_per_wg(int elem_bytes, int d);     // query rows per workgroup of the forward kernel
+int dq_rows_per_wg(int elem_bytes, int d);      // ... and of the dQ kernel
 
 struct Workspace {
     // forward
@@ -26,8 +31,8 @@ struct Workspace {
     float *D;         // [B*H, l_s]      rowsum(dO * out)
     float *dq_part;   // [splits, B, l_s, H, d]
 };
-size_t workspace_bytes(int l_s, int l_x, int B, int H, int d);
-Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d);
+size_t workspace_bytes(int l_s, int l_x, int B, int H, int d, int elem_bytes);
+Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d, int elem_bytes);
 
 template <typename T>
 hipError_t launch_fwd(const SegShape &s, const T *q, const T *k, const T *v, T *out, float *lse,
@@ -37,6 +42,17 @@ template <typename T>
 hipError_t launch_bwd(const SegShape &s, const T *q, const T *k, const T *v, const T *out,
                       const float *lse, const T *dO, T *dq, float *dk_part, float *dv_part,
                       const Workspace &ws, hipStream_t st);
+
+// tuned bf16 kernels (lss_fwd_bf16.hip)
+int fwd_bf16_rows_per_workgroup(int d);
+hipError_t launch_fwd_bf16_main(const SegShape &s, const bf16_t *q, const bf16_t *k, const bf16_t *v, bf16_t *out,
+                                float *lse, const Workspace &ws, int n_splits, hipStream_t st);
+
+// tuned bf16 kernels (lss_bwd_bf16.hip): dQ kernel (also writes D = rowsum(dO * out)) then dK/dV kernel
+int dq_bf16_rows_per_workgroup(int d);
+hipError_t launch_bwd_bf16_main(const SegShape &s, const bf16_t *q, const bf16_t *k, const bf16_t *v,
+                                const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq, float *dk_part,
+                                float *dv_part, const Workspace &ws, int n_splits, hipStream_t st);
 
 // Optional per-kernel timing for benchmarks: when enabled, every launch site brackets its
 // kernel with a pair of HIP events on the launch stream.
