@@ -24,6 +24,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
     # keep the compiler from forming packed-fp32 VALU ops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # matrix-instruction results stay in ordinary VGPRs (the softmax reads them with vector ALU
+    # ops); accumulation-only registers may still be placed in the AGPR half
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
 ]
 
 

@@ -38,7 +38,10 @@ __device__ __forceinline__ Frag<bf16_t> load_frag_tr(const bf16_t *tile, int pit
 }
 
 // Register-staged copy of a [ROWS][D] bf16 tile: issue the global loads early (fetch), store
-// them to LDS later (commit).  256 threads; 16-byte chunks; rows >= rows_ok read as 0.
+// them to LDS later (commit).  256 threads; 16-byte chunks.  The loads are unconditional so that
+// the compiler can count them (a load under a branch forces a full wait on every later use of
+// any loaded register): rows >= rows_ok re-read row rows_ok - 1, and the kernels make sure such
+// rows only ever meet weights that are exactly 0.  Needs rows_ok >= 1.
 template <int D, int ROWS>
 struct TileStage {
     static constexpr int CPR = D / 8;                 // 16-byte chunks per row
@@ -50,9 +53,8 @@ struct TileStage {
     {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const int c = i * 256 + tid, row = c / CPR, col = (c % CPR) * 8;
-            r[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (row < rows_ok) r[i] = *reinterpret_cast<const f32x4 *>(g + row * row_stride + col);
+            const int c = i * 256 + tid, row = min(c / CPR, rows_ok - 1), col = (c % CPR) * 8;
+            r[i] = *reinterpret_cast<const f32x4 *>(g + row * row_stride + col);
         }
     }
     __device__ __forceinline__ void commit(bf16_t *lds, int pitch, int tid) const

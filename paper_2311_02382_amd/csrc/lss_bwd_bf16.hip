@@ -277,12 +277,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(
     auto fetch = [&](int rq0) {
         stQ.fetch(qbase + (int64_t)rq0 * ld, ld, s.l_s - rq0, tid);
         stG.fetch(gbase + (int64_t)rq0 * ld, ld, s.l_s - rq0, tid);
-        if (tid < C::BQ) {
-            const int rr = rq0 + tid;
-            // rows past the segment: lse = +inf makes P (hence dS) exactly 0
-            stL = rr < s.l_s ? lbase[rr] * kLog2e : INFINITY;
-            stD = rr < s.l_s ? dbase[rr] : 0.f;
-        }
+        // every thread loads (unconditionally, clamped); threads < BQ keep the value.
+        // rows past the segment: lse = +inf makes P (hence dS) exactly 0
+        const int rr = rq0 + (tid & (C::BQ - 1)), rc = min(rr, s.l_s - 1);
+        const float lv = lbase[rc], dvv = dbase[rc];
+        stL = rr < s.l_s ? lv * kLog2e : INFINITY;
+        stD = rr < s.l_s ? dvv : 0.f;
     };
     auto commit = [&](int buf) {
         stQ.commit(sQ[buf], C::QP, tid);
@@ -332,11 +332,21 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             const int e = 4 * e4 + i;
-                            float p = fast_exp2(sc[kb2][e] * c - L4[i]);
-                            if (diag && (int64_t)j[kb2] > s.s0 + rq0 + rl + i) p = 0.f;
+                            const float p = fast_exp2(sc[kb2][e] * c - L4[i]);
                             sc[kb2][e] = p;
                             dp[kb2][e] = p * (dp[kb2][e] - D4[i]);
                         }
+                }
+                if (diag) {
+#pragma unroll
+                    for (int kb2 = 0; kb2 < NB; ++kb2) {
+                        // rows of this q-block that come before the lane's key are masked:
+                        // row index within the block, 8*(e/4) + e%4 (+ 4*hh), below `first`
+                        const int first = (int)max<int64_t>(min<int64_t>((int64_t)j[kb2] - s.s0 - rq0 - qb * 32 - 4 * hh, 64), 0);
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            if (8 * (e >> 2) + (e & 3) < first) { sc[kb2][e] = 0.f; dp[kb2][e] = 0.f; }
+                    }
                 }
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
