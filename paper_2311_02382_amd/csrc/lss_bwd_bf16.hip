@@ -214,8 +214,12 @@ __global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(
     __shared__ __attribute__((aligned(16))) float sD[2][C::BQ];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
-    const int bh = blockIdx.y, b = bh / s.H, h = bh % s.H;
-    const int j0 = blockIdx.x * C::BKV;
+    // grid: x = (batch, head), y = key tile.  Workgroups are dispatched x-fastest, so the tiles
+    // with the longest query loops (lowest keys under the causal mask) start first and the tiles no
+    // query sees (plain zero fill) come last; with B*H a multiple of 8 all tiles of one head also
+    // land on one XCD and share its L2 copy of that head's Q and dO.
+    const int bh = blockIdx.x, b = bh / s.H, h = bh % s.H;
+    const int j0 = blockIdx.y * C::BKV;
     const int jw0 = j0 + wave * C::KW;                  // first key of this wavefront
     const int64_t ld = (int64_t)s.H * D;
     const int64_t kv_base = (int64_t)b * s.l_x * ld + (int64_t)h * D;
@@ -413,7 +417,7 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const bf16_t *q, const bf
     }
     {
         using C = DkvBf16Cfg<D>;
-        dim3 grid((s.l_x + C::BKV - 1) / C::BKV, s.B * s.H);
+        dim3 grid(s.B * s.H, (s.l_x + C::BKV - 1) / C::BKV);
         TimedLaunch tl(K_DKV, st);
         hipLaunchKernelGGL((bwd_dkv_bf16_kernel<D>), grid, dim3(C::NT), 0, st, s, q, k, v, dO, lse, ws.D, dk_part,
                            dv_part);
