@@ -1,7 +1,7 @@
 // Tuned bf16 backward of Eq. 2 (Section 3, Principle 3) for gfx950: the two matrix kernels of
 // lss_bwd.hip (same mathematics, same operand roles) rebuilt around
-//   * 64 rows of the owned dimension per wavefront, so each LDS fragment feeds two matrix
-//     instructions;
+//   * in the dQ kernel at d = 64, 64 query rows per wavefront, so each LDS fragment feeds two
+//     matrix instructions;
 //   * row-major LDS tiles read transposed with DS_READ_B64_TR_B16 where the contraction runs over
 //     tile rows (K^T for dQ, Q^T and dO^T for dK and dV) -- no transposing stores;
 //   * double-buffered, register-staged tile loads with one barrier per tile;
@@ -194,14 +194,16 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_bf16_kernel(
 // ------------------------------------------------------------------------------------------ dK, dV
 template <int D>
 struct DkvBf16Cfg {
-    static constexpr int NB = D == 64 ? 2 : 1;          // 32-row key blocks per wavefront
+    // 32-row key blocks per wavefront.  One: two blocks would halve the LDS traffic per flop but
+    // their accumulators leave room for only one wavefront per SIMD, which measures slower.
+    static constexpr int NB = 1;
     static constexpr int WAVES = 4, KW = 32 * NB;       // key rows per wavefront
     static constexpr int BKV = WAVES * KW, BQ = 64, NT = 256;
     static constexpr int QP = D + 8;                    // pitch of the Q and dO tiles (elements)
 };
 
 template <int D>
-__global__ __launch_bounds__(256, 1) void bwd_dkv_bf16_kernel(
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
     SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ dO, const float *__restrict__ lse, const float *__restrict__ Dv,
     float *__restrict__ dk_part, float *__restrict__ dv_part)
