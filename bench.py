@@ -36,6 +36,19 @@ ALGO_PRODUCTS = {"fwd_kernel": 2, "bwd_dq_kernel": 2, "bwd_dkv_kernel": 2}
 EXEC_PRODUCTS = {"fwd_kernel": 2, "bwd_dq_kernel": 3, "bwd_dkv_kernel": 4}
 
 
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.md")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel:
+                return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -43,6 +56,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="lx8k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="before the timed region, run one plain device-to-device copy of this many MiB "
+                         "(a kernel of known traffic, to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave the per-kernel HIP events out of the timed region (roofline becomes null)")
     args = ap.parse_args()
@@ -96,6 +112,13 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calib_copy_mib > 0:
+        src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)      # the calibration kernel: reads and writes calib_copy_mib MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     timing = not args.no_kernel_timing
     lss.lss_timing_reset()
@@ -133,7 +156,8 @@ def main() -> int:
             per_launch = ALGO_PRODUCTS[dom] * 2.0 * w.d * pairs / mfma[dom]["launches_per_step"]
             achieved = per_launch / (mfma[dom]["avg_us"] * 1e-6) / 1e12
             roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                        "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                        "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                        "traffic": measured_traffic(w.name, dom),
                         "avg_launch_us": round(mfma[dom]["avg_us"], 2),
                         "algorithmic_flops_per_launch": per_launch,
                         "executed_over_algorithmic": EXEC_PRODUCTS[dom] / ALGO_PRODUCTS[dom]}
