@@ -280,20 +280,23 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
 
     TileStage<D, C::BQ> stQ, stG;
     float stL = 0.f, stD = 0.f;
+    bool st_ok = false;
     auto fetch = [&](int rq0) {
         stQ.fetch(qbase + (int64_t)rq0 * ld, ld, s.l_s - rq0, tid);
         stG.fetch(gbase + (int64_t)rq0 * ld, ld, s.l_s - rq0, tid);
-        // every thread loads (unconditionally, clamped); threads < BQ keep the value.
-        // rows past the segment: lse = +inf makes P (hence dS) exactly 0
-        const int rr = rq0 + (tid & (C::BQ - 1)), rc = min(rr, s.l_s - 1);
-        const float lv = lbase[rc], dvv = dbase[rc];
-        stL = rr < s.l_s ? lv * kLog2e : INFINITY;
-        stD = rr < s.l_s ? dvv : 0.f;
+        // every thread loads (unconditionally, clamped); threads < BQ keep the value.  Nothing is
+        // computed from the loaded values here, so that no memory wait lands before the tile's
+        // matrix work.
+        const int rr = rq0 + (tid & (C::BQ - 1));
+        st_ok = rr < s.l_s;
+        stL = lbase[min(rr, s.l_s - 1)];
+        stD = dbase[min(rr, s.l_s - 1)];
     };
     auto commit = [&](int buf) {
         stQ.commit(sQ[buf], C::QP, tid);
         stG.commit(sG[buf], C::QP, tid);
-        if (tid < C::BQ) { sL[buf][tid] = stL; sD[buf][tid] = stD; }
+        // rows past the segment: lse = +inf makes P (hence dS) exactly 0
+        if (tid < C::BQ) { sL[buf][tid] = st_ok ? stL * kLog2e : INFINITY; sD[buf][tid] = st_ok ? stD : 0.f; }
     };
     fetch(rq_begin);
     commit(0);
