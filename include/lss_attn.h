@@ -135,7 +135,8 @@ int lss_reduce_partials(const float *const *parts, int n, const int64_t *rows_va
 /*
  * Per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every
  * kernel the library launches is bracketed by a pair of HIP events on its launch stream.
- *   lss_timing_enable(on)   switch recording on (1) or off (0); off by default
+ *   lss_timing_enable(on)   switch recording on (1) or off (0) for every kernel; off by default
+ *   lss_timing_select(mask) record only the kernels whose id bit is set in `mask` (0 = none)
  *   lss_timing_reset()      wait for outstanding events and zero the totals
  *   lss_timing_read(id, &total_ms, &launches)
  *                           wait for outstanding events (blocks the host until those kernels
@@ -145,6 +146,7 @@ int lss_reduce_partials(const float *const *parts, int n, const int64_t *rows_va
  * Not thread-safe against concurrent reads; returns LSS_OK or a negative lss_status.
  */
 int lss_timing_enable(int on);
+int lss_timing_select(unsigned kernel_mask);
 int lss_timing_reset(void);
 int lss_timing_read(int kernel_id, double *total_ms, int64_t *launches);
 const char *lss_timing_kernel_name(int kernel_id);

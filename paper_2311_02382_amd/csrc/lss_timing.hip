@@ -12,7 +12,7 @@ namespace {
 
 struct Record { int id; hipEvent_t start, stop; };
 
-std::atomic<bool> g_on{false};
+std::atomic<unsigned> g_mask{0};         // bit i set: kernel id i is timed
 std::mutex g_mu;
 std::vector<Record> g_open;             // recorded, not yet read back
 std::vector<hipEvent_t> g_free;         // events ready for reuse
@@ -62,16 +62,16 @@ int collect()
 
 } // namespace
 
-void timing_begin(int /*id*/, hipStream_t st)
+void timing_begin(int id, hipStream_t st)
 {
-    if (!g_on.load(std::memory_order_relaxed)) return;
+    if (!((g_mask.load(std::memory_order_relaxed) >> id) & 1u)) return;
     t_start = get_event();
     if (t_start) (void)hipEventRecord(t_start, st);
 }
 
 void timing_end(int id, hipStream_t st)
 {
-    if (!g_on.load(std::memory_order_relaxed) || !t_start) return;
+    if (!((g_mask.load(std::memory_order_relaxed) >> id) & 1u) || !t_start) return;
     hipEvent_t stop = get_event();
     if (!stop) return;
     (void)hipEventRecord(stop, st);
@@ -86,7 +86,13 @@ extern "C" {
 
 int lss_timing_enable(int on)
 {
-    lss::g_on.store(on != 0);
+    lss::g_mask.store(on != 0 ? ~0u : 0u);
+    return LSS_OK;
+}
+
+int lss_timing_select(unsigned kernel_mask)
+{
+    lss::g_mask.store(kernel_mask);
     return LSS_OK;
 }
 

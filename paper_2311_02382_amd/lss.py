@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_E
 
 EXPORTS = ["lss_version", "lss_last_error", "lss_workspace_bytes", "lss_set_workspace",
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
-           "lss_segment_attn_bwd_f32", "lss_reduce_partials", "lss_timing_enable", "lss_timing_reset",
+           "lss_segment_attn_bwd_f32", "lss_reduce_partials", "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
            "lss_timing_read", "lss_timing_kernel_name"]
 
 
@@ -56,10 +56,11 @@ def load():
     lib.lss_reduce_partials.argtypes = [vp, ci, vp, i64, i64, i64, i64, vp, vp]
     lib.lss_reduce_partials.restype = ci
     lib.lss_timing_enable.argtypes = [ci]
+    lib.lss_timing_select.argtypes = [ctypes.c_uint]
     lib.lss_timing_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     lib.lss_timing_kernel_name.argtypes = [ci]
     lib.lss_timing_kernel_name.restype = ctypes.c_char_p
-    for name in ("lss_timing_enable", "lss_timing_reset", "lss_timing_read"):
+    for name in ("lss_timing_enable", "lss_timing_select", "lss_timing_reset", "lss_timing_read"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -195,6 +196,14 @@ def lss_reduce_partials(parts, rows_valid=None, out=None, stream=None):
 
 def lss_timing_enable(on: bool) -> None:
     _check(load().lss_timing_enable(int(bool(on))))
+
+
+def lss_timing_select(kernel_ids) -> None:
+    """Record only the kernels whose ids are listed (an empty list records nothing)."""
+    mask = 0
+    for k in kernel_ids:
+        mask |= 1 << int(k)
+    _check(load().lss_timing_select(mask))
 
 
 def lss_timing_reset() -> None:
