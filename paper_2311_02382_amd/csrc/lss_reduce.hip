@@ -23,8 +23,20 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(ReduceArgs a, int6
         const int row = (int)((i / row_f4) % l_x);      // key row of this float4
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         if (a.accumulate) acc = *reinterpret_cast<const f32x4 *>(out + i * 4);
-        for (int p = 0; p < a.n; ++p)
-            if (row < a.rows_valid[p]) acc += *reinterpret_cast<const f32x4 *>(a.parts[p] + i * 4);
+        // four parts at a time: the loads are independent and issued together, the adds keep list order
+        int p = 0;
+        for (; p + 4 <= a.n; p += 4) {
+            f32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (row < a.rows_valid[p + u]) v[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.parts[p + u] + i * 4));
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc += v[u];
+        }
+        for (; p < a.n; ++p)
+            if (row < a.rows_valid[p]) acc += __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(a.parts[p] + i * 4));
         *reinterpret_cast<f32x4 *>(out + i * 4) = acc;
     }
 }
