@@ -67,6 +67,12 @@ struct TileStage {
     }
 };
 
+// Wait until every outstanding vector-memory load of this wave has returned.  Placed once before
+// a main loop it also tells the compiler's wait-count insertion that nothing loaded earlier (Q
+// fragments, K/V operands) is still pending, so that inside the loop it only ever waits for the
+// loop's own prefetch loads, and only where they are consumed.
+__device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0), others untouched
+
 // 4 floats -> 4 bf16 (round to nearest even), as one 8-byte value
 __device__ __forceinline__ bf16x4 pack4(float a, float b, float c, float d)
 {

@@ -54,20 +54,23 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_bf16_kernel(
     for (int qb = 0; qb < NB; ++qb) {
         r[qb] = rw0 + qb * 32 + lq;
         row_ok[qb] = r[qb] < s.l_s;
-        const int64_t off = ((int64_t)b * s.l_s + r[qb]) * ld + (int64_t)h * D + hh * 8;
+        // rows past the segment re-read its last row (unconditional loads); they are never stored,
+        // and lse = +inf makes their P and dS exactly 0
+        const int rc = min(r[qb], s.l_s - 1);
+        const int64_t off = ((int64_t)b * s.l_s + rc) * ld + (int64_t)h * D + hh * 8;
         float dsum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < D / 16; ++kb) {
-            qf[qb][kb] = row_ok[qb] ? load_frag<bf16_t>(q + off + kb * 16) : zero_frag<bf16_t>();
-            gf[qb][kb] = row_ok[qb] ? load_frag<bf16_t>(dO + off + kb * 16) : zero_frag<bf16_t>();
-            const Frag<bf16_t> of = row_ok[qb] ? load_frag<bf16_t>(out + off + kb * 16) : zero_frag<bf16_t>();
+            qf[qb][kb] = load_frag<bf16_t>(q + off + kb * 16);
+            gf[qb][kb] = load_frag<bf16_t>(dO + off + kb * 16);
+            const Frag<bf16_t> of = load_frag<bf16_t>(out + off + kb * 16);
 #pragma unroll
             for (int e = 0; e < 8; ++e) dsum += (float)gf[qb][kb].v[e] * (float)of.v[e];
         }
         dsum += __shfl_xor(dsum, 32);
         Dr[qb] = dsum;
-        // rows past the segment get lse = +inf, so their P and dS are exactly 0
-        L2[qb] = row_ok[qb] ? lse[(int64_t)bh * s.l_s + r[qb]] * kLog2e : INFINITY;
+        const float lv = lse[(int64_t)bh * s.l_s + rc];
+        L2[qb] = row_ok[qb] ? lv * kLog2e : INFINITY;
         if (row_ok[qb] && hh == 0 && split == 0) Dv[(int64_t)bh * s.l_s + r[qb]] = dsum;
     }
     const float c = kLog2e / sqrtf((float)D);
@@ -92,6 +95,7 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_bf16_kernel(
         stK.commit(sK[0], C::KP, tid);
         stV.commit(sV[0], C::KP, tid);
     }
+    wait_vmem_all();
     __syncthreads();
 
     for (int t = t_begin; t < t_end; ++t) {
@@ -255,11 +259,12 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
     for (int kb2 = 0; kb2 < NB; ++kb2) {
         j[kb2] = jw0 + kb2 * 32 + lq;
         key_ok[kb2] = j[kb2] < s.l_x;
-        const int64_t off = kv_base + (int64_t)j[kb2] * ld + hh * 8;
+        // keys past the sequence re-read its last row (unconditional loads); never stored
+        const int64_t off = kv_base + (int64_t)min(j[kb2], s.l_x - 1) * ld + hh * 8;
 #pragma unroll
         for (int kb = 0; kb < D / 16; ++kb) {
-            kf[kb2][kb] = key_ok[kb2] ? load_frag<bf16_t>(k + off + kb * 16) : zero_frag<bf16_t>();
-            vf[kb2][kb] = key_ok[kb2] ? load_frag<bf16_t>(v + off + kb * 16) : zero_frag<bf16_t>();
+            kf[kb2][kb] = load_frag<bf16_t>(k + off + kb * 16);
+            vf[kb2][kb] = load_frag<bf16_t>(v + off + kb * 16);
         }
     }
 
@@ -300,6 +305,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
     };
     fetch(rq_begin);
     commit(0);
+    wait_vmem_all();
     __syncthreads();
 
     int it = 0;

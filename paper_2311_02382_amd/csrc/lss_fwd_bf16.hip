@@ -63,9 +63,10 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(SegShape s, const bf16
     for (int qb = 0; qb < NB; ++qb) {
         r[qb] = rw0 + qb * 32 + lq;
         row_ok[qb] = r[qb] < s.l_s;
-        const bf16_t *qp = q + ((int64_t)b * s.l_s + r[qb]) * ld + (int64_t)h * D + hh * 8;
+        // rows past the segment re-read its last row (unconditional loads); they are never stored
+        const bf16_t *qp = q + ((int64_t)b * s.l_s + min(r[qb], s.l_s - 1)) * ld + (int64_t)h * D + hh * 8;
 #pragma unroll
-        for (int kb = 0; kb < D / 16; ++kb) qf[qb][kb] = row_ok[qb] ? load_frag<bf16_t>(qp + kb * 16) : zero_frag<bf16_t>();
+        for (int kb = 0; kb < D / 16; ++kb) qf[qb][kb] = load_frag<bf16_t>(qp + kb * 16);
     }
 
     f32x16 o[NB][D / 32];
@@ -92,6 +93,7 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(SegShape s, const bf16
         stK.commit(sK[0], C::KP, tid);
         stV.commit(sV[0], C::VP, tid);
     }
+    wait_vmem_all();
     __syncthreads();
 
     for (int t = t_begin; t < t_end; ++t) {
