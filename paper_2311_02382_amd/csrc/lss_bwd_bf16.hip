@@ -33,7 +33,9 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_bf16_kernel(
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int bh = blockIdx.y, b = bh / s.H, h = bh % s.H, split = blockIdx.z;
-    const int r0 = blockIdx.x * C::BR;
+    // query tiles are dispatched last-first: under the causal mask the last tiles see the most
+    // keys, and starting the longest workgroups first shortens the tail of the launch
+    const int r0 = (gridDim.x - 1 - blockIdx.x) * C::BR;
     const int rw0 = r0 + wave * C::RW;
     const int64_t ld = (int64_t)s.H * D;
 
