@@ -57,6 +57,24 @@ struct TileStage {
             r[i] = *reinterpret_cast<const f32x4 *>(g + row * row_stride + col);
         }
     }
+    // Same loads with the address split into a wavefront-uniform tile pointer and per-thread
+    // 32-bit element offsets computed once (offsets()): inside a loop only the uniform pointer
+    // moves, on the scalar unit, and the vector unit computes no addresses at all.  Offsets are
+    // in bytes; needs ROWS * row_stride * 2 < 2^32.
+    __device__ __forceinline__ void offsets(uint32_t (&off)[N], int64_t row_stride, int rows_ok, int tid) const
+    {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int c = i * 256 + tid, row = min(c / CPR, rows_ok - 1), col = (c % CPR) * 8;
+            off[i] = ((uint32_t)row * (uint32_t)row_stride + (uint32_t)col) * 2u;
+        }
+    }
+    __device__ __forceinline__ void fetch(const bf16_t *__restrict__ g_uniform, const uint32_t (&off)[N])
+    {
+#pragma unroll
+        for (int i = 0; i < N; ++i)
+            r[i] = *reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(g_uniform) + off[i]);
+    }
     __device__ __forceinline__ void commit(bf16_t *lds, int pitch, int tid) const
     {
 #pragma unroll
@@ -66,6 +84,87 @@ struct TileStage {
         }
     }
 };
+
+
+// Global -> LDS load without a register in between: lane i moves BYTES (4 or 16) bytes from
+// g_uniform + voff to lds_uniform + i * BYTES.  Base pointers are wavefront-uniform, voff per lane.
+// Completion is counted like any vector-memory load (wait_vmem_all(), then a barrier, before any
+// wavefront reads the data).  Written as inline assembly on purpose: through the compiler builtin
+// every later LDS read that the compiler cannot prove disjoint would wait for the load at once,
+// which defeats loading a ring slot a whole loop iteration ahead.  M0 (the LDS address register of
+// the instruction) is saved and restored.
+template <int BYTES>
+__device__ __forceinline__ void lds_dma(const void *g_uniform, uint32_t voff, const void *lds_uniform)
+{
+    static_assert(BYTES == 4 || BYTES == 16, "");
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)lds_uniform;
+    uint32_t saved;
+    if (BYTES == 16)
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                     : "=&s"(saved) : "s"(lds_addr), "v"(voff), "s"(g_uniform) : "memory");
+    else
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, %3\n\ts_mov_b32 m0, %0"
+                     : "=&s"(saved) : "s"(lds_addr), "v"(voff), "s"(g_uniform) : "memory");
+}
+
+// [ROWS][D] bf16 tile loaded global -> LDS directly (no registers in between), by 4 wavefronts.
+// One such load instruction moves 16 bytes per lane and writes the wavefront's 64 chunks back to
+// back (1 KB), so rows cannot be padded; instead the 16-byte chunk c of row r sits at chunk
+// position c ^ (r & 7) of its row, which spreads a column of chunks over the LDS banks as padding
+// would.  The permutation is applied on the global side: the lane that fills position p of row r
+// fetches chunk p ^ (r & 7).
+template <int D, int ROWS>
+struct DirectTile {
+    static constexpr int CPR = D / 8;                 // 16-byte chunks per row
+    static constexpr int RPI = 64 / CPR;              // rows per load instruction of one wavefront
+    static constexpr int NI = ROWS / RPI / 4;         // load instructions per wavefront
+    static constexpr int BYTES = ROWS * D * 2;
+    static_assert(ROWS % (RPI * 4) == 0, "tile must divide among 4 wavefronts");
+
+    // global byte offsets (from the tile's first row) of this lane's chunks; rows >= rows_ok
+    // re-read row rows_ok - 1 (the kernels mask what such rows produce).  Needs ROWS * row_stride * 2 < 2^32.
+    static __device__ __forceinline__ void offsets(uint32_t (&off)[NI], int64_t row_stride, int rows_ok, int wave, int lane)
+    {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int row = (i * 4 + wave) * RPI + lane / CPR, pos = lane % CPR;
+            const int chunk = (pos & ~7) | ((pos ^ row) & 7);
+            off[i] = ((uint32_t)min(row, rows_ok - 1) * (uint32_t)row_stride + (uint32_t)chunk * 8u) * 2u;
+        }
+    }
+    // issue the loads; `g_uniform`, `lds_tile` and `wave` must be wavefront-uniform
+    static __device__ __forceinline__ void issue(const bf16_t *g_uniform, const uint32_t (&off)[NI], char *lds_tile, int wave)
+    {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) lds_dma<16>(g_uniform, off[i], lds_tile + (i * 4 + wave) * 1024);
+    }
+    // byte offset inside the tile of the 16-byte chunk c of row r
+    static __device__ __forceinline__ int chunk_offset(int r, int c) { return r * (D * 2) + (((c & ~7) | ((c ^ r) & 7)) * 16); }
+};
+
+// A-operand fragment of the transpose of a DirectTile (see load_frag_tr): `lane_off` is this
+// lane's byte offset for column block `db` (tr_lane_offset_sw), `row0` a multiple of 16.
+template <int D>
+__device__ __forceinline__ Frag<bf16_t> load_frag_tr_sw(const char *tile, int row0, int lane_off)
+{
+    const char *p = tile + row0 * (D * 2) + lane_off;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * (D * 2)));
+    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    Frag<bf16_t> f;
+    f.v = __builtin_bit_cast(bf16x8, both);
+    return f;
+}
+// Byte offset for load_frag_tr_sw, columns [32 db, 32 db + 32): the lane addresses row
+// 4*hh + s/4 (+ 8, + row0: neither changes row & 7) and the 8-byte piece (s % 4) of the 32-byte
+// column group nh -- the layout of tr_lane_offset, with the chunk permutation of DirectTile.
+template <int D>
+__device__ __forceinline__ int tr_lane_offset_sw(int lane, int db)
+{
+    const int grp = lane >> 4, hh = grp >> 1, nh = grp & 1, s = lane & 15;
+    const int row = 4 * hh + (s >> 2), chunk = 4 * db + 2 * nh + ((s & 3) >> 1);
+    return DirectTile<D, 64>::chunk_offset(row, chunk) + (s & 1) * 8;
+}
 
 // Wait until every outstanding vector-memory load of this wave has returned.  Placed once before
 // a main loop it also tells the compiler's wait-count insertion that nothing loaded earlier (Q

@@ -7,6 +7,7 @@
 //   * double-buffered, register-staged tile loads with one barrier per tile;
 //   * D = rowsum(dO * out) computed inside the dQ kernel (no separate launch).
 #include "lss_bf16.h"
+#include <type_traits>
 #include "lss_kernels.h"
 
 namespace lss {
@@ -24,7 +25,7 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void bwd_dq_bf16_kernel(
     SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO, const float *__restrict__ lse,
-    float *__restrict__ Dv, bf16_t *__restrict__ dq, float *__restrict__ dq_part, int n_splits)
+    float *__restrict__ Dv, float *__restrict__ Lsv, bf16_t *__restrict__ dq, float *__restrict__ dq_part, int n_splits)
 {
     using C = DqBf16Cfg<D>;
     constexpr int NB = C::NB;
@@ -73,7 +74,11 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_bf16_kernel(
         Dr[qb] = dsum;
         const float lv = lse[(int64_t)bh * s.l_s + rc];
         L2[qb] = row_ok[qb] ? lv * kLog2e : INFINITY;
-        if (row_ok[qb] && hh == 0 && split == 0) Dv[(int64_t)bh * s.l_s + r[qb]] = dsum;
+        if (row_ok[qb] && hh == 0 && split == 0) {
+            // start values of the dK/dV kernel's accumulators
+            Dv[(int64_t)bh * s.l_s + r[qb]] = -dsum;
+            Lsv[(int64_t)bh * s.l_s + r[qb]] = -lv * sqrtf((float)D);
+        }
     }
     const float c = kLog2e / sqrtf((float)D);
 
@@ -200,28 +205,39 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_bf16_kernel(
 // ------------------------------------------------------------------------------------------ dK, dV
 template <int D>
 struct DkvBf16Cfg {
-    // 32-row key blocks per wavefront.  One: two blocks would halve the LDS traffic per flop but
+    // One 32-row key block per wavefront.  Two blocks would halve the LDS traffic per flop but
     // their accumulators leave room for only one wavefront per SIMD, which measures slower.
-    static constexpr int NB = 1;
-    static constexpr int WAVES = 4, KW = 32 * NB;       // key rows per wavefront
+    static constexpr int WAVES = 4, KW = 32;            // key rows per wavefront
     static constexpr int BKV = WAVES * KW, BQ = 64, NT = 256;
-    static constexpr int QP = D + 8;                    // pitch of the Q and dO tiles (elements)
+    static constexpr int RING = 3;                      // Q/dO tiles resident in LDS
+    static constexpr int NU = D / 16;                   // operand steps of the S/dP products; same for dV/dK
+    using Tile = DirectTile<D, BQ>;
+    // one ring slot: Q tile, dO tile, 64 S-accumulator start values, 64 dP-accumulator start values
+    static constexpr int OFF_G = Tile::BYTES, OFF_L = 2 * Tile::BYTES, OFF_D = OFF_L + BQ * 4;
+    static constexpr int SLOT = OFF_D + BQ * 4;
 };
 
+// The query rows are walked in blocks of 32 (two per 64-row Q/dO tile).  Per block g three stages:
+//     A(g): S and dP products (matrix),  B(g): weights P, dS (vector: exp, multiplies, bf16 packing),
+//     C(g): dV^T and dK^T products (matrix).
+// A wavefront issues in order, and vector work costs it several times the issue time of a matrix
+// instruction, so the stages are software-pipelined: step g issues the matrix instructions of
+// A(g+1) and C(g-1) with the vector work of B(g) spread between them, one element per matrix
+// instruction.  Block g+1 may belong to the next tile and block g-1 to the previous one, hence a
+// ring of three tiles in LDS; tiles travel global -> LDS directly, a full loop iteration ahead.
 template <int D>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
     SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const bf16_t *__restrict__ dO, const float *__restrict__ lse, const float *__restrict__ Dv,
+    const bf16_t *__restrict__ dO, const float *__restrict__ Ls, const float *__restrict__ Dn,
     float *__restrict__ dk_part, float *__restrict__ dv_part)
 {
     using C = DkvBf16Cfg<D>;
-    constexpr int NB = C::NB;
-    __shared__ __attribute__((aligned(16))) bf16_t sQ[2][C::BQ * C::QP];
-    __shared__ __attribute__((aligned(16))) bf16_t sG[2][C::BQ * C::QP];
-    __shared__ __attribute__((aligned(16))) float sL[2][C::BQ];
-    __shared__ __attribute__((aligned(16))) float sD[2][C::BQ];
+    using Tile = typename C::Tile;
+    constexpr int NU = C::NU;
+    __shared__ __attribute__((aligned(1024))) char smem[C::RING * C::SLOT];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // grid: x = (batch, head), y = key tile.  Workgroups are dispatched x-fastest, so the tiles
     // with the longest query loops (lowest keys under the causal mask) start first and the tiles no
     // query sees (plain zero fill) come last; with B*H a multiple of 8 all tiles of one head also
@@ -254,156 +270,208 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
         return;
     }
 
-    int j[NB];
-    bool key_ok[NB];
-    Frag<bf16_t> kf[NB][D / 16], vf[NB][D / 16];
+    // this lane's key (column of the S tile); keys past the sequence re-read its last row
+    // (unconditional loads), take part in all the arithmetic and are never stored
+    const int j = jw0 + lq;
+    const bool key_ok = j < s.l_x;
+    Frag<bf16_t> kf[NU], vf[NU];
+    {
+        const int64_t off = kv_base + (int64_t)min(j, s.l_x - 1) * ld + hh * 8;
 #pragma unroll
-    for (int kb2 = 0; kb2 < NB; ++kb2) {
-        j[kb2] = jw0 + kb2 * 32 + lq;
-        key_ok[kb2] = j[kb2] < s.l_x;
-        // keys past the sequence re-read its last row (unconditional loads); never stored
-        const int64_t off = kv_base + (int64_t)min(j[kb2], s.l_x - 1) * ld + hh * 8;
-#pragma unroll
-        for (int kb = 0; kb < D / 16; ++kb) {
-            kf[kb2][kb] = load_frag<bf16_t>(k + off + kb * 16);
-            vf[kb2][kb] = load_frag<bf16_t>(v + off + kb * 16);
+        for (int kb = 0; kb < NU; ++kb) {
+            kf[kb] = load_frag<bf16_t>(k + off + kb * 16);
+            vf[kb] = load_frag<bf16_t>(v + off + kb * 16);
         }
     }
 
-    f32x16 dk[NB][D / 32], dv[NB][D / 32];
+    f32x16 dk[D / 32], dv[D / 32];
 #pragma unroll
-    for (int kb2 = 0; kb2 < NB; ++kb2)
+    for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) { dk[kb2][db][e] = 0.f; dv[kb2][db][e] = 0.f; }
+        for (int e = 0; e < 16; ++e) { dk[db][e] = 0.f; dv[db][e] = 0.f; }
 
-    const float c = kLog2e / sqrtf((float)D);
+    const float sqrt_d = sqrtf((float)D);
+    const float c = kLog2e / sqrt_d;
     const bf16_t *qbase = q + (int64_t)b * s.l_s * ld + (int64_t)h * D;
     const bf16_t *gbase = dO + (int64_t)b * s.l_s * ld + (int64_t)h * D;
-    const float *lbase = lse + (int64_t)bh * s.l_s, *dbase = Dv + (int64_t)bh * s.l_s;
-    const int tr_off = tr_lane_offset(lane, C::QP);
-    const bool wave_on = jw0 < s.l_x;
+    const float *lbase = Ls + (int64_t)bh * s.l_s, *dbase = Dn + (int64_t)bh * s.l_s;
 
-    TileStage<D, C::BQ> stQ, stG;
-    float stL = 0.f, stD = 0.f;
-    bool st_ok = false;
-    auto fetch = [&](int rq0) {
-        stQ.fetch(qbase + (int64_t)rq0 * ld, ld, s.l_s - rq0, tid);
-        stG.fetch(gbase + (int64_t)rq0 * ld, ld, s.l_s - rq0, tid);
-        // every thread loads (unconditionally, clamped); threads < BQ keep the value.  Nothing is
-        // computed from the loaded values here, so that no memory wait lands before the tile's
-        // matrix work.
-        const int rr = rq0 + (tid & (C::BQ - 1));
-        st_ok = rr < s.l_s;
-        stL = lbase[min(rr, s.l_s - 1)];
-        stD = dbase[min(rr, s.l_s - 1)];
+    // ---- tile loads: all four wavefronts move Q and dO; wavefronts 0 and 1 also the 64 start values
+    uint32_t offF[Tile::NI];                            // this lane's global offsets within a full tile
+    Tile::offsets(offF, ld, C::BQ, wave, lane);
+    auto issue_tile = [&](int rq0, int slot) {
+        const int rows_ok = s.l_s - rq0;
+        uint32_t off[Tile::NI];
+#pragma unroll
+        for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i];
+        if (rows_ok < C::BQ) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
+        char *dst = smem + slot * C::SLOT;
+        Tile::issue(qbase + (int64_t)rq0 * ld, off, dst, wave);
+        Tile::issue(gbase + (int64_t)rq0 * ld, off, dst + C::OFF_G, wave);
+        if (wave < 2) {
+            const float *src = (wave == 0 ? lbase : dbase) + rq0;
+            const uint32_t ro = (uint32_t)min(lane, rows_ok - 1) * 4u;
+            lds_dma<4>(src, ro, dst + (wave == 0 ? C::OFF_L : C::OFF_D));
+        }
     };
-    auto commit = [&](int buf) {
-        stQ.commit(sQ[buf], C::QP, tid);
-        stG.commit(sG[buf], C::QP, tid);
-        // rows past the segment: lse = +inf makes P (hence dS) exactly 0
-        if (tid < C::BQ) { sL[buf][tid] = st_ok ? stL * kLog2e : INFINITY; sD[buf][tid] = st_ok ? stD : 0.f; }
+
+    // ---- per-lane LDS offsets (bytes, within a tile)
+    int a_off[NU];                                      // A-operand chunk of row lq for operand step kb
+#pragma unroll
+    for (int kb = 0; kb < NU; ++kb) a_off[kb] = Tile::chunk_offset(lq, 2 * kb + hh);
+    int t_off[D / 32];                                  // transposed reads, column block db
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) t_off[db] = tr_lane_offset_sw<D>(lane, db);
+
+    // ---- stage pieces.  `tile` / `qb` name a block: LDS address of its ring slot and which half of it.
+    auto load_a = [&](const char *tile, int qb, int kb, Frag<bf16_t> &fq, Frag<bf16_t> &fg) __attribute__((always_inline)) {
+        const char *p = tile + qb * 32 * (D * 2) + a_off[kb];
+        fq = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(p));
+        fg = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(p + C::OFF_G));
     };
-    fetch(rq_begin);
-    commit(0);
+    auto load_c = [&](const char *tile, int qb, int u, Frag<bf16_t> &fq, Frag<bf16_t> &fg) __attribute__((always_inline)) {
+        const int half = u / (D / 32), db = u % (D / 32);
+        fq = load_frag_tr_sw<D>(tile, (qb * 2 + half) * 16, t_off[db]);
+        fg = load_frag_tr_sw<D>(tile + C::OFF_G, (qb * 2 + half) * 16, t_off[db]);
+    };
+    // Accumulators of A start at -lse*sqrt(d) and -D of their rows: C-tile element e of this lane is
+    // query row 8*(e/4) + 4*hh + e%4 of the block.  Where the causal diagonal or the end of the
+    // segment crosses the block (first row: local row r0), the masked elements start at -inf
+    // instead, which B turns into P = dS = 0: rows before the lane's key, and rows past the
+    // segment (whose loads re-read its last row).
+    auto init_a = [&](const char *tile, int qb, int r0, f32x16 &sc, f32x16 &dp) __attribute__((always_inline)) {
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            const f32x4 l4 = *reinterpret_cast<const f32x4 *>(tile + C::OFF_L + (qb * 32 + 8 * e4 + 4 * hh) * 4);
+            const f32x4 d4 = *reinterpret_cast<const f32x4 *>(tile + C::OFF_D + (qb * 32 + 8 * e4 + 4 * hh) * 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { sc[4 * e4 + i] = l4[i]; dp[4 * e4 + i] = d4[i]; }
+        }
+        const bool diag = s.causal && ((int64_t)jw0 + C::KW - 1 > s.s0 + r0);
+        if (diag || r0 + 32 > s.l_s) {
+            const int first = diag ? (int)max<int64_t>(min<int64_t>((int64_t)j - s.s0 - r0 - 4 * hh, 64), 0) : 0;
+            const int end = min(s.l_s - r0, 32) - 4 * hh;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int rr = 8 * (e >> 2) + (e & 3);
+                if (rr < first || rr >= end) sc[e] = -INFINITY;
+            }
+        }
+    };
+    // B for elements [e0, e1): P = 2^(c * (S - lse*sqrt(d))), dS = P * (dP - D); finished pairs are
+    // rounded to bf16 into the operand fragments of C
+    auto b_elems = [&](f32x16 &sc, f32x16 &dp, int e0, int e1, Frag<bf16_t> (&pf)[2], Frag<bf16_t> (&df)[2])
+        __attribute__((always_inline)) {
+#pragma unroll
+        for (int e = e0; e < e1; ++e) {
+            const float p = fast_exp2(sc[e] * c);
+            sc[e] = p;
+            dp[e] = p * dp[e];
+            if (e & 1) {
+                pf[e >> 3].v[(e & 7) - 1] = (bf16_t)sc[e - 1]; pf[e >> 3].v[e & 7] = (bf16_t)sc[e];
+                df[e >> 3].v[(e & 7) - 1] = (bf16_t)dp[e - 1]; df[e >> 3].v[e & 7] = (bf16_t)dp[e];
+            }
+        }
+    };
+    // One pipeline step.  A: block (tile_a, qb_a), first row r0_a, into (sc_a, dp_a).  B: (sc_b, dp_b),
+    // packing into (pf_b, df_b).  C: block (tile_c, qb_c) from (pf_c, df_c) into dk, dv.  The matrix
+    // instructions alternate C, C, A, A (C first: A's accumulator start values are still on their
+    // way from LDS); after each one come the B elements that fall to its slot.  Operand fragments
+    // are read from LDS one unit ahead of their use; those of C's first unit by the step before
+    // (cq[0], cg[0] on entry), and this step leaves there those of the next step's C, block
+    // (tile_cn, qb_cn).
+    Frag<bf16_t> cq[2], cg[2];
+    auto step = [&](auto has_a, auto has_b, auto has_c, const char *tile_a, int qb_a, int r0_a, f32x16 &sc_a,
+                    f32x16 &dp_a, f32x16 &sc_b, f32x16 &dp_b, Frag<bf16_t> (&pf_b)[2], Frag<bf16_t> (&df_b)[2],
+                    const char *tile_c, int qb_c, Frag<bf16_t> (&pf_c)[2], Frag<bf16_t> (&df_c)[2], const char *tile_cn,
+                    int qb_cn) __attribute__((always_inline)) {
+        constexpr bool HA = decltype(has_a)::value, HB = decltype(has_b)::value, HC = decltype(has_c)::value;
+        constexpr int NS = 4 * NU;                      // slots; 16 elements of B spread over them
+        static_assert(NU % 2 == 0, "fragment double buffers assume an even number of units");
+        auto b_slot = [&](int slot) __attribute__((always_inline)) {
+            if (HB) {
+                const int e0 = slot * 16 / NS, e1 = (slot + 1) * 16 / NS;
+                __builtin_amdgcn_sched_barrier(0);
+                b_elems(sc_b, dp_b, e0, e1, pf_b, df_b);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        Frag<bf16_t> aq[2], ag[2];
+        if (HA) { init_a(tile_a, qb_a, r0_a, sc_a, dp_a); load_a(tile_a, qb_a, 0, aq[0], ag[0]); }
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            if (HC && u + 1 < NU) load_c(tile_c, qb_c, u + 1, cq[(u + 1) & 1], cg[(u + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            const int half = u / (D / 32), db = u % (D / 32);
+            if (HC) dv[db] = mma(cg[u & 1], pf_c[half], dv[db]);
+            b_slot(4 * u);
+            if (HC) dk[db] = mma(cq[u & 1], df_c[half], dk[db]);
+            b_slot(4 * u + 1);
+            if (HA && u + 1 < NU) load_a(tile_a, qb_a, u + 1, aq[(u + 1) & 1], ag[(u + 1) & 1]);
+            if (u + 1 == NU) load_c(tile_cn, qb_cn, 0, cq[0], cg[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (HA) sc_a = mma(aq[u & 1], kf[u], sc_a);
+            b_slot(4 * u + 2);
+            if (HA) dp_a = mma(ag[u & 1], vf[u], dp_a);
+            b_slot(4 * u + 3);
+        }
+    };
+    using std::true_type;
+    using std::false_type;
+
+    // ---- pipeline.  Block g of this workgroup = rows rq_begin + 32 g ..; tile t = blocks 2t, 2t+1.
+    const int T = (s.l_s - rq_begin + C::BQ - 1) / C::BQ;
+    issue_tile(rq_begin, 0);
+    if (T > 1) issue_tile(rq_begin + C::BQ, 1);
     wait_vmem_all();
     __syncthreads();
 
-    int it = 0;
-    for (int rq0 = rq_begin; rq0 < s.l_s; rq0 += C::BQ, ++it) {
-        const int cur = it & 1;
-        const bool more = rq0 + C::BQ < s.l_s;
-        if (more) fetch(rq0 + C::BQ);
+    f32x16 sc0, dp0, sc1, dp1;                          // even / odd blocks
+    Frag<bf16_t> pf0[2], df0[2], pf1[2], df1[2];
+    // step -1: A(0) alone (leaves the first loop step's C operands in cq[0], cg[0]).  That step has
+    // no C(-1): it multiplies zeros with tile 0 instead.
+    step(true_type{}, false_type{}, false_type{}, smem, 0, rq_begin, sc0, dp0, sc1, dp1, pf0, df0, smem, 0, pf1, df1, smem, 1);
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { pf1[half].v[e] = (bf16_t)0.f; df1[half].v[e] = (bf16_t)0.f; }
 
-        // skip if the wave has no keys, or every key of the wave lies after every row of the tile
-        const int64_t g_tile_last = s.s0 + min(rq0 + C::BQ, s.l_s) - 1;
-        if (wave_on && !(s.causal && jw0 > g_tile_last)) {
-            const bf16_t *tQ = sQ[cur], *tG = sG[cur];
-            const bool diag = s.causal && ((int64_t)jw0 + C::KW - 1 > s.s0 + rq0);
-#pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                f32x16 sc[NB], dp[NB];
-#pragma unroll
-                for (int kb2 = 0; kb2 < NB; ++kb2)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) { sc[kb2][e] = 0.f; dp[kb2][e] = 0.f; }
-#pragma unroll
-                for (int kb = 0; kb < D / 16; ++kb) {
-                    const Frag<bf16_t> aq = load_frag<bf16_t>(&tQ[(qb * 32 + lq) * C::QP + kb * 16 + hh * 8]);
-                    const Frag<bf16_t> ag = load_frag<bf16_t>(&tG[(qb * 32 + lq) * C::QP + kb * 16 + hh * 8]);
-#pragma unroll
-                    for (int kb2 = 0; kb2 < NB; ++kb2) {
-                        sc[kb2] = mma(aq, kf[kb2][kb], sc[kb2]);
-                        dp[kb2] = mma(ag, vf[kb2][kb], dp[kb2]);
-                    }
-                }
-                // C tile: column = this lane's key, element e = query row qb*32 + 8*(e/4) + 4*hh + e%4
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const int rl = qb * 32 + 8 * e4 + 4 * hh;
-                    const f32x4 L4 = *reinterpret_cast<const f32x4 *>(&sL[cur][rl]);
-                    const f32x4 D4 = *reinterpret_cast<const f32x4 *>(&sD[cur][rl]);
-#pragma unroll
-                    for (int kb2 = 0; kb2 < NB; ++kb2)
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int e = 4 * e4 + i;
-                            const float p = fast_exp2(sc[kb2][e] * c - L4[i]);
-                            sc[kb2][e] = p;
-                            dp[kb2][e] = p * (dp[kb2][e] - D4[i]);
-                        }
-                }
-                if (diag) {
-#pragma unroll
-                    for (int kb2 = 0; kb2 < NB; ++kb2) {
-                        // rows of this q-block that come before the lane's key are masked:
-                        // row index within the block, 8*(e/4) + e%4 (+ 4*hh), below `first`
-                        const int first = (int)max<int64_t>(min<int64_t>((int64_t)j[kb2] - s.s0 - rq0 - qb * 32 - 4 * hh, 64), 0);
-#pragma unroll
-                        for (int e = 0; e < 16; ++e)
-                            if (8 * (e >> 2) + (e & 3) < first) { sc[kb2][e] = 0.f; dp[kb2][e] = 0.f; }
-                    }
-                }
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int ks = qb * 2 + half;
-                    Frag<bf16_t> pf[NB], df[NB];
-#pragma unroll
-                    for (int kb2 = 0; kb2 < NB; ++kb2) {
-                        pf[kb2] = acc_to_frag<bf16_t>(sc[kb2], half);
-                        df[kb2] = acc_to_frag<bf16_t>(dp[kb2], half);
-                    }
-#pragma unroll
-                    for (int db = 0; db < D / 32; ++db) {
-                        const Frag<bf16_t> agt = load_frag_tr(tG, C::QP, ks * 16, db * 32, tr_off);
-                        const Frag<bf16_t> aqt = load_frag_tr(tQ, C::QP, ks * 16, db * 32, tr_off);
-#pragma unroll
-                        for (int kb2 = 0; kb2 < NB; ++kb2) {
-                            dv[kb2][db] = mma(agt, pf[kb2], dv[kb2][db]);
-                            dk[kb2][db] = mma(aqt, df[kb2], dk[kb2][db]);
-                        }
-                    }
-                }
-            }
-        }
-
-        if (more) commit(cur ^ 1);
+    int cur = 0;                                        // ring slot of tile t
+    for (int t = 0; t < T; ++t) {
+        const int nxt = cur == C::RING - 1 ? 0 : cur + 1, prv = cur == 0 ? C::RING - 1 : cur - 1;
+        const char *t_cur = smem + cur * C::SLOT, *t_nxt = smem + nxt * C::SLOT, *t_prv = smem + prv * C::SLOT;
+        const int r0 = rq_begin + t * C::BQ;
+        // even step g = 2t: A(2t+1) [tile t, second half], B(2t), C(2t-1) [tile t-1, second half;
+        // for t = 0 tile 0, times zero]
+        step(true_type{}, true_type{}, true_type{}, t_cur, 1, r0 + 32, sc1, dp1, sc0, dp0, pf0, df0, t > 0 ? t_prv : t_cur, 1,
+             pf1, df1, t_cur, 0);
+        // Tile t+1's loads (issued one iteration ago) have landed for this wavefront; after the
+        // barrier for all, and every wavefront is done with tile t-1, whose slot takes tile t+2.
+        wait_vmem_all();
         __syncthreads();
+        if (t + 2 < T) issue_tile(rq_begin + (t + 2) * C::BQ, prv);
+        // odd step g = 2t+1: A(2t+2) [tile t+1, first half; after the last tile a resident tile,
+        // result unused], B(2t+1), C(2t) [tile t, first half]
+        step(true_type{}, true_type{}, true_type{}, t + 1 < T ? t_nxt : t_cur, 0, r0 + C::BQ, sc0, dp0, sc1, dp1, pf1, df1,
+             t_cur, 0, pf0, df0, t_cur, 1);
+        cur = nxt;
+    }
+    // step 2T: C(2T-1) [tile T-1, second half] alone
+    {
+        const char *t_last = smem + (cur == 0 ? C::RING - 1 : cur - 1) * C::SLOT;
+        step(false_type{}, false_type{}, true_type{}, smem, 0, 0, sc0, dp0, sc0, dp0, pf0, df0, t_last, 1, pf1, df1, t_last, 1);
     }
 
-    const float scale = 1.f / sqrtf((float)D);
-#pragma unroll
-    for (int kb2 = 0; kb2 < NB; ++kb2) {
-        if (!key_ok[kb2]) continue;
-        const int64_t off = kv_base + (int64_t)j[kb2] * ld;
+    if (key_ok) {
+        const float scale = 1.f / sqrt_d;
+        const int64_t off = kv_base + (int64_t)j * ld;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
             for (int e4 = 0; e4 < 4; ++e4) {
                 f32x4 a, bq;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { a[i] = dk[kb2][db][4 * e4 + i] * scale; bq[i] = dv[kb2][db][4 * e4 + i]; }
+                for (int i = 0; i < 4; ++i) { a[i] = dk[db][4 * e4 + i] * scale; bq[i] = dv[db][4 * e4 + i]; }
                 const int col = db * 32 + 8 * e4 + 4 * hh;
                 *reinterpret_cast<f32x4 *>(dk_part + off + col) = a;
                 *reinterpret_cast<f32x4 *>(dv_part + off + col) = bq;
@@ -424,15 +492,15 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const bf16_t *q, const bf
         using C = DqBf16Cfg<D>;
         dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
         TimedLaunch tl(K_DQ, st);
-        hipLaunchKernelGGL((bwd_dq_bf16_kernel<D>), grid, dim3(C::NT), 0, st, s, q, k, v, out, dO, lse, ws.D, dq,
-                           ws.dq_part, n_splits);
+        hipLaunchKernelGGL((bwd_dq_bf16_kernel<D>), grid, dim3(C::NT), 0, st, s, q, k, v, out, dO, lse, ws.D, ws.Ls,
+                           dq, ws.dq_part, n_splits);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     {
         using C = DkvBf16Cfg<D>;
         dim3 grid(s.B * s.H, (s.l_x + C::BKV - 1) / C::BKV);
         TimedLaunch tl(K_DKV, st);
-        hipLaunchKernelGGL((bwd_dkv_bf16_kernel<D>), grid, dim3(C::NT), 0, st, s, q, k, v, dO, lse, ws.D, dk_part,
+        hipLaunchKernelGGL((bwd_dkv_bf16_kernel<D>), grid, dim3(C::NT), 0, st, s, q, k, v, dO, ws.Ls, ws.D, dk_part,
                            dv_part);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }

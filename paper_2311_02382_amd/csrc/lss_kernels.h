@@ -28,7 +28,8 @@ struct Workspace {
     float *o_part;    // [splits, B*H, l_s, d]
     float *lse_part;  // [splits, B*H, l_s]
     // backward
-    float *D;         // [B*H, l_s]      rowsum(dO * out)
+    float *D;         // [B*H, l_s]      rowsum(dO * out)   (bf16 kernels: its negative)
+    float *Ls;        // [B*H, l_s]      bf16 kernels: -lse * sqrt(d), start value of the S accumulators
     float *dq_part;   // [splits, B, l_s, H, d]
 };
 size_t workspace_bytes(int l_s, int l_x, int B, int H, int d, int elem_bytes);
