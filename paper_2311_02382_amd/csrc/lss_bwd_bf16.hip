@@ -398,6 +398,9 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
         };
         Frag<bf16_t> aq[2], ag[2];
         if (HA) { init_a(tile_a, qb_a, r0_a, sc_a, dp_a); load_a(tile_a, qb_a, 0, aq[0], ag[0]); }
+        // B's inputs pass through an empty asm here: its arithmetic depends on nothing else in this
+        // step, and the compiler would otherwise move all of it out of the step, in one lump
+        if (HB) asm volatile("" : "+v"(sc_b), "+v"(dp_b));
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
             if (HC && u + 1 < NU) load_c(tile_c, qb_c, u + 1, cq[(u + 1) & 1], cg[(u + 1) & 1]);
@@ -415,6 +418,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
             if (HA) dp_a = mma(ag[u & 1], vf[u], dp_a);
             b_slot(4 * u + 3);
         }
+        // ... and its results through another one, so that it is not sunk below the step either
+        if (HB) asm volatile("" : "+v"(pf_b[0].v), "+v"(pf_b[1].v), "+v"(df_b[0].v), "+v"(df_b[1].v));
     };
     using std::true_type;
     using std::false_type;
