@@ -335,18 +335,21 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
         fg = load_frag_tr_sw<D>(tile + C::OFF_G, (qb * 2 + half) * 16, t_off[db]);
     };
     // Accumulators of A start at -lse*sqrt(d) and -D of their rows: C-tile element e of this lane is
-    // query row 8*(e/4) + 4*hh + e%4 of the block.  Where the causal diagonal or the end of the
-    // segment crosses the block (first row: local row r0), the masked elements start at -inf
-    // instead, which B turns into P = dS = 0: rows before the lane's key, and rows past the
-    // segment (whose loads re-read its last row).
-    auto init_a = [&](const char *tile, int qb, int r0, f32x16 &sc, f32x16 &dp) __attribute__((always_inline)) {
+    // query row 8*(e/4) + 4*hh + e%4 of the block.  init_load reads the values of element groups
+    // [g0, g1) (4 elements each).
+    auto init_load = [&](const char *tile, int qb, int g0, int g1, f32x16 &sc, f32x16 &dp) __attribute__((always_inline)) {
 #pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
+        for (int e4 = g0; e4 < g1; ++e4) {
             const f32x4 l4 = *reinterpret_cast<const f32x4 *>(tile + C::OFF_L + (qb * 32 + 8 * e4 + 4 * hh) * 4);
             const f32x4 d4 = *reinterpret_cast<const f32x4 *>(tile + C::OFF_D + (qb * 32 + 8 * e4 + 4 * hh) * 4);
 #pragma unroll
             for (int i = 0; i < 4; ++i) { sc[4 * e4 + i] = l4[i]; dp[4 * e4 + i] = d4[i]; }
         }
+    };
+    // Where the causal diagonal or the end of the segment crosses the block (first row: local row
+    // r0), the masked elements start at -inf instead, which B turns into P = dS = 0: rows before
+    // the lane's key, and rows past the segment (whose loads re-read its last row).
+    auto init_mask = [&](int r0, f32x16 &sc) __attribute__((always_inline)) {
         const bool diag = s.causal && ((int64_t)jw0 + C::KW - 1 > s.s0 + r0);
         if (diag || r0 + 32 > s.l_s) {
             const int first = diag ? (int)max<int64_t>(min<int64_t>((int64_t)j - s.s0 - r0 - 4 * hh, 64), 0) : 0;
@@ -375,17 +378,19 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
     };
     // One pipeline step.  A: block (tile_a, qb_a), first row r0_a, into (sc_a, dp_a).  B: (sc_b, dp_b),
     // packing into (pf_b, df_b).  C: block (tile_c, qb_c) from (pf_c, df_c) into dk, dv.  The matrix
-    // instructions alternate C, C, A, A (C first: A's accumulator start values are still on their
-    // way from LDS); after each one come the B elements that fall to its slot.  Operand fragments
-    // are read from LDS one unit ahead of their use; those of C's first unit by the step before
-    // (cq[0], cg[0] on entry), and this step leaves there those of the next step's C, block
-    // (tile_cn, qb_cn).
+    // instructions alternate C, C, A, A; after each one come the B elements that fall to its slot.
+    // Everything read from LDS is requested well before its use: operand fragments one unit ahead;
+    // for the next step (A on block (tile_an, qb_an), C on (tile_cn, qb_cn)) this step's last
+    // unit requests the fragments of C's first unit (cq[0], cg[0]) and, into the three quarters of
+    // B's registers that B is done with by then, the start values of A's accumulators (PRE says
+    // the step before did that for this one).
     Frag<bf16_t> cq[2], cg[2];
-    auto step = [&](auto has_a, auto has_b, auto has_c, const char *tile_a, int qb_a, int r0_a, f32x16 &sc_a,
+    auto step = [&](auto has_a, auto has_b, auto has_c, auto pre, const char *tile_a, int qb_a, int r0_a, f32x16 &sc_a,
                     f32x16 &dp_a, f32x16 &sc_b, f32x16 &dp_b, Frag<bf16_t> (&pf_b)[2], Frag<bf16_t> (&df_b)[2],
-                    const char *tile_c, int qb_c, Frag<bf16_t> (&pf_c)[2], Frag<bf16_t> (&df_c)[2], const char *tile_cn,
-                    int qb_cn) __attribute__((always_inline)) {
+                    const char *tile_c, int qb_c, Frag<bf16_t> (&pf_c)[2], Frag<bf16_t> (&df_c)[2], const char *tile_an,
+                    int qb_an, const char *tile_cn, int qb_cn) __attribute__((always_inline)) {
         constexpr bool HA = decltype(has_a)::value, HB = decltype(has_b)::value, HC = decltype(has_c)::value;
+        constexpr bool PRE = decltype(pre)::value;
         constexpr int NS = 4 * NU;                      // slots; 16 elements of B spread over them
         static_assert(NU % 2 == 0, "fragment double buffers assume an even number of units");
         auto b_slot = [&](int slot) __attribute__((always_inline)) {
@@ -397,7 +402,11 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
             }
         };
         Frag<bf16_t> aq[2], ag[2];
-        if (HA) { init_a(tile_a, qb_a, r0_a, sc_a, dp_a); load_a(tile_a, qb_a, 0, aq[0], ag[0]); }
+        if (HA) {
+            init_load(tile_a, qb_a, PRE ? 3 : 0, 4, sc_a, dp_a);
+            load_a(tile_a, qb_a, 0, aq[0], ag[0]);
+            init_mask(r0_a, sc_a);
+        }
         // B's inputs pass through an empty asm here: its arithmetic depends on nothing else in this
         // step, and the compiler would otherwise move all of it out of the step, in one lump
         if (HB) asm volatile("" : "+v"(sc_b), "+v"(dp_b));
@@ -411,7 +420,10 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
             if (HC) dk[db] = mma(cq[u & 1], df_c[half], dk[db]);
             b_slot(4 * u + 1);
             if (HA && u + 1 < NU) load_a(tile_a, qb_a, u + 1, aq[(u + 1) & 1], ag[(u + 1) & 1]);
-            if (u + 1 == NU) load_c(tile_cn, qb_cn, 0, cq[0], cg[0]);
+            if (u + 1 == NU) {
+                load_c(tile_cn, qb_cn, 0, cq[0], cg[0]);
+                init_load(tile_an, qb_an, 0, 3, sc_b, dp_b);    // elements 0..11 of B are packed by now
+            }
             __builtin_amdgcn_sched_barrier(0);
             if (HA) sc_a = mma(aq[u & 1], kf[u], sc_a);
             b_slot(4 * u + 2);
@@ -435,7 +447,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
     Frag<bf16_t> pf0[2], df0[2], pf1[2], df1[2];
     // step -1: A(0) alone (leaves the first loop step's C operands in cq[0], cg[0]).  That step has
     // no C(-1): it multiplies zeros with tile 0 instead.
-    step(true_type{}, false_type{}, false_type{}, smem, 0, rq_begin, sc0, dp0, sc1, dp1, pf0, df0, smem, 0, pf1, df1, smem, 1);
+    step(true_type{}, false_type{}, false_type{}, false_type{}, smem, 0, rq_begin, sc0, dp0, sc1, dp1, pf0, df0, smem, 0, pf1,
+         df1, smem, 1, smem, 1);
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -445,26 +458,28 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
     for (int t = 0; t < T; ++t) {
         const int nxt = cur == C::RING - 1 ? 0 : cur + 1, prv = cur == 0 ? C::RING - 1 : cur - 1;
         const char *t_cur = smem + cur * C::SLOT, *t_nxt = smem + nxt * C::SLOT, *t_prv = smem + prv * C::SLOT;
+        const char *t_a2 = t + 1 < T ? t_nxt : t_cur;   // tile of A(2t+2) and A(2t+3); past the end: any resident tile
         const int r0 = rq_begin + t * C::BQ;
         // even step g = 2t: A(2t+1) [tile t, second half], B(2t), C(2t-1) [tile t-1, second half;
         // for t = 0 tile 0, times zero]
-        step(true_type{}, true_type{}, true_type{}, t_cur, 1, r0 + 32, sc1, dp1, sc0, dp0, pf0, df0, t > 0 ? t_prv : t_cur, 1,
-             pf1, df1, t_cur, 0);
+        step(true_type{}, true_type{}, true_type{}, true_type{}, t_cur, 1, r0 + 32, sc1, dp1, sc0, dp0, pf0, df0,
+             t > 0 ? t_prv : t_cur, 1, pf1, df1, t_a2, 0, t_cur, 0);
         // Tile t+1's loads (issued one iteration ago) have landed for this wavefront; after the
         // barrier for all, and every wavefront is done with tile t-1, whose slot takes tile t+2.
         wait_vmem_all();
         __syncthreads();
         if (t + 2 < T) issue_tile(rq_begin + (t + 2) * C::BQ, prv);
-        // odd step g = 2t+1: A(2t+2) [tile t+1, first half; after the last tile a resident tile,
-        // result unused], B(2t+1), C(2t) [tile t, first half]
-        step(true_type{}, true_type{}, true_type{}, t + 1 < T ? t_nxt : t_cur, 0, r0 + C::BQ, sc0, dp0, sc1, dp1, pf1, df1,
-             t_cur, 0, pf0, df0, t_cur, 1);
+        // odd step g = 2t+1: A(2t+2) [tile t+1, first half; past the end result unused], B(2t+1),
+        // C(2t) [tile t, first half]
+        step(true_type{}, true_type{}, true_type{}, true_type{}, t_a2, 0, r0 + C::BQ, sc0, dp0, sc1, dp1, pf1, df1, t_cur, 0, pf0,
+             df0, t_a2, 1, t_cur, 1);
         cur = nxt;
     }
     // step 2T: C(2T-1) [tile T-1, second half] alone
     {
         const char *t_last = smem + (cur == 0 ? C::RING - 1 : cur - 1) * C::SLOT;
-        step(false_type{}, false_type{}, true_type{}, smem, 0, 0, sc0, dp0, sc0, dp0, pf0, df0, t_last, 1, pf1, df1, t_last, 1);
+        step(false_type{}, false_type{}, true_type{}, false_type{}, smem, 0, 0, sc0, dp0, sc0, dp0, pf0, df0, t_last, 1, pf1, df1,
+             smem, 0, t_last, 1);
     }
 
     if (key_ok) {
