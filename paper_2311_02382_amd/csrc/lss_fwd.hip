@@ -168,7 +168,8 @@ __global__ __launch_bounds__(256) void fwd_kernel(SegShape s, const T *__restric
 // Fixed-order merge of the split-KV partial results of one query row:
 //   lse = log sum_s exp(lse_s),  out = sum_s exp(lse_s - lse) out_s.
 // One thread per (b*H + h, r, group of 4 columns).
-template <typename T, int D>
+// MAXS: compile-time bound of n_splits (loop unrolling; all loads of a thread issued together)
+template <typename T, int D, int MAXS>
 __global__ __launch_bounds__(256) void fwd_merge_kernel(SegShape s, const float *__restrict__ o_part,
                                                         const float *__restrict__ lse_part, int n_splits,
                                                         T *__restrict__ out, float *__restrict__ lse)
@@ -178,17 +179,28 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(SegShape s, const float 
     if (idx >= rows * (D / 4)) return;
     const int64_t row = idx / (D / 4);
     const int c4 = (int)(idx % (D / 4)) * 4;
+    // all loads of a thread are independent: issue them together, then combine in split order
+    float l[MAXS];
+    f32x4 part[MAXS];
+#pragma unroll
+    for (int sp = 0; sp < MAXS; ++sp) {
+        const int spc = sp < n_splits ? sp : n_splits - 1;
+        l[sp] = __builtin_nontemporal_load(lse_part + spc * rows + row);
+        part[sp] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(o_part + (spc * rows + row) * D + c4));
+    }
     float mx = -INFINITY;
-    for (int sp = 0; sp < n_splits; ++sp) mx = fmaxf(mx, lse_part[sp * rows + row]);
+#pragma unroll
+    for (int sp = 0; sp < MAXS; ++sp)
+        if (sp < n_splits) mx = fmaxf(mx, l[sp]);
     float sum = 0.f;
-    for (int sp = 0; sp < n_splits; ++sp) sum += expf(lse_part[sp * rows + row] - mx);
+#pragma unroll
+    for (int sp = 0; sp < MAXS; ++sp)
+        if (sp < n_splits) sum += expf(l[sp] - mx);
     const float total = mx + logf(sum);
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int sp = 0; sp < n_splits; ++sp) {
-        const float w = expf(lse_part[sp * rows + row] - total);
-        const f32x4 part = *reinterpret_cast<const f32x4 *>(o_part + (sp * rows + row) * D + c4);
-        acc += w * part;
-    }
+#pragma unroll
+    for (int sp = 0; sp < MAXS; ++sp)
+        if (sp < n_splits) acc += expf(l[sp] - total) * part[sp];
     const int r = (int)(row % s.l_s);
     const int64_t bh = row / s.l_s;
     const int64_t b = bh / s.H, h = bh % s.H;
@@ -218,8 +230,15 @@ static hipError_t launch_fwd_d(const SegShape &s, const T *q, const T *k, const 
     const int64_t items = (int64_t)s.B * s.H * s.l_s * (D / 4);
     {
         TimedLaunch tl(K_FWD_MERGE, st);
-        hipLaunchKernelGGL((fwd_merge_kernel<T, D>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, s,
-                           ws.o_part, ws.lse_part, n_splits, out, lse);
+        const dim3 grid((unsigned)((items + 255) / 256)), block(256);
+        if (n_splits <= 2)
+            hipLaunchKernelGGL((fwd_merge_kernel<T, D, 2>), grid, block, 0, st, s, ws.o_part, ws.lse_part, n_splits, out, lse);
+        else if (n_splits <= 4)
+            hipLaunchKernelGGL((fwd_merge_kernel<T, D, 4>), grid, block, 0, st, s, ws.o_part, ws.lse_part, n_splits, out, lse);
+        else if (n_splits <= 8)
+            hipLaunchKernelGGL((fwd_merge_kernel<T, D, 8>), grid, block, 0, st, s, ws.o_part, ws.lse_part, n_splits, out, lse);
+        else
+            hipLaunchKernelGGL((fwd_merge_kernel<T, D, 16>), grid, block, 0, st, s, ws.o_part, ws.lse_part, n_splits, out, lse);
     }
     return hipGetLastError();
 }
