@@ -15,24 +15,38 @@ namespace lss {
 // ------------------------------------------------------------------------------------------ dQ
 template <int D>
 struct DqBf16Cfg {
-    static constexpr int NB = D == 64 ? 2 : 1;          // 32-row query blocks per wavefront
-    static constexpr int WAVES = 4, RW = 32 * NB;
+    static constexpr int WAVES = 4, RW = 32;            // query rows per wavefront
     static constexpr int BR = WAVES * RW, BC = 64, NT = 256;
-    static constexpr int KP = D + 8;    // pitch of the K and V tiles (elements)
+    static constexpr int RING = 3;                      // K/V tiles resident in LDS
+    static constexpr int NU = D / 16;                   // operand steps of the S/dP products; same for dQ
+    using Tile = DirectTile<D, BC>;
+    static constexpr int OFF_V = Tile::BYTES, SLOT = 2 * Tile::BYTES;   // one ring slot: K tile, V tile
 };
 
+// Transposed formulation: S^T = K Q^T and dP^T = V dO^T put the wavefront's 32 queries on the lanes
+// (lse and D are per-lane scalars), and dS^T comes out of the accumulators in the layout the
+// dQ^T += K^T dS^T product wants as its second operand.  The keys are walked in blocks of 32 (two
+// per 64-key K/V tile).  Per block g three stages:
+//     A(g): S^T and dP^T products (matrix),  B(g): dS^T (vector: exp, multiplies, bf16 packing),
+//     C(g): dQ^T product (matrix).
+// As in the dK/dV kernel below the stages are software-pipelined, step g issuing the matrix
+// instructions of A(g+1) and C(g-1) with the vector work of B(g) spread between them, over a ring
+// of three K/V tiles that are loaded global -> LDS directly, a full loop iteration ahead.
+// D = rowsum(dO * out) is computed here, and its negative (with -lse * sqrt(d)) written for the
+// dK/dV kernel.
 template <int D>
-__global__ __launch_bounds__(256, 2) void bwd_dq_bf16_kernel(
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dq_bf16_kernel(
     SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO, const float *__restrict__ lse,
     float *__restrict__ Dv, float *__restrict__ Lsv, bf16_t *__restrict__ dq, float *__restrict__ dq_part, int n_splits)
 {
     using C = DqBf16Cfg<D>;
-    constexpr int NB = C::NB;
-    __shared__ __attribute__((aligned(16))) bf16_t sK[2][C::BC * C::KP];
-    __shared__ __attribute__((aligned(16))) bf16_t sV[2][C::BC * C::KP];
+    using Tile = typename C::Tile;
+    constexpr int NU = C::NU;
+    __shared__ __attribute__((aligned(1024))) char smem[C::RING * C::SLOT];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int bh = blockIdx.y, b = bh / s.H, h = bh % s.H, split = blockIdx.z;
     // query tiles are dispatched last-first: under the causal mask the last tiles see the most
     // keys, and starting the longest workgroups first shortens the tail of the launch
@@ -45,160 +59,227 @@ __global__ __launch_bounds__(256, 2) void bwd_dq_bf16_kernel(
     const int n_tiles = (kv_end + C::BC - 1) / C::BC;
     const int per = (n_tiles + n_splits - 1) / n_splits;
     const int t_begin = split * per, t_end = min(n_tiles, t_begin + per);
+    const int T = max(t_end - t_begin, 0);
 
-    const bool wave_on = rw0 < s.l_s;
-    const int64_t g_wave_last = s.s0 + min(rw0 + C::RW, s.l_s) - 1;
-
-    int r[NB];
-    bool row_ok[NB];
-    float L2[NB], Dr[NB];
-    Frag<bf16_t> qf[NB][D / 16], gf[NB][D / 16];
-#pragma unroll
-    for (int qb = 0; qb < NB; ++qb) {
-        r[qb] = rw0 + qb * 32 + lq;
-        row_ok[qb] = r[qb] < s.l_s;
-        // rows past the segment re-read its last row (unconditional loads); they are never stored,
-        // and lse = +inf makes their P and dS exactly 0
-        const int rc = min(r[qb], s.l_s - 1);
+    // this lane's query row (column of the S^T tile); rows past the segment re-read its last row
+    // (unconditional loads), get lse = +inf, which makes their P and dS exactly 0, and are never stored
+    const int r = rw0 + lq;
+    const bool row_ok = r < s.l_s;
+    Frag<bf16_t> qf[NU], gf[NU];
+    float L2, Dr;
+    {
+        const int rc = min(r, s.l_s - 1);
         const int64_t off = ((int64_t)b * s.l_s + rc) * ld + (int64_t)h * D + hh * 8;
         float dsum = 0.f;
 #pragma unroll
-        for (int kb = 0; kb < D / 16; ++kb) {
-            qf[qb][kb] = load_frag<bf16_t>(q + off + kb * 16);
-            gf[qb][kb] = load_frag<bf16_t>(dO + off + kb * 16);
+        for (int kb = 0; kb < NU; ++kb) {
+            qf[kb] = load_frag<bf16_t>(q + off + kb * 16);
+            gf[kb] = load_frag<bf16_t>(dO + off + kb * 16);
             const Frag<bf16_t> of = load_frag<bf16_t>(out + off + kb * 16);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) dsum += (float)gf[qb][kb].v[e] * (float)of.v[e];
+            for (int e = 0; e < 8; ++e) dsum += (float)gf[kb].v[e] * (float)of.v[e];
         }
         dsum += __shfl_xor(dsum, 32);
-        Dr[qb] = dsum;
+        Dr = dsum;
         const float lv = lse[(int64_t)bh * s.l_s + rc];
-        L2[qb] = row_ok[qb] ? lv * kLog2e : INFINITY;
-        if (row_ok[qb] && hh == 0 && split == 0) {
+        L2 = row_ok ? lv * kLog2e : INFINITY;
+        if (row_ok && hh == 0 && split == 0) {
             // start values of the dK/dV kernel's accumulators
-            Dv[(int64_t)bh * s.l_s + r[qb]] = -dsum;
-            Lsv[(int64_t)bh * s.l_s + r[qb]] = -lv * sqrtf((float)D);
+            Dv[(int64_t)bh * s.l_s + r] = -dsum;
+            Lsv[(int64_t)bh * s.l_s + r] = -lv * sqrtf((float)D);
         }
     }
     const float c = kLog2e / sqrtf((float)D);
-
-    f32x16 acc[NB][D / 32];
+    // -D in all 16 accumulator slots: third operand of each block's first dP^T instruction
+    f32x16 neg_d;
 #pragma unroll
-    for (int qb = 0; qb < NB; ++qb)
+    for (int e = 0; e < 16; ++e) neg_d[e] = -Dr;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    f32x16 acc[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) acc[db] = zero16;
+
+    if (T > 0) {
+        const bf16_t *kbase = k + (int64_t)b * s.l_x * ld + (int64_t)h * D;
+        const bf16_t *vbase = v + (int64_t)b * s.l_x * ld + (int64_t)h * D;
+
+        // ---- tile loads, by all four wavefronts
+        uint32_t offF[Tile::NI];                        // this lane's global offsets within a full tile
+        Tile::offsets(offF, ld, C::BC, wave, lane);
+        auto issue_tile = [&](int t, int slot) {
+            const int j0 = t * C::BC, rows_ok = s.l_x - j0;
+            uint32_t off[Tile::NI];
+#pragma unroll
+            for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i];
+            if (rows_ok < C::BC) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
+            char *dst = smem + slot * C::SLOT;
+            Tile::issue(kbase + (int64_t)j0 * ld, off, dst, wave);
+            Tile::issue(vbase + (int64_t)j0 * ld, off, dst + C::OFF_V, wave);
+        };
+
+        // ---- per-lane LDS offsets (bytes, within a tile)
+        int a_off[NU];                                  // A-operand chunk of row lq for operand step kb
+#pragma unroll
+        for (int kb = 0; kb < NU; ++kb) a_off[kb] = Tile::chunk_offset(lq, 2 * kb + hh);
+        int t_off[D / 32];                              // transposed reads, column block db
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) t_off[db] = tr_lane_offset_sw<D>(lane, db);
+
+        // ---- stage pieces.  `tile` / `kb2` name a block: LDS address of its ring slot and which half of it.
+        auto load_a = [&](const char *tile, int kb2, int kb, Frag<bf16_t> &fk, Frag<bf16_t> &fv) __attribute__((always_inline)) {
+            const char *p = tile + kb2 * 32 * (D * 2) + a_off[kb];
+            fk = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(p));
+            fv = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(p + C::OFF_V));
+        };
+        auto load_c = [&](const char *tile, int kb2, int u, Frag<bf16_t> &fk) __attribute__((always_inline)) {
+            const int half = u / (D / 32), db = u % (D / 32);
+            fk = load_frag_tr_sw<D>(tile, (kb2 * 2 + half) * 16, t_off[db]);
+        };
+        // B for elements [e0, e1): P = 2^(c * S - lse * log2 e), dS = P * (dP - D); finished pairs are
+        // rounded to bf16 into the operand fragments of C
+        auto b_elems = [&](f32x16 &sc, f32x16 &dp, int e0, int e1, Frag<bf16_t> (&df)[2]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int e = e0; e < e1; ++e) {
+                const float p = fast_exp2(sc[e] * c - L2);
+                dp[e] = p * dp[e];
+                if (e & 1) { df[e >> 3].v[(e & 7) - 1] = (bf16_t)dp[e - 1]; df[e >> 3].v[e & 7] = (bf16_t)dp[e]; }
+            }
+        };
+        // Where the causal diagonal or the end of the sequence crosses a block (first key jb), the
+        // masked elements of its finished S^T accumulator are set to -inf before B, which turns them
+        // into P = dS = 0: keys after the lane's row, and keys past the sequence (whose loads
+        // re-read its last row).  C-tile element e of this lane is key 8*(e/4) + 4*hh + e%4 of the block.
+        auto mask_s = [&](int jb, f32x16 &sc) __attribute__((always_inline)) {
+            const bool diag = s.causal && (jb + 31 > s.s0 + rw0);
+            if (diag || jb + 32 > s.l_x) {
+                const int64_t last = s.causal ? min<int64_t>(s.s0 + r, s.l_x - 1) : (int64_t)s.l_x - 1;
+                const int rel = (int)max<int64_t>(min<int64_t>(last - jb - 4 * hh, 64), -1);
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    if (8 * (e >> 2) + (e & 3) > rel) sc[e] = -INFINITY;
+            }
+        };
+
+        // One pipeline step.  A: block (tile_a, kb2_a) into (sc_a, dp_a).  B: (sc_b, dp_b), first key
+        // jb_b, packing into df_b.  C: block (tile_c, kb2_c) from df_c into acc.  Per unit the matrix
+        // instructions go C, A, A; after each one come the B elements that fall to its slot.
+        // Operand fragments are read from LDS one unit ahead of their use; those of the first unit
+        // by the step before (ak[0], av[0], ck[0] on entry), and this step leaves there those of
+        // the next step: A on block (tile_an, kb2_an), C on (tile_cn, kb2_cn).
+        Frag<bf16_t> ak[2], av[2], ck[2];
+        auto step = [&](auto has_a, auto has_b, auto has_c, const char *tile_a, int kb2_a, f32x16 &sc_a, f32x16 &dp_a,
+                        f32x16 &sc_b, f32x16 &dp_b, int jb_b, Frag<bf16_t> (&df_b)[2], const char *tile_c, int kb2_c,
+                        Frag<bf16_t> (&df_c)[2], const char *tile_an, int kb2_an, const char *tile_cn, int kb2_cn)
+            __attribute__((always_inline)) {
+            constexpr bool HA = decltype(has_a)::value, HB = decltype(has_b)::value, HC = decltype(has_c)::value;
+            constexpr int NS = 3 * NU;                  // slots; 16 elements of B spread over them
+            static_assert(NU % 2 == 0, "fragment double buffers assume an even number of units");
+            auto b_slot = [&](int slot) __attribute__((always_inline)) {
+                if (HB) {
+                    const int e0 = slot * 16 / NS, e1 = (slot + 1) * 16 / NS;
+                    __builtin_amdgcn_sched_barrier(0);
+                    b_elems(sc_b, dp_b, e0, e1, df_b);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            if (HB) {
+                mask_s(jb_b, sc_b);
+                // B's inputs pass through an empty asm here: its arithmetic depends on nothing else in
+                // this step, and the compiler would otherwise move all of it out of the step, in one lump
+                asm volatile("" : "+v"(sc_b), "+v"(dp_b));
+            }
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                if (u + 1 < NU) {
+                    if (HC) load_c(tile_c, kb2_c, u + 1, ck[(u + 1) & 1]);
+                    if (HA) load_a(tile_a, kb2_a, u + 1, ak[(u + 1) & 1], av[(u + 1) & 1]);
+                } else {
+                    load_c(tile_cn, kb2_cn, 0, ck[0]);
+                    load_a(tile_an, kb2_an, 0, ak[0], av[0]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                const int half = u / (D / 32), db = u % (D / 32);
+                if (HC) acc[db] = mma(ck[u & 1], df_c[half], acc[db]);
+                b_slot(3 * u);
+                if (HA) sc_a = mma(ak[u & 1], qf[u], u == 0 ? zero16 : sc_a);
+                b_slot(3 * u + 1);
+                if (HA) dp_a = mma(av[u & 1], gf[u], u == 0 ? neg_d : dp_a);
+                b_slot(3 * u + 2);
+            }
+            // ... and its results through another one, so that it is not sunk below the step either
+            if (HB) asm volatile("" : "+v"(df_b[0].v), "+v"(df_b[1].v));
+        };
+        using std::true_type;
+        using std::false_type;
+
+        // ---- pipeline.  Block g = keys (t_begin + g/2) * 64 + (g%2) * 32 ..; tile t = blocks 2t, 2t+1.
+        issue_tile(t_begin, 0);
+        if (T > 1) issue_tile(t_begin + 1, 1);
+        wait_vmem_all();
+        __syncthreads();
+
+        f32x16 sc0, dp0, sc1, dp1;                      // even / odd blocks
+        Frag<bf16_t> df0[2], df1[2];
+        // step -1: A(0) alone.  The first loop step has no C(-1): it multiplies zeros with tile 0 instead.
+        load_a(smem, 0, 0, ak[0], av[0]);
+        step(true_type{}, false_type{}, false_type{}, smem, 0, sc0, dp0, sc1, dp1, 0, df0, smem, 0, df1, smem, 1, smem, 1);
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) df1[half].v[e] = (bf16_t)0.f;
+
+        int cur = 0;                                    // ring slot of tile t
+        for (int t = 0; t < T; ++t) {
+            const int nxt = cur == C::RING - 1 ? 0 : cur + 1, prv = cur == 0 ? C::RING - 1 : cur - 1;
+            const char *t_cur = smem + cur * C::SLOT, *t_nxt = smem + nxt * C::SLOT, *t_prv = smem + prv * C::SLOT;
+            const char *t_a2 = t + 1 < T ? t_nxt : t_cur;   // tile of A(2t+2), A(2t+3); past the end: any resident tile
+            const int j0 = (t_begin + t) * C::BC;
+            // even step g = 2t: A(2t+1) [tile t, second half], B(2t), C(2t-1) [tile t-1, second half;
+            // for t = 0 tile 0, times zero]
+            step(true_type{}, true_type{}, true_type{}, t_cur, 1, sc1, dp1, sc0, dp0, j0, df0, t > 0 ? t_prv : t_cur, 1, df1,
+                 t_a2, 0, t_cur, 0);
+            // Tile t+1's loads (issued one iteration ago) have landed for this wavefront; after the
+            // barrier for all, and every wavefront is done with tile t-1, whose slot takes tile t+2.
+            wait_vmem_all();
+            __syncthreads();
+            if (t + 2 < T) issue_tile(t_begin + t + 2, prv);
+            // odd step g = 2t+1: A(2t+2) [tile t+1, first half; past the end result unused], B(2t+1),
+            // C(2t) [tile t, first half]
+            step(true_type{}, true_type{}, true_type{}, t_a2, 0, sc0, dp0, sc1, dp1, j0 + 32, df1, t_cur, 0, df0, t_a2, 1, t_cur,
+                 1);
+            cur = nxt;
+        }
+        // step 2T: C(2T-1) [tile T-1, second half] alone
+        {
+            const char *t_last = smem + (cur == 0 ? C::RING - 1 : cur - 1) * C::SLOT;
+            step(false_type{}, false_type{}, true_type{}, smem, 0, sc0, dp0, sc0, dp0, 0, df0, t_last, 1, df1, smem, 0, t_last,
+                 1);
+        }
+    }
+
+    if (!row_ok) return;
+    const float scale = 1.f / sqrtf((float)D);
+    if (n_splits == 1) {
+        bf16_t *dst0 = dq + ((int64_t)b * s.l_s + r) * ld + (int64_t)h * D;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[qb][db][e] = 0.f;
-
-    const bf16_t *kbase = k + (int64_t)b * s.l_x * ld + (int64_t)h * D;
-    const bf16_t *vbase = v + (int64_t)b * s.l_x * ld + (int64_t)h * D;
-    const int tr_off = tr_lane_offset(lane, C::KP);
-
-    TileStage<D, C::BC> stK, stV;
-    if (t_begin < t_end) {
-        const int j0 = t_begin * C::BC;
-        stK.fetch(kbase + (int64_t)j0 * ld, ld, s.l_x - j0, tid);
-        stV.fetch(vbase + (int64_t)j0 * ld, ld, s.l_x - j0, tid);
-        stK.commit(sK[0], C::KP, tid);
-        stV.commit(sV[0], C::KP, tid);
-    }
-    wait_vmem_all();
-    __syncthreads();
-
-    for (int t = t_begin; t < t_end; ++t) {
-        const int cur = (t - t_begin) & 1;
-        const int j0 = t * C::BC;
-        const bool more = t + 1 < t_end;
-        if (more) {
-            const int j1 = j0 + C::BC;
-            stK.fetch(kbase + (int64_t)j1 * ld, ld, s.l_x - j1, tid);
-            stV.fetch(vbase + (int64_t)j1 * ld, ld, s.l_x - j1, tid);
-        }
-
-        if (wave_on && !(s.causal && j0 > g_wave_last)) {
-            const bf16_t *tK = sK[cur], *tV = sV[cur];
-            const bool tail = j0 + C::BC > s.l_x;
-            const bool diag = s.causal && (j0 + C::BC - 1 > s.s0 + rw0);
+            for (int e4 = 0; e4 < 4; ++e4)
+                *reinterpret_cast<bf16x4 *>(dst0 + db * 32 + 8 * e4 + 4 * hh) =
+                    pack4(acc[db][4 * e4] * scale, acc[db][4 * e4 + 1] * scale, acc[db][4 * e4 + 2] * scale,
+                          acc[db][4 * e4 + 3] * scale);
+    } else {
+        float *dst0 = dq_part + (int64_t)split * s.B * s.l_s * ld + ((int64_t)b * s.l_s + r) * ld + (int64_t)h * D;
 #pragma unroll
-            for (int kb2 = 0; kb2 < 2; ++kb2) {
-                f32x16 sc[NB], dp[NB];
+        for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-                for (int qb = 0; qb < NB; ++qb)
+            for (int e4 = 0; e4 < 4; ++e4) {
+                f32x4 val;
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) { sc[qb][e] = 0.f; dp[qb][e] = 0.f; }
-#pragma unroll
-                for (int kb = 0; kb < D / 16; ++kb) {
-                    const Frag<bf16_t> ak = load_frag<bf16_t>(&tK[(kb2 * 32 + lq) * C::KP + kb * 16 + hh * 8]);
-                    const Frag<bf16_t> av = load_frag<bf16_t>(&tV[(kb2 * 32 + lq) * C::KP + kb * 16 + hh * 8]);
-#pragma unroll
-                    for (int qb = 0; qb < NB; ++qb) {
-                        sc[qb] = mma(ak, qf[qb][kb], sc[qb]);
-                        dp[qb] = mma(av, gf[qb][kb], dp[qb]);
-                    }
-                }
-#pragma unroll
-                for (int qb = 0; qb < NB; ++qb) {
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const float p = fast_exp2(sc[qb][e] * c - L2[qb]);
-                        sc[qb][e] = p * (dp[qb][e] - Dr[qb]);
-                    }
-                    if (tail || diag) {
-                        const int64_t last = s.causal ? min<int64_t>(s.s0 + r[qb], s.l_x - 1) : (int64_t)s.l_x - 1;
-                        const int rel = (int)max<int64_t>(min<int64_t>(last - j0 - 4 * hh, 2 * C::BC), -1);
-#pragma unroll
-                        for (int e = 0; e < 16; ++e)
-                            if (kb2 * 32 + 8 * (e >> 2) + (e & 3) > rel) sc[qb][e] = 0.f;
-                    }
-                }
-#pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    const int ks = kb2 * 2 + half;
-                    Frag<bf16_t> df[NB];
-#pragma unroll
-                    for (int qb = 0; qb < NB; ++qb) df[qb] = acc_to_frag<bf16_t>(sc[qb], half);
-#pragma unroll
-                    for (int db = 0; db < D / 32; ++db) {
-                        const Frag<bf16_t> a = load_frag_tr(tK, C::KP, ks * 16, db * 32, tr_off);
-#pragma unroll
-                        for (int qb = 0; qb < NB; ++qb) acc[qb][db] = mma(a, df[qb], acc[qb][db]);
-                    }
-                }
+                for (int i = 0; i < 4; ++i) val[i] = acc[db][4 * e4 + i] * scale;
+                *reinterpret_cast<f32x4 *>(dst0 + db * 32 + 8 * e4 + 4 * hh) = val;
             }
-        }
-
-        if (more) {
-            stK.commit(sK[cur ^ 1], C::KP, tid);
-            stV.commit(sV[cur ^ 1], C::KP, tid);
-        }
-        __syncthreads();
-    }
-
-    const float scale = 1.f / sqrtf((float)D);
-#pragma unroll
-    for (int qb = 0; qb < NB; ++qb) {
-        if (!row_ok[qb]) continue;
-        if (n_splits == 1) {
-            bf16_t *dst0 = dq + ((int64_t)b * s.l_s + r[qb]) * ld + (int64_t)h * D;
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4)
-                    *reinterpret_cast<bf16x4 *>(dst0 + db * 32 + 8 * e4 + 4 * hh) =
-                        pack4(acc[qb][db][4 * e4] * scale, acc[qb][db][4 * e4 + 1] * scale,
-                              acc[qb][db][4 * e4 + 2] * scale, acc[qb][db][4 * e4 + 3] * scale);
-        } else {
-            float *dst0 = dq_part + (int64_t)split * s.B * s.l_s * ld + ((int64_t)b * s.l_s + r[qb]) * ld + (int64_t)h * D;
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    f32x4 val;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) val[i] = acc[qb][db][4 * e4 + i] * scale;
-                    *reinterpret_cast<f32x4 *>(dst0 + db * 32 + 8 * e4 + 4 * hh) = val;
-                }
-        }
     }
 }
 
