@@ -166,11 +166,13 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dq_bf16_kernel(
         // instructions go C, A, A; after each one come the B elements that fall to its slot.
         // Operand fragments are read from LDS one unit ahead of their use; those of the first unit
         // by the step before (ak[0], av[0], ck[0] on entry), and this step leaves there those of
-        // the next step: A on block (tile_an, kb2_an), C on (tile_cn, kb2_cn).
+        // the next step: A on block (tile_an, kb2_an), C on (tile_cn, kb2_cn).  `mid` runs before
+        // those last reads: the even steps put the loop's barrier there, because the next step's
+        // blocks may lie in the tile that the barrier publishes.
         Frag<bf16_t> ak[2], av[2], ck[2];
         auto step = [&](auto has_a, auto has_b, auto has_c, const char *tile_a, int kb2_a, f32x16 &sc_a, f32x16 &dp_a,
                         f32x16 &sc_b, f32x16 &dp_b, int jb_b, Frag<bf16_t> (&df_b)[2], const char *tile_c, int kb2_c,
-                        Frag<bf16_t> (&df_c)[2], const char *tile_an, int kb2_an, const char *tile_cn, int kb2_cn)
+                        Frag<bf16_t> (&df_c)[2], const char *tile_an, int kb2_an, const char *tile_cn, int kb2_cn, auto &&mid)
             __attribute__((always_inline)) {
             constexpr bool HA = decltype(has_a)::value, HB = decltype(has_b)::value, HC = decltype(has_c)::value;
             constexpr int NS = 3 * NU;                  // slots; 16 elements of B spread over them
@@ -195,6 +197,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dq_bf16_kernel(
                     if (HC) load_c(tile_c, kb2_c, u + 1, ck[(u + 1) & 1]);
                     if (HA) load_a(tile_a, kb2_a, u + 1, ak[(u + 1) & 1], av[(u + 1) & 1]);
                 } else {
+                    mid();
                     load_c(tile_cn, kb2_cn, 0, ck[0]);
                     load_a(tile_an, kb2_an, 0, ak[0], av[0]);
                 }
@@ -223,7 +226,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dq_bf16_kernel(
         Frag<bf16_t> df0[2], df1[2];
         // step -1: A(0) alone.  The first loop step has no C(-1): it multiplies zeros with tile 0 instead.
         load_a(smem, 0, 0, ak[0], av[0]);
-        step(true_type{}, false_type{}, false_type{}, smem, 0, sc0, dp0, sc1, dp1, 0, df0, smem, 0, df1, smem, 1, smem, 1);
+        auto nothing = [] {};
+        step(true_type{}, false_type{}, false_type{}, smem, 0, sc0, dp0, sc1, dp1, 0, df0, smem, 0, df1, smem, 1, smem, 1, nothing);
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -237,24 +241,26 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dq_bf16_kernel(
             const int j0 = (t_begin + t) * C::BC;
             // even step g = 2t: A(2t+1) [tile t, second half], B(2t), C(2t-1) [tile t-1, second half;
             // for t = 0 tile 0, times zero]
+            // Before its last reads (which may touch tile t+1): tile t+1's loads, issued one iteration
+            // ago, have landed for this wavefront; after the barrier for all, and every wavefront has
+            // requested its last operands from tile t-1, whose slot takes tile t+2.
             step(true_type{}, true_type{}, true_type{}, t_cur, 1, sc1, dp1, sc0, dp0, j0, df0, t > 0 ? t_prv : t_cur, 1, df1,
-                 t_a2, 0, t_cur, 0);
-            // Tile t+1's loads (issued one iteration ago) have landed for this wavefront; after the
-            // barrier for all, and every wavefront is done with tile t-1, whose slot takes tile t+2.
-            wait_vmem_all();
-            __syncthreads();
-            if (t + 2 < T) issue_tile(t_begin + t + 2, prv);
+                 t_a2, 0, t_cur, 0, [&] {
+                     wait_vmem_all();
+                     __syncthreads();
+                     if (t + 2 < T) issue_tile(t_begin + t + 2, prv);
+                 });
             // odd step g = 2t+1: A(2t+2) [tile t+1, first half; past the end result unused], B(2t+1),
             // C(2t) [tile t, first half]
             step(true_type{}, true_type{}, true_type{}, t_a2, 0, sc0, dp0, sc1, dp1, j0 + 32, df1, t_cur, 0, df0, t_a2, 1, t_cur,
-                 1);
+                 1, nothing);
             cur = nxt;
         }
         // step 2T: C(2T-1) [tile T-1, second half] alone
         {
             const char *t_last = smem + (cur == 0 ? C::RING - 1 : cur - 1) * C::SLOT;
             step(false_type{}, false_type{}, true_type{}, smem, 0, sc0, dp0, sc0, dp0, 0, df0, t_last, 1, df1, smem, 0, t_last,
-                 1);
+                 1, nothing);
         }
     }
 
@@ -464,12 +470,14 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
     // for the next step (A on block (tile_an, qb_an), C on (tile_cn, qb_cn)) this step's last
     // unit requests the fragments of C's first unit (cq[0], cg[0]) and, into the three quarters of
     // B's registers that B is done with by then, the start values of A's accumulators (PRE says
-    // the step before did that for this one).
+    // the step before did that for this one).  `mid` runs before those last requests: the even
+    // steps put the loop's barrier there, because the next step's A block may lie in the tile that
+    // the barrier publishes.
     Frag<bf16_t> cq[2], cg[2];
     auto step = [&](auto has_a, auto has_b, auto has_c, auto pre, const char *tile_a, int qb_a, int r0_a, f32x16 &sc_a,
                     f32x16 &dp_a, f32x16 &sc_b, f32x16 &dp_b, Frag<bf16_t> (&pf_b)[2], Frag<bf16_t> (&df_b)[2],
                     const char *tile_c, int qb_c, Frag<bf16_t> (&pf_c)[2], Frag<bf16_t> (&df_c)[2], const char *tile_an,
-                    int qb_an, const char *tile_cn, int qb_cn) __attribute__((always_inline)) {
+                    int qb_an, const char *tile_cn, int qb_cn, auto &&mid) __attribute__((always_inline)) {
         constexpr bool HA = decltype(has_a)::value, HB = decltype(has_b)::value, HC = decltype(has_c)::value;
         constexpr bool PRE = decltype(pre)::value;
         constexpr int NS = 4 * NU;                      // slots; 16 elements of B spread over them
@@ -502,6 +510,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
             b_slot(4 * u + 1);
             if (HA && u + 1 < NU) load_a(tile_a, qb_a, u + 1, aq[(u + 1) & 1], ag[(u + 1) & 1]);
             if (u + 1 == NU) {
+                mid();
                 load_c(tile_cn, qb_cn, 0, cq[0], cg[0]);
                 init_load(tile_an, qb_an, 0, 3, sc_b, dp_b);    // elements 0..11 of B are packed by now
             }
@@ -528,8 +537,9 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
     Frag<bf16_t> pf0[2], df0[2], pf1[2], df1[2];
     // step -1: A(0) alone (leaves the first loop step's C operands in cq[0], cg[0]).  That step has
     // no C(-1): it multiplies zeros with tile 0 instead.
+    auto nothing = [] {};
     step(true_type{}, false_type{}, false_type{}, false_type{}, smem, 0, rq_begin, sc0, dp0, sc1, dp1, pf0, df0, smem, 0, pf1,
-         df1, smem, 1, smem, 1);
+         df1, smem, 1, smem, 1, nothing);
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -543,24 +553,26 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
         const int r0 = rq_begin + t * C::BQ;
         // even step g = 2t: A(2t+1) [tile t, second half], B(2t), C(2t-1) [tile t-1, second half;
         // for t = 0 tile 0, times zero]
+        // Before its last requests (which may touch tile t+1): tile t+1's loads, issued one iteration
+        // ago, have landed for this wavefront; after the barrier for all, and every wavefront has
+        // requested its last operands from tile t-1, whose slot takes tile t+2.
         step(true_type{}, true_type{}, true_type{}, true_type{}, t_cur, 1, r0 + 32, sc1, dp1, sc0, dp0, pf0, df0,
-             t > 0 ? t_prv : t_cur, 1, pf1, df1, t_a2, 0, t_cur, 0);
-        // Tile t+1's loads (issued one iteration ago) have landed for this wavefront; after the
-        // barrier for all, and every wavefront is done with tile t-1, whose slot takes tile t+2.
-        wait_vmem_all();
-        __syncthreads();
-        if (t + 2 < T) issue_tile(rq_begin + (t + 2) * C::BQ, prv);
+             t > 0 ? t_prv : t_cur, 1, pf1, df1, t_a2, 0, t_cur, 0, [&] {
+                 wait_vmem_all();
+                 __syncthreads();
+                 if (t + 2 < T) issue_tile(rq_begin + (t + 2) * C::BQ, prv);
+             });
         // odd step g = 2t+1: A(2t+2) [tile t+1, first half; past the end result unused], B(2t+1),
         // C(2t) [tile t, first half]
         step(true_type{}, true_type{}, true_type{}, true_type{}, t_a2, 0, r0 + C::BQ, sc0, dp0, sc1, dp1, pf1, df1, t_cur, 0, pf0,
-             df0, t_a2, 1, t_cur, 1);
+             df0, t_a2, 1, t_cur, 1, nothing);
         cur = nxt;
     }
     // step 2T: C(2T-1) [tile T-1, second half] alone
     {
         const char *t_last = smem + (cur == 0 ? C::RING - 1 : cur - 1) * C::SLOT;
         step(false_type{}, false_type{}, true_type{}, false_type{}, smem, 0, 0, sc0, dp0, sc0, dp0, pf0, df0, t_last, 1, pf1, df1,
-             smem, 0, t_last, 1);
+             smem, 0, t_last, 1, nothing);
     }
 
     if (key_ok) {

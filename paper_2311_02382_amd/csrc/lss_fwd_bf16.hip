@@ -1,47 +1,57 @@
 // Tuned bf16 forward of Eq. 2 (Section 3, Principle 3) for gfx950.
 //
 // Same mathematics and operand roles as the generic kernel in lss_fwd.hip (S^T = K Q^T with one
-// query per lane, then O^T += V^T P^T with P^T fed straight from the S^T registers); what differs:
-//   * a wavefront owns 64 query rows (two 32-column B blocks), so every K / V^T fragment read from
-//     LDS feeds two matrix instructions -- LDS traffic per flop is halved;
-//   * V stays row-major in LDS and is read transposed by DS_READ_B64_TR_B16 (no transposing store);
-//   * K/V tiles are double-buffered: the next tile's global loads are in flight while the current
-//     one is consumed, one barrier per tile;
-//   * the running maximum is only raised when a score exceeds it by more than 2^8 (log2 domain), so
-//     the accumulator rescale is a rare wave-uniform branch; weights stay <= 2^8 and the final
-//     division by the row sum, which uses the same maximum, makes the result independent of it;
-//   * waves whose rows are past the segment, or entirely above the causal diagonal for a tile, skip
-//     that tile's arithmetic.
+// query per lane, then O^T += V^T P^T with P^T fed straight from the S^T registers).  The keys are
+// walked in blocks of 32 (two per 64-key K/V tile).  Per block g three stages:
+//     A(g): S^T product (matrix),  B(g): weights P^T (vector: exp, row sum, bf16 packing),
+//     C(g): O^T product (matrix).
+// A wavefront issues in order, and vector work costs it several times the issue time of a matrix
+// instruction, so the stages are software-pipelined: step g issues the matrix instructions of
+// A(g+1) and C(g-1) with the vector work of B(g) spread between them.  K/V tiles travel
+// global -> LDS directly (no registers in between), a full loop iteration ahead, into a ring of
+// three unpadded, swizzled tiles; V is read transposed by DS_READ_B64_TR_B16.
+//
+// Softmax: B subtracts the running maximum m as it stands (no pass over the block first) and
+// tracks the largest weight it produced.  Only when some weight exceeds 2^8 -- a score more than 8
+// (log2 domain) above m, or a row seeing its first key -- does a rare, wavefront-uniform fix-up
+// raise m to the exact maximum, rescale the row sum and the accumulator, and redo the block's
+// weights.  The final division by the row sum, which uses the same m, makes the result independent
+// of when m was raised.  The row sum adds the weights as rounded to bf16, the values the matrix
+// product uses.
 #include "lss_bf16.h"
+#include <type_traits>
 #include "lss_kernels.h"
 
 namespace lss {
 
-// NB = 32-row query blocks per wavefront: 2 for d = 64; 1 for d = 128, where two blocks of
-// accumulators do not fit the register file.
 template <int D>
 struct FwdBf16Cfg {
-    static constexpr int NB = D == 64 ? 2 : 1;
-    static constexpr int WAVES = 4, RW = 32 * NB;       // query rows per wavefront
+    static constexpr int WAVES = 4, RW = 32;            // query rows per wavefront
     static constexpr int BR = WAVES * RW, BC = 64, NT = 256;
-    static constexpr int KP = D + 8;                    // K tile pitch (elements): 16 rows hit 64 distinct banks
-    static constexpr int VP = D + 8;                    // V tile pitch
-    static constexpr float kRescaleThreshold = 8.0f;    // log2 domain
+    static constexpr int RING = 3;                      // K/V tiles resident in LDS
+    static constexpr int NU = D / 16;                   // operand steps of the S^T product; same for O^T
+    using Tile = DirectTile<D, BC>;
+    static constexpr int OFF_V = Tile::BYTES, SLOT = 2 * Tile::BYTES;   // one ring slot: K tile, V tile
+    static constexpr float kMaxWeight = 256.0f;         // 2^8: largest weight B may produce without a fix-up
 };
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
 template <int D>
-__global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(SegShape s, const bf16_t *__restrict__ q,
-                                                       const bf16_t *__restrict__ k,
-                                                       const bf16_t *__restrict__ v, bf16_t *__restrict__ out,
-                                                       float *__restrict__ lse, float *__restrict__ o_part,
-                                                       float *__restrict__ lse_part, int n_splits)
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape s, const bf16_t *__restrict__ q,
+                                                                       const bf16_t *__restrict__ k,
+                                                                       const bf16_t *__restrict__ v,
+                                                                       bf16_t *__restrict__ out, float *__restrict__ lse,
+                                                                       float *__restrict__ o_part,
+                                                                       float *__restrict__ lse_part, int n_splits)
 {
     using C = FwdBf16Cfg<D>;
-    constexpr int NB = C::NB;
-    __shared__ __attribute__((aligned(16))) bf16_t sK[2][C::BC * C::KP];
-    __shared__ __attribute__((aligned(16))) bf16_t sV[2][C::BC * C::VP];
+    using Tile = typename C::Tile;
+    constexpr int NU = C::NU;
+    __shared__ __attribute__((aligned(1024))) char smem[C::RING * C::SLOT];
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int bh = blockIdx.y, b = bh / s.H, h = bh % s.H, split = blockIdx.z;
     // query tiles are dispatched last-first: under the causal mask the last tiles see the most
     // keys, and starting the longest workgroups first shortens the tail of the launch
@@ -54,186 +64,243 @@ __global__ __launch_bounds__(256, 2) void fwd_bf16_kernel(SegShape s, const bf16
     const int n_tiles = (kv_end + C::BC - 1) / C::BC;
     const int per = (n_tiles + n_splits - 1) / n_splits;
     const int t_begin = split * per, t_end = min(n_tiles, t_begin + per);
+    const int T = max(t_end - t_begin, 0);
 
-    const bool wave_on = rw0 < s.l_s;
-    const int64_t g_wave_last = s.s0 + min(rw0 + C::RW, s.l_s) - 1;   // last global position of the wave
+    // this lane's query row (column of the S^T tile); rows past the segment re-read its last row
+    // (unconditional loads), are computed like any other and never stored
+    const int r = rw0 + lq;
+    const bool row_ok = r < s.l_s;
+    Frag<bf16_t> qf[NU];
+    {
+        const bf16_t *qp = q + ((int64_t)b * s.l_s + min(r, s.l_s - 1)) * ld + (int64_t)h * D + hh * 8;
+#pragma unroll
+        for (int kb = 0; kb < NU; ++kb) qf[kb] = load_frag<bf16_t>(qp + kb * 16);
+    }
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 o[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) o[db] = zero16;
+    float m = -INFINITY, l = 0.f;                       // running maximum (log2 domain); this lane's half of the row sum
+    const float c = kLog2e / sqrtf((float)D);
 
-    int r[NB];
-    bool row_ok[NB];
-    Frag<bf16_t> qf[NB][D / 16];
+    if (T > 0) {
+        const bf16_t *kbase = k + (int64_t)b * s.l_x * ld + (int64_t)h * D;
+        const bf16_t *vbase = v + (int64_t)b * s.l_x * ld + (int64_t)h * D;
+
+        // ---- tile loads, by all four wavefronts
+        uint32_t offF[Tile::NI];                        // this lane's global offsets within a full tile
+        Tile::offsets(offF, ld, C::BC, wave, lane);
+        auto issue_tile = [&](int t, int slot) {
+            const int j0 = t * C::BC, rows_ok = s.l_x - j0;
+            uint32_t off[Tile::NI];
 #pragma unroll
-    for (int qb = 0; qb < NB; ++qb) {
-        r[qb] = rw0 + qb * 32 + lq;
-        row_ok[qb] = r[qb] < s.l_s;
-        // rows past the segment re-read its last row (unconditional loads); they are never stored
-        const bf16_t *qp = q + ((int64_t)b * s.l_s + min(r[qb], s.l_s - 1)) * ld + (int64_t)h * D + hh * 8;
+            for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i];
+            if (rows_ok < C::BC) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
+            char *dst = smem + slot * C::SLOT;
+            Tile::issue(kbase + (int64_t)j0 * ld, off, dst, wave);
+            Tile::issue(vbase + (int64_t)j0 * ld, off, dst + C::OFF_V, wave);
+        };
+
+        // ---- per-lane LDS offsets (bytes, within a tile)
+        int a_off[NU];                                  // A-operand chunk of row lq for operand step kb
 #pragma unroll
-        for (int kb = 0; kb < D / 16; ++kb) qf[qb][kb] = load_frag<bf16_t>(qp + kb * 16);
+        for (int kb = 0; kb < NU; ++kb) a_off[kb] = Tile::chunk_offset(lq, 2 * kb + hh);
+        int t_off[D / 32];                              // transposed reads, column block db
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) t_off[db] = tr_lane_offset_sw<D>(lane, db);
+
+        // ---- stage pieces.  `tile` / `kb2` name a block: LDS address of its ring slot and which half of it.
+        auto load_a = [&](const char *tile, int kb2, int kb, Frag<bf16_t> &fk) __attribute__((always_inline)) {
+            fk = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(tile + kb2 * 32 * (D * 2) + a_off[kb]));
+        };
+        auto load_c = [&](const char *tile, int kb2, int u, Frag<bf16_t> &fv) __attribute__((always_inline)) {
+            const int half = u / (D / 32), db = u % (D / 32);
+            fv = load_frag_tr_sw<D>(tile + C::OFF_V, (kb2 * 2 + half) * 16, t_off[db]);
+        };
+        // Where the causal diagonal or the end of the sequence crosses a block (first key jb), the
+        // masked elements of its finished S^T accumulator are set to -inf, which B turns into weight
+        // 0: keys after the lane's row, and keys past the sequence (whose loads re-read its last
+        // row).  C-tile element e of this lane is key 8*(e/4) + 4*hh + e%4 of the block.
+        auto mask_s = [&](int jb, f32x16 &sc) __attribute__((always_inline)) {
+            const bool diag = s.causal && (jb + 31 > s.s0 + rw0);
+            if (diag || jb + 32 > s.l_x) {
+                const int64_t last = s.causal ? min<int64_t>(s.s0 + r, s.l_x - 1) : (int64_t)s.l_x - 1;
+                const int rel = (int)max<int64_t>(min<int64_t>(last - jb - 4 * hh, 64), -1);
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    if (8 * (e >> 2) + (e & 3) > rel) sc[e] = -INFINITY;
+            }
+        };
+        // B for elements [e0, e1) (pairs): weight = 2^(c * S - m); the pair is rounded to bf16 into
+        // the operand fragment of C, added (as rounded) to the row sum, and tracked in pmax.
+        // A row that has seen no key yet (m = -inf) subtracts a huge negative number instead, so that
+        // any real score gives weight +inf and forces the fix-up, while masked scores still give 0.
+        bf16x2_t ones2;
+        ones2[0] = (bf16_t)1.0f; ones2[1] = (bf16_t)1.0f;
+        auto b_elems = [&](const f32x16 &sc, float m_sub, int e0, int e1, float &psum, float &pmax, Frag<bf16_t> (&pf)[2])
+            __attribute__((always_inline)) {
+#pragma unroll
+            for (int e = e0; e < e1; e += 2) {
+                const float p0 = fast_exp2(sc[e] * c - m_sub), p1 = fast_exp2(sc[e + 1] * c - m_sub);
+                pmax = fmaxf(fmaxf(pmax, p0), p1);
+                bf16x2_t pr;
+                pr[0] = (bf16_t)p0; pr[1] = (bf16_t)p1;
+                pf[e >> 3].v[e & 7] = pr[0]; pf[e >> 3].v[(e & 7) + 1] = pr[1];
+                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, psum, false);
+            }
+        };
+        auto m_sub_of = [](float mm) { return mm == -INFINITY ? -1e30f : mm; };
+        // The fix-up: raise m to the exact maximum over what the row has seen including this block,
+        // rescale what was accumulated under the old m (row sum l0 before this block; accumulator,
+        // to which this block has not been added yet) and redo the block's weights.
+        auto fixup = [&](const f32x16 &sc, float l0, Frag<bf16_t> (&pf)[2]) __attribute__((always_inline)) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[e]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m, mx * c);
+            const float alpha = (m == -INFINITY) ? 0.f : fast_exp2(m - m_new);
+            m = m_new;
+            l = l0 * alpha;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+            float pm = 0.f;
+            b_elems(sc, m_sub_of(m), 0, 16, l, pm, pf);
+        };
+
+        // One pipeline step.  A: block (tile_a, kb2_a) into sc_a.  B: sc_b, first key jb_b, packing
+        // into pf_b.  C: block (tile_c, kb2_c) from pf_c into o.  Per unit the matrix instructions
+        // go C, A; after each one come the B elements that fall to its slot.  Operand fragments are
+        // read from LDS one unit ahead of their use; those of the first unit by the step before
+        // (ak[0], cv[0] on entry), and this step leaves there those of the next step: A on block
+        // (tile_an, kb2_an), C on (tile_cn, kb2_cn).  `mid` runs before those last reads: the even
+        // steps put the loop's barrier there, because the next step's blocks may lie in the tile
+        // that the barrier publishes.
+        Frag<bf16_t> ak[2], cv[2];
+        auto step = [&](auto has_a, auto has_b, auto has_c, const char *tile_a, int kb2_a, f32x16 &sc_a, f32x16 &sc_b,
+                        int jb_b, Frag<bf16_t> (&pf_b)[2], const char *tile_c, int kb2_c, Frag<bf16_t> (&pf_c)[2],
+                        const char *tile_an, int kb2_an, const char *tile_cn, int kb2_cn, auto &&mid)
+            __attribute__((always_inline)) {
+            constexpr bool HA = decltype(has_a)::value, HB = decltype(has_b)::value, HC = decltype(has_c)::value;
+            constexpr int NS = 2 * NU;                  // slots; 8 element pairs of B spread over them
+            static_assert(NU % 2 == 0, "fragment double buffers assume an even number of units");
+            const float l0 = l, m_sub = m_sub_of(m);
+            float pmax = 0.f;
+            auto b_slot = [&](int slot) __attribute__((always_inline)) {
+                if (HB) {
+                    const int e0 = 2 * (slot * 8 / NS), e1 = 2 * ((slot + 1) * 8 / NS);
+                    __builtin_amdgcn_sched_barrier(0);
+                    b_elems(sc_b, m_sub, e0, e1, l, pmax, pf_b);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            if (HB) {
+                mask_s(jb_b, sc_b);
+                // B's inputs pass through an empty asm here: its arithmetic depends on nothing else in
+                // this step, and the compiler would otherwise move all of it out of the step, in one lump
+                asm volatile("" : "+v"(sc_b));
+            }
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                if (u + 1 < NU) {
+                    if (HC) load_c(tile_c, kb2_c, u + 1, cv[(u + 1) & 1]);
+                    if (HA) load_a(tile_a, kb2_a, u + 1, ak[(u + 1) & 1]);
+                } else {
+                    mid();
+                    load_c(tile_cn, kb2_cn, 0, cv[0]);
+                    load_a(tile_an, kb2_an, 0, ak[0]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                const int half = u / (D / 32), db = u % (D / 32);
+                if (HC) o[db] = mma(cv[u & 1], pf_c[half], o[db]);
+                b_slot(2 * u);
+                if (HA) sc_a = mma(ak[u & 1], qf[u], u == 0 ? zero16 : sc_a);
+                b_slot(2 * u + 1);
+            }
+            if (HB) {
+                // ... and its results through another one, so that it is not sunk below the step either
+                asm volatile("" : "+v"(pf_b[0].v), "+v"(pf_b[1].v), "+v"(l), "+v"(pmax));
+                if (__any(pmax > C::kMaxWeight)) fixup(sc_b, l0, pf_b);
+            }
+        };
+        using std::true_type;
+        using std::false_type;
+
+        // ---- pipeline.  Block g = keys (t_begin + g/2) * 64 + (g%2) * 32 ..; tile t = blocks 2t, 2t+1.
+        issue_tile(t_begin, 0);
+        if (T > 1) issue_tile(t_begin + 1, 1);
+        wait_vmem_all();
+        __syncthreads();
+
+        f32x16 sc0, sc1;                                // even / odd blocks
+        Frag<bf16_t> pf0[2], pf1[2];
+        // step -1: A(0) alone.  The first loop step has no C(-1): it multiplies zeros with tile 0 instead.
+        load_a(smem, 0, 0, ak[0]);
+        auto nothing = [] {};
+        step(true_type{}, false_type{}, false_type{}, smem, 0, sc0, sc1, 0, pf0, smem, 0, pf1, smem, 1, smem, 1, nothing);
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf1[half].v[e] = (bf16_t)0.f;
+
+        int cur = 0;                                    // ring slot of tile t
+        for (int t = 0; t < T; ++t) {
+            const int nxt = cur == C::RING - 1 ? 0 : cur + 1, prv = cur == 0 ? C::RING - 1 : cur - 1;
+            const char *t_cur = smem + cur * C::SLOT, *t_nxt = smem + nxt * C::SLOT, *t_prv = smem + prv * C::SLOT;
+            const char *t_a2 = t + 1 < T ? t_nxt : t_cur;   // tile of A(2t+2), A(2t+3); past the end: any resident tile
+            const int j0 = (t_begin + t) * C::BC;
+            // even step g = 2t: A(2t+1) [tile t, second half], B(2t), C(2t-1) [tile t-1, second half;
+            // for t = 0 tile 0, times zero]
+            // Before its last reads (which may touch tile t+1): tile t+1's loads, issued one iteration
+            // ago, have landed for this wavefront; after the barrier for all, and every wavefront has
+            // requested its last operands from tile t-1, whose slot takes tile t+2.
+            step(true_type{}, true_type{}, true_type{}, t_cur, 1, sc1, sc0, j0, pf0, t > 0 ? t_prv : t_cur, 1, pf1, t_a2, 0,
+                 t_cur, 0, [&] {
+                     wait_vmem_all();
+                     __syncthreads();
+                     if (t + 2 < T) issue_tile(t_begin + t + 2, prv);
+                 });
+            // odd step g = 2t+1: A(2t+2) [tile t+1, first half; past the end result unused], B(2t+1),
+            // C(2t) [tile t, first half]
+            step(true_type{}, true_type{}, true_type{}, t_a2, 0, sc0, sc1, j0 + 32, pf1, t_cur, 0, pf0, t_a2, 1, t_cur, 1,
+                 nothing);
+            cur = nxt;
+        }
+        // step 2T: C(2T-1) [tile T-1, second half] alone
+        {
+            const char *t_last = smem + (cur == 0 ? C::RING - 1 : cur - 1) * C::SLOT;
+            step(false_type{}, false_type{}, true_type{}, smem, 0, sc0, sc0, 0, pf0, t_last, 1, pf1, smem, 0, t_last, 1, nothing);
+        }
     }
 
-    f32x16 o[NB][D / 32];
-#pragma unroll
-    for (int qb = 0; qb < NB; ++qb)
+    const float l_tot = l + __shfl_xor(l, 32);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    const float lse_nat = l_tot > 0.f ? (m + log2f(l_tot)) * kLn2 : -INFINITY;
+    if (!row_ok) return;
+    if (n_splits == 1) {
+        bf16_t *op = out + ((int64_t)b * s.l_s + r) * ld + (int64_t)h * D;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) o[qb][db][e] = 0.f;
-    float m[NB], l[NB];
+            for (int e4 = 0; e4 < 4; ++e4)
+                *reinterpret_cast<bf16x4 *>(op + db * 32 + 8 * e4 + 4 * hh) =
+                    pack4(o[db][4 * e4] * inv, o[db][4 * e4 + 1] * inv, o[db][4 * e4 + 2] * inv, o[db][4 * e4 + 3] * inv);
+        if (hh == 0) lse[(int64_t)bh * s.l_s + r] = lse_nat;
+    } else {
+        const int64_t row = ((int64_t)split * gridDim.y + bh) * s.l_s + r;
+        float *op = o_part + row * D;
 #pragma unroll
-    for (int qb = 0; qb < NB; ++qb) { m[qb] = -INFINITY; l[qb] = 0.f; }
-    const float c = kLog2e / sqrtf((float)D);
-
-    const bf16_t *kbase = k + (int64_t)b * s.l_x * ld + (int64_t)h * D;
-    const bf16_t *vbase = v + (int64_t)b * s.l_x * ld + (int64_t)h * D;
-    const int tr_off = tr_lane_offset(lane, C::VP);
-
-    TileStage<D, C::BC> stK, stV;
-    if (t_begin < t_end) {
-        const int j0 = t_begin * C::BC;
-        stK.fetch(kbase + (int64_t)j0 * ld, ld, s.l_x - j0, tid);
-        stV.fetch(vbase + (int64_t)j0 * ld, ld, s.l_x - j0, tid);
-        stK.commit(sK[0], C::KP, tid);
-        stV.commit(sV[0], C::VP, tid);
-    }
-    wait_vmem_all();
-    __syncthreads();
-
-    for (int t = t_begin; t < t_end; ++t) {
-        const int cur = (t - t_begin) & 1;
-        const int j0 = t * C::BC;
-        const bool more = t + 1 < t_end;
-        if (more) {
-            const int j1 = j0 + C::BC;
-            stK.fetch(kbase + (int64_t)j1 * ld, ld, s.l_x - j1, tid);
-            stV.fetch(vbase + (int64_t)j1 * ld, ld, s.l_x - j1, tid);
-        }
-
-        // a wave takes part in a tile if it has rows and at least one of them sees the tile
-        if (wave_on && !(s.causal && j0 > g_wave_last)) {
-            const bf16_t *tK = sK[cur], *tV = sV[cur];
-            f32x16 sc[NB][2];
+        for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int kb2 = 0; kb2 < 2; ++kb2) {
+            for (int e4 = 0; e4 < 4; ++e4) {
+                f32x4 val;
 #pragma unroll
-                for (int qb = 0; qb < NB; ++qb)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) sc[qb][kb2][e] = 0.f;
-#pragma unroll
-                for (int kb = 0; kb < D / 16; ++kb) {
-                    const Frag<bf16_t> a = load_frag<bf16_t>(&tK[(kb2 * 32 + lq) * C::KP + kb * 16 + hh * 8]);
-#pragma unroll
-                    for (int qb = 0; qb < NB; ++qb) sc[qb][kb2] = mma(a, qf[qb][kb], sc[qb][kb2]);
-                }
+                for (int i = 0; i < 4; ++i) val[i] = o[db][4 * e4 + i] * inv;
+                *reinterpret_cast<f32x4 *>(op + db * 32 + 8 * e4 + 4 * hh) = val;
             }
-
-            const bool tail = j0 + C::BC > s.l_x;
-            const bool diag = s.causal && (j0 + C::BC - 1 > s.s0 + rw0);
-            if (tail || diag) {
-#pragma unroll
-                for (int qb = 0; qb < NB; ++qb) {
-                    // last visible key of this lane's query, relative to the lane's first key of the tile
-                    const int64_t last = s.causal ? min<int64_t>(s.s0 + r[qb], s.l_x - 1) : (int64_t)s.l_x - 1;
-                    const int rel = (int)max<int64_t>(min<int64_t>(last - j0 - 4 * hh, 2 * C::BC), -1);
-#pragma unroll
-                    for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e)
-                            if (kb2 * 32 + 8 * (e >> 2) + (e & 3) > rel) sc[qb][kb2][e] = -INFINITY;
-                }
-            }
-
-            float cand[NB];
-            bool raise = false;
-#pragma unroll
-            for (int qb = 0; qb < NB; ++qb) {
-                float mx = -INFINITY;
-#pragma unroll
-                for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[qb][kb2][e]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                cand[qb] = mx * c;
-                raise |= cand[qb] > m[qb] + C::kRescaleThreshold;
-            }
-            if (__any(raise)) {
-#pragma unroll
-                for (int qb = 0; qb < NB; ++qb) {
-                    const float m_new = fmaxf(m[qb], cand[qb]);
-                    const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m[qb] - m_new);
-                    m[qb] = m_new;
-                    l[qb] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-                        for (int e = 0; e < 16; ++e) o[qb][db][e] *= alpha;
-                }
-            }
-#pragma unroll
-            for (int qb = 0; qb < NB; ++qb) {
-                const float m_eff = (m[qb] == -INFINITY) ? 0.f : m[qb];
-                float psum = 0.f;
-#pragma unroll
-                for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const float p = fast_exp2(sc[qb][kb2][e] * c - m_eff);
-                        sc[qb][kb2][e] = p;
-                        psum += p;
-                    }
-                l[qb] += psum;
-            }
-
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                Frag<bf16_t> pf[NB];
-#pragma unroll
-                for (int qb = 0; qb < NB; ++qb) pf[qb] = acc_to_frag<bf16_t>(sc[qb][ks >> 1], ks & 1);
-#pragma unroll
-                for (int db = 0; db < D / 32; ++db) {
-                    const Frag<bf16_t> a = load_frag_tr(tV, C::VP, ks * 16, db * 32, tr_off);
-#pragma unroll
-                    for (int qb = 0; qb < NB; ++qb) o[qb][db] = mma(a, pf[qb], o[qb][db]);
-                }
-            }
-        }
-
-        if (more) {
-            stK.commit(sK[cur ^ 1], C::KP, tid);
-            stV.commit(sV[cur ^ 1], C::VP, tid);
-        }
-        __syncthreads();
-    }
-
-#pragma unroll
-    for (int qb = 0; qb < NB; ++qb) {
-        const float l_tot = l[qb] + __shfl_xor(l[qb], 32);
-        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        const float lse_nat = l_tot > 0.f ? (m[qb] + log2f(l_tot)) * kLn2 : -INFINITY;
-        if (!row_ok[qb]) continue;
-        if (n_splits == 1) {
-            bf16_t *op = out + ((int64_t)b * s.l_s + r[qb]) * ld + (int64_t)h * D;
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4)
-                    *reinterpret_cast<bf16x4 *>(op + db * 32 + 8 * e4 + 4 * hh) =
-                        pack4(o[qb][db][4 * e4] * inv, o[qb][db][4 * e4 + 1] * inv, o[qb][db][4 * e4 + 2] * inv,
-                              o[qb][db][4 * e4 + 3] * inv);
-            if (hh == 0) lse[(int64_t)bh * s.l_s + r[qb]] = lse_nat;
-        } else {
-            const int64_t row = ((int64_t)split * gridDim.y + bh) * s.l_s + r[qb];
-            float *op = o_part + row * D;
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    f32x4 val;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) val[i] = o[qb][db][4 * e4 + i] * inv;
-                    *reinterpret_cast<f32x4 *>(op + db * 32 + 8 * e4 + 4 * hh) = val;
-                }
-            if (hh == 0) lse_part[row] = lse_nat;
-        }
+        if (hh == 0) lse_part[row] = lse_nat;
     }
 }
 
