@@ -11,11 +11,11 @@
 // global -> LDS directly (no registers in between), a full loop iteration ahead, into a ring of
 // three unpadded, swizzled tiles; V is read transposed by DS_READ_B64_TR_B16.
 //
-// Softmax: B subtracts the running maximum m as it stands (no pass over the block first) and
-// tracks the largest weight it produced.  Only when some weight exceeds 2^8 -- a score more than 8
-// (log2 domain) above m, or a row seeing its first key -- does a rare, wavefront-uniform fix-up
-// raise m to the exact maximum, rescale the row sum and the accumulator, and redo the block's
-// weights.  The final division by the row sum, which uses the same m, makes the result independent
+// Softmax: B subtracts the running maximum m as it stands (no pass over the block first).  Only
+// when the block's weights of some row add up to more than 2^8 -- so no weight can be larger
+// without this being noticed: a score well above m, or a row seeing its first key -- does a rare,
+// wavefront-uniform fix-up raise m to the exact maximum, rescale the row sum and the accumulator,
+// and redo the block's weights.  The final division by the row sum, which uses the same m, makes the result independent
 // of when m was raised.  The row sum adds the weights as rounded to bf16, the values the matrix
 // product uses.
 #include "lss_bf16.h"
@@ -32,7 +32,7 @@ struct FwdBf16Cfg {
     static constexpr int NU = D / 16;                   // operand steps of the S^T product; same for O^T
     using Tile = DirectTile<D, BC>;
     static constexpr int OFF_V = Tile::BYTES, SLOT = 2 * Tile::BYTES;   // one ring slot: K tile, V tile
-    static constexpr float kMaxWeight = 256.0f;         // 2^8: largest weight B may produce without a fix-up
+    static constexpr float kMaxBlockSum = 256.0f;       // 2^8: largest sum of a lane's weights of one block without a fix-up
 };
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -132,17 +132,16 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
             }
         };
         // B for elements [e0, e1) (pairs): weight = 2^(c * S - m); the pair is rounded to bf16 into
-        // the operand fragment of C, added (as rounded) to the row sum, and tracked in pmax.
+        // the operand fragment of C and added (as rounded) to the row sum.
         // A row that has seen no key yet (m = -inf) subtracts a huge negative number instead, so that
         // any real score gives weight +inf and forces the fix-up, while masked scores still give 0.
         bf16x2_t ones2;
         ones2[0] = (bf16_t)1.0f; ones2[1] = (bf16_t)1.0f;
-        auto b_elems = [&](const f32x16 &sc, float m_sub, int e0, int e1, float &psum, float &pmax, Frag<bf16_t> (&pf)[2])
+        auto b_elems = [&](const f32x16 &sc, float m_sub, int e0, int e1, float &psum, Frag<bf16_t> (&pf)[2])
             __attribute__((always_inline)) {
 #pragma unroll
             for (int e = e0; e < e1; e += 2) {
                 const float p0 = fast_exp2(sc[e] * c - m_sub), p1 = fast_exp2(sc[e + 1] * c - m_sub);
-                pmax = fmaxf(fmaxf(pmax, p0), p1);
                 bf16x2_t pr;
                 pr[0] = (bf16_t)p0; pr[1] = (bf16_t)p1;
                 pf[e >> 3].v[e & 7] = pr[0]; pf[e >> 3].v[(e & 7) + 1] = pr[1];
@@ -166,8 +165,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
             for (int db = 0; db < D / 32; ++db)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
-            float pm = 0.f;
-            b_elems(sc, m_sub_of(m), 0, 16, l, pm, pf);
+            b_elems(sc, m_sub_of(m), 0, 16, l, pf);
         };
 
         // One pipeline step.  A: block (tile_a, kb2_a) into sc_a.  B: sc_b, first key jb_b, packing
@@ -187,12 +185,11 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
             constexpr int NS = 2 * NU;                  // slots; 8 element pairs of B spread over them
             static_assert(NU % 2 == 0, "fragment double buffers assume an even number of units");
             const float l0 = l, m_sub = m_sub_of(m);
-            float pmax = 0.f;
             auto b_slot = [&](int slot) __attribute__((always_inline)) {
                 if (HB) {
                     const int e0 = 2 * (slot * 8 / NS), e1 = 2 * ((slot + 1) * 8 / NS);
                     __builtin_amdgcn_sched_barrier(0);
-                    b_elems(sc_b, m_sub, e0, e1, l, pmax, pf_b);
+                    b_elems(sc_b, m_sub, e0, e1, l, pf_b);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             };
@@ -221,8 +218,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
             }
             if (HB) {
                 // ... and its results through another one, so that it is not sunk below the step either
-                asm volatile("" : "+v"(pf_b[0].v), "+v"(pf_b[1].v), "+v"(l), "+v"(pmax));
-                if (__any(pmax > C::kMaxWeight)) fixup(sc_b, l0, pf_b);
+                asm volatile("" : "+v"(pf_b[0].v), "+v"(pf_b[1].v), "+v"(l));
+                if (__any(!(l - l0 <= C::kMaxBlockSum))) fixup(sc_b, l0, pf_b);
             }
         };
         using std::true_type;
