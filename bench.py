@@ -31,10 +31,11 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak (published)
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak (published)
 
 # Matrix products each kernel contributes to the strict count (per pair: 2*d flops each).
-# fwd: S and PV.  dq kernel: dP and dQ (it also recomputes S).  dkv kernel: dV and dK (it also
-# recomputes S and dP).  Together the six products of the 12*d count.
-ALGO_PRODUCTS = {"fwd_kernel": 2, "bwd_dq_kernel": 2, "bwd_dkv_kernel": 2}
-EXEC_PRODUCTS = {"fwd_kernel": 2, "bwd_dq_kernel": 3, "bwd_dkv_kernel": 4}
+# fwd: S and PV.  The backward's main kernel holds two kinds of workgroup: dQ (dP and dQ; it also
+# recomputes S) and dK/dV (dV and dK; it also recomputes S and dP).  Together the six products of
+# the 12*d count.  (bwd_dq_kernel / bwd_dkv_kernel: the fp32 path, which launches them separately.)
+ALGO_PRODUCTS = {"fwd_kernel": 2, "bwd_main_kernel": 4, "bwd_dq_kernel": 2, "bwd_dkv_kernel": 2}
+EXEC_PRODUCTS = {"fwd_kernel": 2, "bwd_main_kernel": 7, "bwd_dq_kernel": 3, "bwd_dkv_kernel": 4}
 
 
 def measured_traffic(workload: str, kernel: str):

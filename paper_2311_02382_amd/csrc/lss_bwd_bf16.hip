@@ -32,25 +32,25 @@ struct DqBf16Cfg {
 // As in the dK/dV kernel below the stages are software-pipelined, step g issuing the matrix
 // instructions of A(g+1) and C(g-1) with the vector work of B(g) spread between them, over a ring
 // of three K/V tiles that are loaded global -> LDS directly, a full loop iteration ahead.
-// D = rowsum(dO * out) is computed here, and its negative (with -lse * sqrt(d)) written for the
-// dK/dV kernel.
+// D = rowsum(dO * out) of the wavefront's own rows is computed here.
 template <int D>
-__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dq_bf16_kernel(
-    SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO, const float *__restrict__ lse,
-    float *__restrict__ Dv, float *__restrict__ Lsv, bf16_t *__restrict__ dq, float *__restrict__ dq_part, int n_splits)
+__device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const bf16_t *__restrict__ q,
+                                            const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+                                            const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO,
+                                            const float *__restrict__ lse, bf16_t *__restrict__ dq,
+                                            float *__restrict__ dq_part, int n_splits, int q_tile, int n_q_tiles, int bh,
+                                            int split)
 {
     using C = DqBf16Cfg<D>;
     using Tile = typename C::Tile;
     constexpr int NU = C::NU;
-    __shared__ __attribute__((aligned(1024))) char smem[C::RING * C::SLOT];
 
     const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int bh = blockIdx.y, b = bh / s.H, h = bh % s.H, split = blockIdx.z;
+    const int b = bh / s.H, h = bh % s.H;
     // query tiles are dispatched last-first: under the causal mask the last tiles see the most
     // keys, and starting the longest workgroups first shortens the tail of the launch
-    const int r0 = (gridDim.x - 1 - blockIdx.x) * C::BR;
+    const int r0 = (n_q_tiles - 1 - q_tile) * C::BR;
     const int rw0 = r0 + wave * C::RW;
     const int64_t ld = (int64_t)s.H * D;
 
@@ -83,11 +83,6 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dq_bf16_kernel(
         Dr = dsum;
         const float lv = lse[(int64_t)bh * s.l_s + rc];
         L2 = row_ok ? lv * kLog2e : INFINITY;
-        if (row_ok && hh == 0 && split == 0) {
-            // start values of the dK/dV kernel's accumulators
-            Dv[(int64_t)bh * s.l_s + r] = -dsum;
-            Lsv[(int64_t)bh * s.l_s + r] = -lv * sqrtf((float)D);
-        }
     }
     const float c = kLog2e / sqrtf((float)D);
     // -D in all 16 accumulator slots: third operand of each block's first dP^T instruction
@@ -313,24 +308,20 @@ struct DkvBf16Cfg {
 // instruction.  Block g+1 may belong to the next tile and block g-1 to the previous one, hence a
 // ring of three tiles in LDS; tiles travel global -> LDS directly, a full loop iteration ahead.
 template <int D>
-__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
-    SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const bf16_t *__restrict__ dO, const float *__restrict__ Ls, const float *__restrict__ Dn,
-    float *__restrict__ dk_part, float *__restrict__ dv_part)
+__device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, const bf16_t *__restrict__ q,
+                                             const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+                                             const bf16_t *__restrict__ dO, const float *__restrict__ Ls,
+                                             const float *__restrict__ Dn, float *__restrict__ dk_part,
+                                             float *__restrict__ dv_part, int bh, int key_tile)
 {
     using C = DkvBf16Cfg<D>;
     using Tile = typename C::Tile;
     constexpr int NU = C::NU;
-    __shared__ __attribute__((aligned(1024))) char smem[C::RING * C::SLOT];
 
     const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // grid: x = (batch, head), y = key tile.  Workgroups are dispatched x-fastest, so the tiles
-    // with the longest query loops (lowest keys under the causal mask) start first and the tiles no
-    // query sees (plain zero fill) come last; with B*H a multiple of 8 all tiles of one head also
-    // land on one XCD and share its L2 copy of that head's Q and dO.
-    const int bh = blockIdx.x, b = bh / s.H, h = bh % s.H;
-    const int j0 = blockIdx.y * C::BKV;
+    const int b = bh / s.H, h = bh % s.H;
+    const int j0 = key_tile * C::BKV;
     const int jw0 = j0 + wave * C::KW;                  // first key of this wavefront
     const int64_t ld = (int64_t)s.H * D;
     const int64_t kv_base = (int64_t)b * s.l_x * ld + (int64_t)h * D;
@@ -594,6 +585,61 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_dkv_bf16_kernel(
 
 int dq_bf16_rows_per_workgroup(int d) { return d == 64 ? DqBf16Cfg<64>::BR : DqBf16Cfg<128>::BR; }
 
+// ------------------------------------------------------------------------------------------ launch
+// Start values of the dK/dV accumulators, per query row: -D = -rowsum(dO * out) and -lse * sqrt(d).
+// One 16-byte chunk of a row per thread, D/8 consecutive lanes per row.
+template <int D>
+__global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(SegShape s, const bf16_t *__restrict__ out,
+                                                            const bf16_t *__restrict__ dO, const float *__restrict__ lse,
+                                                            float *__restrict__ Dn, float *__restrict__ Ls)
+{
+    constexpr int CPR = D / 8;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t rows = (int64_t)s.B * s.l_s * s.H;
+    const int64_t row = min(idx / CPR, rows - 1);       // memory order [b][r][h]; whole lane groups stay in range
+    const int cpos = (int)(idx % CPR);
+    const Frag<bf16_t> g = load_frag<bf16_t>(dO + row * D + cpos * 8);
+    const Frag<bf16_t> o = load_frag<bf16_t>(out + row * D + cpos * 8);
+    float dsum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dsum += (float)g.v[e] * (float)o.v[e];
+#pragma unroll
+    for (int sh = 1; sh < CPR; sh <<= 1) dsum += __shfl_xor(dsum, sh);
+    if (cpos == 0 && idx / CPR < rows) {
+        const int h = (int)(row % s.H), r = (int)((row / s.H) % s.l_s), b = (int)(row / ((int64_t)s.H * s.l_s));
+        const int64_t o_idx = ((int64_t)b * s.H + h) * s.l_s + r;
+        Dn[o_idx] = -dsum;
+        Ls[o_idx] = -lse[o_idx] * sqrtf((float)D);
+    }
+}
+
+// dQ and dK/dV in one launch: the two kinds of workgroup do not depend on each other, so together
+// they fill the chip better than one after the other (each alone ends in a tail of part-filled
+// compute units, and short segments are mostly tail).  Workgroups [0, n_dkv) take the key tiles of
+// dK/dV, (batch, head) fastest -- longest query loops first, see bwd_dkv_body -- and the rest the
+// (query tile, batch*head, key split) triples of dQ, query tile fastest.
+template <int D>
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
+    SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO, const float *__restrict__ lse,
+    const float *__restrict__ Ls, const float *__restrict__ Dn, bf16_t *__restrict__ dq, float *__restrict__ dq_part,
+    float *__restrict__ dk_part, float *__restrict__ dv_part, int n_splits, int n_dkv, int n_q_tiles)
+{
+    constexpr int SMEM = DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT > DkvBf16Cfg<D>::RING * DkvBf16Cfg<D>::SLOT
+                             ? DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT
+                             : DkvBf16Cfg<D>::RING * DkvBf16Cfg<D>::SLOT;
+    __shared__ __attribute__((aligned(1024))) char smem[SMEM];
+    const int bhs = s.B * s.H;
+    const int id = blockIdx.x;
+    if (id < n_dkv) {
+        bwd_dkv_body<D>(smem, s, q, k, v, dO, Ls, Dn, dk_part, dv_part, id % bhs, id / bhs);
+    } else {
+        const int j = id - n_dkv;
+        bwd_dq_body<D>(smem, s, q, k, v, out, dO, lse, dq, dq_part, n_splits, j % n_q_tiles, n_q_tiles,
+                       (j / n_q_tiles) % bhs, j / (n_q_tiles * bhs));
+    }
+}
+
 template <int D>
 static hipError_t launch_bwd_bf16_d(const SegShape &s, const bf16_t *q, const bf16_t *k, const bf16_t *v,
                                     const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq,
@@ -602,25 +648,25 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const bf16_t *q, const bf
 {
     hipError_t e;
     {
-        using C = DqBf16Cfg<D>;
-        dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
-        TimedLaunch tl(K_DQ, st);
-        hipLaunchKernelGGL((bwd_dq_bf16_kernel<D>), grid, dim3(C::NT), 0, st, s, q, k, v, out, dO, lse, ws.D, ws.Ls,
-                           dq, ws.dq_part, n_splits);
+        const int64_t items = (int64_t)s.B * s.l_s * s.H * (D / 8);
+        TimedLaunch tl(K_ROWDOT, st);
+        hipLaunchKernelGGL((bwd_prep_bf16_kernel<D>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, s, out, dO,
+                           lse, ws.D, ws.Ls);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     {
-        using C = DkvBf16Cfg<D>;
-        dim3 grid(s.B * s.H, (s.l_x + C::BKV - 1) / C::BKV);
-        TimedLaunch tl(K_DKV, st);
-        hipLaunchKernelGGL((bwd_dkv_bf16_kernel<D>), grid, dim3(C::NT), 0, st, s, q, k, v, dO, ws.Ls, ws.D, dk_part,
-                           dv_part);
+        const int n_q_tiles = (s.l_s + DqBf16Cfg<D>::BR - 1) / DqBf16Cfg<D>::BR;
+        const int n_dkv = s.B * s.H * ((s.l_x + DkvBf16Cfg<D>::BKV - 1) / DkvBf16Cfg<D>::BKV);
+        const int n_dq = n_q_tiles * s.B * s.H * n_splits;
+        TimedLaunch tl(K_BWD_MAIN, st);
+        hipLaunchKernelGGL((bwd_main_bf16_kernel<D>), dim3((unsigned)(n_dkv + n_dq)), dim3(256), 0, st, s, q, k, v, out, dO,
+                           lse, ws.Ls, ws.D, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dkv, n_q_tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-// dQ kernel then dK/dV kernel; the caller runs the dQ split merge in between or after.
+// accumulator start values, then dQ and dK/dV in one launch; the caller runs the dQ split merge
 hipError_t launch_bwd_bf16_main(const SegShape &s, const bf16_t *q, const bf16_t *k, const bf16_t *v,
                                 const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq, float *dk_part,
                                 float *dv_part, const Workspace &ws, int n_splits, hipStream_t st)
