@@ -318,8 +318,14 @@ static hipError_t launch_bwd_d(const SegShape &s, const T *q, const T *k, const 
                                const Workspace &ws, hipStream_t st)
 {
     hipError_t e;
-    const int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H, dq_rows_per_wg((int)sizeof(T), D));
+    int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H, dq_rows_per_wg((int)sizeof(T), D));
     if constexpr (sizeof(T) == 2) {
+        // The dQ workgroups share their launch with the dK/dV ones and need not fill the chip alone:
+        // keys are split only so far that a dQ workgroup (64 key tiles at most) does not outlast the
+        // rest of the launch.  Never more splits than the workspace was sized for.
+        const int64_t kv_extent = s.causal ? (s.s0 + s.l_s < s.l_x ? s.s0 + s.l_s : (int64_t)s.l_x) : (int64_t)s.l_x;
+        const int want = (int)((kv_extent + 64 * 64 - 1) / (64 * 64));
+        if (want < n_splits) n_splits = want < 1 ? 1 : want;
         if ((e = launch_bwd_bf16_main(s, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st)) != hipSuccess)
             return e;
     } else {

@@ -615,15 +615,16 @@ __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(SegShape s, const bf
 
 // dQ and dK/dV in one launch: the two kinds of workgroup do not depend on each other, so together
 // they fill the chip better than one after the other (each alone ends in a tail of part-filled
-// compute units, and short segments are mostly tail).  Workgroups [0, n_dkv) take the key tiles of
-// dK/dV, (batch, head) fastest -- longest query loops first, see bwd_dkv_body -- and the rest the
-// (query tile, batch*head, key split) triples of dQ, query tile fastest.
+// compute units, and short segments are mostly tail).  Workgroups [0, n_dq) take the (query tile,
+// batch*head, key split) triples of dQ, query tile fastest -- with few key splits they are the
+// longest of the launch and start first -- and the rest the key tiles of dK/dV, (batch, head)
+// fastest, longest query loops first (see bwd_dkv_body).
 template <int D>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO, const float *__restrict__ lse,
     const float *__restrict__ Ls, const float *__restrict__ Dn, bf16_t *__restrict__ dq, float *__restrict__ dq_part,
-    float *__restrict__ dk_part, float *__restrict__ dv_part, int n_splits, int n_dkv, int n_q_tiles)
+    float *__restrict__ dk_part, float *__restrict__ dv_part, int n_splits, int n_dq, int n_q_tiles)
 {
     constexpr int SMEM = DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT > DkvBf16Cfg<D>::RING * DkvBf16Cfg<D>::SLOT
                              ? DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT
@@ -631,12 +632,12 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     __shared__ __attribute__((aligned(1024))) char smem[SMEM];
     const int bhs = s.B * s.H;
     const int id = blockIdx.x;
-    if (id < n_dkv) {
-        bwd_dkv_body<D>(smem, s, q, k, v, dO, Ls, Dn, dk_part, dv_part, id % bhs, id / bhs);
+    if (id >= n_dq) {
+        const int j = id - n_dq;
+        bwd_dkv_body<D>(smem, s, q, k, v, dO, Ls, Dn, dk_part, dv_part, j % bhs, j / bhs);
     } else {
-        const int j = id - n_dkv;
-        bwd_dq_body<D>(smem, s, q, k, v, out, dO, lse, dq, dq_part, n_splits, j % n_q_tiles, n_q_tiles,
-                       (j / n_q_tiles) % bhs, j / (n_q_tiles * bhs));
+        bwd_dq_body<D>(smem, s, q, k, v, out, dO, lse, dq, dq_part, n_splits, id % n_q_tiles, n_q_tiles,
+                       (id / n_q_tiles) % bhs, id / (n_q_tiles * bhs));
     }
 }
 
@@ -660,7 +661,7 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const bf16_t *q, const bf
         const int n_dq = n_q_tiles * s.B * s.H * n_splits;
         TimedLaunch tl(K_BWD_MAIN, st);
         hipLaunchKernelGGL((bwd_main_bf16_kernel<D>), dim3((unsigned)(n_dkv + n_dq)), dim3(256), 0, st, s, q, k, v, out, dO,
-                           lse, ws.Ls, ws.D, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dkv, n_q_tiles);
+                           lse, ws.Ls, ws.D, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;
