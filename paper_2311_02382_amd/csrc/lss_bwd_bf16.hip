@@ -615,10 +615,12 @@ __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(SegShape s, const bf
 
 // dQ and dK/dV in one launch: the two kinds of workgroup do not depend on each other, so together
 // they fill the chip better than one after the other (each alone ends in a tail of part-filled
-// compute units, and short segments are mostly tail).  Workgroups [0, n_dq) take the (query tile,
-// batch*head, key split) triples of dQ, query tile fastest -- with few key splits they are the
-// longest of the launch and start first -- and the rest the key tiles of dK/dV, (batch, head)
-// fastest, longest query loops first (see bwd_dkv_body).
+// compute units, and short segments are mostly tail).  Workgroups [0, n_dq) take the (batch*head,
+// query tile, key split) triples of dQ -- with few key splits they are the longest of the launch
+// and start first -- and the rest the key tiles of dK/dV, longest query loops first (see
+// bwd_dkv_body).  In both parts (batch, head) runs fastest: consecutive workgroups go to
+// consecutive XCDs, so with B*H a multiple of 8 the workgroups of one head share one XCD's L2 copy
+// of that head's K, V, Q and dO.
 template <int D>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
@@ -636,8 +638,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
         const int j = id - n_dq;
         bwd_dkv_body<D>(smem, s, q, k, v, dO, Ls, Dn, dk_part, dv_part, j % bhs, j / bhs);
     } else {
-        bwd_dq_body<D>(smem, s, q, k, v, out, dO, lse, dq, dq_part, n_splits, id % n_q_tiles, n_q_tiles,
-                       (id / n_q_tiles) % bhs, id / (n_q_tiles * bhs));
+        bwd_dq_body<D>(smem, s, q, k, v, out, dO, lse, dq, dq_part, n_splits, (id / bhs) % n_q_tiles, n_q_tiles, id % bhs,
+                       id / (n_q_tiles * bhs));
     }
 }
 

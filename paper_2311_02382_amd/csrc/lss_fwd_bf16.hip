@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
                                                                        const bf16_t *__restrict__ v,
                                                                        bf16_t *__restrict__ out, float *__restrict__ lse,
                                                                        float *__restrict__ o_part,
-                                                                       float *__restrict__ lse_part, int n_splits)
+                                                                       float *__restrict__ lse_part, int n_splits, int n_q_tiles)
 {
     using C = FwdBf16Cfg<D>;
     using Tile = typename C::Tile;
@@ -52,10 +52,14 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
 
     const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int bh = blockIdx.y, b = bh / s.H, h = bh % s.H, split = blockIdx.z;
-    // query tiles are dispatched last-first: under the causal mask the last tiles see the most
-    // keys, and starting the longest workgroups first shortens the tail of the launch
-    const int r0 = (gridDim.x - 1 - blockIdx.x) * C::BR;
+    // 1-D grid, (batch, head) fastest: consecutive workgroups go to consecutive XCDs, so with B*H a
+    // multiple of 8 all workgroups of one head land on one XCD and share its L2 copy of that head's
+    // K and V.  Then query tiles, last first: under the causal mask the last tiles see the most
+    // keys, and starting the longest workgroups first shortens the tail of the launch.  Then splits.
+    const int bhs = s.B * s.H;
+    const int bh = blockIdx.x % bhs, b = bh / s.H, h = bh % s.H;
+    const int q_tile = (blockIdx.x / bhs) % n_q_tiles, split = blockIdx.x / (bhs * n_q_tiles);
+    const int r0 = (n_q_tiles - 1 - q_tile) * C::BR;
     const int rw0 = r0 + wave * C::RW;                  // first row of this wavefront
     const int64_t ld = (int64_t)s.H * D;
 
@@ -286,7 +290,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
                     pack4(o[db][4 * e4] * inv, o[db][4 * e4 + 1] * inv, o[db][4 * e4 + 2] * inv, o[db][4 * e4 + 3] * inv);
         if (hh == 0) lse[(int64_t)bh * s.l_s + r] = lse_nat;
     } else {
-        const int64_t row = ((int64_t)split * gridDim.y + bh) * s.l_s + r;
+        const int64_t row = ((int64_t)split * bhs + bh) * s.l_s + r;
         float *op = o_part + row * D;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
@@ -308,10 +312,11 @@ static hipError_t launch_fwd_main(const SegShape &s, const bf16_t *q, const bf16
                                   float *lse, const Workspace &ws, int n_splits, hipStream_t st)
 {
     using C = FwdBf16Cfg<D>;
-    dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
+    const int n_q_tiles = (s.l_s + C::BR - 1) / C::BR;
+    dim3 grid((unsigned)(n_q_tiles * s.B * s.H * n_splits));
     TimedLaunch tl(K_FWD, st);
     hipLaunchKernelGGL((fwd_bf16_kernel<D>), grid, dim3(C::NT), 0, st, s, q, k, v, out, lse, ws.o_part, ws.lse_part,
-                       n_splits);
+                       n_splits, n_q_tiles);
     return hipGetLastError();
 }
 
