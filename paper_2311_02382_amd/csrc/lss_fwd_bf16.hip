@@ -15,9 +15,8 @@
 // when the block's weights of some row add up to more than 2^8 -- so no weight can be larger
 // without this being noticed: a score well above m, or a row seeing its first key -- does a rare,
 // wavefront-uniform fix-up raise m to the exact maximum, rescale the row sum and the accumulator,
-// and redo the block's weights.  The final division by the row sum, which uses the same m, makes the result independent
-// of when m was raised.  The row sum adds the weights as rounded to bf16, the values the matrix
-// product uses.
+// and redo the block's weights.  The final division by the row sum, which uses the same m, makes
+// the result independent of when m was raised.
 #include "lss_bf16.h"
 #include <type_traits>
 #include "lss_kernels.h"
@@ -34,8 +33,6 @@ struct FwdBf16Cfg {
     static constexpr int OFF_V = Tile::BYTES, SLOT = 2 * Tile::BYTES;   // one ring slot: K tile, V tile
     static constexpr float kMaxBlockSum = 256.0f;       // 2^8: largest sum of a lane's weights of one block without a fix-up
 };
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 template <int D>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape s, const bf16_t *__restrict__ q,
@@ -135,21 +132,18 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
                     if (8 * (e >> 2) + (e & 3) > rel) sc[e] = -INFINITY;
             }
         };
-        // B for elements [e0, e1) (pairs): weight = 2^(c * S - m); the pair is rounded to bf16 into
-        // the operand fragment of C and added (as rounded) to the row sum.
+        // B for elements [e0, e1) (pairs): weight = 2^(c * S - m); the pair is added to the row sum
+        // and rounded to bf16 into the operand fragment of C.
         // A row that has seen no key yet (m = -inf) subtracts a huge negative number instead, so that
         // any real score gives weight +inf and forces the fix-up, while masked scores still give 0.
-        bf16x2_t ones2;
-        ones2[0] = (bf16_t)1.0f; ones2[1] = (bf16_t)1.0f;
         auto b_elems = [&](const f32x16 &sc, float m_sub, int e0, int e1, float &psum, Frag<bf16_t> (&pf)[2])
             __attribute__((always_inline)) {
 #pragma unroll
             for (int e = e0; e < e1; e += 2) {
                 const float p0 = fast_exp2(sc[e] * c - m_sub), p1 = fast_exp2(sc[e + 1] * c - m_sub);
-                bf16x2_t pr;
-                pr[0] = (bf16_t)p0; pr[1] = (bf16_t)p1;
-                pf[e >> 3].v[e & 7] = pr[0]; pf[e >> 3].v[(e & 7) + 1] = pr[1];
-                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, psum, false);
+                pf[e >> 3].v[e & 7] = (bf16_t)p0; pf[e >> 3].v[(e & 7) + 1] = (bf16_t)p1;
+                psum += p0;
+                psum += p1;
             }
         };
         auto m_sub_of = [](float mm) { return mm == -INFINITY ? -1e30f : mm; };
