@@ -102,6 +102,9 @@ def main() -> int:
     dK = torch.empty(kd.shape, dtype=torch.float32, device=dev)
     dV = torch.empty(kd.shape, dtype=torch.float32, device=dev)
     rows_valid = [s0 + l_s if w.causal else w.l_x for s0 in offs]
+    # the partials' only consumer here is the segment sum, which is told how many rows of each are
+    # valid: key tiles no query of a segment sees need not be filled with zeros
+    lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, 1)
 
     def step():
         for i, s0 in enumerate(offs):

@@ -64,6 +64,25 @@ int lss_version(void);
 const char *lss_last_error(void);
 
 /*
+ * Process-wide options, all 0 by default.
+ *
+ * LSS_OPT_SKIP_MASKED_TAIL: with a value != 0, causal backward calls leave
+ * UNWRITTEN the 128-row key tiles of dk_partial / dv_partial that lie entirely
+ * at or beyond row seg_offset + l_s (keys no query of the segment sees; by
+ * default they are filled with zeros).  For callers whose only use of the
+ * partials is lss_reduce_partials() with rows_valid[i] = seg_offset + l_s,
+ * which never reads those rows: short segments of long sequences then stop
+ * paying for writing l_x rows of zeros per call.  (The segment sum of Section
+ * 3, Principle 3 only needs the rows a segment contributes to.)
+ *
+ * Returns LSS_OK, or LSS_ERR_RANGE for an unknown option.
+ */
+typedef enum {
+    LSS_OPT_SKIP_MASKED_TAIL = 1
+} lss_option;
+int lss_set_option(int option, int value);
+
+/*
  * Bytes of device scratch that one forward or backward call of this shape may use
  * (split-KV partial outputs, the row terms D = rowsum(dO * out), partial dQ).
  * Depends on the shape only, not on seg_offset or causal.  Returns 0 for an
@@ -96,7 +115,8 @@ int lss_segment_attn_fwd(const void *q_seg, const void *k, const void *v,
  *   out, lse: what the forward call wrote;  dO [B, l_s, H, d] bf16
  *   dq [B, l_s, H, d] bf16 (written)
  *   dk_partial, dv_partial [B, l_x, H, d] float (every row written; with
- *   causal != 0 the rows >= seg_offset + l_s are exactly 0)
+ *   causal != 0 the rows >= seg_offset + l_s are exactly 0 -- but see
+ *   LSS_OPT_SKIP_MASKED_TAIL)
  */
 int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v,
                          int64_t seg_offset, int64_t l_s, int64_t l_x,

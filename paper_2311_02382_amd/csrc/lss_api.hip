@@ -6,6 +6,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <atomic>
 #include <mutex>
 
 namespace lss {
@@ -68,6 +69,7 @@ Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d, int
 namespace {
 
 thread_local char g_err[256] = "";
+std::atomic<int> g_skip_masked_tail{0};
 std::mutex g_ws_mutex;
 void *g_ws_ptr = nullptr;
 size_t g_ws_bytes = 0;
@@ -114,7 +116,7 @@ int fwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
         return fail(LSS_ERR_ALIGN, "forward: tensor pointers must be 16-byte aligned");
     lss::Workspace ws;
     if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), &ws)) return rc;
-    const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0};
+    const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0, 0};
     const hipError_t e = lss::launch_fwd<T>(s, static_cast<const T *>(q), static_cast<const T *>(k),
                                             static_cast<const T *>(v), static_cast<T *>(out), lse, ws,
                                             static_cast<hipStream_t>(stream));
@@ -144,7 +146,8 @@ int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
     }
     lss::Workspace ws;
     if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), &ws)) return rc;
-    const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0};
+    const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0,
+                          g_skip_masked_tail.load(std::memory_order_relaxed)};
     const hipError_t e = lss::launch_bwd<T>(s, static_cast<const T *>(q), static_cast<const T *>(k),
                                             static_cast<const T *>(v), static_cast<const T *>(out), lse,
                                             static_cast<const T *>(dO), static_cast<T *>(dq), dk_part, dv_part, ws, st);
@@ -157,6 +160,15 @@ int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
 extern "C" {
 
 int lss_version(void) { return 100; }
+
+int lss_set_option(int option, int value)
+{
+    if (option == LSS_OPT_SKIP_MASKED_TAIL) {
+        g_skip_masked_tail.store(value != 0 ? 1 : 0);
+        return LSS_OK;
+    }
+    return fail(LSS_ERR_RANGE, "unknown option %d", option);
+}
 
 const char *lss_last_error(void) { return g_err; }
 

@@ -228,7 +228,9 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, const T *__res
 #pragma unroll
         for (int e = 0; e < 16; ++e) { dk[db][e] = 0.f; dv[db][e] = 0.f; }
 
-    if (rq_begin < s.l_s) {
+    const bool hidden = s.causal && j0 >= s.s0 + s.l_s;     // no query of the segment sees this tile
+    if (hidden && s.skip_tail) return;                      // the caller asked for such tiles to stay unwritten
+    if (!hidden) {
         Frag<T> kf[D / 16], vf[D / 16];
 #pragma unroll
         for (int kb = 0; kb < D / 16; ++kb) {

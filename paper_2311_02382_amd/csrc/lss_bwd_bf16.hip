@@ -334,8 +334,10 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
         rq_begin = rq_begin / C::BQ * C::BQ;
     }
 
-    if (rq_begin >= s.l_s) {
-        // no query of the segment sees this tile: its partial rows are zero (coalesced fill)
+    if (s.causal && j0 >= s.s0 + s.l_s) {
+        // no query of the segment sees this tile: its partial rows are zero (coalesced fill), or stay
+        // unwritten if the caller asked for that
+        if (s.skip_tail) return;
         constexpr int F4 = D / 4;                       // float4 per (row, head)
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         for (int i = tid; i < C::BKV * F4; i += C::NT) {

@@ -14,6 +14,7 @@ struct SegShape {
     int l_s, l_x;    // query rows of the segment, key/value rows of the sequence
     int B, H, d;
     int causal;
+    int skip_tail;   // causal backward: leave key tiles that no query of the segment sees unwritten (not zero-filled)
 };
 
 // How many key ranges ("splits") a query tile's keys are divided into so that a

@@ -19,7 +19,7 @@ LSS_OK = 0
 STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_ERR_UNSUPPORTED_D",
                 -4: "LSS_ERR_ALIGN", -5: "LSS_ERR_RANGE", -6: "LSS_ERR_WORKSPACE", -7: "LSS_ERR_LAUNCH"}
 
-EXPORTS = ["lss_version", "lss_last_error", "lss_workspace_bytes", "lss_set_workspace",
+EXPORTS = ["lss_version", "lss_last_error", "lss_set_option", "lss_workspace_bytes", "lss_set_workspace",
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
            "lss_segment_attn_bwd_f32", "lss_reduce_partials", "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
            "lss_timing_read", "lss_timing_kernel_name"]
@@ -42,6 +42,8 @@ def load():
     lib = ctypes.CDLL(str(LIB_PATH))
     i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.lss_version.restype = ci
+    lib.lss_set_option.restype = ci
+    lib.lss_set_option.argtypes = [ci, ci]
     lib.lss_last_error.restype = ctypes.c_char_p
     lib.lss_workspace_bytes.argtypes = [i64, i64, i64, i64, i64, ci]
     lib.lss_workspace_bytes.restype = sz
@@ -196,6 +198,14 @@ def lss_reduce_partials(parts, rows_valid=None, out=None, stream=None):
 
 def lss_timing_enable(on: bool) -> None:
     _check(load().lss_timing_enable(int(bool(on))))
+
+
+LSS_OPT_SKIP_MASKED_TAIL = 1
+
+
+def lss_set_option(option: int, value: int) -> None:
+    """Process-wide option, see include/lss_attn.h."""
+    _check(load().lss_set_option(int(option), int(value)))
 
 
 def lss_timing_select(kernel_ids) -> None:

@@ -122,6 +122,8 @@ WORKLOADS = {
     "lx24k": Workload("lx24k", B=4, l_x=24576, N=6, H=16, d=64, causal=True, qkv_std=0.125, seed=3000),
     "lx32k_d128": Workload("lx32k_d128", B=1, l_x=32768, N=16, H=16, d=128, causal=False, qkv_std=1.0, seed=4000),
     "lx50k": Workload("lx50k", B=1, l_x=50112, N=48, H=8, d=64, causal=True, qkv_std=1.0, seed=5000),
+    # segments as short as the paper's largest runs give one GPU: 58 rows of a 50,112-token sequence
+    "lx50k_skinny": Workload("lx50k_skinny", B=4, l_x=50112, N=864, H=8, d=64, causal=True, qkv_std=1.0, seed=6000),
 }
 
 

@@ -93,3 +93,11 @@ def test_backward_and_reduce_argument_checks(lib):
     assert red(bad, 2, None, 256, 1, 1, 64, 0x3000, None) == -4
     nul = (ctypes.c_void_p * 2)(0x1000, None)
     assert red(nul, 2, None, 256, 1, 1, 64, 0x3000, None) == -1
+
+
+def test_options(lib):
+    lib.lss_set_option.restype = ctypes.c_int
+    assert lib.lss_set_option(1, 1) == 0        # LSS_OPT_SKIP_MASKED_TAIL on
+    assert lib.lss_set_option(1, 0) == 0        # ... and off again (process-wide state)
+    assert lib.lss_set_option(77, 1) == -5      # unknown option
+    assert b"option" in lib.lss_last_error()

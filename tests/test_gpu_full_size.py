@@ -134,6 +134,16 @@ def test_lx50k_ragged_tails():
     check_segment(W, 23, [(0, 6)], None)
 
 
+def test_lx50k_skinny_segments():
+    # 58-row segments (less than half a query tile; one Q/dO tile per dK/dV workgroup)
+    W = Workload("lx50k_skinny")
+    w = W.w
+    assert w.l_s == 58
+    check_segment(W, w.N - 1, [(0, 0), (w.B - 1, w.H - 1)], (1, 2))    # s0 = 50,054: sees the whole sequence
+    check_segment(W, 0, [(2, 5)], (2, 5))                               # s0 = 0: 58 keys, all diagonal
+    check_segment(W, 431, [(3, 1)], (0, 6))
+
+
 def test_lx50k_full_sweep_segment_sum_is_exact_and_reproducible():
     # all 48 segments back to back; dk partials accumulated with the library's fixed-order sum
     W = Workload("lx50k")

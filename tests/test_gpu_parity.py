@@ -171,3 +171,38 @@ def test_canary_rows_are_untouched():
                              dv_partial=big_v[256:256 + nk].view(B, l_x, H, d))
     for big, m in ((big_k, nk), (big_v, nk), (big_q, n)):
         assert torch.all(big[:256] == 3.0) and torch.all(big[256 + m:] == 3.0)
+
+
+@pytest.mark.parametrize("kind", ["bf16", "f32"])
+def test_skip_masked_tail_option(kind):
+    # with the option on, key tiles that no query of the segment sees stay unwritten; everything
+    # the segment sum reads is bit-identical to the default, and so is the segment sum itself
+    B, l_x, H, d = 1, 1000, 2, 64
+    Q, K, V, DO = stage_all(B, l_x, H, d, 131, kind)
+    fwd, bwd = lss.lss_segment_attn_fwd, lss.lss_segment_attn_bwd       # dispatch on the tensors' dtype
+    segs = [(0, 58), (58, 300), (358, 642)]
+    parts = {0: [], 1: []}
+    try:
+        for opt in (0, 1):
+            lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, opt)
+            for s0, l_s in segs:
+                q = Q.dev[:, s0:s0 + l_s].contiguous()
+                out, lse = fwd(q, K.dev, V.dev, s0, True)
+                dk = torch.full((B, l_x, H, d), 7.0, dtype=torch.float32, device="cuda")
+                dv = torch.full((B, l_x, H, d), 7.0, dtype=torch.float32, device="cuda")
+                bwd(q, K.dev, V.dev, s0, out, lse, DO.dev[:, s0:s0 + l_s].contiguous(), True, dk_partial=dk, dv_partial=dv)
+                parts[opt].append((dk, dv))
+    finally:
+        lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, 0)
+    rows_valid = [s0 + l_s for s0, l_s in segs]
+    for (s0, l_s), (dk0, dv0), (dk1, dv1) in zip(segs, parts[0], parts[1]):
+        hi = s0 + l_s
+        assert torch.equal(dk0[:, :hi], dk1[:, :hi]) and torch.equal(dv0[:, :hi], dv1[:, :hi])
+        assert torch.count_nonzero(dk0[:, hi:]) == 0                    # default: zeros
+        first_hidden_tile = -(-hi // 128) * 128                         # tiles are 128 keys
+        assert torch.all(dk1[:, first_hidden_tile:] == 7.0) and torch.all(dv1[:, first_hidden_tile:] == 7.0)
+        assert torch.count_nonzero(dk1[:, hi:first_hidden_tile]) == 0   # rest of the last visited tile
+    for which in (0, 1):
+        a = lss.lss_reduce_partials([p[which] for p in parts[0]], rows_valid)
+        b = lss.lss_reduce_partials([p[which] for p in parts[1]], rows_valid)
+        assert torch.equal(a, b)
