@@ -158,7 +158,7 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
 
         // One pipeline step.  A: block (tile_a, kb2_a) into (sc_a, dp_a).  B: (sc_b, dp_b), first key
         // jb_b, packing into df_b.  C: block (tile_c, kb2_c) from df_c into acc.  Per unit the matrix
-        // instructions go C, A, A; after each one come the B elements that fall to its slot.
+        // instructions go C, A, A (A, A, C in the last unit); after each one come the B elements that fall to its slot.
         // Operand fragments are read from LDS one unit ahead of their use; those of the first unit
         // by the step before (ak[0], av[0], ck[0] on entry), and this step leaves there those of
         // the next step: A on block (tile_an, kb2_an), C on (tile_cn, kb2_cn).  `mid` runs before
@@ -188,22 +188,30 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
             }
 #pragma unroll
             for (int u = 0; u < NU; ++u) {
+                const int half = u / (D / 32), db = u % (D / 32);
                 if (u + 1 < NU) {
                     if (HC) load_c(tile_c, kb2_c, u + 1, ck[(u + 1) & 1]);
                     if (HA) load_a(tile_a, kb2_a, u + 1, ak[(u + 1) & 1], av[(u + 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (HC) acc[db] = mma(ck[u & 1], df_c[half], acc[db]);
+                    b_slot(3 * u);
+                    if (HA) sc_a = mma(ak[u & 1], qf[u], u == 0 ? zero16 : sc_a);
+                    b_slot(3 * u + 1);
+                    if (HA) dp_a = mma(av[u & 1], gf[u], u == 0 ? neg_d : dp_a);
+                    b_slot(3 * u + 2);
                 } else {
+                    // last unit: A first, so that its results are there when the next step's B wants them
+                    if (HA) sc_a = mma(ak[u & 1], qf[u], sc_a);
+                    b_slot(3 * u);
+                    if (HA) dp_a = mma(av[u & 1], gf[u], dp_a);
+                    b_slot(3 * u + 1);
                     mid();
                     load_c(tile_cn, kb2_cn, 0, ck[0]);
                     load_a(tile_an, kb2_an, 0, ak[0], av[0]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (HC) acc[db] = mma(ck[u & 1], df_c[half], acc[db]);
+                    b_slot(3 * u + 2);
                 }
-                __builtin_amdgcn_sched_barrier(0);
-                const int half = u / (D / 32), db = u % (D / 32);
-                if (HC) acc[db] = mma(ck[u & 1], df_c[half], acc[db]);
-                b_slot(3 * u);
-                if (HA) sc_a = mma(ak[u & 1], qf[u], u == 0 ? zero16 : sc_a);
-                b_slot(3 * u + 1);
-                if (HA) dp_a = mma(av[u & 1], gf[u], u == 0 ? neg_d : dp_a);
-                b_slot(3 * u + 2);
             }
             // ... and its results through another one, so that it is not sunk below the step either
             if (HB) asm volatile("" : "+v"(df_b[0].v), "+v"(df_b[1].v));
@@ -458,7 +466,8 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
     };
     // One pipeline step.  A: block (tile_a, qb_a), first row r0_a, into (sc_a, dp_a).  B: (sc_b, dp_b),
     // packing into (pf_b, df_b).  C: block (tile_c, qb_c) from (pf_c, df_c) into dk, dv.  The matrix
-    // instructions alternate C, C, A, A; after each one come the B elements that fall to its slot.
+    // instructions alternate C, C, A, A (A, A, C, C in the last unit); after each one come the B
+    // elements that fall to its slot.
     // Everything read from LDS is requested well before its use: operand fragments one unit ahead;
     // for the next step (A on block (tile_an, qb_an), C on (tile_cn, qb_cn)) this step's last
     // unit requests the fragments of C's first unit (cq[0], cg[0]) and, into the three quarters of
@@ -494,24 +503,35 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
         if (HB) asm volatile("" : "+v"(sc_b), "+v"(dp_b));
 #pragma unroll
         for (int u = 0; u < NU; ++u) {
-            if (HC && u + 1 < NU) load_c(tile_c, qb_c, u + 1, cq[(u + 1) & 1], cg[(u + 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
             const int half = u / (D / 32), db = u % (D / 32);
-            if (HC) dv[db] = mma(cg[u & 1], pf_c[half], dv[db]);
-            b_slot(4 * u);
-            if (HC) dk[db] = mma(cq[u & 1], df_c[half], dk[db]);
-            b_slot(4 * u + 1);
-            if (HA && u + 1 < NU) load_a(tile_a, qb_a, u + 1, aq[(u + 1) & 1], ag[(u + 1) & 1]);
-            if (u + 1 == NU) {
+            if (u + 1 < NU) {
+                if (HC) load_c(tile_c, qb_c, u + 1, cq[(u + 1) & 1], cg[(u + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (HC) dv[db] = mma(cg[u & 1], pf_c[half], dv[db]);
+                b_slot(4 * u);
+                if (HC) dk[db] = mma(cq[u & 1], df_c[half], dk[db]);
+                b_slot(4 * u + 1);
+                if (HA) load_a(tile_a, qb_a, u + 1, aq[(u + 1) & 1], ag[(u + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (HA) sc_a = mma(aq[u & 1], kf[u], sc_a);
+                b_slot(4 * u + 2);
+                if (HA) dp_a = mma(ag[u & 1], vf[u], dp_a);
+                b_slot(4 * u + 3);
+            } else {
+                // last unit: A first, so that its results are there when the next step's B wants them
+                if (HA) sc_a = mma(aq[u & 1], kf[u], sc_a);
+                b_slot(4 * u);
+                if (HA) dp_a = mma(ag[u & 1], vf[u], dp_a);
+                b_slot(4 * u + 1);
                 mid();
                 load_c(tile_cn, qb_cn, 0, cq[0], cg[0]);
                 init_load(tile_an, qb_an, 0, 3, sc_b, dp_b);    // elements 0..11 of B are packed by now
+                __builtin_amdgcn_sched_barrier(0);
+                if (HC) dv[db] = mma(cg[u & 1], pf_c[half], dv[db]);
+                b_slot(4 * u + 2);
+                if (HC) dk[db] = mma(cq[u & 1], df_c[half], dk[db]);
+                b_slot(4 * u + 3);
             }
-            __builtin_amdgcn_sched_barrier(0);
-            if (HA) sc_a = mma(aq[u & 1], kf[u], sc_a);
-            b_slot(4 * u + 2);
-            if (HA) dp_a = mma(ag[u & 1], vf[u], dp_a);
-            b_slot(4 * u + 3);
         }
         // ... and its results through another one, so that it is not sunk below the step either
         if (HB) asm volatile("" : "+v"(pf_b[0].v), "+v"(pf_b[1].v), "+v"(df_b[0].v), "+v"(df_b[1].v));

@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
 
         // One pipeline step.  A: block (tile_a, kb2_a) into sc_a.  B: sc_b, first key jb_b, packing
         // into pf_b.  C: block (tile_c, kb2_c) from pf_c into o.  Per unit the matrix instructions
-        // go C, A; after each one come the B elements that fall to its slot.  Operand fragments are
+        // go C, A (A, C in the last unit); after each one come the B elements that fall to its slot.  Operand fragments are
         // read from LDS one unit ahead of their use; those of the first unit by the step before
         // (ak[0], cv[0] on entry), and this step leaves there those of the next step: A on block
         // (tile_an, kb2_an), C on (tile_cn, kb2_cn).  `mid` runs before those last reads: the even
@@ -199,20 +199,26 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
             }
 #pragma unroll
             for (int u = 0; u < NU; ++u) {
+                const int half = u / (D / 32), db = u % (D / 32);
                 if (u + 1 < NU) {
                     if (HC) load_c(tile_c, kb2_c, u + 1, cv[(u + 1) & 1]);
                     if (HA) load_a(tile_a, kb2_a, u + 1, ak[(u + 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (HC) o[db] = mma(cv[u & 1], pf_c[half], o[db]);
+                    b_slot(2 * u);
+                    if (HA) sc_a = mma(ak[u & 1], qf[u], u == 0 ? zero16 : sc_a);
+                    b_slot(2 * u + 1);
                 } else {
+                    // last unit: A first, so that its result is there when the next step's B wants it
+                    if (HA) sc_a = mma(ak[u & 1], qf[u], sc_a);
+                    b_slot(2 * u);
                     mid();
                     load_c(tile_cn, kb2_cn, 0, cv[0]);
                     load_a(tile_an, kb2_an, 0, ak[0]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (HC) o[db] = mma(cv[u & 1], pf_c[half], o[db]);
+                    b_slot(2 * u + 1);
                 }
-                __builtin_amdgcn_sched_barrier(0);
-                const int half = u / (D / 32), db = u % (D / 32);
-                if (HC) o[db] = mma(cv[u & 1], pf_c[half], o[db]);
-                b_slot(2 * u);
-                if (HA) sc_a = mma(ak[u & 1], qf[u], u == 0 ? zero16 : sc_a);
-                b_slot(2 * u + 1);
             }
             if (HB) {
                 // ... and its results through another one, so that it is not sunk below the step either
