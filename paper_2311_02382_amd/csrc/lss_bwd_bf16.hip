@@ -108,9 +108,8 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
 #pragma unroll
             for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i];
             if (rows_ok < C::BC) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
-            char *dst = smem + slot * C::SLOT;
-            Tile::issue(kbase + (int64_t)j0 * ld, off, dst, wave);
-            Tile::issue(vbase + (int64_t)j0 * ld, off, dst + C::OFF_V, wave);
+            static_assert(C::OFF_V == Tile::BYTES, "V tile follows K tile");
+            Tile::issue_pair(kbase + (int64_t)j0 * ld, vbase + (int64_t)j0 * ld, off, smem + slot * C::SLOT, wave);
         };
 
         // ---- per-lane LDS offsets (bytes, within a tile)
@@ -393,9 +392,9 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
 #pragma unroll
         for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i];
         if (rows_ok < C::BQ) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
+        static_assert(C::OFF_G == Tile::BYTES, "dO tile follows Q tile");
         char *dst = smem + slot * C::SLOT;
-        Tile::issue(qbase + (int64_t)rq0 * ld, off, dst, wave);
-        Tile::issue(gbase + (int64_t)rq0 * ld, off, dst + C::OFF_G, wave);
+        Tile::issue_pair(qbase + (int64_t)rq0 * ld, gbase + (int64_t)rq0 * ld, off, dst, wave);
         if (wave < 2) {
             const float *src = (wave == 0 ? lbase : dbase) + rq0;
             const uint32_t ro = (uint32_t)min(lane, rows_ok - 1) * 4u;

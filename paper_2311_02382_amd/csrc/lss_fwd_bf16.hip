@@ -97,9 +97,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
 #pragma unroll
             for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i];
             if (rows_ok < C::BC) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
-            char *dst = smem + slot * C::SLOT;
-            Tile::issue(kbase + (int64_t)j0 * ld, off, dst, wave);
-            Tile::issue(vbase + (int64_t)j0 * ld, off, dst + C::OFF_V, wave);
+            static_assert(C::OFF_V == Tile::BYTES, "V tile follows K tile");
+            Tile::issue_pair(kbase + (int64_t)j0 * ld, vbase + (int64_t)j0 * ld, off, smem + slot * C::SLOT, wave);
         };
 
         // ---- per-lane LDS offsets (bytes, within a tile)
