@@ -1,5 +1,5 @@
-// bf16-only building blocks of the tuned kernels (gfx950): LDS transpose reads, packed
-// conversions, register-staged tile prefetch.
+// bf16-only building blocks of the tuned kernels (gfx950): direct global -> LDS tile loads into
+// swizzled tiles, LDS transpose reads, packed conversions.
 #pragma once
 #include "lss_common.h"
 
@@ -8,83 +8,6 @@ namespace lss {
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
-// DS_READ_B64_TR_B16: within each group of 16 lanes, lane i receives element (i % 4) of the
-// 8-byte rows addressed by lanes (i / 4) + 4 * t, t = 0..3.  With lane s of a group addressing
-// row (s / 4), 4-element column chunk (s % 4) of a row-major tile, lane i ends up with column i
-// of 4 consecutive rows: a 4 x 16 block read transposed.
-//
-// tr_lane_offset(): element offset (within a row-major tile of `pitch` elements per row) that
-// this lane passes so that, over the two reads of load_frag_tr, it receives for tile column
-// (lane % 32) the 8 rows  8*a + 4*(lane/32) + t  (a = 0, 1; t = 0..3) -- exactly the rows that
-// slots 4*a + t of a C-tile half carry (see lss_common.h).
-__device__ __forceinline__ int tr_lane_offset(int lane, int pitch)
-{
-    const int grp = lane >> 4, hh = grp >> 1, nh = grp & 1, s = lane & 15;
-    return (4 * hh + (s >> 2)) * pitch + 16 * nh + 4 * (s & 3);
-}
-
-// A-operand fragment of the TRANSPOSE of a row-major LDS tile: rows [row0, row0+16) become the
-// contraction slots, columns [col0, col0+32) the 32 rows of the operand.
-__device__ __forceinline__ Frag<bf16_t> load_frag_tr(const bf16_t *tile, int pitch, int row0, int col0, int lane_off)
-{
-    const bf16_t *p = tile + row0 * pitch + col0 + lane_off;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * pitch));
-    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    Frag<bf16_t> f;
-    f.v = __builtin_bit_cast(bf16x8, both);
-    return f;
-}
-
-// Register-staged copy of a [ROWS][D] bf16 tile: issue the global loads early (fetch), store
-// them to LDS later (commit).  256 threads; 16-byte chunks.  The loads are unconditional so that
-// the compiler can count them (a load under a branch forces a full wait on every later use of
-// any loaded register): rows >= rows_ok re-read row rows_ok - 1, and the kernels make sure such
-// rows only ever meet weights that are exactly 0.  Needs rows_ok >= 1.
-template <int D, int ROWS>
-struct TileStage {
-    static constexpr int CPR = D / 8;                 // 16-byte chunks per row
-    static constexpr int N = ROWS * CPR / 256;        // chunks per thread
-    static_assert(ROWS * CPR % 256 == 0, "tile must divide among 256 threads");
-    f32x4 r[N];
-
-    __device__ __forceinline__ void fetch(const bf16_t *__restrict__ g, int64_t row_stride, int rows_ok, int tid)
-    {
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const int c = i * 256 + tid, row = min(c / CPR, rows_ok - 1), col = (c % CPR) * 8;
-            r[i] = *reinterpret_cast<const f32x4 *>(g + row * row_stride + col);
-        }
-    }
-    // Same loads with the address split into a wavefront-uniform tile pointer and per-thread
-    // 32-bit element offsets computed once (offsets()): inside a loop only the uniform pointer
-    // moves, on the scalar unit, and the vector unit computes no addresses at all.  Offsets are
-    // in bytes; needs ROWS * row_stride * 2 < 2^32.
-    __device__ __forceinline__ void offsets(uint32_t (&off)[N], int64_t row_stride, int rows_ok, int tid) const
-    {
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const int c = i * 256 + tid, row = min(c / CPR, rows_ok - 1), col = (c % CPR) * 8;
-            off[i] = ((uint32_t)row * (uint32_t)row_stride + (uint32_t)col) * 2u;
-        }
-    }
-    __device__ __forceinline__ void fetch(const bf16_t *__restrict__ g_uniform, const uint32_t (&off)[N])
-    {
-#pragma unroll
-        for (int i = 0; i < N; ++i)
-            r[i] = *reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(g_uniform) + off[i]);
-    }
-    __device__ __forceinline__ void commit(bf16_t *lds, int pitch, int tid) const
-    {
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const int c = i * 256 + tid, row = c / CPR, col = (c % CPR) * 8;
-            *reinterpret_cast<f32x4 *>(lds + row * pitch + col) = r[i];
-        }
-    }
-};
-
 
 // Global -> LDS load without a register in between: lane i moves BYTES (4 or 16) bytes from
 // g_uniform + voff to lds_uniform + i * BYTES.  Base pointers are wavefront-uniform, voff per lane.
@@ -132,15 +55,10 @@ struct DirectTile {
             off[i] = ((uint32_t)min(row, rows_ok - 1) * (uint32_t)row_stride + (uint32_t)chunk * 8u) * 2u;
         }
     }
-    // issue the loads; `g_uniform`, `lds_tile` and `wave` must be wavefront-uniform
-    static __device__ __forceinline__ void issue(const bf16_t *g_uniform, const uint32_t (&off)[NI], char *lds_tile, int wave)
-    {
-#pragma unroll
-        for (int i = 0; i < NI; ++i) lds_dma<16>(g_uniform, off[i], lds_tile + (i * 4 + wave) * 1024);
-    }
-    // The same for two tensors with one set of offsets, the second tile following the first in LDS
-    // (lds_tile + BYTES): one assembly block, so that M0 is saved and restored once and merely
-    // stepped by 4 KB (four wavefronts x 1 KB) from load to load.
+    // Issue the loads of two tensors' tiles with one set of offsets, the second tile following the
+    // first in LDS (lds_tile + BYTES).  Base pointers, `lds_tile` and `wave` must be wavefront-uniform.
+    // One assembly block (see lds_dma for why assembly), so that M0 is saved and restored once and
+    // merely stepped by 4 KB (four wavefronts x 1 KB) from load to load.
     static __device__ __forceinline__ void issue_pair(const bf16_t *g0_uniform, const bf16_t *g1_uniform,
                                                       const uint32_t (&off)[NI], char *lds_tile, int wave)
     {
@@ -175,8 +93,16 @@ struct DirectTile {
     static __device__ __forceinline__ int chunk_offset(int r, int c) { return r * (D * 2) + (((c & ~7) | ((c ^ r) & 7)) * 16); }
 };
 
-// A-operand fragment of the transpose of a DirectTile (see load_frag_tr): `lane_off` is this
-// lane's byte offset for column block `db` (tr_lane_offset_sw), `row0` a multiple of 16.
+// DS_READ_B64_TR_B16: within each group of 16 lanes, lane i receives element (i % 4) of the
+// 8-byte rows addressed by lanes (i / 4) + 4 * t, t = 0..3.  With lane s of a group addressing
+// row (s / 4), 4-element column chunk (s % 4) of a row-major tile, lane i ends up with column i
+// of 4 consecutive rows: a 4 x 16 block read transposed.  (Lane mapping measured on the GPU.)
+//
+// A-operand fragment of the TRANSPOSE of a DirectTile: rows [row0, row0+16) become the contraction
+// slots, the 32 columns of block `db` the 32 rows of the operand.  `lane_off` is this lane's byte
+// offset for that column block (tr_lane_offset_sw), `row0` a multiple of 16.  Over the two reads
+// the lane receives, for tile column (lane % 32), the 8 rows 8*a + 4*(lane/32) + t (a = 0, 1;
+// t = 0..3) -- exactly the rows that slots 4*a + t of a C-tile half carry (see lss_common.h).
 template <int D>
 __device__ __forceinline__ Frag<bf16_t> load_frag_tr_sw(const char *tile, int row0, int lane_off)
 {
@@ -188,9 +114,10 @@ __device__ __forceinline__ Frag<bf16_t> load_frag_tr_sw(const char *tile, int ro
     f.v = __builtin_bit_cast(bf16x8, both);
     return f;
 }
-// Byte offset for load_frag_tr_sw, columns [32 db, 32 db + 32): the lane addresses row
-// 4*hh + s/4 (+ 8, + row0: neither changes row & 7) and the 8-byte piece (s % 4) of the 32-byte
-// column group nh -- the layout of tr_lane_offset, with the chunk permutation of DirectTile.
+// Byte offset for load_frag_tr_sw, columns [32 db, 32 db + 32): within its group of 16 lanes, lane
+// s addresses row 4*hh + s/4 (+ 8, + row0: neither changes row & 7) and the 8-byte piece (s % 4)
+// of the 32-byte column group nh (hh, nh: bits 1 and 0 of the group index), at the position the
+// chunk permutation of DirectTile gives it.
 template <int D>
 __device__ __forceinline__ int tr_lane_offset_sw(int lane, int db)
 {
@@ -199,10 +126,9 @@ __device__ __forceinline__ int tr_lane_offset_sw(int lane, int db)
     return DirectTile<D, 64>::chunk_offset(row, chunk) + (s & 1) * 8;
 }
 
-// Wait until every outstanding vector-memory load of this wave has returned.  Placed once before
-// a main loop it also tells the compiler's wait-count insertion that nothing loaded earlier (Q
-// fragments, K/V operands) is still pending, so that inside the loop it only ever waits for the
-// loop's own prefetch loads, and only where they are consumed.
+// Wait until every outstanding vector-memory load of this wave has returned, the direct
+// global -> LDS ones included (their data is then in LDS; a barrier publishes it to the other
+// wavefronts).
 __device__ __forceinline__ void wait_vmem_all() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0), others untouched
 
 // 4 floats -> 4 bf16 (round to nearest even), as one 8-byte value

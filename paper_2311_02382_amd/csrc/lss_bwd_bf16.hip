@@ -1,11 +1,15 @@
 // Tuned bf16 backward of Eq. 2 (Section 3, Principle 3) for gfx950: the two matrix kernels of
-// lss_bwd.hip (same mathematics, same operand roles) rebuilt around
-//   * in the dQ kernel at d = 64, 64 query rows per wavefront, so each LDS fragment feeds two
-//     matrix instructions;
+// lss_bwd.hip (same mathematics, same operand roles) rebuilt as two kinds of workgroup that share
+// one launch (bwd_main_bf16_kernel):
+//   * 32 x 32 blocks, three stages per block (score-side products, vector work, output-side
+//     products), software-pipelined so that the vector work of one block sits between the matrix
+//     instructions of its neighbours;
+//   * 64-row tiles loaded global -> LDS directly into a ring of three unpadded, swizzled tiles, a
+//     full loop iteration ahead, one barrier per tile;
 //   * row-major LDS tiles read transposed with DS_READ_B64_TR_B16 where the contraction runs over
 //     tile rows (K^T for dQ, Q^T and dO^T for dK and dV) -- no transposing stores;
-//   * double-buffered, register-staged tile loads with one barrier per tile;
-//   * D = rowsum(dO * out) computed inside the dQ kernel (no separate launch).
+//   * lse, D = rowsum(dO * out) and the masks folded into accumulator start values where the
+//     layout allows (a small kernel prepares -D and -lse * sqrt(d) per row).
 #include "lss_bf16.h"
 #include <type_traits>
 #include "lss_kernels.h"
