@@ -206,3 +206,19 @@ def test_skip_masked_tail_option(kind):
         a = lss.lss_reduce_partials([p[which] for p in parts[0]], rows_valid)
         b = lss.lss_reduce_partials([p[which] for p in parts[1]], rows_valid)
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_running_maximum_keeps_rising_and_large_scores(causal):
+    # Scores that grow along the keys (every block brings a new maximum, by much more than the
+    # forward kernel's lazy threshold), on top of large random ones (|score| up to ~50): the
+    # softmax must neither overflow nor lose the early, tiny weights' normalisation.
+    B, l_x, H, d = 1, 640, 2, 64
+    q, k, v, do = synth.make_inputs(B, l_x, H, d, 151, 2.0)
+    u = np.zeros(d, dtype=np.float32); u[:8] = 1.0
+    ramp = (np.arange(l_x, dtype=np.float32) / l_x)[None, :, None, None]
+    k = k + 6.0 * ramp * u                  # key j leans 6 j / l_x towards u
+    q = q + 3.0 * u                         # every query leans towards u: score grows by ~18*8/8 per unit of ramp
+    Q, K, V, DO = (Staged(a.astype(np.float32), "bf16") for a in (q, k, v, do))
+    for s0, l_s in ((0, 200), (200, 440)):
+        run_segment(Q, K, V, DO, s0, l_s, causal, "bf16", tag=f"ramp s0={s0}")
