@@ -215,7 +215,15 @@ static hipError_t launch_fwd_d(const SegShape &s, const T *q, const T *k, const 
                                const Workspace &ws, hipStream_t st)
 {
     using C = FwdCfg<T, D>;
-    const int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H, fwd_rows_per_wg((int)sizeof(T), D));
+    int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H, fwd_rows_per_wg((int)sizeof(T), D));
+    {
+        // the split count above only knows the shape; under the causal mask a segment near the start of
+        // the sequence sees few keys, and a split of fewer than 8 key tiles costs more (partial
+        // outputs, merge) than it gains
+        const int64_t kv_extent = s.causal ? (s.s0 + s.l_s < s.l_x ? s.s0 + s.l_s : (int64_t)s.l_x) : (int64_t)s.l_x;
+        const int cap = (int)((kv_extent + 63) / 64 / 8);
+        if (cap < n_splits) n_splits = cap < 1 ? 1 : cap;
+    }
     hipError_t e;
     if constexpr (sizeof(T) == 2) {
         e = launch_fwd_bf16_main(s, q, k, v, out, lse, ws, n_splits, st);
