@@ -126,6 +126,22 @@ __device__ __forceinline__ int tr_lane_offset_sw(int lane, int db)
     return DirectTile<D, 64>::chunk_offset(row, chunk) + (s & 1) * 8;
 }
 
+// Workgroup order for grids of (batch*head, inner) work items.  Consecutive workgroup ids go to
+// consecutive XCDs (8 of them, each with its own L2).  Item `id` is given batch*head
+// bh = id % 8 + 8 * (id / 8 / n_inner) and inner index (id / 8) % n_inner: an XCD sees ONE head at
+// a time (all inner items of head x, then of head x + 8, ...), so what the workgroups of a head
+// share (K and V, or Q and dO) stays in that XCD's L2.  Grid size xcd_grid(bhs, n_inner); ids
+// whose bh falls past bhs (bhs not a multiple of 8) have no work: xcd_item returns false.
+constexpr int kXcds = 8;
+inline int xcd_grid(int bhs, int n_inner) { return kXcds * ((bhs + kXcds - 1) / kXcds) * n_inner; }
+__device__ __forceinline__ bool xcd_item(int id, int bhs, int n_inner, int &bh, int &inner)
+{
+    const int x = id % kXcds, rest = id / kXcds;
+    inner = rest % n_inner;
+    bh = x + kXcds * (rest / n_inner);
+    return bh < bhs;
+}
+
 // Wait until every outstanding vector-memory load of this wave has returned, the direct
 // global -> LDS ones included (their data is then in LDS; a barrier publishes it to the other
 // wavefronts).

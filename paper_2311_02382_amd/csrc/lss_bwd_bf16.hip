@@ -642,16 +642,16 @@ __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(SegShape s, const bf
 // they fill the chip better than one after the other (each alone ends in a tail of part-filled
 // compute units, and short segments are mostly tail).  Workgroups [0, n_dq) take the (batch*head,
 // query tile, key split) triples of dQ -- with few key splits they are the longest of the launch
-// and start first -- and the rest the key tiles of dK/dV, longest query loops first (see
-// bwd_dkv_body).  In both parts (batch, head) runs fastest: consecutive workgroups go to
-// consecutive XCDs, so with B*H a multiple of 8 the workgroups of one head share one XCD's L2 copy
-// of that head's K, V, Q and dO.
+// and start first -- and the rest the (batch*head, key tile) pairs of dK/dV.  Both parts are laid
+// out in XCD order (xcd_item): an XCD works on one head at a time, whose workgroups share that
+// head's K, V, Q and dO in its L2; within a head the longest workgroups come first (last query
+// tiles; first key tiles, the zero-fill ones last).
 template <int D>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO, const float *__restrict__ lse,
     const float *__restrict__ Ls, const float *__restrict__ Dn, bf16_t *__restrict__ dq, float *__restrict__ dq_part,
-    float *__restrict__ dk_part, float *__restrict__ dv_part, int n_splits, int n_dq, int n_q_tiles)
+    float *__restrict__ dk_part, float *__restrict__ dv_part, int n_splits, int n_dq, int n_q_tiles, int n_key_tiles)
 {
     constexpr int SMEM = DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT > DkvBf16Cfg<D>::RING * DkvBf16Cfg<D>::SLOT
                              ? DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT
@@ -659,12 +659,14 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     __shared__ __attribute__((aligned(1024))) char smem[SMEM];
     const int bhs = s.B * s.H;
     const int id = blockIdx.x;
+    int bh, inner;
     if (id >= n_dq) {
-        const int j = id - n_dq;
-        bwd_dkv_body<D>(smem, s, q, k, v, dO, Ls, Dn, dk_part, dv_part, j % bhs, j / bhs);
+        if (!xcd_item(id - n_dq, bhs, n_key_tiles, bh, inner)) return;
+        bwd_dkv_body<D>(smem, s, q, k, v, dO, Ls, Dn, dk_part, dv_part, bh, inner);
     } else {
-        bwd_dq_body<D>(smem, s, q, k, v, out, dO, lse, dq, dq_part, n_splits, (id / bhs) % n_q_tiles, n_q_tiles, id % bhs,
-                       id / (n_q_tiles * bhs));
+        if (!xcd_item(id, bhs, n_q_tiles * n_splits, bh, inner)) return;
+        bwd_dq_body<D>(smem, s, q, k, v, out, dO, lse, dq, dq_part, n_splits, inner % n_q_tiles, n_q_tiles, bh,
+                       inner / n_q_tiles);
     }
 }
 
@@ -684,11 +686,11 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const bf16_t *q, const bf
     }
     {
         const int n_q_tiles = (s.l_s + DqBf16Cfg<D>::BR - 1) / DqBf16Cfg<D>::BR;
-        const int n_dkv = s.B * s.H * ((s.l_x + DkvBf16Cfg<D>::BKV - 1) / DkvBf16Cfg<D>::BKV);
-        const int n_dq = n_q_tiles * s.B * s.H * n_splits;
+        const int n_key_tiles = (s.l_x + DkvBf16Cfg<D>::BKV - 1) / DkvBf16Cfg<D>::BKV;
+        const int n_dq = xcd_grid(s.B * s.H, n_q_tiles * n_splits), n_dkv = xcd_grid(s.B * s.H, n_key_tiles);
         TimedLaunch tl(K_BWD_MAIN, st);
         hipLaunchKernelGGL((bwd_main_bf16_kernel<D>), dim3((unsigned)(n_dkv + n_dq)), dim3(256), 0, st, s, q, k, v, out, dO,
-                           lse, ws.Ls, ws.D, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles);
+                           lse, ws.Ls, ws.D, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;

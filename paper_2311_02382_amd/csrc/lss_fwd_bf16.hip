@@ -49,13 +49,15 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
 
     const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    // 1-D grid, (batch, head) fastest: consecutive workgroups go to consecutive XCDs, so with B*H a
-    // multiple of 8 all workgroups of one head land on one XCD and share its L2 copy of that head's
-    // K and V.  Then query tiles, last first: under the causal mask the last tiles see the most
-    // keys, and starting the longest workgroups first shortens the tail of the launch.  Then splits.
+    // 1-D grid in XCD order (xcd_item): one head at a time per XCD, whose workgroups share its K and
+    // V in that XCD's L2.  Within a head: query tiles, last first -- under the causal mask the last
+    // tiles see the most keys, and starting the longest workgroups first shortens the tail of the
+    // launch -- then key splits.
     const int bhs = s.B * s.H;
-    const int bh = blockIdx.x % bhs, b = bh / s.H, h = bh % s.H;
-    const int q_tile = (blockIdx.x / bhs) % n_q_tiles, split = blockIdx.x / (bhs * n_q_tiles);
+    int bh, inner;
+    if (!xcd_item(blockIdx.x, bhs, n_q_tiles * n_splits, bh, inner)) return;
+    const int b = bh / s.H, h = bh % s.H;
+    const int q_tile = inner % n_q_tiles, split = inner / n_q_tiles;
     const int r0 = (n_q_tiles - 1 - q_tile) * C::BR;
     const int rw0 = r0 + wave * C::RW;                  // first row of this wavefront
     const int64_t ld = (int64_t)s.H * D;
@@ -312,7 +314,7 @@ static hipError_t launch_fwd_main(const SegShape &s, const bf16_t *q, const bf16
 {
     using C = FwdBf16Cfg<D>;
     const int n_q_tiles = (s.l_s + C::BR - 1) / C::BR;
-    dim3 grid((unsigned)(n_q_tiles * s.B * s.H * n_splits));
+    dim3 grid((unsigned)xcd_grid(s.B * s.H, n_q_tiles * n_splits));
     TimedLaunch tl(K_FWD, st);
     hipLaunchKernelGGL((fwd_bf16_kernel<D>), grid, dim3(C::NT), 0, st, s, q, k, v, out, lse, ws.o_part, ws.lse_part,
                        n_splits, n_q_tiles);
