@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <atomic>
+#include <initializer_list>
 #include <mutex>
 
 namespace lss {
@@ -138,10 +139,14 @@ int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
         return fail(LSS_ERR_ALIGN, "backward: tensor pointers must be 16-byte aligned");
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (l_s == 0) {     // an empty segment contributes nothing: the partials are all zero
-        const size_t bytes = (size_t)B * l_x * H * d * sizeof(float);
-        hipError_t e = hipMemsetAsync(dk_part, 0, bytes, st);
-        if (e == hipSuccess) e = hipMemsetAsync(dv_part, 0, bytes, st);
-        if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "backward memset failed: %s", hipGetErrorString(e));
+        // Written by the sum kernel over one part with no valid rows (it reads nothing then):
+        // a kernel launch, not a memset, so that a caller may record the call into a graph.
+        const int64_t none = 0;
+        for (float *part : {dk_part, dv_part}) {
+            const float *src = part;
+            const hipError_t e = lss::launch_reduce(&src, 1, &none, l_x, B, H, d, part, st);
+            if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "backward zero fill failed: %s", hipGetErrorString(e));
+        }
         return LSS_OK;
     }
     lss::Workspace ws;
