@@ -134,3 +134,46 @@ def reduce_partials(parts):
     if rc != 0:
         raise ValueError("lss_oracle_reduce_partials failed")
     return out
+
+
+# ---- the linear maps either side of the segment attention (fused-communication form) ----------
+# Section 2.2 says only that x is "linearly transformed" into Q, K and V, each the size of x; the
+# reading taken here is Q = x W_q, K = x W_k, V = x W_v with square E_m x E_m weights and no bias.
+# Section 3, Principle 3 and Fig. 2(ii): a segment projects its query from its own rows x_i, and
+# the key and value from the gathered sequence x.  W_kv holds [W_k | W_v] side by side (E_m x 2E_m).
+# Head h of a projected row is its columns [h d, (h+1) d), as in the attention functions above.
+# Plain numpy float64 matrix products; nothing is blocked or fused.
+
+def project_qkv(x, w_q, w_kv, seg_offset: int, l_s: int, H: int):
+    """Q_i = x_i W_q, K = x W_k, V = x W_v.  x [B,l_x,E]; returns q_seg [B,l_s,H,d], k, v [B,l_x,H,d]."""
+    x, w_q, w_kv = _f64(x), _f64(w_q), _f64(w_kv)
+    B, l_x, E = x.shape
+    if w_q.shape != (E, E) or w_kv.shape != (E, 2 * E) or E % H:
+        raise ValueError("weights must be [E,E] and [E,2E], E a multiple of H")
+    if not (0 <= seg_offset and seg_offset + l_s <= l_x):
+        raise ValueError("segment outside the sequence")
+    d = E // H
+    x_i = x[:, seg_offset:seg_offset + l_s, :]
+    q = np.matmul(x_i, w_q).reshape(B, l_s, H, d)
+    k = np.matmul(x, w_kv[:, :E]).reshape(B, l_x, H, d)
+    v = np.matmul(x, w_kv[:, E:]).reshape(B, l_x, H, d)
+    return q, k, v
+
+
+def project_bwd(dq, dk_partial, dv_partial, w_q, w_kv):
+    """Gradients with respect to the projections' inputs, for one segment.
+
+    dx_q [B,l_s,E] = dQ_i W_q^T is the gradient reaching the segment's own rows x_i through the
+    query; dx_partial [B,l_x,E] = dK_part W_k^T + dV_part W_v^T is this segment's contribution to
+    the gradient of the gathered x, the quantity the reduce-scatter of Fig. 2(v) sums over segments.
+    """
+    dq, dk, dv = _f64(dq), _f64(dk_partial), _f64(dv_partial)
+    w_q, w_kv = _f64(w_q), _f64(w_kv)
+    B, l_s, H, d = dq.shape
+    E = H * d
+    l_x = dk.shape[1]
+    if dk.shape != (B, l_x, H, d) or dv.shape != dk.shape or w_q.shape != (E, E) or w_kv.shape != (E, 2 * E):
+        raise ValueError("shapes disagree")
+    dx_q = np.matmul(dq.reshape(B, l_s, E), w_q.T)
+    dx_part = np.matmul(dk.reshape(B, l_x, E), w_kv[:, :E].T) + np.matmul(dv.reshape(B, l_x, E), w_kv[:, E:].T)
+    return dx_q, dx_part

@@ -140,3 +140,15 @@ def make_inputs(B, l_x, H, d, seed, qkv_std=1.0):
 
 def workload_inputs(w: Workload):
     return make_inputs(w.B, w.l_x, w.H, w.d, w.seed, w.qkv_std)
+
+
+def make_projection_inputs(B, l_x, H, d, seed, qkv_std=1.0):
+    """Inputs of the linear maps around the attention: x [B, l_x, E], W_q [E, E], W_kv [E, 2E]
+    (E = H d) as float32, from streams seed+4..6.  x ~ N(0, 1); weight entries ~ N(0, qkv_std^2 / E),
+    so that projected rows have the standard deviation qkv_std the attention workloads use."""
+    E = H * d
+    x = normal_f32(seed + 4, B * l_x * E, 1.0).reshape(B, l_x, E)
+    w_std = qkv_std / float(np.sqrt(E))
+    w_q = normal_f32(seed + 5, E * E, w_std).reshape(E, E)
+    w_kv = normal_f32(seed + 6, E * 2 * E, w_std).reshape(E, 2 * E)
+    return x, w_q, w_kv
