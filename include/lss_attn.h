@@ -153,6 +153,50 @@ int lss_reduce_partials(const float *const *parts, int n, const int64_t *rows_va
                         float *out, void *stream);
 
 /*
+ * The linear maps in front of the attention, in the fused-communication form
+ * (Section 3, Principle 3; Fig. 2(ii), (iii)): a segment computes its query from
+ * its own rows of the layer input, and key and value from the gathered sequence,
+ *     Q_i = x_i W_q,    K = x W_k,    V = x W_v.
+ * Section 2.2 only says that x is linearly transformed into Q, K and V of the
+ * size of x: read here as square E_m x E_m weights (E_m = H*d) and no bias.
+ *   x      [B, l_x, E_m] bf16, the gathered sequence; x_i is its rows
+ *          seg_offset .. seg_offset + l_s - 1
+ *   w_q    [E_m, E_m] bf16 row-major;  w_kv [E_m, 2 E_m] bf16 row-major holds
+ *          W_k in columns 0 .. E_m-1 and W_v in columns E_m .. 2 E_m-1
+ *   q_seg  [B, l_s, H, d] bf16 (written);  k, v [B, l_x, H, d] bf16 (written)
+ * bf16 matrix cores, fp32 accumulation, one rounding to bf16 at the end.
+ * E_m must be a multiple of 128 (LSS_ERR_SHAPE otherwise).  Uses no workspace.
+ */
+int lss_project_qkv(const void *x, const void *w_q, const void *w_kv,
+                    int64_t seg_offset, int64_t l_s, int64_t l_x,
+                    int64_t B, int64_t H, int64_t d,
+                    void *q_seg, void *k, void *v, void *stream);
+
+/*
+ * Backward of those maps with respect to their inputs (Fig. 2(v)):
+ *     dx_q       = dQ_i W_q^T                         [B, l_s, E_m] float (written)
+ *     dx_partial = dK_part W_k^T + dV_part W_v^T      [B, l_x, E_m] float (written)
+ * dx_q is the gradient that reaches the segment's own rows x_i through the query;
+ * dx_partial is this segment's contribution to the gradient of the gathered x,
+ * the quantity the reduce-scatter adds over segments: sum it with
+ * lss_reduce_partials(parts, n, rows_valid, l_x, B, 1, E_m, ...).
+ *   dq          [B, l_s, H, d] bf16;  dk_partial, dv_partial [B, l_x, H, d] float,
+ *               as lss_segment_attn_bwd wrote them
+ *   rows_valid  leading rows (per batch entry) of the partials that hold data:
+ *               l_x, or seg_offset + l_s for a causal segment.  Later rows are not
+ *               read; those rows of dx_partial are written as zeros (with
+ *               LSS_OPT_SKIP_MASKED_TAIL, 256-row tiles entirely past rows_valid
+ *               are left unwritten instead).
+ * The partials are rounded to bf16 as matrix-core operands; accumulation is fp32.
+ * Same restrictions as lss_project_qkv.
+ */
+int lss_project_bwd(const void *dq, const float *dk_partial, const float *dv_partial,
+                    const void *w_q, const void *w_kv,
+                    int64_t l_s, int64_t l_x, int64_t rows_valid,
+                    int64_t B, int64_t H, int64_t d,
+                    float *dx_q, float *dx_partial, void *stream);
+
+/*
  * Per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every
  * kernel the library launches is bracketed by a pair of HIP events on its launch stream.
  *   lss_timing_enable(on)   switch recording on (1) or off (0) for every kernel; off by default

@@ -226,6 +226,50 @@ int lss_segment_attn_bwd_f32(const void *q_seg, const void *k, const void *v, in
                            dv_partial, stream);
 }
 
+int lss_project_qkv(const void *x, const void *w_q, const void *w_kv, int64_t seg_offset, int64_t l_s, int64_t l_x,
+                    int64_t B, int64_t H, int64_t d, void *q_seg, void *k, void *v, void *stream)
+{
+    if (int rc = check_shape(seg_offset, l_s, l_x, B, H, d)) return rc;
+    const int64_t E = H * d;
+    if (E % 128 != 0) return fail(LSS_ERR_SHAPE, "projections: E_m = H*d = %lld is not a multiple of 128", (long long)E);
+    if (B * l_x >= (int64_t)1 << 31) return fail(LSS_ERR_SHAPE, "projections: B*l_x = %lld exceeds 2^31", (long long)(B * l_x));
+    if (B == 0) return LSS_OK;
+    if (!x || !w_q || !w_kv || !k || !v || (l_s > 0 && !q_seg)) return fail(LSS_ERR_NULL, "project_qkv: NULL tensor pointer");
+    if (misaligned(x) || misaligned(w_q) || misaligned(w_kv) || misaligned(q_seg) || misaligned(k) || misaligned(v))
+        return fail(LSS_ERR_ALIGN, "project_qkv: tensor pointers must be 16-byte aligned");
+    using lss::bf16_t;
+    const hipError_t e = lss::launch_project_qkv(static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(w_q),
+                                                 static_cast<const bf16_t *>(w_kv), seg_offset, (int)l_s, (int)l_x, (int)B,
+                                                 (int)E, static_cast<bf16_t *>(q_seg), static_cast<bf16_t *>(k),
+                                                 static_cast<bf16_t *>(v), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "project_qkv launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+int lss_project_bwd(const void *dq, const float *dk_partial, const float *dv_partial, const void *w_q, const void *w_kv,
+                    int64_t l_s, int64_t l_x, int64_t rows_valid, int64_t B, int64_t H, int64_t d, float *dx_q,
+                    float *dx_partial, void *stream)
+{
+    if (int rc = check_shape(0, l_s, l_x, B, H, d)) return rc;
+    const int64_t E = H * d;
+    if (E % 128 != 0) return fail(LSS_ERR_SHAPE, "projections: E_m = H*d = %lld is not a multiple of 128", (long long)E);
+    if (rows_valid < 0 || rows_valid > l_x) return fail(LSS_ERR_RANGE, "project_bwd: rows_valid = %lld outside [0, %lld]", (long long)rows_valid, (long long)l_x);
+    if (B == 0) return LSS_OK;
+    if (!dk_partial || !dv_partial || !w_q || !w_kv || !dx_partial || (l_s > 0 && (!dq || !dx_q)))
+        return fail(LSS_ERR_NULL, "project_bwd: NULL tensor pointer");
+    if (misaligned(dq) || misaligned(dk_partial) || misaligned(dv_partial) || misaligned(w_q) || misaligned(w_kv) ||
+        misaligned(dx_q) || misaligned(dx_partial))
+        return fail(LSS_ERR_ALIGN, "project_bwd: tensor pointers must be 16-byte aligned");
+    using lss::bf16_t;
+    const hipError_t e = lss::launch_project_bwd(static_cast<const bf16_t *>(dq), dk_partial, dv_partial,
+                                                 static_cast<const bf16_t *>(w_q), static_cast<const bf16_t *>(w_kv),
+                                                 (int)l_s, (int)l_x, (int)rows_valid, (int)B, (int)E,
+                                                 g_skip_masked_tail.load(std::memory_order_relaxed), dx_q, dx_partial,
+                                                 static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "project_bwd launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
 int lss_reduce_partials(const float *const *parts, int n, const int64_t *rows_valid, int64_t l_x, int64_t B,
                         int64_t H, int64_t d, float *out, void *stream)
 {

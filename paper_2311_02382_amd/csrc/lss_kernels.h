@@ -58,7 +58,7 @@ hipError_t launch_bwd_bf16_main(const SegShape &s, const bf16_t *q, const bf16_t
 
 // Optional per-kernel timing for benchmarks: when enabled, every launch site brackets its
 // kernel with a pair of HIP events on the launch stream.
-enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_BWD_MAIN, K_COUNT };
+enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_BWD_MAIN, K_PROJ_FWD, K_PROJ_BWD, K_PROJ_BWD_Q, K_COUNT };
 void timing_begin(int id, hipStream_t st);
 void timing_end(int id, hipStream_t st);
 struct TimedLaunch {    // RAII bracket around one kernel launch
@@ -70,5 +70,12 @@ struct TimedLaunch {    // RAII bracket around one kernel launch
 constexpr int kMaxReduceParts = 64;
 hipError_t launch_reduce(const float *const *parts, int n, const int64_t *rows_valid, int64_t l_x,
                          int64_t B, int64_t H, int64_t d, float *out, hipStream_t st);
+
+// the linear maps around the attention (lss_proj.hip); E = H * d, a multiple of 128
+hipError_t launch_project_qkv(const bf16_t *x, const bf16_t *w_q, const bf16_t *w_kv, int64_t s0, int l_s, int l_x,
+                              int B, int E, bf16_t *q_seg, bf16_t *k, bf16_t *v, hipStream_t st);
+hipError_t launch_project_bwd(const bf16_t *dq, const float *dk_part, const float *dv_part, const bf16_t *w_q,
+                              const bf16_t *w_kv, int l_s, int l_x, int rows_valid, int B, int E, int skip_tail,
+                              float *dx_q, float *dx_part, hipStream_t st);
 
 } // namespace lss

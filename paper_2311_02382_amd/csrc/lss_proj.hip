@@ -1,0 +1,343 @@
+// The linear maps either side of the segment attention, in the fused-communication form of
+// Section 3, Principle 3 (Fig. 2(ii), (iii), (v)), as bf16 matrix-core GEMMs for gfx950:
+//     forward   Q_i = x_i W_q (the segment's own rows),  [K | V] = x [W_k | W_v] (gathered sequence)
+//     backward  dx_q = dQ_i W_q^T,  dx_partial = dK_part W_k^T + dV_part W_v^T
+// dx_partial is what the segment sum (the reduce-scatter's arithmetic) then adds over segments.
+//
+// One kernel template computes C[m, n] = sum_k A[m, k] W'[k, n] for a short list of jobs.  A
+// workgroup owns a 256 (m) x 128 (n) tile of C, held transposed in the accumulators (lane = row m
+// of A, as the attention kernels hold one query per lane): C^T += W'^T A^T, so the weights are the
+// A operand of the matrix instruction and the activations its B operand.  Each of the four
+// wavefronts owns 128 (m) x 64 (n): 4 x 2 accumulator tiles, 8 matrix instructions per 6 operand
+// fragments.  The contraction runs in tiles of 64 through a ring of three LDS slots, loaded
+// global -> LDS directly two tiles ahead, one barrier per tile.
+//   W_TR   weights stored [k][n] (forward: W as given).  Their fragments come from the LDS tile
+//          by transposing reads; otherwise the weights are stored [n][k] (backward: W as given
+//          IS W'^T) and are read plainly.
+//   A_F32  A is float (the dK/dV partials): rounded to bf16 on the way into LDS, through
+//          registers; the contraction index runs over dK's columns, then dV's.
+#include "lss_bf16.h"
+#include "lss_kernels.h"
+
+#include <mutex>
+#include <type_traits>
+
+namespace lss {
+
+namespace {
+
+constexpr int PM = 256, PN = 128, PK = 64;      // workgroup tile, contraction tile
+constexpr int P_RING = 3;
+constexpr int P_ABYTES = PM * PK * 2, P_WBYTES = PN * PK * 2, P_SLOT = P_ABYTES + P_WBYTES;
+constexpr int P_LDS = P_RING * P_SLOT;          // 144 KB: one workgroup per compute unit
+
+struct ProjJob {
+    const void *a0, *a1;        // A: [batches][rows][lda]; a1 serves contraction indices >= k_split (or is unused)
+    const bf16_t *w;            // weights, row stride ldw
+    void *c0, *c1;              // C: [batches][rows][ldc]; columns >= n_split go to c1 (column n - n_split)
+    int64_t a_batch_stride, c_batch_stride;     // elements
+    int rows, rows_ok;          // rows per batch; leading rows of A that hold data (the rest count as 0)
+    int batches, N, K, k_split, n_split, ldw;
+    int wg_begin, m_tiles, n_tiles;             // first workgroup id of the job, tiles per batch, column tiles
+};
+struct ProjArgs {
+    ProjJob job[2];
+    int n_jobs, lda, ldc, skip_tail;
+};
+
+using ATile = DirectTile<PK, PM>;               // activations [256 m][64 k]
+using WTileTr = DirectTile<PN, PK>;             // weights [64 k][128 n]
+using WTile = DirectTile<PK, PN>;               // weights [128 n][64 k]
+
+template <bool A_F32, bool W_TR>
+__global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs args)
+{
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    using OutT = typename std::conditional<A_F32 || !W_TR, float, bf16_t>::type;     // backward maps write float
+
+    const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+
+    // ---- which tile: jobs back to back; inside a job consecutive ids go to consecutive XCDs, and an
+    // XCD walks the column tiles of one row tile before the next, so the A rows it streams from HBM
+    // are re-read from its own L2
+    int ji = 0;
+    if (args.n_jobs > 1 && (int)blockIdx.x >= args.job[1].wg_begin) ji = 1;
+    const ProjJob &J = args.job[ji];
+    const int id = blockIdx.x - J.wg_begin;
+    const int slot_id = id / kXcds;
+    const int n_tile = slot_id % J.n_tiles;
+    const int bm = id % kXcds + kXcds * (slot_id / J.n_tiles);
+    if (bm >= J.batches * J.m_tiles) return;
+    const int batch = bm / J.m_tiles, m0 = (bm % J.m_tiles) * PM, n0 = n_tile * PN;
+
+    const int rows_here = min(J.rows - m0, PM);                     // rows of C this tile owns
+    const int rows_data = min(min(J.rows, J.rows_ok) - m0, PM);     // of which this many have data in A
+
+    // ---- output addressing.  Accumulator tile (mb, nb), element v of this lane: row
+    // m = 128 wm + 32 mb + lq, columns n = 64 wn + 32 nb + 8 (v / 4) + 4 hh + (v % 4).
+    OutT *cbase;
+    {
+        const bool second = n0 >= J.n_split;
+        OutT *c = static_cast<OutT *>(second ? J.c1 : J.c0);
+        cbase = c + (int64_t)batch * J.c_batch_stride + (int64_t)m0 * args.ldc + (n0 - (second ? J.n_split : 0));
+    }
+    auto store_tiles = [&](const f32x16 (&acc)[4][2]) {
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+            const int m = 128 * wm + 32 * mb + lq;
+            if (m >= rows_here) continue;
+            const bool data = m < rows_data;
+            OutT *row = cbase + (int64_t)m * args.ldc + 64 * wn + 4 * hh;
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 val = {0.f, 0.f, 0.f, 0.f};
+                    if (data) val = f32x4{acc[mb][nb][4 * g], acc[mb][nb][4 * g + 1], acc[mb][nb][4 * g + 2], acc[mb][nb][4 * g + 3]};
+                    if constexpr (std::is_same<OutT, float>::value)
+                        *reinterpret_cast<f32x4 *>(row + 32 * nb + 8 * g) = val;
+                    else
+                        *reinterpret_cast<bf16x4 *>(row + 32 * nb + 8 * g) = pack4(val[0], val[1], val[2], val[3]);
+                }
+        }
+    };
+
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = zero16;
+
+    if (rows_data <= 0) {       // no row of this tile has data: its rows of C are zero
+        if (!args.skip_tail) store_tiles(acc);
+        return;
+    }
+
+    const int T = J.K / PK;
+    const int t_split = J.k_split / PK;
+
+    // ---- tile loads
+    uint32_t offA[ATile::NI], offW[W_TR ? WTileTr::NI : WTile::NI];
+    if constexpr (!A_F32) ATile::offsets(offA, args.lda, rows_data, wave, lane);
+    if constexpr (W_TR) WTileTr::offsets(offW, J.ldw, PK, wave, lane);
+    else WTile::offsets(offW, J.ldw, PN, wave, lane);
+
+    const char *a0 = static_cast<const char *>(J.a0), *a1 = static_cast<const char *>(J.a1);
+    constexpr int AE = A_F32 ? 4 : 2;           // bytes per element of A
+    const int64_t a_tile0 = ((int64_t)batch * J.a_batch_stride + (int64_t)m0 * args.lda) * AE;
+    auto a_src = [&](int t) -> const char * {   // first element of contraction tile t of this row tile
+        return (t < t_split ? a0 + (int64_t)t * PK * AE : a1 + (int64_t)(t - t_split) * PK * AE) + a_tile0;
+    };
+    auto issue_w = [&](int t, int slot) {
+        char *dst = smem + slot * P_SLOT + P_ABYTES;
+        const bf16_t *src = W_TR ? J.w + (int64_t)t * PK * J.ldw + n0 : J.w + (int64_t)n0 * J.ldw + (int64_t)t * PK;
+#pragma unroll
+        for (int i = 0; i < (W_TR ? WTileTr::NI : WTile::NI); ++i) lds_dma<16>(src, offW[i], dst + (i * 4 + wave) * 1024);
+    };
+    auto issue_a = [&](int t, int slot) {       // bf16 A: direct
+        char *dst = smem + slot * P_SLOT;
+        const char *src = a_src(t);
+#pragma unroll
+        for (int i = 0; i < ATile::NI; ++i) lds_dma<16>(src, offA[i], dst + (i * 4 + wave) * 1024);
+    };
+    // float A: thread `tid` converts the 8-element chunks tid, tid + 256, ... of the tile
+    // (chunk c is columns 8 (c % 8) .. + 7 of row c / 8) and writes them where the direct load would
+    f32x4 stage[A_F32 ? 16 : 1];
+    auto fetch_a = [&](int t) {
+        if constexpr (A_F32) {
+            const char *src = a_src(t);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = i * 256 + tid, row = min(c >> 3, rows_data - 1);
+                const f32x4 *p = reinterpret_cast<const f32x4 *>(src + ((int64_t)row * args.lda + (c & 7) * 8) * 4);
+                stage[2 * i] = __builtin_nontemporal_load(p);
+                stage[2 * i + 1] = __builtin_nontemporal_load(p + 1);
+            }
+        }
+    };
+    auto stash_a = [&](int slot) {
+        if constexpr (A_F32) {
+            char *dst = smem + slot * P_SLOT;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int c = i * 256 + tid;
+                bf16x8 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { v[e] = (bf16_t)stage[2 * i][e]; v[4 + e] = (bf16_t)stage[2 * i + 1][e]; }
+                *reinterpret_cast<bf16x8 *>(dst + ATile::chunk_offset(c >> 3, c & 7)) = v;
+            }
+        }
+    };
+    constexpr int LOADS_PER_TILE = ATile::NI + (W_TR ? WTileTr::NI : WTile::NI);    // direct loads of one wavefront
+
+    // ---- per-lane LDS offsets of the operand fragments of contraction step ks (16 indices)
+    // B operand, row m of A: with plain weights slot e carries index 8 hh + e (one 16-byte read);
+    // with transposed weight reads slot 4 a + t carries index 8 a + 4 hh + t (two 8-byte reads),
+    // the order load_frag_tr_sw delivers.
+    int b_off[4][4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int m = 128 * wm + 32 * mb + lq;
+            b_off[mb][ks] = W_TR ? ATile::chunk_offset(m, 2 * ks) + hh * 8 : ATile::chunk_offset(m, 2 * ks + hh);
+        }
+    int w_off[2][4];            // plain weights: row n = 64 wn + 32 nb + lq, chunk 2 ks + hh
+    int wt_off[2];              // transposed reads: column block 2 wn + nb
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        wt_off[nb] = tr_lane_offset_sw<PN>(lane, 2 * wn + nb);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) w_off[nb][ks] = WTile::chunk_offset(64 * wn + 32 * nb + lq, 2 * ks + hh);
+    }
+    auto compute = [&](int slot) {
+        const char *at = smem + slot * P_SLOT, *wt = at + P_ABYTES;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            Frag<bf16_t> fb[4], fw[2];
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                if constexpr (W_TR) fw[nb] = load_frag_tr_sw<PN>(wt, ks * 16, wt_off[nb]);
+                else fw[nb] = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(wt + w_off[nb][ks]));
+            }
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+                if constexpr (W_TR) {
+                    const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(at + b_off[mb][ks]);
+                    // the chunk after 2 ks of the same row: the swizzle flips bit 0 of the chunk position
+                    const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(at + (b_off[mb][ks] ^ 16));
+                    fb[mb].v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                } else {
+                    fb[mb] = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(at + b_off[mb][ks]));
+                }
+            }
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mma(fw[nb], fb[mb], acc[mb][nb]);
+        }
+    };
+
+    // ---- main loop: tile t is computed from slot t % 3 while tiles t + 1 and t + 2 are on their way
+    if constexpr (A_F32) {
+        fetch_a(0);
+        issue_w(0, 0);
+        if (T > 1) issue_w(1, 1);
+        stash_a(0);
+        if (T > 1) fetch_a(1);
+        wait_vmem_all();        // the weights of tiles 0 and 1 (and the rows just fetched) have arrived
+        __syncthreads();
+        for (int t = 0; t < T; ++t) {
+            if (t + 2 < T) issue_w(t + 2, (t + 2) % P_RING);
+            compute(t % P_RING);
+            if (t + 1 < T) stash_a((t + 1) % P_RING);   // slot last read during tile t - 2
+            wait_vmem_all();
+            if (t + 2 < T) fetch_a(t + 2);              // in flight across the barrier, used after tile t + 1
+            __syncthreads();
+        }
+    } else {
+        issue_a(0, 0); issue_w(0, 0);
+        if (T > 1) { issue_a(1, 1); issue_w(1, 1); }
+        if (T > 1) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS_PER_TILE); else wait_vmem_all();
+        __syncthreads();
+        for (int t = 0; t < T; ++t) {
+            if (t + 2 < T) {    // its slot was last read during tile t - 1, which every wavefront has left
+                issue_a(t + 2, (t + 2) % P_RING); issue_w(t + 2, (t + 2) % P_RING);
+            }
+            compute(t % P_RING);
+            if (t + 2 < T) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS_PER_TILE);     // all but tile t + 2: tile t + 1 is in
+            else wait_vmem_all();
+            __syncthreads();
+        }
+    }
+    store_tiles(acc);
+}
+
+template <bool A_F32, bool W_TR>
+hipError_t launch_proj(ProjArgs &args, int kernel_id, hipStream_t st)
+{
+    int wgs = 0;
+    for (int j = 0; j < args.n_jobs; ++j) {
+        ProjJob &J = args.job[j];
+        J.m_tiles = (J.rows + PM - 1) / PM;
+        J.n_tiles = J.N / PN;
+        J.wg_begin = wgs;
+        wgs += xcd_grid(J.batches * J.m_tiles, J.n_tiles);
+    }
+    if (wgs == 0) return hipSuccess;
+    static std::once_flag once;
+    static hipError_t attr = hipSuccess;
+    std::call_once(once, [] {
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(proj_gemm_kernel<A_F32, W_TR>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+    });
+    if (attr != hipSuccess) return attr;
+    TimedLaunch tl(kernel_id, st);
+    hipLaunchKernelGGL((proj_gemm_kernel<A_F32, W_TR>), dim3(wgs), dim3(256), P_LDS, st, args);
+    return hipGetLastError();
+}
+
+} // namespace
+
+hipError_t launch_project_qkv(const bf16_t *x, const bf16_t *w_q, const bf16_t *w_kv, int64_t s0, int l_s, int l_x,
+                              int B, int E, bf16_t *q_seg, bf16_t *k, bf16_t *v, hipStream_t st)
+{
+    ProjArgs args{};
+    args.lda = args.ldc = E;
+    args.skip_tail = 0;
+    int n = 0;
+    {   // [K | V] = x [W_k | W_v]: the batches of x are contiguous, one tall matrix
+        ProjJob &J = args.job[n++];
+        J.a0 = x; J.a1 = nullptr; J.w = w_kv; J.c0 = k; J.c1 = v;
+        J.a_batch_stride = J.c_batch_stride = 0;
+        J.rows = J.rows_ok = B * l_x; J.batches = 1;
+        J.N = 2 * E; J.K = E; J.k_split = E; J.n_split = E; J.ldw = 2 * E;
+    }
+    if (l_s > 0) {  // Q_i = x_i W_q
+        ProjJob &J = args.job[n++];
+        J.a0 = x + s0 * E; J.a1 = nullptr; J.w = w_q; J.c0 = q_seg; J.c1 = nullptr;
+        J.a_batch_stride = (int64_t)l_x * E; J.c_batch_stride = (int64_t)l_s * E;
+        J.rows = J.rows_ok = l_s; J.batches = B;
+        J.N = E; J.K = E; J.k_split = E; J.n_split = E; J.ldw = E;
+    }
+    args.n_jobs = n;
+    return launch_proj<false, true>(args, K_PROJ_FWD, st);
+}
+
+hipError_t launch_project_bwd(const bf16_t *dq, const float *dk_part, const float *dv_part, const bf16_t *w_q,
+                              const bf16_t *w_kv, int l_s, int l_x, int rows_valid, int B, int E, int skip_tail,
+                              float *dx_q, float *dx_part, hipStream_t st)
+{
+    {   // dx_partial = dK_part W_k^T + dV_part W_v^T: one contraction over the 2E columns of [dK | dV]
+        ProjArgs args{};
+        args.lda = args.ldc = E;
+        args.skip_tail = skip_tail;
+        ProjJob &J = args.job[0];
+        J.a0 = dk_part; J.a1 = dv_part; J.w = w_kv; J.c0 = dx_part; J.c1 = nullptr;
+        J.a_batch_stride = J.c_batch_stride = (int64_t)l_x * E;
+        J.rows = l_x; J.rows_ok = rows_valid; J.batches = B;
+        J.N = E; J.K = 2 * E; J.k_split = E; J.n_split = E; J.ldw = 2 * E;
+        args.n_jobs = 1;
+        const hipError_t e = launch_proj<true, false>(args, K_PROJ_BWD, st);
+        if (e != hipSuccess) return e;
+    }
+    if (l_s > 0) {  // dx_q = dQ_i W_q^T
+        ProjArgs args{};
+        args.lda = args.ldc = E;
+        args.skip_tail = 0;
+        ProjJob &J = args.job[0];
+        J.a0 = dq; J.a1 = nullptr; J.w = w_q; J.c0 = dx_q; J.c1 = nullptr;
+        J.a_batch_stride = J.c_batch_stride = (int64_t)l_s * E;
+        J.rows = J.rows_ok = l_s; J.batches = B;
+        J.N = E; J.K = E; J.k_split = E; J.n_split = E; J.ldw = E;
+        args.n_jobs = 1;
+        const hipError_t e = launch_proj<false, false>(args, K_PROJ_BWD_Q, st);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+} // namespace lss

@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_E
 
 EXPORTS = ["lss_version", "lss_last_error", "lss_set_option", "lss_workspace_bytes", "lss_set_workspace",
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
-           "lss_segment_attn_bwd_f32", "lss_reduce_partials", "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
+           "lss_segment_attn_bwd_f32", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd", "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
            "lss_timing_read", "lss_timing_kernel_name"]
 
 
@@ -57,6 +57,10 @@ def load():
         getattr(lib, name).restype = ci
     lib.lss_reduce_partials.argtypes = [vp, ci, vp, i64, i64, i64, i64, vp, vp]
     lib.lss_reduce_partials.restype = ci
+    lib.lss_project_qkv.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, vp, vp, vp]
+    lib.lss_project_qkv.restype = ci
+    lib.lss_project_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, vp, vp]
+    lib.lss_project_bwd.restype = ci
     lib.lss_timing_enable.argtypes = [ci]
     lib.lss_timing_select.argtypes = [ctypes.c_uint]
     lib.lss_timing_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -194,6 +198,60 @@ def lss_reduce_partials(parts, rows_valid=None, out=None, stream=None):
         rv = (ctypes.c_int64 * len(parts))(*[int(x) for x in rows_valid])
     _check(load().lss_reduce_partials(arr, len(parts), rv, l_x, B, H, d, _ptr(out), _stream_ptr(stream)))
     return out
+
+
+def lss_project_qkv(x, w_q, w_kv, seg_offset, l_s, H, q_seg=None, k=None, v=None, stream=None):
+    """Q_i = x_i W_q, K = x W_k, V = x W_v.  x [B,l_x,E] bf16, w_q [E,E], w_kv [E,2E] = [W_k | W_v].
+
+    Returns (q_seg [B,l_s,H,d], k [B,l_x,H,d], v [B,l_x,H,d]) in bf16.
+    """
+    if x.dim() != 3 or x.dtype != torch.bfloat16:
+        raise ValueError("x must be bf16 [B, l_x, E]")
+    B, l_x, E = x.shape
+    if E % H:
+        raise ValueError("E must be a multiple of H")
+    d = E // H
+    if tuple(w_q.shape) != (E, E) or tuple(w_kv.shape) != (E, 2 * E):
+        raise ValueError("w_q must be [E, E] and w_kv [E, 2E]")
+    if q_seg is None:
+        q_seg = torch.empty((B, l_s, H, d), dtype=torch.bfloat16, device=x.device)
+    if k is None:
+        k = torch.empty((B, l_x, H, d), dtype=torch.bfloat16, device=x.device)
+    if v is None:
+        v = torch.empty((B, l_x, H, d), dtype=torch.bfloat16, device=x.device)
+    if tuple(q_seg.shape) != (B, l_s, H, d) or tuple(k.shape) != (B, l_x, H, d) or tuple(v.shape) != (B, l_x, H, d):
+        raise ValueError("output shapes disagree with x, l_s and H")
+    for t in (x, w_q, w_kv, q_seg, k, v):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != torch.bfloat16:
+            raise ValueError("tensors must be contiguous bf16 device tensors")
+    _check(load().lss_project_qkv(_ptr(x), _ptr(w_q), _ptr(w_kv), int(seg_offset), int(l_s), l_x, B, H, d,
+                                  _ptr(q_seg), _ptr(k), _ptr(v), _stream_ptr(stream)))
+    return q_seg, k, v
+
+
+def lss_project_bwd(dq, dk_partial, dv_partial, w_q, w_kv, rows_valid=None, dx_q=None, dx_partial=None, stream=None):
+    """dx_q = dQ_i W_q^T [B,l_s,E] and dx_partial = dK_part W_k^T + dV_part W_v^T [B,l_x,E], both float32."""
+    if dq.dim() != 4 or dk_partial.dim() != 4 or dk_partial.shape != dv_partial.shape:
+        raise ValueError("dq must be [B,l_s,H,d]; partials [B,l_x,H,d]")
+    B, l_s, H, d = dq.shape
+    l_x, E = dk_partial.shape[1], H * d
+    if tuple(dk_partial.shape) != (B, l_x, H, d) or tuple(w_q.shape) != (E, E) or tuple(w_kv.shape) != (E, 2 * E):
+        raise ValueError("shapes disagree")
+    if rows_valid is None:
+        rows_valid = l_x
+    if dx_q is None:
+        dx_q = torch.empty((B, l_s, E), dtype=torch.float32, device=dq.device)
+    if dx_partial is None:
+        dx_partial = torch.empty((B, l_x, E), dtype=torch.float32, device=dq.device)
+    if tuple(dx_q.shape) != (B, l_s, E) or tuple(dx_partial.shape) != (B, l_x, E):
+        raise ValueError("output shapes disagree")
+    for t, dt in ((dq, torch.bfloat16), (w_q, torch.bfloat16), (w_kv, torch.bfloat16), (dk_partial, torch.float32),
+                  (dv_partial, torch.float32), (dx_q, torch.float32), (dx_partial, torch.float32)):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != dt:
+            raise ValueError("tensors must be contiguous device tensors of the documented types")
+    _check(load().lss_project_bwd(_ptr(dq), _ptr(dk_partial), _ptr(dv_partial), _ptr(w_q), _ptr(w_kv), l_s, l_x,
+                                  int(rows_valid), B, H, d, _ptr(dx_q), _ptr(dx_partial), _stream_ptr(stream)))
+    return dx_q, dx_partial
 
 
 def lss_timing_enable(on: bool) -> None:

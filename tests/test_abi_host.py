@@ -101,3 +101,29 @@ def test_options(lib):
     assert lib.lss_set_option(1, 0) == 0        # ... and off again (process-wide state)
     assert lib.lss_set_option(77, 1) == -5      # unknown option
     assert b"option" in lib.lss_last_error()
+
+
+def test_projection_argument_checks(lib):
+    fwd, bwd = lib.lss_project_qkv, lib.lss_project_bwd
+
+    def f(x=0x1000, wq=0x2000, wkv=0x3000, s0=0, l_s=128, l_x=256, B=1, H=2, d=64, q=0x4000, k=0x5000, v=0x6000):
+        return fwd(x, wq, wkv, s0, l_s, l_x, B, H, d, q, k, v, None)
+
+    assert f(H=1) == -2 and b"multiple of 128" in lib.lss_last_error()     # E_m = 64
+    assert f(H=3) == -2                                                     # E_m = 192
+    assert f(d=32) == -3
+    assert f(s0=200) == -5
+    assert f(x=0) == -1 and f(wkv=0) == -1 and f(q=0) == -1
+    assert f(k=0x5008) == -4
+    assert f(B=0) == 0
+    assert f(l_s=0, q=0, B=0) == 0
+
+    def g(dq=0x1000, dk=0x2000, dv=0x3000, wq=0x4000, wkv=0x5000, l_s=128, l_x=256, rv=256, B=1, H=2, d=64,
+          dxq=0x6000, dxp=0x7000):
+        return bwd(dq, dk, dv, wq, wkv, l_s, l_x, rv, B, H, d, dxq, dxp, None)
+
+    assert g(H=1) == -2
+    assert g(rv=257) == -5 and g(rv=-1) == -5
+    assert g(dk=0) == -1 and g(dxp=0) == -1 and g(dq=0) == -1
+    assert g(dv=0x3004) == -4
+    assert g(B=0) == 0

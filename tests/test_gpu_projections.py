@@ -1,0 +1,126 @@
+"""GPU parity of the linear maps around the attention (fused-communication form, Section 3,
+Principle 3; Fig. 2(ii), (iii), (v)) against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_02382_amd import lss, synth
+from _util import TOL, Staged, rel_err, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def stage_proj(B, l_x, H, d, seed, std=1.0):
+    x, w_q, w_kv = synth.make_projection_inputs(B, l_x, H, d, seed, std)
+    return Staged(x, "bf16"), Staged(w_q, "bf16"), Staged(w_kv, "bf16")
+
+
+def assert_close_elementwise(got, ref, tag):
+    # one rounding to bf16 (2^-9 relative) of a sum accumulated in fp32
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    assert np.all(np.isfinite(got)), tag
+    bound = 2.0 ** -8 * np.abs(ref) + 1e-4 * np.abs(ref).max()
+    bad = np.abs(got - ref) > bound
+    assert not bad.any(), f"{tag}: {bad.sum()} elements off, worst {np.abs(got - ref).max()}"
+
+
+SHAPES = [  # B, l_x, H, d, s0, l_s
+    (1, 1024, 4, 64, 256, 256),     # the tiny workload's shape
+    (2, 1000, 2, 64, 437, 300),     # E_m = 128: one column tile; ragged rows, unaligned segment
+    (1, 700, 2, 128, 0, 700),       # head width 128; the segment is the whole sequence
+    (2, 2500, 8, 64, 2442, 58),     # E_m = 512: 20 row tiles and a tail; a skinny last segment
+    (3, 130, 2, 64, 1, 1),          # shorter than one tile; a one-row segment
+]
+
+
+@pytest.mark.parametrize("B,l_x,H,d,s0,l_s", SHAPES)
+def test_project_qkv_matches_oracle(B, l_x, H, d, s0, l_s):
+    X, WQ, WKV = stage_proj(B, l_x, H, d, 9100 + l_x)
+    q, k, v = lss.lss_project_qkv(X.dev, WQ.dev, WKV.dev, s0, l_s, H)
+    rq, rk, rv = oracle.project_qkv(X.f64, WQ.f64, WKV.f64, s0, l_s, H)
+    for name, got, ref in (("q", q, rq), ("k", k, rk), ("v", v, rv)):
+        assert rel_err(to_np(got), ref) <= TOL["bf16"]["t"], name
+        assert_close_elementwise(to_np(got), ref, f"{name} {B, l_x, H, d, s0, l_s}")
+
+
+@pytest.mark.parametrize("skip_tail", [False, True])
+@pytest.mark.parametrize("B,l_x,H,d,s0,l_s", SHAPES)
+def test_project_bwd_matches_oracle(B, l_x, H, d, s0, l_s, skip_tail):
+    _, WQ, WKV = stage_proj(B, l_x, H, d, 9200 + l_x)
+    E = H * d
+    n = B * l_x * E
+    dk = synth.normal_f32(9300, n).reshape(B, l_x, H, d)
+    dv = synth.normal_f32(9301, n).reshape(B, l_x, H, d)
+    DQ = Staged(synth.normal_f32(9302, B * l_s * E).reshape(B, l_s, H, d), "bf16")
+    rows_valid = s0 + l_s
+    dk[:, rows_valid:] = 0.0
+    dv[:, rows_valid:] = 0.0
+    rdxq, rdxp = oracle.project_bwd(DQ.f64, dk, dv, WQ.f64, WKV.f64)
+    # the device copies carry NaN where the library must not read
+    dk_dev, dv_dev = torch.from_numpy(dk).cuda(), torch.from_numpy(dv).cuda()
+    dk_dev[:, rows_valid:] = float("nan")
+    dv_dev[:, rows_valid:] = float("nan")
+    canary = -7.25
+    dxp = torch.full((B, l_x, E), canary, dtype=torch.float32, device="cuda")
+    lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, int(skip_tail))
+    try:
+        dxq, dxp = lss.lss_project_bwd(DQ.dev, dk_dev, dv_dev, WQ.dev, WKV.dev, rows_valid, dx_partial=dxp)
+    finally:
+        lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, 0)
+    assert rel_err(to_np(dxq), rdxq) <= TOL["bf16"]["t"]
+    got = to_np(dxp)
+    assert rel_err(got[:, :rows_valid], rdxp[:, :rows_valid]) <= TOL["bf16"]["t"]
+    first_skipped = -(-rows_valid // 256) * 256 if skip_tail else l_x     # whole 256-row tiles past the data
+    assert not np.any(got[:, rows_valid:min(first_skipped, l_x)])
+    assert np.all(got[:, first_skipped:] == canary)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_whole_chain_matches_oracle(causal):
+    # x -> (Q_i, K, V) -> E_i -> gradients -> dx, all segments of the tiny workload's shape, against
+    # the oracle's chain on the same x and weights.  Every stage's bf16 rounding (Q, K, V, E, dQ,
+    # the partials as operands) enters here, so the bound is twice the single-stage one.
+    B, l_x, H, d, N = 1, 1024, 4, 64, 4
+    l_s, E = l_x // N, H * d
+    X, WQ, WKV = stage_proj(B, l_x, H, d, 9400)
+    DO = Staged(synth.normal_f32(9401, B * l_x * E).reshape(B, l_x, H, d), "bf16")
+    parts, ref_parts = [], []
+    dx = torch.zeros((B, l_x, E), dtype=torch.float32, device="cuda")
+    ref_dx = np.zeros((B, l_x, E))
+    rows_valid = []
+    for s0 in range(0, l_x, l_s):
+        q, k, v = lss.lss_project_qkv(X.dev, WQ.dev, WKV.dev, s0, l_s, H)
+        out, lse = lss.lss_segment_attn_fwd(q, k, v, s0, causal)
+        do = DO.dev[:, s0:s0 + l_s].contiguous()
+        dq, dk, dv = lss.lss_segment_attn_bwd(q, k, v, s0, out, lse, do, causal)
+        rv = s0 + l_s if causal else l_x
+        dxq, dxp = lss.lss_project_bwd(dq, dk, dv, WQ.dev, WKV.dev, rv)
+        dx[:, s0:s0 + l_s] += dxq
+        parts.append(dxp); rows_valid.append(rv)
+        rq, rk, rvv = oracle.project_qkv(X.f64, WQ.f64, WKV.f64, s0, l_s, H)
+        rdq, rdk, rdv = oracle.segment_bwd(rq, rk, rvv, DO.f64[:, s0:s0 + l_s], s0, causal)
+        a, p = oracle.project_bwd(rdq, rdk, rdv, WQ.f64, WKV.f64)
+        ref_dx[:, s0:s0 + l_s] += a
+        ref_parts.append(p)
+    total = lss.lss_reduce_partials([p.view(B, l_x, 1, E) for p in parts], rows_valid).view(B, l_x, E)
+    dx += total
+    ref_dx += oracle.reduce_partials(ref_parts)
+    assert rel_err(to_np(total), oracle.reduce_partials(ref_parts)) <= 2 * TOL["bf16"]["t"]
+    assert rel_err(to_np(dx), ref_dx) <= 2 * TOL["bf16"]["t"]
+
+
+def test_projections_bitwise_reproducible_and_empty_segment():
+    B, l_x, H, d = 2, 600, 2, 64
+    X, WQ, WKV = stage_proj(B, l_x, H, d, 9500)
+    a = lss.lss_project_qkv(X.dev, WQ.dev, WKV.dev, 100, 200, H)
+    b = lss.lss_project_qkv(X.dev, WQ.dev, WKV.dev, 100, 200, H)
+    assert all(torch.equal(s, t) for s, t in zip(a, b))
+    # l_s = 0: K and V are still produced
+    q0, k0, v0 = lss.lss_project_qkv(X.dev, WQ.dev, WKV.dev, 600, 0, H)
+    assert q0.numel() == 0 and torch.equal(k0, a[1]) and torch.equal(v0, a[2])
+    # rows_valid = 0: nothing is read, everything is zero
+    nan = torch.full((B, l_x, H, d), float("nan"), dtype=torch.float32, device="cuda")
+    dq0 = torch.empty((B, 0, H, d), dtype=torch.bfloat16, device="cuda")
+    _, dxp = lss.lss_project_bwd(dq0, nan, nan, WQ.dev, WKV.dev, 0)
+    assert torch.count_nonzero(dxp) == 0
