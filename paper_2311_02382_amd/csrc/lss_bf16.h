@@ -30,28 +30,31 @@ __device__ __forceinline__ void lds_dma(const void *g_uniform, uint32_t voff, co
                      : "=&s"(saved) : "s"(lds_addr), "v"(voff), "s"(g_uniform) : "memory");
 }
 
-// [ROWS][D] bf16 tile loaded global -> LDS directly (no registers in between), by 4 wavefronts.
+// [ROWS][D] bf16 tile loaded global -> LDS directly (no registers in between), by WAVES wavefronts.
 // One such load instruction moves 16 bytes per lane and writes the wavefront's 64 chunks back to
 // back (1 KB), so rows cannot be padded; instead the 16-byte chunk c of row r sits at chunk
 // position c ^ (r & 7) of its row, which spreads a column of chunks over the LDS banks as padding
 // would.  The permutation is applied on the global side: the lane that fills position p of row r
 // fetches chunk p ^ (r & 7).
-template <int D, int ROWS>
+template <int D, int ROWS, int WAVES = 4>
 struct DirectTile {
     static constexpr int CPR = D / 8;                 // 16-byte chunks per row
     static constexpr int RPI = 64 / CPR;              // rows per load instruction of one wavefront
-    static constexpr int NI = ROWS / RPI / 4;         // load instructions per wavefront
+    static constexpr int NI = ROWS / RPI / WAVES;     // load instructions per wavefront
     static constexpr int BYTES = ROWS * D * 2;
-    static_assert(ROWS % (RPI * 4) == 0, "tile must divide among 4 wavefronts");
+    static_assert(ROWS % (RPI * WAVES) == 0, "tile must divide among the wavefronts");
 
     // global byte offsets (from the tile's first row) of this lane's chunks; rows >= rows_ok
-    // re-read row rows_ok - 1 (the kernels mask what such rows produce).  Needs ROWS * row_stride * 2 < 2^32.
-    static __device__ __forceinline__ void offsets(uint32_t (&off)[NI], int64_t row_stride, int rows_ok, int wave, int lane)
+    // re-read row rows_ok - 1 and chunks >= chunks_ok re-read chunk chunks_ok - 1 (the kernels mask
+    // or discard what such rows and columns produce).  Load instruction i of wavefront `wave` fills
+    // the 1 KB at byte (i * WAVES + wave) * 1024 of the tile.  Needs ROWS * row_stride * 2 < 2^32.
+    static __device__ __forceinline__ void offsets(uint32_t (&off)[NI], int64_t row_stride, int rows_ok, int wave, int lane,
+                                                   int chunks_ok = CPR)
     {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const int row = (i * 4 + wave) * RPI + lane / CPR, pos = lane % CPR;
-            const int chunk = (pos & ~7) | ((pos ^ row) & 7);
+            const int row = (i * WAVES + wave) * RPI + lane / CPR, pos = lane % CPR;
+            const int chunk = min((pos & ~7) | ((pos ^ row) & 7), chunks_ok - 1);
             off[i] = ((uint32_t)min(row, rows_ok - 1) * (uint32_t)row_stride + (uint32_t)chunk * 8u) * 2u;
         }
     }
@@ -62,7 +65,7 @@ struct DirectTile {
     static __device__ __forceinline__ void issue_pair(const bf16_t *g0_uniform, const bf16_t *g1_uniform,
                                                       const uint32_t (&off)[NI], char *lds_tile, int wave)
     {
-        static_assert(NI == 2 || NI == 4, "");
+        static_assert((NI == 2 || NI == 4) && WAVES == 4, "");
         const uint32_t lds_addr = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)(lds_tile + wave * 1024);
         uint32_t saved;
         if constexpr (NI == 2) {

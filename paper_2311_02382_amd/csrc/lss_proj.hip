@@ -5,12 +5,15 @@
 // dx_partial is what the segment sum (the reduce-scatter's arithmetic) then adds over segments.
 //
 // One kernel template computes C[m, n] = sum_k A[m, k] W'[k, n] for a short list of jobs.  A
-// workgroup owns a 256 (m) x 128 (n) tile of C, held transposed in the accumulators (lane = row m
-// of A, as the attention kernels hold one query per lane): C^T += W'^T A^T, so the weights are the
-// A operand of the matrix instruction and the activations its B operand.  Each of the four
-// wavefronts owns 128 (m) x 64 (n): 4 x 2 accumulator tiles, 8 matrix instructions per 6 operand
-// fragments.  The contraction runs in tiles of 64 through a ring of three LDS slots, loaded
-// global -> LDS directly two tiles ahead, one barrier per tile.
+// workgroup of eight wavefronts owns a 256 (m) x 256 (n) tile of C, held transposed in the
+// accumulators (lane = row m of A, as the attention kernels hold one query per lane):
+// C^T += W'^T A^T, so the weights are the A operand of the matrix instruction and the activations
+// its B operand.  Each wavefront owns 128 (m) x 64 (n): 4 x 2 accumulator tiles, 8 matrix
+// instructions per 6 operand fragments; two wavefronts share a SIMD, so one's LDS reads and barrier
+// waits hide behind the other's matrix instructions.  The contraction runs in tiles of 64 through
+// two LDS slots (64 KB each), the next tile loaded global -> LDS directly while the current one is
+// multiplied; one barrier per tile.  The finished tile goes through LDS once more so that it is
+// written to memory as whole rows.
 //   W_TR   weights stored [k][n] (forward: W as given).  Their fragments come from the LDS tile
 //          by transposing reads; otherwise the weights are stored [n][k] (backward: W as given
 //          IS W'^T) and are read plainly.
@@ -26,10 +29,10 @@ namespace lss {
 
 namespace {
 
-constexpr int PM = 256, PN = 128, PK = 64;      // workgroup tile, contraction tile
-constexpr int P_RING = 3;
+constexpr int PM = 256, PN = 256, PK = 64;      // workgroup tile, contraction tile
+constexpr int P_WAVES = 8, P_NT = 64 * P_WAVES;
 constexpr int P_ABYTES = PM * PK * 2, P_WBYTES = PN * PK * 2, P_SLOT = P_ABYTES + P_WBYTES;
-constexpr int P_LDS = P_RING * P_SLOT;          // 144 KB: one workgroup per compute unit
+constexpr int P_LDS = 2 * P_SLOT;               // 128 KB: one workgroup per compute unit
 
 struct ProjJob {
     const void *a0, *a1;        // A: [batches][rows][lda]; a1 serves contraction indices >= k_split (or is unused)
@@ -45,15 +48,55 @@ struct ProjArgs {
     int n_jobs, lda, ldc, skip_tail;
 };
 
-using ATile = DirectTile<PK, PM>;               // activations [256 m][64 k]
-using WTileTr = DirectTile<PN, PK>;             // weights [64 k][128 n]
-using WTile = DirectTile<PK, PN>;               // weights [128 n][64 k]
+using ATile = DirectTile<PK, PM, P_WAVES>;      // activations [256 m][64 k]
+using WTile = DirectTile<PK, PN, P_WAVES>;      // weights [256 n][64 k]
+
+// Weights [64 k][256 n], read transposed.  Loaded directly like a DirectTile, but its 512-byte rows
+// all start at the same LDS bank, so the 16-byte chunk c of row r sits at chunk position
+// c ^ 4 (r % 4): the eight rows that one transposing read touches (64 bytes of each) then spread
+// evenly over the banks.
+struct WTileTr {
+    static constexpr int NI = PK * (PN / 8) / 64 / P_WAVES;     // load instructions per wavefront (2 rows each)
+    // chunks >= chunks_ok (columns past the matrix) re-read chunk chunks_ok - 1; chunks_ok is a multiple of 8
+    static __device__ __forceinline__ void offsets(uint32_t (&off)[NI], int ldw, int wave, int lane, int chunks_ok)
+    {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int row = (i * P_WAVES + wave) * 2 + lane / 32, pos = lane % 32;
+            const int chunk = min(pos ^ (4 * (row & 3)), chunks_ok - 1);
+            off[i] = ((uint32_t)row * (uint32_t)ldw + (uint32_t)chunk * 8u) * 2u;
+        }
+    }
+    // Transposing reads (see load_frag_tr_sw for the instruction's lane mapping): within its group
+    // of 16 lanes, lane s addresses row 8 hh + s / 4 and the 8-byte piece s % 4 of the 32-byte
+    // column group nh of column block db (hh, nh: bits 1 and 0 of the group index).
+    static __device__ __forceinline__ int lane_offset(int lane, int db)
+    {
+        const int grp = lane >> 4, hh = grp >> 1, nh = grp & 1, s = lane & 15;
+        const int row = 8 * hh + (s >> 2), chunk = 4 * db + 2 * nh + ((s & 3) >> 1);
+        return row * (PN * 2) + ((chunk ^ (4 * (row & 3))) * 16) + (s & 1) * 8;
+    }
+    // A-operand fragment of the transposed tile for contraction step ks: operand row = column
+    // (lane % 32) of block db, slot e = contraction index 16 ks + 8 hh + e -- the order in which a
+    // plain 16-byte read delivers the other operand.
+    static __device__ __forceinline__ Frag<bf16_t> load_frag(const char *tile, int ks, int lane_off)
+    {
+        const char *p = tile + ks * 16 * (PN * 2) + lane_off;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * (PN * 2)));
+        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        Frag<bf16_t> f;
+        f.v = __builtin_bit_cast(bf16x8, both);
+        return f;
+    }
+};
 
 template <bool A_F32, bool W_TR>
-__global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs args)
+__global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     using OutT = typename std::conditional<A_F32 || !W_TR, float, bf16_t>::type;     // backward maps write float
+    constexpr bool OUT_F32 = std::is_same<OutT, float>::value;
 
     const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -74,33 +117,58 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs args)
 
     const int rows_here = min(J.rows - m0, PM);                     // rows of C this tile owns
     const int rows_data = min(min(J.rows, J.rows_ok) - m0, PM);     // of which this many have data in A
+    const int cols_here = min(J.N - n0, PN);                        // a multiple of 64
 
-    // ---- output addressing.  Accumulator tile (mb, nb), element v of this lane: row
-    // m = 128 wm + 32 mb + lq, columns n = 64 wn + 32 nb + 8 (v / 4) + 4 hh + (v % 4).
-    OutT *cbase;
-    {
-        const bool second = n0 >= J.n_split;
-        OutT *c = static_cast<OutT *>(second ? J.c1 : J.c0);
-        cbase = c + (int64_t)batch * J.c_batch_stride + (int64_t)m0 * args.ldc + (n0 - (second ? J.n_split : 0));
-    }
-    auto store_tiles = [&](const f32x16 (&acc)[4][2]) {
+    // ---- the finished tile -> memory, through LDS so that whole rows are written: a pass covers
+    // 16-byte chunks [0, 32) of every row (bf16: all 256 columns, one pass; float: 128 columns, two
+    // passes); chunk c of row m sits at chunk position c ^ (m % 32) of the row's 512 bytes.
+    // Accumulator tile (mb, nb), element v of this lane: row m = 128 wm + 32 mb + lq, columns
+    // n = 64 wn + 32 nb + 8 (v / 4) + 4 hh + (v % 4).
+    constexpr int CW = OUT_F32 ? 4 : 8;         // columns per 16-byte chunk
+    constexpr int PASSES = OUT_F32 ? 2 : 1;
+    auto store_tiles = [&](const f32x16 (&acc)[4][2], bool from_acc) {
+        OutT *c0 = static_cast<OutT *>(J.c0) + (int64_t)batch * J.c_batch_stride + (int64_t)m0 * args.ldc;
+        OutT *c1 = static_cast<OutT *>(J.c1) + (int64_t)batch * J.c_batch_stride + (int64_t)m0 * args.ldc;
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-            const int m = 128 * wm + 32 * mb + lq;
-            if (m >= rows_here) continue;
-            const bool data = m < rows_data;
-            OutT *row = cbase + (int64_t)m * args.ldc + 64 * wn + 4 * hh;
+        for (int pass = 0; pass < PASSES; ++pass) {
+            if (from_acc) {
+                __syncthreads();        // every wavefront is done with what the LDS held
+                if (!OUT_F32 || (wn >> 1) == pass) {
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
+                    for (int mb = 0; mb < 4; ++mb) {
+                        const int m = 128 * wm + 32 * mb + lq;
+                        const bool data = m < rows_data;
+                        char *row = smem + m * 512;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    f32x4 val = {0.f, 0.f, 0.f, 0.f};
-                    if (data) val = f32x4{acc[mb][nb][4 * g], acc[mb][nb][4 * g + 1], acc[mb][nb][4 * g + 2], acc[mb][nb][4 * g + 3]};
-                    if constexpr (std::is_same<OutT, float>::value)
-                        *reinterpret_cast<f32x4 *>(row + 32 * nb + 8 * g) = val;
-                    else
-                        *reinterpret_cast<bf16x4 *>(row + 32 * nb + 8 * g) = pack4(val[0], val[1], val[2], val[3]);
+                        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) {
+                                f32x4 val = {0.f, 0.f, 0.f, 0.f};
+                                if (data) val = f32x4{acc[mb][nb][4 * g], acc[mb][nb][4 * g + 1], acc[mb][nb][4 * g + 2], acc[mb][nb][4 * g + 3]};
+                                if constexpr (OUT_F32) {
+                                    const int c = 16 * (wn & 1) + 8 * nb + 2 * g + hh;
+                                    *reinterpret_cast<f32x4 *>(row + ((c ^ (m & 31)) * 16)) = val;
+                                } else {
+                                    const int c = 8 * wn + 4 * nb + g;
+                                    *reinterpret_cast<bf16x4 *>(row + ((c ^ (m & 31)) * 16) + hh * 8) = pack4(val[0], val[1], val[2], val[3]);
+                                }
+                            }
+                    }
                 }
+                __syncthreads();
+            }
+            // thread tid: chunk tid % 32 of rows tid / 32, + 16, ...
+            const int c = tid & 31;
+            const int n = n0 + pass * 128 + c * CW;         // column of C; a chunk never straddles n_split
+            const bool col_ok = pass * 128 + c * CW < cols_here;
+            OutT *dst = n < J.n_split ? c0 + n : c1 + (n - J.n_split);
+#pragma unroll
+            for (int i = 0; i < PM / 16; ++i) {
+                const int m = i * 16 + (tid >> 5);
+                f32x4 raw = {0.f, 0.f, 0.f, 0.f};
+                if (from_acc) raw = *reinterpret_cast<const f32x4 *>(smem + m * 512 + ((c ^ (m & 31)) * 16));
+                if (col_ok && m < rows_here) *reinterpret_cast<f32x4 *>(dst + (int64_t)m * args.ldc) = raw;
+            }
         }
     };
 
@@ -112,7 +180,7 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs args)
         for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = zero16;
 
     if (rows_data <= 0) {       // no row of this tile has data: its rows of C are zero
-        if (!args.skip_tail) store_tiles(acc);
+        if (!args.skip_tail) store_tiles(acc, false);
         return;
     }
 
@@ -122,8 +190,8 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs args)
     // ---- tile loads
     uint32_t offA[ATile::NI], offW[W_TR ? WTileTr::NI : WTile::NI];
     if constexpr (!A_F32) ATile::offsets(offA, args.lda, rows_data, wave, lane);
-    if constexpr (W_TR) WTileTr::offsets(offW, J.ldw, PK, wave, lane);
-    else WTile::offsets(offW, J.ldw, PN, wave, lane);
+    if constexpr (W_TR) WTileTr::offsets(offW, J.ldw, wave, lane, cols_here / 8);
+    else WTile::offsets(offW, J.ldw, cols_here, wave, lane);
 
     const char *a0 = static_cast<const char *>(J.a0), *a1 = static_cast<const char *>(J.a1);
     constexpr int AE = A_F32 ? 4 : 2;           // bytes per element of A
@@ -135,26 +203,27 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs args)
         char *dst = smem + slot * P_SLOT + P_ABYTES;
         const bf16_t *src = W_TR ? J.w + (int64_t)t * PK * J.ldw + n0 : J.w + (int64_t)n0 * J.ldw + (int64_t)t * PK;
 #pragma unroll
-        for (int i = 0; i < (W_TR ? WTileTr::NI : WTile::NI); ++i) lds_dma<16>(src, offW[i], dst + (i * 4 + wave) * 1024);
+        for (int i = 0; i < (W_TR ? WTileTr::NI : WTile::NI); ++i) lds_dma<16>(src, offW[i], dst + (i * P_WAVES + wave) * 1024);
     };
     auto issue_a = [&](int t, int slot) {       // bf16 A: direct
         char *dst = smem + slot * P_SLOT;
         const char *src = a_src(t);
 #pragma unroll
-        for (int i = 0; i < ATile::NI; ++i) lds_dma<16>(src, offA[i], dst + (i * 4 + wave) * 1024);
+        for (int i = 0; i < ATile::NI; ++i) lds_dma<16>(src, offA[i], dst + (i * P_WAVES + wave) * 1024);
     };
-    // float A: thread `tid` converts the 8-element chunks tid, tid + 256, ... of the tile
+    // float A: thread `tid` converts the 8-element chunks tid, tid + 512, ... of the tile
     // (chunk c is columns 8 (c % 8) .. + 7 of row c / 8) and writes them where the direct load would
-    f32x4 stage[A_F32 ? 16 : 1];
+    constexpr int FCH = PM * 8 / P_NT;          // chunks per thread
+    f32x4 stage[A_F32 ? 2 * FCH : 1];
     auto fetch_a = [&](int t) {
         if constexpr (A_F32) {
             const char *src = a_src(t);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int c = i * 256 + tid, row = min(c >> 3, rows_data - 1);
+            for (int i = 0; i < FCH; ++i) {
+                const int c = i * P_NT + tid, row = min(c >> 3, rows_data - 1);
                 const f32x4 *p = reinterpret_cast<const f32x4 *>(src + ((int64_t)row * args.lda + (c & 7) * 8) * 4);
-                stage[2 * i] = __builtin_nontemporal_load(p);
-                stage[2 * i + 1] = __builtin_nontemporal_load(p + 1);
+                stage[2 * i] = p[0];       // (re-read from L2 by the workgroups of the other column tiles)
+                stage[2 * i + 1] = p[1];
             }
         }
     };
@@ -162,8 +231,8 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs args)
         if constexpr (A_F32) {
             char *dst = smem + slot * P_SLOT;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int c = i * 256 + tid;
+            for (int i = 0; i < FCH; ++i) {
+                const int c = i * P_NT + tid;
                 bf16x8 v;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) { v[e] = (bf16_t)stage[2 * i][e]; v[4 + e] = (bf16_t)stage[2 * i + 1][e]; }
@@ -171,25 +240,22 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs args)
             }
         }
     };
-    constexpr int LOADS_PER_TILE = ATile::NI + (W_TR ? WTileTr::NI : WTile::NI);    // direct loads of one wavefront
 
-    // ---- per-lane LDS offsets of the operand fragments of contraction step ks (16 indices)
-    // B operand, row m of A: with plain weights slot e carries index 8 hh + e (one 16-byte read);
-    // with transposed weight reads slot 4 a + t carries index 8 a + 4 hh + t (two 8-byte reads),
-    // the order load_frag_tr_sw delivers.
+    // ---- per-lane LDS offsets of the operand fragments of contraction step ks (16 indices): slot e
+    // of a fragment carries index 16 ks + 8 hh + e
     int b_off[4][4];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const int m = 128 * wm + 32 * mb + lq;
-            b_off[mb][ks] = W_TR ? ATile::chunk_offset(m, 2 * ks) + hh * 8 : ATile::chunk_offset(m, 2 * ks + hh);
+            b_off[mb][ks] = ATile::chunk_offset(m, 2 * ks + hh);
         }
     int w_off[2][4];            // plain weights: row n = 64 wn + 32 nb + lq, chunk 2 ks + hh
     int wt_off[2];              // transposed reads: column block 2 wn + nb
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-        wt_off[nb] = tr_lane_offset_sw<PN>(lane, 2 * wn + nb);
+        wt_off[nb] = WTileTr::lane_offset(lane, 2 * wn + nb);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) w_off[nb][ks] = WTile::chunk_offset(64 * wn + 32 * nb + lq, 2 * ks + hh);
     }
@@ -200,20 +266,11 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs args)
             Frag<bf16_t> fb[4], fw[2];
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
-                if constexpr (W_TR) fw[nb] = load_frag_tr_sw<PN>(wt, ks * 16, wt_off[nb]);
+                if constexpr (W_TR) fw[nb] = WTileTr::load_frag(wt, ks, wt_off[nb]);
                 else fw[nb] = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(wt + w_off[nb][ks]));
             }
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb) {
-                if constexpr (W_TR) {
-                    const bf16x4 lo = *reinterpret_cast<const bf16x4 *>(at + b_off[mb][ks]);
-                    // the chunk after 2 ks of the same row: the swizzle flips bit 0 of the chunk position
-                    const bf16x4 hi = *reinterpret_cast<const bf16x4 *>(at + (b_off[mb][ks] ^ 16));
-                    fb[mb].v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                } else {
-                    fb[mb] = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(at + b_off[mb][ks]));
-                }
-            }
+            for (int mb = 0; mb < 4; ++mb) fb[mb] = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(at + b_off[mb][ks]));
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -221,39 +278,37 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs args)
         }
     };
 
-    // ---- main loop: tile t is computed from slot t % 3 while tiles t + 1 and t + 2 are on their way
+    // ---- main loop: tile t is multiplied from slot t % 2 while tile t + 1 travels into the other slot
+    // (last read during tile t - 1, which every wavefront left at the barrier)
     if constexpr (A_F32) {
         fetch_a(0);
         issue_w(0, 0);
-        if (T > 1) issue_w(1, 1);
         stash_a(0);
         if (T > 1) fetch_a(1);
-        wait_vmem_all();        // the weights of tiles 0 and 1 (and the rows just fetched) have arrived
+        wait_vmem_all();
         __syncthreads();
         for (int t = 0; t < T; ++t) {
-            if (t + 2 < T) issue_w(t + 2, (t + 2) % P_RING);
-            compute(t % P_RING);
-            if (t + 1 < T) stash_a((t + 1) % P_RING);   // slot last read during tile t - 2
+            const int slot = t & 1;
+            if (t + 1 < T) issue_w(t + 1, slot ^ 1);
+            compute(slot);
+            if (t + 1 < T) stash_a(slot ^ 1);
             wait_vmem_all();
-            if (t + 2 < T) fetch_a(t + 2);              // in flight across the barrier, used after tile t + 1
+            if (t + 2 < T) fetch_a(t + 2);      // in flight across the barrier, stashed after tile t + 1
             __syncthreads();
         }
     } else {
         issue_a(0, 0); issue_w(0, 0);
-        if (T > 1) { issue_a(1, 1); issue_w(1, 1); }
-        if (T > 1) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS_PER_TILE); else wait_vmem_all();
+        wait_vmem_all();
         __syncthreads();
         for (int t = 0; t < T; ++t) {
-            if (t + 2 < T) {    // its slot was last read during tile t - 1, which every wavefront has left
-                issue_a(t + 2, (t + 2) % P_RING); issue_w(t + 2, (t + 2) % P_RING);
-            }
-            compute(t % P_RING);
-            if (t + 2 < T) __builtin_amdgcn_s_waitcnt(0x0F70 | LOADS_PER_TILE);     // all but tile t + 2: tile t + 1 is in
-            else wait_vmem_all();
+            const int slot = t & 1;
+            if (t + 1 < T) { issue_a(t + 1, slot ^ 1); issue_w(t + 1, slot ^ 1); }
+            compute(slot);
+            wait_vmem_all();
             __syncthreads();
         }
     }
-    store_tiles(acc);
+    store_tiles(acc, true);
 }
 
 template <bool A_F32, bool W_TR>
@@ -263,7 +318,7 @@ hipError_t launch_proj(ProjArgs &args, int kernel_id, hipStream_t st)
     for (int j = 0; j < args.n_jobs; ++j) {
         ProjJob &J = args.job[j];
         J.m_tiles = (J.rows + PM - 1) / PM;
-        J.n_tiles = J.N / PN;
+        J.n_tiles = (J.N + PN - 1) / PN;
         J.wg_begin = wgs;
         wgs += xcd_grid(J.batches * J.m_tiles, J.n_tiles);
     }
@@ -276,7 +331,7 @@ hipError_t launch_proj(ProjArgs &args, int kernel_id, hipStream_t st)
     });
     if (attr != hipSuccess) return attr;
     TimedLaunch tl(kernel_id, st);
-    hipLaunchKernelGGL((proj_gemm_kernel<A_F32, W_TR>), dim3(wgs), dim3(256), P_LDS, st, args);
+    hipLaunchKernelGGL((proj_gemm_kernel<A_F32, W_TR>), dim3(wgs), dim3(P_NT), P_LDS, st, args);
     return hipGetLastError();
 }
 
