@@ -6,7 +6,12 @@ segments of the sequence, forward then backward (Eq. 2 of Section 3 and its grad
 followed by the segment sum of the dK and dV partials (the arithmetic of the
 reduce-scatter of Fig. 2(v)).  Inputs are resident in HBM before the timed region.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lx8k]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lx8k] [--projections]
+
+With --projections every segment also runs the linear maps either side of the attention in
+the fused-communication form (Q_i, K, V from x before the forward; dx_q and dx_partial after
+the backward; Fig. 2(ii), (v)), the segment sum then runs on the dx partials, and `value`
+counts the projections' flops as well: a second workload, not the headline one.
 
 Prints ONE JSON line.  `value` is the strict-count rate: 12*d flops per unmasked
 (query, key) pair and head (six matrix products: S, PV, dV, dP, dQ, dK), recomputation not
@@ -57,6 +62,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="lx8k")
+    ap.add_argument("--projections", action="store_true",
+                    help="also run the Q/K/V projections and their backward around every segment")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device-to-device copy of this many MiB "
@@ -92,27 +99,50 @@ def main() -> int:
     (qd, qb), (kd, kb), (vd, vb), (dod, dob) = map(stage, (q, k, v, do))
     del q, k, v, do
     offs, l_s = w.offsets(), w.l_s
+    E = w.H * w.d
     q_seg = [qd[:, s0:s0 + l_s].contiguous() for s0 in offs]
     do_seg = [dod[:, s0:s0 + l_s].contiguous() for s0 in offs]
     out = [torch.empty_like(t) for t in q_seg]
     dq = [torch.empty_like(t) for t in q_seg]
     lse = [torch.empty((w.B, w.H, l_s), dtype=torch.float32, device=dev) for _ in offs]
-    dk_part = [torch.empty(kd.shape, dtype=torch.float32, device=dev) for _ in offs]
-    dv_part = [torch.empty(kd.shape, dtype=torch.float32, device=dev) for _ in offs]
-    dK = torch.empty(kd.shape, dtype=torch.float32, device=dev)
-    dV = torch.empty(kd.shape, dtype=torch.float32, device=dev)
     rows_valid = [s0 + l_s if w.causal else w.l_x for s0 in offs]
+    if args.projections:
+        # Q, K and V are produced from x inside the step; the dK/dV partials of a segment are
+        # consumed at once by the backward projection, so one pair of buffers serves all segments
+        (xd, xb), (wqd, wqb), (wkvd, wkvb) = map(stage, synth.make_projection_inputs(w.B, w.l_x, w.H, w.d, w.seed, w.qkv_std))
+        dk_one = torch.empty(kd.shape, dtype=torch.float32, device=dev)
+        dv_one = torch.empty(kd.shape, dtype=torch.float32, device=dev)
+        dx_q = [torch.empty((w.B, l_s, E), dtype=torch.float32, device=dev) for _ in offs]
+        dx_part = [torch.empty((w.B, w.l_x, 1, E), dtype=torch.float32, device=dev) for _ in offs]
+        dX = torch.empty((w.B, w.l_x, 1, E), dtype=torch.float32, device=dev)
+    else:
+        dk_part = [torch.empty(kd.shape, dtype=torch.float32, device=dev) for _ in offs]
+        dv_part = [torch.empty(kd.shape, dtype=torch.float32, device=dev) for _ in offs]
+        dK = torch.empty(kd.shape, dtype=torch.float32, device=dev)
+        dV = torch.empty(kd.shape, dtype=torch.float32, device=dev)
     # the partials' only consumer here is the segment sum, which is told how many rows of each are
     # valid: key tiles no query of a segment sees need not be filled with zeros
     lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, 1)
 
-    def step():
+    def step_attention():
         for i, s0 in enumerate(offs):
             lss.lss_segment_attn_fwd(q_seg[i], kd, vd, s0, w.causal, out=out[i], lse=lse[i])
             lss.lss_segment_attn_bwd(q_seg[i], kd, vd, s0, out[i], lse[i], do_seg[i], w.causal,
                                      dq=dq[i], dk_partial=dk_part[i], dv_partial=dv_part[i])
         lss.lss_reduce_partials(dk_part, rows_valid, out=dK)
         lss.lss_reduce_partials(dv_part, rows_valid, out=dV)
+
+    def step_with_projections():
+        for i, s0 in enumerate(offs):     # every segment projects K and V itself, as every GPU would
+            lss.lss_project_qkv(xd, wqd, wkvd, s0, l_s, w.H, q_seg=q_seg[i], k=kd, v=vd)
+            lss.lss_segment_attn_fwd(q_seg[i], kd, vd, s0, w.causal, out=out[i], lse=lse[i])
+            lss.lss_segment_attn_bwd(q_seg[i], kd, vd, s0, out[i], lse[i], do_seg[i], w.causal,
+                                     dq=dq[i], dk_partial=dk_one, dv_partial=dv_one)
+            lss.lss_project_bwd(dq[i], dk_one, dv_one, wqd, wkvd, rows_valid[i], dx_q=dx_q[i],
+                                dx_partial=dx_part[i].view(w.B, w.l_x, E))
+        lss.lss_reduce_partials(dx_part, rows_valid, out=dX)
+
+    step = step_with_projections if args.projections else step_attention
 
     for _ in range(args.warmup):
         step()
@@ -172,7 +202,12 @@ def main() -> int:
     pairs = w.pairs()                       # unmasked (query, key) pairs x B x H, whole sequence
     flops_strict = 12.0 * pairs * w.d
     flops_fa = 14.0 * pairs * w.d
-    value = flops_strict / (ms_per_step * 1e-3) / 1e12
+    # projections: 2 flops per multiply-add of Q_i, K, V and of dx_q, dx_partial (rows that hold data)
+    proj_flops = {"proj_fwd_kernel": sum(2.0 * w.B * E * (2 * E * w.l_x + E * l_s) for _ in offs),
+                  "proj_bwd_kernel": sum(2.0 * w.B * E * 2 * E * rv for rv in rows_valid),
+                  "proj_bwd_q_kernel": sum(2.0 * w.B * E * E * l_s for _ in offs)}
+    flops_proj = sum(proj_flops.values()) if args.projections else 0.0
+    value = (flops_strict + flops_proj) / (ms_per_step * 1e-3) / 1e12
 
     kernels, roofline = {}, None
     if timing:
@@ -192,12 +227,14 @@ def main() -> int:
         for name, kk in kernels.items():
             if name in ALGO_PRODUCTS:
                 kk["algorithmic_tflops"] = round(ALGO_PRODUCTS[name] * 2.0 * w.d * pairs / (kk["ms_per_step"] * 1e-3) / 1e12, 2)
+            if name in proj_flops:
+                kk["algorithmic_tflops"] = round(proj_flops[name] / (kk["ms_per_step"] * 1e-3) / 1e12, 2)
             kk["avg_us"] = round(kk["avg_us"], 2)
             kk["ms_per_step"] = round(kk["ms_per_step"], 4)
         if "reduce_partials_kernel" in kernels:
             # algorithmic bytes of the segment sum: valid rows of every part read once, l_x rows written
             row_bytes = w.B * w.H * w.d * 4
-            byts = 2 * (sum(rows_valid) + w.l_x) * row_bytes
+            byts = (1 if args.projections else 2) * (sum(rows_valid) + w.l_x) * row_bytes
             kernels["reduce_partials_kernel"]["algorithmic_GBps"] = round(
                 byts / (kernels["reduce_partials_kernel"]["ms_per_step"] * 1e-3) / 1e9, 1)
 
@@ -206,17 +243,24 @@ def main() -> int:
         import oracle
         sample = list(range(w.N)) if w.pairs() * w.d < 4e10 else sorted({w.N // 2 - 1, w.N - 1})
         kh, vh = synth.bf16_bits_to_f64(kb).reshape(kb.shape), synth.bf16_bits_to_f64(vb).reshape(vb.shape)
-        t_cpu, p_cpu = 0.0, 0
+        if args.projections:
+            xh, wqh, wkvh = (synth.bf16_bits_to_f64(b_).reshape(b_.shape) for b_ in (xb, wqb, wkvb))
+        t_cpu, p_cpu, f_cpu = 0.0, 0, 0.0
         for i in sample:
             s0 = offs[i]
             qh = synth.bf16_bits_to_f64(qb[:, s0:s0 + l_s]).reshape(w.B, l_s, w.H, w.d)
             doh = synth.bf16_bits_to_f64(dob[:, s0:s0 + l_s]).reshape(w.B, l_s, w.H, w.d)
             t = time.perf_counter()
+            if args.projections:
+                qh, kh, vh = oracle.project_qkv(xh, wqh, wkvh, s0, l_s, w.H)
             oracle.segment_fwd(qh, kh, vh, s0, w.causal)
-            oracle.segment_bwd(qh, kh, vh, doh, s0, w.causal)
+            g_ = oracle.segment_bwd(qh, kh, vh, doh, s0, w.causal)
+            if args.projections:
+                oracle.project_bwd(g_[0], g_[1], g_[2], wqh, wkvh)
+                f_cpu += 2.0 * w.B * E * (2 * E * w.l_x + E * l_s) + 2.0 * w.B * E * (2 * E * rows_valid[i] + E * l_s)
             t_cpu += time.perf_counter() - t
             p_cpu += w.segment_pairs(i)
-        cpu_baseline = {"value": round(12.0 * p_cpu * w.d / t_cpu / 1e12, 6), "unit": "TFLOP/s",
+        cpu_baseline = {"value": round((12.0 * p_cpu * w.d + f_cpu) / t_cpu / 1e12, 6), "unit": "TFLOP/s",
                         "cores": oracle.threads(), "kind": "oracle",
                         "sample": f"segments {sample} of {w.N} (fwd+bwd, all batches and heads), "
                                   f"{t_cpu:.1f} s of fp64 CPU work, same strict flop count"}
@@ -226,8 +270,10 @@ def main() -> int:
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "B": w.B, "l_x": w.l_x, "N": w.N, "l_s": l_s, "H": w.H, "d": w.d,
-                   "causal": w.causal, "step": "fwd+bwd of all N segments, then segment sum of dK and dV"},
+        "config": {"workload": w.name + ("+projections" if args.projections else ""), "B": w.B, "l_x": w.l_x,
+                   "N": w.N, "l_s": l_s, "H": w.H, "d": w.d, "causal": w.causal,
+                   "step": ("per segment: Q_i, K, V from x, fwd, bwd, dx_q and dx_partial; then segment sum of dx"
+                            if args.projections else "fwd+bwd of all N segments, then segment sum of dK and dV")},
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "tflops_with_recompute_count_14Pd": round(flops_fa / (ms_per_step * 1e-3) / 1e12, 2),
         "gpu_ms_per_step_events": round(gpu_ms / args.steps, 4),

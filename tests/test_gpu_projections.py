@@ -124,3 +124,47 @@ def test_projections_bitwise_reproducible_and_empty_segment():
     dq0 = torch.empty((B, 0, H, d), dtype=torch.bfloat16, device="cuda")
     _, dxp = lss.lss_project_bwd(dq0, nan, nan, WQ.dev, WKV.dev, 0)
     assert torch.count_nonzero(dxp) == 0
+
+
+@pytest.mark.parametrize("name,seg", [("lx8k", 7), ("lx8k", 2), ("lx32k_d128", 15), ("lx50k_skinny", 863)])
+def test_full_size_projections_on_sampled_rows(name, seg):
+    # The benchmark's shapes, through the calls bench.py --projections makes.  A projected row
+    # depends on its own input row only, so the oracle is run on a sample of rows: tile corners,
+    # the ragged tail, random picks; and, for the backward map, rows either side of rows_valid.
+    w = synth.WORKLOADS[name]
+    B, l_x, H, d, l_s = w.B, w.l_x, w.H, w.d, w.l_s
+    E, s0 = H * d, seg * w.l_s
+    X, WQ, WKV = stage_proj(B, l_x, H, d, w.seed, w.qkv_std)
+    q, k, v = lss.lss_project_qkv(X.dev, WQ.dev, WKV.dev, s0, l_s, H)
+    rng = np.random.default_rng(seg)
+    rows = sorted({0, 1, 255, 256, 257, l_x // 2, l_x - 257, l_x - 256, l_x - 1, s0, s0 + l_s - 1}
+                  | set(int(r) for r in rng.integers(0, l_x, size=24)))
+    for b in {0, B - 1}:
+        xs = X.f64[b:b + 1, rows]
+        _, rk, rv = oracle.project_qkv(xs, WQ.f64, WKV.f64, 0, 0, H)
+        assert_close_elementwise(to_np(k[b:b + 1, rows]), rk, f"{name} k batch {b}")
+        assert_close_elementwise(to_np(v[b:b + 1, rows]), rv, f"{name} v batch {b}")
+        qrows = sorted({0, l_s // 2, l_s - 1} | set(int(r) for r in rng.integers(0, l_s, size=8)))
+        rq, _, _ = oracle.project_qkv(X.f64[b:b + 1, [s0 + r for r in qrows]], WQ.f64, WKV.f64, 0, len(qrows), H)
+        assert_close_elementwise(to_np(q[b:b + 1, qrows]), rq, f"{name} q batch {b}")
+    del k, v
+    # backward map on seeded partials (any values do: the map is linear in them)
+    rows_valid = s0 + l_s if w.causal else l_x
+    gen = torch.Generator(device="cuda"); gen.manual_seed(seg)
+    dk = torch.randn((B, l_x, H, d), device="cuda", generator=gen)
+    dv = torch.randn((B, l_x, H, d), device="cuda", generator=gen)
+    dq = torch.randn((B, l_s, H, d), device="cuda", generator=gen).to(torch.bfloat16)
+    dk[:, rows_valid:] = float("nan")
+    dv[:, rows_valid:] = float("nan")
+    dxq, dxp = lss.lss_project_bwd(dq, dk, dv, WQ.dev, WKV.dev, rows_valid)
+    brows = sorted(r for r in set(rows) | {rows_valid - 1, max(rows_valid - 256, 0)} if r < rows_valid)
+    for b in {0, B - 1}:
+        _, rp = oracle.project_bwd(np.zeros((1, 0, H, d)), to_np(dk[b:b + 1, brows]), to_np(dv[b:b + 1, brows]),
+                                   WQ.f64, WKV.f64)
+        assert rel_err(to_np(dxp[b:b + 1, brows]), rp) <= TOL["bf16"]["t"]
+        qrows = sorted({0, l_s - 1} | set(int(r) for r in rng.integers(0, l_s, size=8)))
+        rqx, _ = oracle.project_bwd(to_np(dq[b:b + 1, qrows]), np.zeros((1, 0, H, d)), np.zeros((1, 0, H, d)),
+                                    WQ.f64, WKV.f64)
+        assert rel_err(to_np(dxq[b:b + 1, qrows]), rqx) <= TOL["bf16"]["t"]
+    assert torch.count_nonzero(dxp[:, rows_valid:]) == 0
+    assert torch.isfinite(dxp).all() and torch.isfinite(dxq).all()
