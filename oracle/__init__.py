@@ -47,6 +47,12 @@ def _load():
         lib.lss_oracle_segment_bwd.argtypes = [dp, dp, dp, i64, i64, i64, i64, i64, i64, ci, dp, dp, dp, dp]
         lib.lss_oracle_segment_weights.argtypes = [dp, dp, i64, i64, i64, i64, i64, i64, ci, dp]
         lib.lss_oracle_reduce_partials.argtypes = [dp, ci, i64, dp]
+        f64, u64 = ctypes.c_double, ctypes.c_uint64
+        lib.lss_oracle_segment_fwd_dropout.argtypes = [dp, dp, dp, i64, i64, i64, i64, i64, i64, ci, f64, u64, dp, dp]
+        lib.lss_oracle_segment_bwd_dropout.argtypes = [dp, dp, dp, i64, i64, i64, i64, i64, i64, ci, f64, u64, dp, dp, dp, dp]
+        lib.lss_oracle_dropout_mask.argtypes = [f64, u64, i64, i64, i64, i64, i64, dp]
+        for f in (lib.lss_oracle_segment_fwd_dropout, lib.lss_oracle_segment_bwd_dropout, lib.lss_oracle_dropout_mask):
+            f.restype = ci
         for f in (lib.lss_oracle_segment_fwd, lib.lss_oracle_segment_bwd,
                   lib.lss_oracle_segment_weights, lib.lss_oracle_reduce_partials,
                   lib.lss_oracle_threads):
@@ -121,6 +127,41 @@ def segment_weights(q_seg, k, seg_offset: int, causal: bool = True):
     if rc != 0:
         raise ValueError(f"lss_oracle_segment_weights rejected the shape (rc={rc})")
     return P
+
+
+def segment_fwd_dropout(q_seg, k, v, seg_offset: int, causal: bool, p: float, seed: int):
+    """Eq. 2 with dropout on the weights (Section 2.2): returns (out, lse); lse is that of the scores."""
+    q_seg, k, v = _f64(q_seg), _f64(k), _f64(v)
+    B, l_s, l_x, H, d = _dims(q_seg, k, v)
+    out = np.empty((B, l_s, H, d), dtype=np.float64)
+    lse = np.empty((B, H, l_s), dtype=np.float64)
+    rc = _load().lss_oracle_segment_fwd_dropout(_p(q_seg), _p(k), _p(v), seg_offset, l_s, l_x, B, H, d,
+                                                int(bool(causal)), float(p), int(seed), _p(out), _p(lse))
+    if rc != 0:
+        raise ValueError(f"lss_oracle_segment_fwd_dropout rejected the arguments (rc={rc})")
+    return out, lse
+
+
+def segment_bwd_dropout(q_seg, k, v, d_out, seg_offset: int, causal: bool, p: float, seed: int):
+    """Gradient of the forward with dropout, same mask.  Returns (dq, dk_partial, dv_partial)."""
+    q_seg, k, v = _f64(q_seg), _f64(k), _f64(v)
+    B, l_s, l_x, H, d = _dims(q_seg, k, v)
+    d_out = _f64(d_out, q_seg.shape)
+    dq, dk, dv = np.empty_like(q_seg), np.empty_like(k), np.empty_like(k)
+    rc = _load().lss_oracle_segment_bwd_dropout(_p(q_seg), _p(k), _p(v), seg_offset, l_s, l_x, B, H, d,
+                                                int(bool(causal)), float(p), int(seed), _p(d_out), _p(dq), _p(dk), _p(dv))
+    if rc != 0:
+        raise ValueError(f"lss_oracle_segment_bwd_dropout failed (rc={rc})")
+    return dq, dk, dv
+
+
+def dropout_mask(p: float, seed: int, seg_offset: int, l_s: int, l_x: int, B: int, H: int):
+    """Keep mask of a segment's weights: uint8 [B, H, l_s, l_x], 1 = kept (all key positions, masked or not)."""
+    mask = np.empty((B, H, l_s, l_x), dtype=np.uint8)
+    rc = _load().lss_oracle_dropout_mask(float(p), int(seed), seg_offset, l_s, l_x, B, H, _p(mask))
+    if rc != 0:
+        raise ValueError(f"lss_oracle_dropout_mask rejected the arguments (rc={rc})")
+    return mask
 
 
 def reduce_partials(parts):

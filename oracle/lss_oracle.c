@@ -21,7 +21,8 @@
  *   - "decoder-only (GPT)" (Section 5.1) means a causal mask: the query at
  *     global position g = s0 + r sees keys j <= g.  Masked pairs have weight
  *     exactly 0 (they are simply left out of the sums).
- *   - no dropout on the attention weights.
+ *   - no dropout on the attention weights in the functions of the headline
+ *     path; the *_dropout functions at the end of this file add it.
  *   - the backward pass is the textbook gradient of Eq. 2; a segment's
  *     dK/dV "partial" is the contribution of its own query rows only, and the
  *     sum over segments (the arithmetic of the reduce-scatter in Fig. 2(v))
@@ -217,5 +218,172 @@ int lss_oracle_reduce_partials(const double *const *parts, int n, int64_t n_elem
         for (int i = 0; i < n; ++i) s += parts[i][e];
         out[e] = s;
     }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Dropout on the attention weights.  Section 2.2 says the scores are
+ * "normalized by a dropout and a SoftMax"; the reading taken here is the
+ * usual one of the framework the paper was written in: the softmax row A_w
+ * is computed first, then each weight is kept with probability 1 - p and the
+ * kept ones are divided by 1 - p, and E = dropout(A_w) V.  lse stays the
+ * logsumexp of the scores.
+ *
+ * The keep decision of a weight is a function of (seed, b*H + h, GLOBAL query
+ * position, key position) alone, so that a segment drops exactly what the
+ * sequential computation would drop at those positions and the segments'
+ * outputs still concatenate to the full-sequence result (Section 3,
+ * Principle 3).  It is a counter-based generator built from a published
+ * 32-bit integer mixing function (two multiply-xorshift rounds), not a
+ * stream: nothing depends on the order of evaluation.  The HIP library
+ * implements the same function on its side.
+ * ------------------------------------------------------------------------ */
+static uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352dU;
+    x ^= x >> 15; x *= 0x846ca68bU;
+    x ^= x >> 16;
+    return x;
+}
+/* the two 32-bit keys of one (seed, batch*head, global row) */
+static void row_keys(uint64_t seed, uint32_t bh, uint32_t row, uint32_t *k1, uint32_t *k2)
+{
+    const uint32_t a = mix32((uint32_t)seed + 0x9e3779b9U * (bh + 1U));
+    *k1 = mix32(a ^ row);
+    *k2 = mix32(*k1 + (uint32_t)(seed >> 32) + 0x85ebca6bU);
+}
+static uint32_t drop_threshold(double p)
+{
+    const double t = floor(p * 4294967296.0 + 0.5);
+    return t >= 4294967295.0 ? 4294967295U : (t <= 0.0 ? 0U : (uint32_t)t);
+}
+/* 1 if the weight at key position col is kept */
+static int keep(uint32_t k1, uint32_t k2, uint32_t col, uint32_t thr)
+{
+    return mix32(mix32(col ^ k1) + k2) >= thr;
+}
+
+/* keep mask of one segment: mask [B, H, l_s, l_x] bytes (1 = kept), all key positions */
+int lss_oracle_dropout_mask(double p, uint64_t seed, int64_t s0, int64_t l_s, int64_t l_x, int64_t B,
+                            int64_t H, unsigned char *mask)
+{
+    if (l_s < 0 || l_x < 1 || s0 < 0 || s0 + l_s > l_x || B < 0 || H < 1 || !(p >= 0.0 && p < 1.0)) return -1;
+    const uint32_t thr = drop_threshold(p);
+    for (int64_t bh = 0; bh < B * H; ++bh)
+        for (int64_t r = 0; r < l_s; ++r) {
+            uint32_t k1, k2;
+            row_keys(seed, (uint32_t)bh, (uint32_t)(s0 + r), &k1, &k2);
+            for (int64_t j = 0; j < l_x; ++j) mask[(bh * l_s + r) * l_x + j] = (unsigned char)keep(k1, k2, (uint32_t)j, thr);
+        }
+    return 0;
+}
+
+/* Forward with dropout: as lss_oracle_segment_fwd, with out = sum_j keep_j P[j] / (1 - p) v[j]. */
+int lss_oracle_segment_fwd_dropout(const double *q_seg, const double *k, const double *v,
+                                   int64_t s0, int64_t l_s, int64_t l_x, int64_t B, int64_t H,
+                                   int64_t d, int causal, double p, uint64_t seed, double *out, double *lse)
+{
+    if (l_s < 0 || l_x < 1 || s0 < 0 || s0 + l_s > l_x || B < 0 || H < 1 || d < 1 || !(p >= 0.0 && p < 1.0)) return -1;
+    const uint32_t thr = drop_threshold(p);
+    const double inv_keep = 1.0 / (1.0 - p);
+    const int64_t rows = B * H * l_s;
+#pragma omp parallel
+    {
+        double *P = (double *)malloc(sizeof(double) * (size_t)l_x);
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t t = 0; t < rows; ++t) {
+            const int64_t r = t % l_s, h = (t / l_s) % H, b = t / (l_s * H);
+            const int64_t nj = visible(s0, r, l_x, causal);
+            const double *q_row = q_seg + IDX4(b, r, h, 0, l_s, H, d);
+            lse[(b * H + h) * l_s + r] = row_softmax(q_row, k, b, h, l_x, H, d, nj, P);
+            uint32_t k1, k2;
+            row_keys(seed, (uint32_t)(b * H + h), (uint32_t)(s0 + r), &k1, &k2);
+            double *o_row = out + IDX4(b, r, h, 0, l_s, H, d);
+            for (int64_t c = 0; c < d; ++c) o_row[c] = 0.0;
+            for (int64_t j = 0; j < nj; ++j) {
+                if (!keep(k1, k2, (uint32_t)j, thr)) continue;
+                const double w = P[j] * inv_keep;
+                const double *v_row = v + IDX4(b, j, h, 0, l_x, H, d);
+                for (int64_t c = 0; c < d; ++c) o_row[c] += w * v_row[c];
+            }
+        }
+        free(P);
+    }
+    return 0;
+}
+
+/*
+ * Backward with dropout.  With A = softmax row, M_j = keep_j / (1 - p), out = sum_j A_j M_j v_j:
+ *   dA[j] = M_j (dO[r].v[j]);  D = sum_j A[j] dA[j];  dS[j] = A[j] (dA[j] - D);
+ *   dq[r] = sum_j dS[j] k[j] / sqrt(d);
+ *   dk_part[j] = sum_r dS[r][j] q[r] / sqrt(d);  dv_part[j] = sum_r A[r][j] M[r][j] dO[r].
+ */
+int lss_oracle_segment_bwd_dropout(const double *q_seg, const double *k, const double *v,
+                                   int64_t s0, int64_t l_s, int64_t l_x, int64_t B, int64_t H,
+                                   int64_t d, int causal, double p, uint64_t seed, const double *dO,
+                                   double *dq, double *dk_part, double *dv_part)
+{
+    if (l_s < 0 || l_x < 1 || s0 < 0 || s0 + l_s > l_x || B < 0 || H < 1 || d < 1 || !(p >= 0.0 && p < 1.0)) return -1;
+    const uint32_t thr = drop_threshold(p);
+    const double inv_keep = 1.0 / (1.0 - p);
+    const double inv_sqrt_d = 1.0 / sqrt((double)d);
+    const size_t w_elems = (size_t)(l_s > 0 ? l_s : 1) * (size_t)l_x;
+    double *AMm = (double *)malloc(sizeof(double) * w_elems);   /* A_j M_j */
+    double *dSm = (double *)malloc(sizeof(double) * w_elems);
+    if (!AMm || !dSm) { free(AMm); free(dSm); return -2; }
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t h = 0; h < H; ++h) {
+#pragma omp parallel for schedule(dynamic, 4)
+            for (int64_t r = 0; r < l_s; ++r) {
+                const int64_t nj = visible(s0, r, l_x, causal);
+                double *AM = AMm + r * l_x, *dS = dSm + r * l_x;
+                const double *q_row = q_seg + IDX4(b, r, h, 0, l_s, H, d);
+                const double *do_row = dO + IDX4(b, r, h, 0, l_s, H, d);
+                row_softmax(q_row, k, b, h, l_x, H, d, nj, AM);     /* AM holds A for now */
+                uint32_t k1, k2;
+                row_keys(seed, (uint32_t)(b * H + h), (uint32_t)(s0 + r), &k1, &k2);
+                double D = 0.0;
+                for (int64_t j = 0; j < nj; ++j) {
+                    const double *v_row = v + IDX4(b, j, h, 0, l_x, H, d);
+                    double dp = 0.0;
+                    for (int64_t c = 0; c < d; ++c) dp += do_row[c] * v_row[c];
+                    const double mj = keep(k1, k2, (uint32_t)j, thr) ? inv_keep : 0.0;
+                    dS[j] = mj * dp;                                 /* dA[j] */
+                    D += AM[j] * dS[j];
+                }
+                for (int64_t j = 0; j < nj; ++j) {
+                    const double a = AM[j];
+                    dS[j] = a * (dS[j] - D);
+                    AM[j] = keep(k1, k2, (uint32_t)j, thr) ? a * inv_keep : 0.0;
+                }
+                for (int64_t j = nj; j < l_x; ++j) { AM[j] = 0.0; dS[j] = 0.0; }
+                double *dq_row = dq + IDX4(b, r, h, 0, l_s, H, d);
+                for (int64_t c = 0; c < d; ++c) dq_row[c] = 0.0;
+                for (int64_t j = 0; j < nj; ++j) {
+                    const double *k_row = k + IDX4(b, j, h, 0, l_x, H, d);
+                    for (int64_t c = 0; c < d; ++c) dq_row[c] += dS[j] * k_row[c];
+                }
+                for (int64_t c = 0; c < d; ++c) dq_row[c] *= inv_sqrt_d;
+            }
+#pragma omp parallel for schedule(static)
+            for (int64_t j = 0; j < l_x; ++j) {
+                double *dk_row = dk_part + IDX4(b, j, h, 0, l_x, H, d);
+                double *dv_row = dv_part + IDX4(b, j, h, 0, l_x, H, d);
+                for (int64_t c = 0; c < d; ++c) { dk_row[c] = 0.0; dv_row[c] = 0.0; }
+                for (int64_t r = 0; r < l_s; ++r) {
+                    const double ds = dSm[r * l_x + j], am = AMm[r * l_x + j];
+                    if (ds == 0.0 && am == 0.0) continue;
+                    const double *q_row = q_seg + IDX4(b, r, h, 0, l_s, H, d);
+                    const double *do_row = dO + IDX4(b, r, h, 0, l_s, H, d);
+                    for (int64_t c = 0; c < d; ++c) {
+                        dk_row[c] += ds * q_row[c];
+                        dv_row[c] += am * do_row[c];
+                    }
+                }
+                for (int64_t c = 0; c < d; ++c) dk_row[c] *= inv_sqrt_d;
+            }
+        }
+    free(AMm);
+    free(dSm);
     return 0;
 }
