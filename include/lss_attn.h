@@ -9,7 +9,8 @@
  * width d; heads are independent column slices of the E_m = H*d columns.  The
  * models are decoder-only (Section 5.1), so with causal != 0 the query at global
  * position g = seg_offset + r sees keys j <= g; masked pairs have weight 0.
- * There is no dropout on the weights.
+ * The headline entry points apply no dropout to the weights; the *_dropout
+ * pair below does.
  *
  * The backward pass is the gradient of Eq. 2.  Each segment produces dQ_i and
  * its own contribution ("partial") to dK and dV; the sum of the partials over
@@ -137,6 +138,36 @@ int lss_segment_attn_bwd_f32(const void *q_seg, const void *k, const void *v,
                              int64_t B, int64_t H, int64_t d, int causal,
                              const void *out, const float *lse, const void *dO,
                              void *dq, float *dk_partial, float *dv_partial, void *stream);
+
+/*
+ * Forward and backward with dropout on the attention weights.  Section 2.2 has
+ * the scores "normalized by a dropout and a SoftMax"; read as: the softmax row
+ * A_w is computed, each weight is kept with probability 1 - p_drop and kept
+ * weights are divided by 1 - p_drop, and E_i = dropout(A_w) V.  lse is still the
+ * logsumexp of the scores.  The keep decision of a weight depends only on
+ * (seed, batch*head, GLOBAL query position seg_offset + r, key position): a
+ * segment drops exactly what the sequential computation drops at those
+ * positions, so segment outputs still concatenate to the full-sequence result
+ * and the partials still add up (Section 3, Principles 3 and 4).  The backward
+ * call must be given the same p_drop and seed as the forward call.
+ *   p_drop      in [0, 1) (LSS_ERR_RANGE otherwise); 0 is exactly the plain call
+ *   seed        any 64-bit value
+ *   elem_bytes  2: q_seg, k, v, out, dO, dq are bf16;  4: float
+ * All other arguments as in lss_segment_attn_fwd / lss_segment_attn_bwd.
+ * With p_drop > 0 these calls run on the library's general kernels (one code
+ * for both storage types), not on the tuned bf16 ones.
+ */
+int lss_segment_attn_fwd_dropout(const void *q_seg, const void *k, const void *v,
+                                 int64_t seg_offset, int64_t l_s, int64_t l_x,
+                                 int64_t B, int64_t H, int64_t d, int causal,
+                                 double p_drop, uint64_t seed, int elem_bytes,
+                                 void *out, float *lse, void *stream);
+int lss_segment_attn_bwd_dropout(const void *q_seg, const void *k, const void *v,
+                                 int64_t seg_offset, int64_t l_s, int64_t l_x,
+                                 int64_t B, int64_t H, int64_t d, int causal,
+                                 double p_drop, uint64_t seed, int elem_bytes,
+                                 const void *out, const float *lse, const void *dO,
+                                 void *dq, float *dk_partial, float *dv_partial, void *stream);
 
 /*
  * Segment sum of partials (Fig. 2(v): what the reduce-scatter adds up):

@@ -4,6 +4,7 @@
 #include "lss_common.h"
 #include "lss_kernels.h"
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <atomic>
@@ -96,6 +97,23 @@ int check_shape(int64_t s0, int64_t l_s, int64_t l_x, int64_t B, int64_t H, int6
     return LSS_OK;
 }
 
+// the kernels' dropout arguments from the probability and the seed (p already checked to be in [0, 1))
+lss::DropArgs dropout_args(double p, uint64_t seed)
+{
+    const double t = std::floor(p * 4294967296.0 + 0.5);
+    lss::DropArgs a;
+    a.thr = t >= 4294967295.0 ? 4294967295u : (t <= 0.0 ? 0u : (uint32_t)t);
+    a.scale = (float)(1.0 / (1.0 - p));
+    a.seed_lo = (uint32_t)seed;
+    a.seed_hi = (uint32_t)(seed >> 32);
+    return a;
+}
+int check_dropout(double p)
+{
+    if (!(p >= 0.0 && p < 1.0)) return fail(LSS_ERR_RANGE, "dropout probability %g is outside [0, 1)", p);
+    return LSS_OK;
+}
+
 int get_workspace(int l_s, int l_x, int B, int H, int d, int elem_bytes, lss::Workspace *ws)
 {
     const size_t need = lss::workspace_bytes(l_s, l_x, B, H, d, elem_bytes);
@@ -108,9 +126,10 @@ int get_workspace(int l_s, int l_x, int B, int H, int d, int elem_bytes, lss::Wo
 
 template <typename T>
 int fwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_s, int64_t l_x, int64_t B,
-             int64_t H, int64_t d, int causal, void *out, float *lse, void *stream)
+             int64_t H, int64_t d, int causal, double p_drop, uint64_t seed, void *out, float *lse, void *stream)
 {
     if (int rc = check_shape(s0, l_s, l_x, B, H, d)) return rc;
+    if (int rc = check_dropout(p_drop)) return rc;
     if (l_s == 0 || B == 0) return LSS_OK;
     if (!q || !k || !v || !out || !lse) return fail(LSS_ERR_NULL, "forward: NULL tensor pointer");
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
@@ -118,7 +137,8 @@ int fwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
     lss::Workspace ws;
     if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), &ws)) return rc;
     const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0, 0};
-    const hipError_t e = lss::launch_fwd<T>(s, static_cast<const T *>(q), static_cast<const T *>(k),
+    const lss::DropArgs drop = dropout_args(p_drop, seed);
+    const hipError_t e = lss::launch_fwd<T>(s, drop, static_cast<const T *>(q), static_cast<const T *>(k),
                                             static_cast<const T *>(v), static_cast<T *>(out), lse, ws,
                                             static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "forward launch failed: %s", hipGetErrorString(e));
@@ -127,10 +147,11 @@ int fwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
 
 template <typename T>
 int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_s, int64_t l_x, int64_t B,
-             int64_t H, int64_t d, int causal, const void *out, const float *lse, const void *dO, void *dq,
-             float *dk_part, float *dv_part, void *stream)
+             int64_t H, int64_t d, int causal, double p_drop, uint64_t seed, const void *out, const float *lse,
+             const void *dO, void *dq, float *dk_part, float *dv_part, void *stream)
 {
     if (int rc = check_shape(s0, l_s, l_x, B, H, d)) return rc;
+    if (int rc = check_dropout(p_drop)) return rc;
     if (B == 0) return LSS_OK;
     if (!k || !v || !dk_part || !dv_part) return fail(LSS_ERR_NULL, "backward: NULL tensor pointer");
     if (l_s > 0 && (!q || !out || !lse || !dO || !dq)) return fail(LSS_ERR_NULL, "backward: NULL tensor pointer");
@@ -153,7 +174,8 @@ int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
     if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), &ws)) return rc;
     const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0,
                           g_skip_masked_tail.load(std::memory_order_relaxed)};
-    const hipError_t e = lss::launch_bwd<T>(s, static_cast<const T *>(q), static_cast<const T *>(k),
+    const lss::DropArgs drop = dropout_args(p_drop, seed);
+    const hipError_t e = lss::launch_bwd<T>(s, drop, static_cast<const T *>(q), static_cast<const T *>(k),
                                             static_cast<const T *>(v), static_cast<const T *>(out), lse,
                                             static_cast<const T *>(dO), static_cast<T *>(dq), dk_part, dv_part, ws, st);
     if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "backward launch failed: %s", hipGetErrorString(e));
@@ -198,7 +220,7 @@ int lss_segment_attn_fwd(const void *q_seg, const void *k, const void *v, int64_
                          int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, void *out, float *lse,
                          void *stream)
 {
-    return fwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, out, lse, stream);
+    return fwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, out, lse, stream);
 }
 
 int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
@@ -206,15 +228,15 @@ int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v, int64_
                          const float *lse, const void *dO, void *dq, float *dk_partial, float *dv_partial,
                          void *stream)
 {
-    return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, out, lse, dO, dq, dk_partial,
-                                 dv_partial, stream);
+    return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, out, lse, dO, dq,
+                                 dk_partial, dv_partial, stream);
 }
 
 int lss_segment_attn_fwd_f32(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
                              int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, void *out, float *lse,
                              void *stream)
 {
-    return fwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, out, lse, stream);
+    return fwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, out, lse, stream);
 }
 
 int lss_segment_attn_bwd_f32(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
@@ -222,8 +244,33 @@ int lss_segment_attn_bwd_f32(const void *q_seg, const void *k, const void *v, in
                              const float *lse, const void *dO, void *dq, float *dk_partial, float *dv_partial,
                              void *stream)
 {
-    return bwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, out, lse, dO, dq, dk_partial,
+    return bwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, out, lse, dO, dq, dk_partial,
                            dv_partial, stream);
+}
+
+int lss_segment_attn_fwd_dropout(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
+                                 int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, double p_drop,
+                                 uint64_t seed, int elem_bytes, void *out, float *lse, void *stream)
+{
+    if (elem_bytes == 2)
+        return fwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, out, lse, stream);
+    if (elem_bytes == 4)
+        return fwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, out, lse, stream);
+    return fail(LSS_ERR_SHAPE, "elem_bytes = %d: 2 (bf16) or 4 (float)", elem_bytes);
+}
+
+int lss_segment_attn_bwd_dropout(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
+                                 int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, double p_drop,
+                                 uint64_t seed, int elem_bytes, const void *out, const float *lse, const void *dO,
+                                 void *dq, float *dk_partial, float *dv_partial, void *stream)
+{
+    if (elem_bytes == 2)
+        return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, out, lse, dO,
+                                     dq, dk_partial, dv_partial, stream);
+    if (elem_bytes == 4)
+        return bwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, out, lse, dO, dq,
+                               dk_partial, dv_partial, stream);
+    return fail(LSS_ERR_SHAPE, "elem_bytes = %d: 2 (bf16) or 4 (float)", elem_bytes);
 }
 
 int lss_project_qkv(const void *x, const void *w_q, const void *w_kv, int64_t seg_offset, int64_t l_s, int64_t l_x,

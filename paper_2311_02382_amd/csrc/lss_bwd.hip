@@ -1,6 +1,8 @@
 // Backward of Eq. 2 (Section 3, Principle 3) for one segment.  With P the softmax weights
 // recomputed from lse, dP = dO V^T and D[r] = dO[r] . out[r] (= sum_j P dP):
 //     dS = P * (dP - D);   dQ = dS K / sqrt(d);   dK_part = dS^T Q / sqrt(d);   dV_part = P^T dO.
+// With dropout on the weights (template flag DROP; mask M = keep / (1 - p), out = (P * M) V): dP is
+// replaced by M * dP and dV_part = (P * M)^T dO; D = dO . out still equals sum_j P (M dP).
 // dK_part/dV_part hold this segment's contribution only; their sum over segments is the
 // arithmetic of the reduce-scatter of Fig. 2(v).
 //
@@ -12,6 +14,8 @@
 //                      S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS.
 #include "lss_common.h"
 #include "lss_kernels.h"
+
+#include <type_traits>
 
 namespace lss {
 
@@ -51,8 +55,8 @@ struct DqCfg {
     static constexpr int TP = BC + E;   // pitch of the transposed K tile
 };
 
-template <typename T, int D>
-__global__ __launch_bounds__(256) void bwd_dq_kernel(SegShape s, const T *__restrict__ q,
+template <typename T, int D, bool DROP>
+__global__ __launch_bounds__(256) void bwd_dq_kernel(SegShape s, DropArgs dr, const T *__restrict__ q,
                                                      const T *__restrict__ k, const T *__restrict__ v,
                                                      const T *__restrict__ dO, const float *__restrict__ lse,
                                                      const float *__restrict__ Dv, T *__restrict__ dq,
@@ -90,6 +94,8 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(SegShape s, const T *__rest
     const float L2 = row_ok ? lse[(int64_t)bh * s.l_s + r] * kLog2e : INFINITY;
     const float Dr = row_ok ? Dv[(int64_t)bh * s.l_s + r] : 0.f;
     const float c = kLog2e / sqrtf((float)D);
+    DropKeys drop = {0u, 0u};
+    if (DROP) drop = drop_row_keys(dr.seed_lo, dr.seed_hi, (uint32_t)bh, (uint32_t)g);
 
     f32x16 acc[D / 32];
 #pragma unroll
@@ -129,7 +135,12 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(SegShape s, const T *__rest
                     const int key = j0 + kb2 * 32 + 8 * (e >> 2) + 4 * hh + (e & 3);
                     if (key >= s.l_x || (s.causal && key > g)) p = 0.f;
                 }
-                ds[kb2][e] = p * (dp[e] - Dr);
+                float dpe = dp[e];
+                if (DROP) {
+                    const int key = j0 + kb2 * 32 + 8 * (e >> 2) + 4 * hh + (e & 3);
+                    dpe = drop_keep(drop, (uint32_t)key, dr.thr) ? dpe * dr.scale : 0.f;
+                }
+                ds[kb2][e] = p * (dpe - Dr);
             }
         }
 #pragma unroll
@@ -191,8 +202,8 @@ struct DkvCfg {
     static constexpr int TP = BQ + E;   // pitch of their transposed copies
 };
 
-template <typename T, int D>
-__global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, const T *__restrict__ q,
+template <typename T, int D, bool DROP>
+__global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, DropArgs dr, const T *__restrict__ q,
                                                       const T *__restrict__ k, const T *__restrict__ v,
                                                       const T *__restrict__ dO, const float *__restrict__ lse,
                                                       const float *__restrict__ Dv,
@@ -205,6 +216,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, const T *__res
     __shared__ __attribute__((aligned(16))) T sGt[D * C::TP];
     __shared__ __attribute__((aligned(16))) float sL[C::BQ];
     __shared__ __attribute__((aligned(16))) float sD[C::BQ];
+    __shared__ __attribute__((aligned(16))) uint32_t sK1[DROP ? C::BQ : 4], sK2[DROP ? C::BQ : 4];   // dropout keys of the tile's rows
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int bh = blockIdx.y, b = bh / s.H, h = bh % s.H;
@@ -250,6 +262,11 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, const T *__res
                 // rows past the segment: lse = +inf makes P (hence dS) exactly 0
                 sL[tid] = rr < s.l_s ? lse[(int64_t)bh * s.l_s + rr] * kLog2e : INFINITY;
                 sD[tid] = rr < s.l_s ? Dv[(int64_t)bh * s.l_s + rr] : 0.f;
+                if (DROP) {
+                    const DropKeys kk = drop_row_keys(dr.seed_lo, dr.seed_hi, (uint32_t)bh, (uint32_t)(s.s0 + rr));
+                    sK1[tid] = kk.k1;
+                    sK2[tid] = kk.k2;
+                }
             }
             __syncthreads();
 
@@ -278,8 +295,15 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, const T *__res
                         const int e = 4 * e4 + i;
                         float p = fast_exp2(sc[e] * c - L4[i]);
                         if (diag && (int64_t)j > s.s0 + rq0 + rl + i) p = 0.f;
-                        sc[e] = p;
-                        dp[e] = p * (dp[e] - D4[i]);
+                        float pv = p, dpe = dp[e];
+                        if (DROP) {
+                            const DropKeys kk = {sK1[rl + i], sK2[rl + i]};
+                            const float mk = drop_keep(kk, (uint32_t)j, dr.thr) ? dr.scale : 0.f;
+                            pv = p * mk;
+                            dpe *= mk;
+                        }
+                        sc[e] = pv;
+                        dp[e] = p * (dpe - D4[i]);
                     }
                 }
 #pragma unroll
@@ -315,22 +339,14 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, const T *__res
 }
 
 template <typename T, int D>
-static hipError_t launch_bwd_d(const SegShape &s, const T *q, const T *k, const T *v, const T *out,
+static hipError_t launch_bwd_d(const SegShape &s, const DropArgs &dr, const T *q, const T *k, const T *v, const T *out,
                                const float *lse, const T *dO, T *dq, float *dk_part, float *dv_part,
                                const Workspace &ws, hipStream_t st)
 {
     hipError_t e;
     int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H, dq_rows_per_wg((int)sizeof(T), D));
-    if constexpr (sizeof(T) == 2) {
-        // The dQ workgroups share their launch with the dK/dV ones and need not fill the chip alone:
-        // keys are split only so far that a dQ workgroup (64 key tiles at most) does not outlast the
-        // rest of the launch.  Never more splits than the workspace was sized for.
-        const int64_t kv_extent = s.causal ? (s.s0 + s.l_s < s.l_x ? s.s0 + s.l_s : (int64_t)s.l_x) : (int64_t)s.l_x;
-        const int want = (int)((kv_extent + 64 * 64 - 1) / (64 * 64));
-        if (want < n_splits) n_splits = want < 1 ? 1 : want;
-        if ((e = launch_bwd_bf16_main(s, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st)) != hipSuccess)
-            return e;
-    } else {
+    auto generic = [&](auto drop) -> hipError_t {      // the three generic kernels; `drop`: with dropout
+        constexpr bool DROP = decltype(drop)::value;
         {
             const int64_t threads = (int64_t)s.B * s.l_s * s.H * 16;
             TimedLaunch tl(K_ROWDOT, st);
@@ -342,7 +358,7 @@ static hipError_t launch_bwd_d(const SegShape &s, const T *q, const T *k, const 
             using C = DqCfg<T, D>;
             dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
             TimedLaunch tl(K_DQ, st);
-            hipLaunchKernelGGL((bwd_dq_kernel<T, D>), grid, dim3(C::NT), 0, st, s, q, k, v, dO, lse, ws.D, dq,
+            hipLaunchKernelGGL((bwd_dq_kernel<T, D, DROP>), grid, dim3(C::NT), 0, st, s, dr, q, k, v, dO, lse, ws.D, dq,
                                ws.dq_part, n_splits);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
@@ -350,10 +366,25 @@ static hipError_t launch_bwd_d(const SegShape &s, const T *q, const T *k, const 
             using C = DkvCfg<T, D>;
             dim3 grid((s.l_x + C::BKV - 1) / C::BKV, s.B * s.H);
             TimedLaunch tl(K_DKV, st);
-            hipLaunchKernelGGL((bwd_dkv_kernel<T, D>), grid, dim3(C::NT), 0, st, s, q, k, v, dO, lse, ws.D, dk_part,
+            hipLaunchKernelGGL((bwd_dkv_kernel<T, D, DROP>), grid, dim3(C::NT), 0, st, s, dr, q, k, v, dO, lse, ws.D, dk_part,
                                dv_part);
             if ((e = hipGetLastError()) != hipSuccess) return e;
         }
+        return hipSuccess;
+    };
+    if (dr.thr != 0) {          // dropout: the generic kernels, for both storage types
+        if ((e = generic(std::true_type{})) != hipSuccess) return e;
+    } else if constexpr (sizeof(T) == 2) {
+        // The dQ workgroups share their launch with the dK/dV ones and need not fill the chip alone:
+        // keys are split only so far that a dQ workgroup (64 key tiles at most) does not outlast the
+        // rest of the launch.  Never more splits than the workspace was sized for.
+        const int64_t kv_extent = s.causal ? (s.s0 + s.l_s < s.l_x ? s.s0 + s.l_s : (int64_t)s.l_x) : (int64_t)s.l_x;
+        const int want = (int)((kv_extent + 64 * 64 - 1) / (64 * 64));
+        if (want < n_splits) n_splits = want < 1 ? 1 : want;
+        if ((e = launch_bwd_bf16_main(s, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st)) != hipSuccess)
+            return e;
+    } else {
+        if ((e = generic(std::false_type{})) != hipSuccess) return e;
     }
     if (n_splits > 1) {
         const int64_t n4 = (int64_t)s.B * s.l_s * s.H * D / 4;
@@ -366,17 +397,18 @@ static hipError_t launch_bwd_d(const SegShape &s, const T *q, const T *k, const 
 }
 
 template <typename T>
-hipError_t launch_bwd(const SegShape &s, const T *q, const T *k, const T *v, const T *out, const float *lse,
-                      const T *dO, T *dq, float *dk_part, float *dv_part, const Workspace &ws, hipStream_t st)
+hipError_t launch_bwd(const SegShape &s, const DropArgs &dr, const T *q, const T *k, const T *v, const T *out,
+                      const float *lse, const T *dO, T *dq, float *dk_part, float *dv_part, const Workspace &ws,
+                      hipStream_t st)
 {
-    if (s.d == 64) return launch_bwd_d<T, 64>(s, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, st);
-    return launch_bwd_d<T, 128>(s, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, st);
+    if (s.d == 64) return launch_bwd_d<T, 64>(s, dr, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, st);
+    return launch_bwd_d<T, 128>(s, dr, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, st);
 }
 
-template hipError_t launch_bwd<bf16_t>(const SegShape &, const bf16_t *, const bf16_t *, const bf16_t *,
+template hipError_t launch_bwd<bf16_t>(const SegShape &, const DropArgs &, const bf16_t *, const bf16_t *, const bf16_t *,
                                        const bf16_t *, const float *, const bf16_t *, bf16_t *, float *, float *,
                                        const Workspace &, hipStream_t);
-template hipError_t launch_bwd<float>(const SegShape &, const float *, const float *, const float *,
+template hipError_t launch_bwd<float>(const SegShape &, const DropArgs &, const float *, const float *, const float *,
                                       const float *, const float *, const float *, float *, float *, float *,
                                       const Workspace &, hipStream_t);
 

@@ -21,8 +21,8 @@ struct FwdCfg {
     static constexpr int VP = BC + E;   // pitch of the transposed V tile
 };
 
-template <typename T, int D>
-__global__ __launch_bounds__(256) void fwd_kernel(SegShape s, const T *__restrict__ q,
+template <typename T, int D, bool DROP>
+__global__ __launch_bounds__(256) void fwd_kernel(SegShape s, DropArgs dr, const T *__restrict__ q,
                                                   const T *__restrict__ k, const T *__restrict__ v,
                                                   T *__restrict__ out, float *__restrict__ lse,
                                                   float *__restrict__ o_part,
@@ -61,6 +61,8 @@ __global__ __launch_bounds__(256) void fwd_kernel(SegShape s, const T *__restric
         for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
     float m = -INFINITY, l = 0.f;               // running max (log2 domain) and sum, per query
     const float c = kLog2e / sqrtf((float)D);   // score -> log2 domain
+    DropKeys drop = {0u, 0u};                   // dropout: the keys of this lane's global row
+    if (DROP) drop = drop_row_keys(dr.seed_lo, dr.seed_hi, (uint32_t)bh, (uint32_t)g);
 
     const T *kbase = k + (int64_t)b * s.l_x * ld + (int64_t)h * D;
     const T *vbase = v + (int64_t)b * s.l_x * ld + (int64_t)h * D;
@@ -112,8 +114,13 @@ __global__ __launch_bounds__(256) void fwd_kernel(SegShape s, const T *__restric
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const float p = fast_exp2(sc[kb2][e] * c - m_use);
-                sc[kb2][e] = p;
-                psum += p;
+                psum += p;          // the row sum (hence lse and the normalisation) is that of the softmax
+                if (DROP) {         // the weight that multiplies V is dropped or scaled by 1 / (1 - p_drop)
+                    const int key = j0 + kb2 * 32 + 8 * (e >> 2) + 4 * hh + (e & 3);
+                    sc[kb2][e] = drop_keep(drop, (uint32_t)key, dr.thr) ? p * dr.scale : 0.f;
+                } else {
+                    sc[kb2][e] = p;
+                }
             }
         l = l * alpha + psum;       // each half keeps the sum of its own keys
         m = m_new;
@@ -211,8 +218,8 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(SegShape s, const float 
 }
 
 template <typename T, int D>
-static hipError_t launch_fwd_d(const SegShape &s, const T *q, const T *k, const T *v, T *out, float *lse,
-                               const Workspace &ws, hipStream_t st)
+static hipError_t launch_fwd_d(const SegShape &s, const DropArgs &drop, const T *q, const T *k, const T *v, T *out,
+                               float *lse, const Workspace &ws, hipStream_t st)
 {
     using C = FwdCfg<T, D>;
     int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H, fwd_rows_per_wg((int)sizeof(T), D));
@@ -225,12 +232,17 @@ static hipError_t launch_fwd_d(const SegShape &s, const T *q, const T *k, const 
         if (cap < n_splits) n_splits = cap < 1 ? 1 : cap;
     }
     hipError_t e;
-    if constexpr (sizeof(T) == 2) {
+    const dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
+    if (drop.thr != 0) {        // dropout: the generic kernel, for both storage types
+        TimedLaunch tl(K_FWD, st);
+        hipLaunchKernelGGL((fwd_kernel<T, D, true>), grid, dim3(C::NT), 0, st, s, drop, q, k, v, out, lse, ws.o_part,
+                           ws.lse_part, n_splits);
+        e = hipGetLastError();
+    } else if constexpr (sizeof(T) == 2) {
         e = launch_fwd_bf16_main(s, q, k, v, out, lse, ws, n_splits, st);
     } else {
-        dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
         TimedLaunch tl(K_FWD, st);
-        hipLaunchKernelGGL((fwd_kernel<T, D>), grid, dim3(C::NT), 0, st, s, q, k, v, out, lse, ws.o_part,
+        hipLaunchKernelGGL((fwd_kernel<T, D, false>), grid, dim3(C::NT), 0, st, s, drop, q, k, v, out, lse, ws.o_part,
                            ws.lse_part, n_splits);
         e = hipGetLastError();
     }
@@ -252,16 +264,16 @@ static hipError_t launch_fwd_d(const SegShape &s, const T *q, const T *k, const 
 }
 
 template <typename T>
-hipError_t launch_fwd(const SegShape &s, const T *q, const T *k, const T *v, T *out, float *lse,
+hipError_t launch_fwd(const SegShape &s, const DropArgs &drop, const T *q, const T *k, const T *v, T *out, float *lse,
                       const Workspace &ws, hipStream_t st)
 {
-    if (s.d == 64) return launch_fwd_d<T, 64>(s, q, k, v, out, lse, ws, st);
-    return launch_fwd_d<T, 128>(s, q, k, v, out, lse, ws, st);
+    if (s.d == 64) return launch_fwd_d<T, 64>(s, drop, q, k, v, out, lse, ws, st);
+    return launch_fwd_d<T, 128>(s, drop, q, k, v, out, lse, ws, st);
 }
 
-template hipError_t launch_fwd<bf16_t>(const SegShape &, const bf16_t *, const bf16_t *, const bf16_t *,
+template hipError_t launch_fwd<bf16_t>(const SegShape &, const DropArgs &, const bf16_t *, const bf16_t *, const bf16_t *,
                                        bf16_t *, float *, const Workspace &, hipStream_t);
-template hipError_t launch_fwd<float>(const SegShape &, const float *, const float *, const float *, float *,
+template hipError_t launch_fwd<float>(const SegShape &, const DropArgs &, const float *, const float *, const float *, float *,
                                       float *, const Workspace &, hipStream_t);
 
 } // namespace lss

@@ -17,6 +17,15 @@ struct SegShape {
     int skip_tail;   // causal backward: leave key tiles that no query of the segment sees unwritten (not zero-filled)
 };
 
+// Dropout on the attention weights (Section 2.2); thr == 0 means none.  A weight is kept when its
+// 32-bit random number (lss_common.h: drop_keep) is >= thr; kept weights are multiplied by
+// scale = 1 / (1 - p).
+struct DropArgs {
+    uint32_t thr;
+    float scale;
+    uint32_t seed_lo, seed_hi;
+};
+
 // How many key ranges ("splits") a query tile's keys are divided into so that a
 // skinny segment (l_s << l_x) still fills the chip.  Shape-only, deterministic.
 // `rows_per_wg` is the query-tile height of the kernel that will run (it differs per dtype).
@@ -37,11 +46,11 @@ size_t workspace_bytes(int l_s, int l_x, int B, int H, int d, int elem_bytes);
 Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d, int elem_bytes);
 
 template <typename T>
-hipError_t launch_fwd(const SegShape &s, const T *q, const T *k, const T *v, T *out, float *lse,
+hipError_t launch_fwd(const SegShape &s, const DropArgs &drop, const T *q, const T *k, const T *v, T *out, float *lse,
                       const Workspace &ws, hipStream_t st);
 
 template <typename T>
-hipError_t launch_bwd(const SegShape &s, const T *q, const T *k, const T *v, const T *out,
+hipError_t launch_bwd(const SegShape &s, const DropArgs &drop, const T *q, const T *k, const T *v, const T *out,
                       const float *lse, const T *dO, T *dq, float *dk_part, float *dv_part,
                       const Workspace &ws, hipStream_t st);
 

@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_E
 
 EXPORTS = ["lss_version", "lss_last_error", "lss_set_option", "lss_workspace_bytes", "lss_set_workspace",
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
-           "lss_segment_attn_bwd_f32", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd", "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
+           "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd", "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
            "lss_timing_read", "lss_timing_kernel_name"]
 
 
@@ -55,6 +55,12 @@ def load():
                        ("lss_segment_attn_bwd", bwd), ("lss_segment_attn_bwd_f32", bwd)):
         getattr(lib, name).argtypes = args
         getattr(lib, name).restype = ci
+    f64, u64 = ctypes.c_double, ctypes.c_uint64
+    lib.lss_segment_attn_fwd_dropout.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, f64, u64, ci, vp, vp, vp]
+    lib.lss_segment_attn_bwd_dropout.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, f64, u64, ci,
+                                                 vp, vp, vp, vp, vp, vp, vp]
+    lib.lss_segment_attn_fwd_dropout.restype = ci
+    lib.lss_segment_attn_bwd_dropout.restype = ci
     lib.lss_reduce_partials.argtypes = [vp, ci, vp, i64, i64, i64, i64, vp, vp]
     lib.lss_reduce_partials.restype = ci
     lib.lss_project_qkv.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, vp, vp, vp]
@@ -137,8 +143,10 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr())
 
 
-def lss_segment_attn_fwd(q_seg, k, v, seg_offset, causal=True, out=None, lse=None, stream=None):
-    """Forward of one segment; dispatches on dtype (bf16 -> lss_segment_attn_fwd, f32 -> _f32).
+def lss_segment_attn_fwd(q_seg, k, v, seg_offset, causal=True, out=None, lse=None, stream=None,
+                         p_drop=None, seed=0):
+    """Forward of one segment; dispatches on dtype (bf16 -> lss_segment_attn_fwd, f32 -> _f32), or calls
+    lss_segment_attn_fwd_dropout when p_drop is given.
 
     Returns (out [B,l_s,H,d] in the input dtype, lse [B,H,l_s] float32).
     """
@@ -149,6 +157,11 @@ def lss_segment_attn_fwd(q_seg, k, v, seg_offset, causal=True, out=None, lse=Non
         lse = torch.empty((B, H, l_s), dtype=torch.float32, device=q_seg.device)
     f32 = q_seg.dtype == torch.float32
     _ensure_workspace(l_s, l_x, B, H, d, 4 if f32 else 2, q_seg.device)
+    if p_drop is not None:
+        _check(load().lss_segment_attn_fwd_dropout(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d,
+                                                   int(bool(causal)), float(p_drop), int(seed) & (2 ** 64 - 1),
+                                                   4 if f32 else 2, _ptr(out), _ptr(lse), _stream_ptr(stream)))
+        return out, lse
     fn = load().lss_segment_attn_fwd_f32 if f32 else load().lss_segment_attn_fwd
     _check(fn(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d, int(bool(causal)),
               _ptr(out), _ptr(lse), _stream_ptr(stream)))
@@ -156,7 +169,7 @@ def lss_segment_attn_fwd(q_seg, k, v, seg_offset, causal=True, out=None, lse=Non
 
 
 def lss_segment_attn_bwd(q_seg, k, v, seg_offset, out, lse, d_out, causal=True,
-                         dq=None, dk_partial=None, dv_partial=None, stream=None):
+                         dq=None, dk_partial=None, dv_partial=None, stream=None, p_drop=None, seed=0):
     """Backward of one segment.  Returns (dq, dk_partial, dv_partial); partials are float32 [B,l_x,H,d]."""
     B, l_s, l_x, H, d = _dims(q_seg, k, v)
     for t in (out, d_out):
@@ -172,6 +185,12 @@ def lss_segment_attn_bwd(q_seg, k, v, seg_offset, out, lse, d_out, causal=True,
         dv_partial = torch.empty(k.shape, dtype=torch.float32, device=k.device)
     f32 = q_seg.dtype == torch.float32
     _ensure_workspace(l_s, l_x, B, H, d, 4 if f32 else 2, q_seg.device)
+    if p_drop is not None:
+        _check(load().lss_segment_attn_bwd_dropout(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d,
+                                                   int(bool(causal)), float(p_drop), int(seed) & (2 ** 64 - 1),
+                                                   4 if f32 else 2, _ptr(out), _ptr(lse), _ptr(d_out), _ptr(dq),
+                                                   _ptr(dk_partial), _ptr(dv_partial), _stream_ptr(stream)))
+        return dq, dk_partial, dv_partial
     fn = load().lss_segment_attn_bwd_f32 if f32 else load().lss_segment_attn_bwd
     _check(fn(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d, int(bool(causal)),
               _ptr(out), _ptr(lse), _ptr(d_out), _ptr(dq), _ptr(dk_partial), _ptr(dv_partial),

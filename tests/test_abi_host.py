@@ -127,3 +127,23 @@ def test_projection_argument_checks(lib):
     assert g(dk=0) == -1 and g(dxp=0) == -1 and g(dq=0) == -1
     assert g(dv=0x3004) == -4
     assert g(B=0) == 0
+
+
+def test_dropout_argument_checks(lib):
+    fwd, bwd = lib.lss_segment_attn_fwd_dropout, lib.lss_segment_attn_bwd_dropout
+
+    def f(p=0.1, eb=2, d=64, s0=0):
+        return fwd(0x1000, 0x2000, 0x3000, s0, 128, 256, 1, 1, d, 1, p, 7, eb, 0x4000, 0x5000, None)
+
+    assert f(p=1.0) == -5 and b"dropout" in lib.lss_last_error()
+    assert f(p=-0.5) == -5
+    assert f(p=float("nan")) == -5
+    assert f(eb=3) == -2
+    assert f(d=32) == -3
+    assert f(s0=200) == -5
+    assert f() == -6            # arguments fine: stops at the missing workspace
+    assert f(eb=4) == -6
+    assert bwd(0x1000, 0x2000, 0x3000, 0, 128, 256, 1, 1, 64, 1, 1.5, 7, 2, 0x4000, 0x5000, 0x6000, 0x7000,
+               0x8000, 0x9000, None) == -5
+    assert bwd(0x1000, 0x2000, 0x3000, 0, 128, 256, 1, 1, 64, 1, 0.5, 7, 2, 0x4000, 0x5000, 0x6000, 0x7000,
+               0x8000, 0x9000, None) == -6
