@@ -64,6 +64,9 @@ def main() -> int:
     ap.add_argument("--workload", default="lx8k")
     ap.add_argument("--projections", action="store_true",
                     help="also run the Q/K/V projections and their backward around every segment")
+    ap.add_argument("--dropout", type=float, default=None, metavar="P",
+                    help="run forward and backward with dropout probability P on the attention weights "
+                         "(a further workload: the library's general kernels serve it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device-to-device copy of this many MiB "
@@ -124,20 +127,22 @@ def main() -> int:
     # valid: key tiles no query of a segment sees need not be filled with zeros
     lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, 1)
 
+    drop = {} if args.dropout is None else {"p_drop": args.dropout, "seed": w.seed}
+
     def step_attention():
         for i, s0 in enumerate(offs):
-            lss.lss_segment_attn_fwd(q_seg[i], kd, vd, s0, w.causal, out=out[i], lse=lse[i])
+            lss.lss_segment_attn_fwd(q_seg[i], kd, vd, s0, w.causal, out=out[i], lse=lse[i], **drop)
             lss.lss_segment_attn_bwd(q_seg[i], kd, vd, s0, out[i], lse[i], do_seg[i], w.causal,
-                                     dq=dq[i], dk_partial=dk_part[i], dv_partial=dv_part[i])
+                                     dq=dq[i], dk_partial=dk_part[i], dv_partial=dv_part[i], **drop)
         lss.lss_reduce_partials(dk_part, rows_valid, out=dK)
         lss.lss_reduce_partials(dv_part, rows_valid, out=dV)
 
     def step_with_projections():
         for i, s0 in enumerate(offs):     # every segment projects K and V itself, as every GPU would
             lss.lss_project_qkv(xd, wqd, wkvd, s0, l_s, w.H, q_seg=q_seg[i], k=kd, v=vd)
-            lss.lss_segment_attn_fwd(q_seg[i], kd, vd, s0, w.causal, out=out[i], lse=lse[i])
+            lss.lss_segment_attn_fwd(q_seg[i], kd, vd, s0, w.causal, out=out[i], lse=lse[i], **drop)
             lss.lss_segment_attn_bwd(q_seg[i], kd, vd, s0, out[i], lse[i], do_seg[i], w.causal,
-                                     dq=dq[i], dk_partial=dk_one, dv_partial=dv_one)
+                                     dq=dq[i], dk_partial=dk_one, dv_partial=dv_one, **drop)
             lss.lss_project_bwd(dq[i], dk_one, dv_one, wqd, wkvd, rows_valid[i], dx_q=dx_q[i],
                                 dx_partial=dx_part[i].view(w.B, w.l_x, E))
         lss.lss_reduce_partials(dx_part, rows_valid, out=dX)
@@ -253,8 +258,12 @@ def main() -> int:
             t = time.perf_counter()
             if args.projections:
                 qh, kh, vh = oracle.project_qkv(xh, wqh, wkvh, s0, l_s, w.H)
-            oracle.segment_fwd(qh, kh, vh, s0, w.causal)
-            g_ = oracle.segment_bwd(qh, kh, vh, doh, s0, w.causal)
+            if args.dropout is None:
+                oracle.segment_fwd(qh, kh, vh, s0, w.causal)
+                g_ = oracle.segment_bwd(qh, kh, vh, doh, s0, w.causal)
+            else:
+                oracle.segment_fwd_dropout(qh, kh, vh, s0, w.causal, args.dropout, w.seed)
+                g_ = oracle.segment_bwd_dropout(qh, kh, vh, doh, s0, w.causal, args.dropout, w.seed)
             if args.projections:
                 oracle.project_bwd(g_[0], g_[1], g_[2], wqh, wkvh)
                 f_cpu += 2.0 * w.B * E * (2 * E * w.l_x + E * l_s) + 2.0 * w.B * E * (2 * E * rows_valid[i] + E * l_s)
@@ -270,7 +279,8 @@ def main() -> int:
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name + ("+projections" if args.projections else ""), "B": w.B, "l_x": w.l_x,
+        "config": {"workload": w.name + ("+projections" if args.projections else "")
+                               + (f"+dropout{args.dropout}" if args.dropout is not None else ""), "B": w.B, "l_x": w.l_x,
                    "N": w.N, "l_s": l_s, "H": w.H, "d": w.d, "causal": w.causal,
                    "step": ("per segment: Q_i, K, V from x, fwd, bwd, dx_q and dx_partial; then segment sum of dx"
                             if args.projections else "fwd+bwd of all N segments, then segment sum of dK and dV")},
