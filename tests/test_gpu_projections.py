@@ -168,3 +168,32 @@ def test_full_size_projections_on_sampled_rows(name, seg):
         assert rel_err(to_np(dxq[b:b + 1, qrows]), rqx) <= TOL["bf16"]["t"]
     assert torch.count_nonzero(dxp[:, rows_valid:]) == 0
     assert torch.isfinite(dxp).all() and torch.isfinite(dxq).all()
+
+
+def test_projection_random_shapes_sweep():
+    # seeded random problems, E_m in {128, 256, 384, 640}: column tiles that are cut by the matrix
+    # edge (E_m not a multiple of 256), row counts around the 256-row tile, segments at either end
+    rng = np.random.default_rng(4242)
+    for case in range(16):
+        H, d = [(2, 64), (4, 64), (3, 128), (6, 64), (5, 128), (10, 64)][case % 6]
+        E = H * d
+        B = int(rng.integers(1, 4))
+        l_x = int(rng.choice([1, 5, 255, 256, 257, 300, 511, 513, 700]))
+        l_s = int(rng.integers(1, l_x + 1))
+        s0 = int(rng.choice([0, l_x - l_s]))
+        X, WQ, WKV = stage_proj(B, l_x, H, d, 9600 + case)
+        q, k, v = lss.lss_project_qkv(X.dev, WQ.dev, WKV.dev, s0, l_s, H)
+        for name, got, ref in zip("qkv", (q, k, v), oracle.project_qkv(X.f64, WQ.f64, WKV.f64, s0, l_s, H)):
+            assert_close_elementwise(to_np(got), ref, f"case {case} {name} {(B, l_x, H, d, s0, l_s)}")
+        rows_valid = int(rng.integers(0, l_x + 1))
+        dk = synth.normal_f32(9700 + case, B * l_x * E).reshape(B, l_x, H, d)
+        dv = synth.normal_f32(9800 + case, B * l_x * E).reshape(B, l_x, H, d)
+        dk[:, rows_valid:] = 0.0
+        dv[:, rows_valid:] = 0.0
+        DQ = Staged(synth.normal_f32(9900 + case, B * l_s * E).reshape(B, l_s, H, d), "bf16")
+        dxq, dxp = lss.lss_project_bwd(DQ.dev, torch.from_numpy(dk).cuda(), torch.from_numpy(dv).cuda(), WQ.dev,
+                                       WKV.dev, rows_valid)
+        rq, rp = oracle.project_bwd(DQ.f64, dk, dv, WQ.f64, WKV.f64)
+        assert rel_err(to_np(dxq), rq) <= TOL["bf16"]["t"], f"case {case} dx_q"
+        assert rel_err(to_np(dxp), rp, floor=1e-3) <= TOL["bf16"]["t"], f"case {case} dx_partial"
+        assert not np.any(to_np(dxp)[:, rows_valid:])
