@@ -196,7 +196,8 @@ int lss_reduce_partials(const float *const *parts, int n, const int64_t *rows_va
  *          W_k in columns 0 .. E_m-1 and W_v in columns E_m .. 2 E_m-1
  *   q_seg  [B, l_s, H, d] bf16 (written);  k, v [B, l_x, H, d] bf16 (written)
  * bf16 matrix cores, fp32 accumulation, one rounding to bf16 at the end.
- * E_m must be a multiple of 128 (LSS_ERR_SHAPE otherwise).  Uses no workspace.
+ * E_m must be a multiple of 128 and at most 65536 (LSS_ERR_SHAPE otherwise).
+ * Uses no workspace.
  */
 int lss_project_qkv(const void *x, const void *w_q, const void *w_kv,
                     int64_t seg_offset, int64_t l_s, int64_t l_x,

@@ -278,7 +278,8 @@ int lss_project_qkv(const void *x, const void *w_q, const void *w_kv, int64_t se
 {
     if (int rc = check_shape(seg_offset, l_s, l_x, B, H, d)) return rc;
     const int64_t E = H * d;
-    if (E % 128 != 0) return fail(LSS_ERR_SHAPE, "projections: E_m = H*d = %lld is not a multiple of 128", (long long)E);
+    if (E % 128 != 0 || E > 65536)
+        return fail(LSS_ERR_SHAPE, "projections: E_m = H*d = %lld is not a multiple of 128 or exceeds 65536", (long long)E);
     if (B * l_x >= (int64_t)1 << 31) return fail(LSS_ERR_SHAPE, "projections: B*l_x = %lld exceeds 2^31", (long long)(B * l_x));
     if (B == 0) return LSS_OK;
     if (!x || !w_q || !w_kv || !k || !v || (l_s > 0 && !q_seg)) return fail(LSS_ERR_NULL, "project_qkv: NULL tensor pointer");
@@ -299,7 +300,8 @@ int lss_project_bwd(const void *dq, const float *dk_partial, const float *dv_par
 {
     if (int rc = check_shape(0, l_s, l_x, B, H, d)) return rc;
     const int64_t E = H * d;
-    if (E % 128 != 0) return fail(LSS_ERR_SHAPE, "projections: E_m = H*d = %lld is not a multiple of 128", (long long)E);
+    if (E % 128 != 0 || E > 65536)
+        return fail(LSS_ERR_SHAPE, "projections: E_m = H*d = %lld is not a multiple of 128 or exceeds 65536", (long long)E);
     if (rows_valid < 0 || rows_valid > l_x) return fail(LSS_ERR_RANGE, "project_bwd: rows_valid = %lld outside [0, %lld]", (long long)rows_valid, (long long)l_x);
     if (B == 0) return LSS_OK;
     if (!dk_partial || !dv_partial || !w_q || !w_kv || !dx_partial || (l_s > 0 && (!dq || !dx_q)))

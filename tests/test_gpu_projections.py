@@ -197,3 +197,55 @@ def test_projection_random_shapes_sweep():
         assert rel_err(to_np(dxq), rq) <= TOL["bf16"]["t"], f"case {case} dx_q"
         assert rel_err(to_np(dxp), rp, floor=1e-3) <= TOL["bf16"]["t"], f"case {case} dx_partial"
         assert not np.any(to_np(dxp)[:, rows_valid:])
+
+
+def test_projections_and_dropout_record_into_a_graph():
+    # projections, the dropout pair and the segment sum of dx recorded once, replayed on fresh inputs
+    # with eager work in between; every replay equals the eager calls bit for bit
+    B, l_x, H, d, s0, l_s, p, seed = 2, 600, 2, 64, 300, 200, 0.2, 99
+    E = H * d
+
+    def fresh(sd):
+        X, WQ, WKV = stage_proj(B, l_x, H, d, sd)
+        DO = Staged(synth.normal_f32(sd + 50, B * l_s * E).reshape(B, l_s, H, d), "bf16")
+        return X.dev, WQ.dev, WKV.dev, DO.dev
+
+    x, wq, wkv, do = [t.clone() for t in fresh(800)]
+    q = torch.empty((B, l_s, H, d), dtype=torch.bfloat16, device="cuda")
+    k, v = (torch.empty((B, l_x, H, d), dtype=torch.bfloat16, device="cuda") for _ in range(2))
+    out, dq = torch.empty_like(q), torch.empty_like(q)
+    lse = torch.empty((B, H, l_s), dtype=torch.float32, device="cuda")
+    dk, dv = (torch.empty((B, l_x, H, d), dtype=torch.float32, device="cuda") for _ in range(2))
+    dxq = torch.empty((B, l_s, E), dtype=torch.float32, device="cuda")
+    dxp, tot = (torch.empty((B, l_x, E), dtype=torch.float32, device="cuda") for _ in range(2))
+
+    def step():
+        lss.lss_project_qkv(x, wq, wkv, s0, l_s, H, q_seg=q, k=k, v=v)
+        lss.lss_segment_attn_fwd(q, k, v, s0, True, out=out, lse=lse, p_drop=p, seed=seed)
+        lss.lss_segment_attn_bwd(q, k, v, s0, out, lse, do, True, dq=dq, dk_partial=dk, dv_partial=dv,
+                                 p_drop=p, seed=seed)
+        lss.lss_project_bwd(dq, dk, dv, wq, wkv, s0 + l_s, dx_q=dxq, dx_partial=dxp)
+        lss.lss_reduce_partials([dxp.view(B, l_x, 1, E), dxp.view(B, l_x, 1, E)], [s0 + l_s, 100],
+                                out=tot.view(B, l_x, 1, E))
+
+    results = (q, k, v, out, lse, dq, dk, dv, dxq, dxp, tot)
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for sd in (801, 802, 803):
+        for dst, src in zip((x, wq, wkv, do), fresh(sd)):
+            dst.copy_(src)
+        for t in results:
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in results]
+        for t in results:
+            t.fill_(float("nan"))
+        step()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(got, results)):
+            assert torch.equal(a, b), f"seed {sd}: result {i} differs between replay and eager"
+        assert all(torch.isfinite(t).all() for t in got)
