@@ -33,6 +33,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak (published)
+PEAK_F32_TFLOPS = 157.3        # ... and the fp32 matrix peak, for --dtype f32
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak (published)
 
 # Matrix products each kernel contributes to the strict count (per pair: 2*d flops each).
@@ -64,6 +65,8 @@ def main() -> int:
     ap.add_argument("--workload", default="lx8k")
     ap.add_argument("--projections", action="store_true",
                     help="also run the Q/K/V projections and their backward around every segment")
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16",
+                    help="storage type: bf16 (the benchmark) or f32 (the single-precision twins of the entry points)")
     ap.add_argument("--dropout", type=float, default=None, metavar="P",
                     help="run forward and backward with dropout probability P on the attention weights "
                          "(a further workload: the library's general kernels serve it)")
@@ -95,9 +98,29 @@ def main() -> int:
     w = synth.WORKLOADS[args.workload]
     q, k, v, do = synth.workload_inputs(w)
 
+    f32 = args.dtype == "f32"
+    if f32 and args.projections:
+        print("bench.py: the projections are bf16 only; --dtype f32 cannot be combined with --projections", file=sys.stderr)
+        return 2
+    peak = PEAK_F32_TFLOPS if f32 else PEAK_BF16_TFLOPS
+
+    class HostCopy:
+        """What the oracle reads: exactly the values the device tensor holds, widened to float64 on demand."""
+        def __init__(self, arr, is_bits):
+            self.arr, self.is_bits, self.shape = arr, is_bits, arr.shape
+
+        def __getitem__(self, idx):
+            return HostCopy(self.arr[idx], self.is_bits)
+
+        def f64(self):
+            return synth.bf16_bits_to_f64(self.arr).reshape(self.arr.shape) if self.is_bits else self.arr.astype(np.float64)
+
     def stage(x):
+        if f32:
+            x = np.ascontiguousarray(x, dtype=np.float32)
+            return torch.from_numpy(x).to(dev), HostCopy(x, False)
         bits = synth.f32_to_bf16_bits(x)
-        return torch.from_numpy(bits.view(np.int16).reshape(x.shape)).to(dev).view(torch.bfloat16), bits
+        return torch.from_numpy(bits.view(np.int16).reshape(x.shape)).to(dev).view(torch.bfloat16), HostCopy(bits, True)
 
     (qd, qb), (kd, kb), (vd, vb), (dod, dob) = map(stage, (q, k, v, do))
     del q, k, v, do
@@ -223,8 +246,8 @@ def main() -> int:
         if mfma:
             per_launch = ALGO_PRODUCTS[dom] * 2.0 * w.d * pairs / mfma[dom]["launches_per_step"]
             achieved = per_launch / (mfma[dom]["avg_us"] * 1e-6) / 1e12
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                        "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
+                        "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                         "traffic": measured_traffic(w.name, dom),
                         "avg_launch_us": round(mfma[dom]["avg_us"], 2),
                         "algorithmic_flops_per_launch": per_launch,
@@ -247,14 +270,13 @@ def main() -> int:
     if not args.no_cpu_baseline:
         import oracle
         sample = list(range(w.N)) if w.pairs() * w.d < 4e10 else sorted({w.N // 2 - 1, w.N - 1})
-        kh, vh = synth.bf16_bits_to_f64(kb).reshape(kb.shape), synth.bf16_bits_to_f64(vb).reshape(vb.shape)
+        kh, vh = kb.f64(), vb.f64()
         if args.projections:
-            xh, wqh, wkvh = (synth.bf16_bits_to_f64(b_).reshape(b_.shape) for b_ in (xb, wqb, wkvb))
+            xh, wqh, wkvh = (b_.f64() for b_ in (xb, wqb, wkvb))
         t_cpu, p_cpu, f_cpu = 0.0, 0, 0.0
         for i in sample:
             s0 = offs[i]
-            qh = synth.bf16_bits_to_f64(qb[:, s0:s0 + l_s]).reshape(w.B, l_s, w.H, w.d)
-            doh = synth.bf16_bits_to_f64(dob[:, s0:s0 + l_s]).reshape(w.B, l_s, w.H, w.d)
+            qh, doh = qb[:, s0:s0 + l_s].f64(), dob[:, s0:s0 + l_s].f64()
             t = time.perf_counter()
             if args.projections:
                 qh, kh, vh = oracle.project_qkv(xh, wqh, wkvh, s0, l_s, w.H)
@@ -278,13 +300,14 @@ def main() -> int:
         "metric": "segment-attention fwd+bwd TFLOP/s on 1 MI355X; % of bf16 MFMA peak",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": w.name + ("+projections" if args.projections else "")
-                               + (f"+dropout{args.dropout}" if args.dropout is not None else ""), "B": w.B, "l_x": w.l_x,
+                               + (f"+dropout{args.dropout}" if args.dropout is not None else "")
+                               + ("+f32" if f32 else ""), "B": w.B, "l_x": w.l_x,
                    "N": w.N, "l_s": l_s, "H": w.H, "d": w.d, "causal": w.causal,
                    "step": ("per segment: Q_i, K, V from x, fwd, bwd, dx_q and dx_partial; then segment sum of dx"
                             if args.projections else "fwd+bwd of all N segments, then segment sum of dK and dV")},
-        "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        ("frac_of_f32_peak" if f32 else "frac_of_bf16_peak"): round(value / peak, 4),
         "tflops_with_recompute_count_14Pd": round(flops_fa / (ms_per_step * 1e-3) / 1e12, 2),
         "gpu_ms_per_step_events": round(gpu_ms / args.steps, 4),
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels,
