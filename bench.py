@@ -266,34 +266,69 @@ def main() -> int:
             kernels["reduce_partials_kernel"]["algorithmic_GBps"] = round(
                 byts / (kernels["reduce_partials_kernel"]["ms_per_step"] * 1e-3) / 1e9, 1)
 
+    # forward-only and backward-only rates from the survey pass (kernel times, launch gaps not included)
+    rates = None
+    if kernels:
+        t_f = sum(kernels[n_]["ms_per_step"] for n_ in ("fwd_kernel", "fwd_merge_kernel") if n_ in kernels)
+        t_b = sum(kernels[n_]["ms_per_step"] for n_ in ("bwd_rowdot_kernel", "bwd_main_kernel", "bwd_dq_kernel",
+                                                        "bwd_dkv_kernel", "bwd_dq_merge_kernel") if n_ in kernels)
+        if t_f > 0 and t_b > 0:
+            rates = {"fwd_only_tflops": round(4.0 * pairs * w.d / (t_f * 1e-3) / 1e12, 2),
+                     "bwd_only_tflops": round(8.0 * pairs * w.d / (t_b * 1e-3) / 1e12, 2),
+                     "note": "strict counts 4*P*d and 8*P*d over the summed kernel times of one step"}
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
-        sample = list(range(w.N)) if w.pairs() * w.d < 4e10 else sorted({w.N // 2 - 1, w.N - 1})
+        # A bounded sample of the same workload: about 1e12 fp64 flops (10-30 s on the machine's cores).  The
+        # whole workload if it is that small; otherwise the middle and the last segment, and of those
+        # only the (batch, head) slices (0, 0) and (B-1, H-1) -- heads are independent, so a slice is a
+        # complete, smaller problem of the same shape.  (With projections the slices cannot be cut
+        # out of x, so the sample is then whole segments.)
+        budget = 1.0e12
+        seg_flops = [12.0 * w.segment_pairs(i) * w.d for i in range(w.N)]
+        if sum(seg_flops) <= budget:
+            sample, slices = list(range(w.N)), None
+        else:
+            sample = sorted({w.N // 2 - 1, w.N - 1})
+            slices = None if args.projections or sum(seg_flops[i] for i in sample) <= budget else \
+                sorted({(0, 0), (w.B - 1, w.H - 1)})
         kh, vh = kb.f64(), vb.f64()
         if args.projections:
             xh, wqh, wkvh = (b_.f64() for b_ in (xb, wqb, wkvb))
-        t_cpu, p_cpu, f_cpu = 0.0, 0, 0.0
+        t_cpu, flops_cpu = 0.0, 0.0
+
+        def oracle_segment(qh, kh_, vh_, doh, s0):
+            if args.dropout is None:
+                oracle.segment_fwd(qh, kh_, vh_, s0, w.causal)
+                return oracle.segment_bwd(qh, kh_, vh_, doh, s0, w.causal)
+            oracle.segment_fwd_dropout(qh, kh_, vh_, s0, w.causal, args.dropout, w.seed)
+            return oracle.segment_bwd_dropout(qh, kh_, vh_, doh, s0, w.causal, args.dropout, w.seed)
+
         for i in sample:
             s0 = offs[i]
             qh, doh = qb[:, s0:s0 + l_s].f64(), dob[:, s0:s0 + l_s].f64()
-            t = time.perf_counter()
-            if args.projections:
-                qh, kh, vh = oracle.project_qkv(xh, wqh, wkvh, s0, l_s, w.H)
-            if args.dropout is None:
-                oracle.segment_fwd(qh, kh, vh, s0, w.causal)
-                g_ = oracle.segment_bwd(qh, kh, vh, doh, s0, w.causal)
+            if slices is None:
+                t = time.perf_counter()
+                if args.projections:
+                    qh, kh, vh = oracle.project_qkv(xh, wqh, wkvh, s0, l_s, w.H)
+                g_ = oracle_segment(qh, kh, vh, doh, s0)
+                if args.projections:
+                    oracle.project_bwd(g_[0], g_[1], g_[2], wqh, wkvh)
+                    flops_cpu += 2.0 * w.B * E * (2 * E * w.l_x + E * l_s) + 2.0 * w.B * E * (2 * E * rows_valid[i] + E * l_s)
+                t_cpu += time.perf_counter() - t
+                flops_cpu += seg_flops[i]
             else:
-                oracle.segment_fwd_dropout(qh, kh, vh, s0, w.causal, args.dropout, w.seed)
-                g_ = oracle.segment_bwd_dropout(qh, kh, vh, doh, s0, w.causal, args.dropout, w.seed)
-            if args.projections:
-                oracle.project_bwd(g_[0], g_[1], g_[2], wqh, wkvh)
-                f_cpu += 2.0 * w.B * E * (2 * E * w.l_x + E * l_s) + 2.0 * w.B * E * (2 * E * rows_valid[i] + E * l_s)
-            t_cpu += time.perf_counter() - t
-            p_cpu += w.segment_pairs(i)
-        cpu_baseline = {"value": round((12.0 * p_cpu * w.d + f_cpu) / t_cpu / 1e12, 6), "unit": "TFLOP/s",
+                for (b_, h_) in slices:
+                    cut = [np.ascontiguousarray(a[b_:b_ + 1, :, h_:h_ + 1]) for a in (qh, kh, vh, doh)]
+                    t = time.perf_counter()
+                    oracle_segment(cut[0], cut[1], cut[2], cut[3], s0)
+                    t_cpu += time.perf_counter() - t
+                    flops_cpu += seg_flops[i] / (w.B * w.H)
+        what = "all batches and heads" if slices is None else f"(batch, head) slices {slices}"
+        cpu_baseline = {"value": round(flops_cpu / t_cpu / 1e12, 6), "unit": "TFLOP/s",
                         "cores": oracle.threads(), "kind": "oracle",
-                        "sample": f"segments {sample} of {w.N} (fwd+bwd, all batches and heads), "
+                        "sample": f"segments {sample} of {w.N} (fwd+bwd, {what}), "
                                   f"{t_cpu:.1f} s of fp64 CPU work, same strict flop count"}
 
     line = {
@@ -310,7 +345,7 @@ def main() -> int:
         ("frac_of_f32_peak" if f32 else "frac_of_bf16_peak"): round(value / peak, 4),
         "tflops_with_recompute_count_14Pd": round(flops_fa / (ms_per_step * 1e-3) / 1e12, 2),
         "gpu_ms_per_step_events": round(gpu_ms / args.steps, 4),
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "rates": rates, "kernels": kernels,
     }
     print(json.dumps(line))
     return 0
