@@ -285,3 +285,24 @@ def test_random_shapes_sweep():
         # a row that sees a single key has dS = 0 exactly: measure against the size of the cancelling terms
         run_segment(Q, K, V, DO, s0, l_s, causal, kind, tag=f"case {case}: {(B, l_x, H, d, s0, l_s, causal, kind)}",
                     floor=1e-2)
+
+
+def test_non_default_stream_and_many_heads():
+    # calls enqueued on a stream of the caller's (the library never synchronises or switches
+    # streams), and a shape with far more (batch, head) pairs than compute units
+    B, l_x, H, d, s0, l_s = 3, 200, 171, 64, 60, 140            # B*H = 513: not a multiple of the 8 XCDs
+    Q, K, V, DO = stage_all(B, l_x, H, d, 7100, "bf16")
+    q, do = Q.dev[:, s0:s0 + l_s].contiguous(), DO.dev[:, s0:s0 + l_s].contiguous()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        out, lse = lss.lss_segment_attn_fwd(q, K.dev, V.dev, s0, True)                   # picks up the current stream
+        dq, dk, dv = lss.lss_segment_attn_bwd(q, K.dev, V.dev, s0, out, lse, do, True, stream=side)
+        tot = lss.lss_reduce_partials([dk, dv], [s0 + l_s, s0 + l_s], stream=side)
+    side.synchronize()
+    ro, rl = oracle.segment_fwd(Q.f64[:, s0:s0 + l_s], K.f64, V.f64, s0, True)
+    rdq, rdk, rdv = oracle.segment_bwd(Q.f64[:, s0:s0 + l_s], K.f64, V.f64, DO.f64[:, s0:s0 + l_s], s0, True)
+    t = TOL["bf16"]
+    assert rel_err(to_np(out), ro) <= t["t"] and lse_err(to_np(lse), rl) <= t["lse"]
+    for got, ref in ((dq, rdq), (dk, rdk), (dv, rdv), (tot, rdk + rdv)):
+        assert rel_err(to_np(got), ref) <= t["t"]
