@@ -259,22 +259,33 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) w_off[nb][ks] = WTile::chunk_offset(64 * wn + 32 * nb + lq, 2 * ks + hh);
     }
+    // One contraction tile: four steps of 16 indices.  The six operand fragments of step ks + 1 are
+    // requested from LDS before the eight matrix instructions of step ks are issued (two sets of
+    // fragment registers), so a wavefront's matrix instructions wait for reads that are a whole step
+    // old instead of for the ones just issued.
+    struct Frags { Frag<bf16_t> fb[4], fw[2]; };
+    auto load_frags = [&](const char *at, const char *wt, int ks, Frags &f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+            if constexpr (W_TR) f.fw[nb] = WTileTr::load_frag(wt, ks, wt_off[nb]);
+            else f.fw[nb] = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(wt + w_off[nb][ks]));
+        }
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) f.fb[mb] = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(at + b_off[mb][ks]));
+    };
     auto compute = [&](int slot) {
         const char *at = smem + slot * P_SLOT, *wt = at + P_ABYTES;
+        Frags f[2];
+        load_frags(at, wt, 0, f[0]);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            Frag<bf16_t> fb[4], fw[2];
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                if constexpr (W_TR) fw[nb] = WTileTr::load_frag(wt, ks, wt_off[nb]);
-                else fw[nb] = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(wt + w_off[nb][ks]));
-            }
-#pragma unroll
-            for (int mb = 0; mb < 4; ++mb) fb[mb] = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(at + b_off[mb][ks]));
+            if (ks + 1 < 4) load_frags(at, wt, ks + 1, f[(ks + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mma(fw[nb], fb[mb], acc[mb][nb]);
+                for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mma(f[ks & 1].fw[nb], f[ks & 1].fb[mb], acc[mb][nb]);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
