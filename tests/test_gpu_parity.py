@@ -306,3 +306,19 @@ def test_non_default_stream_and_many_heads():
     assert rel_err(to_np(out), ro) <= t["t"] and lse_err(to_np(lse), rl) <= t["lse"]
     for got, ref in ((dq, rdq), (dk, rdk), (dv, rdv), (tot, rdk + rdv)):
         assert rel_err(to_np(got), ref) <= t["t"]
+
+
+def test_random_skinny_shapes_sweep():
+    # short segments of long sequences: the forward and dQ workgroups split the keys (2 to 16 ranges,
+    # ragged last range, ranges cut by the causal diagonal), both head widths, both mask modes
+    rng = np.random.default_rng(77)
+    for case in range(10):
+        d = 128 if case % 3 == 2 else 64
+        B, H = 1, int(rng.integers(1, 3))
+        l_x = int(rng.integers(2000, 9000))
+        l_s = int(rng.choice([1, 17, 58, 64, 100, 129, 200]))
+        s0 = int(rng.choice([l_x - l_s, int(rng.integers(0, l_x - l_s + 1)), int(rng.integers(0, 64))]))
+        causal = bool(case % 2 == 0)
+        Q, K, V, DO = stage_all(B, l_x, H, d, 6000 + case, "bf16")
+        run_segment(Q, K, V, DO, s0, l_s, causal, "bf16", tag=f"case {case}: {(B, l_x, H, d, s0, l_s, causal)}",
+                    floor=1e-2)
