@@ -345,46 +345,55 @@ static hipError_t launch_bwd_d(const SegShape &s, const DropArgs &dr, const T *q
 {
     hipError_t e;
     int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H, dq_rows_per_wg((int)sizeof(T), D));
-    auto generic = [&](auto drop) -> hipError_t {      // the three generic kernels; `drop`: with dropout
-        constexpr bool DROP = decltype(drop)::value;
-        {
-            const int64_t threads = (int64_t)s.B * s.l_s * s.H * 16;
-            TimedLaunch tl(K_ROWDOT, st);
-            hipLaunchKernelGGL((bwd_rowdot_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                               s, out, dO, ws.D);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-        }
-        {
-            using C = DqCfg<T, D>;
-            dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
-            TimedLaunch tl(K_DQ, st);
-            hipLaunchKernelGGL((bwd_dq_kernel<T, D, DROP>), grid, dim3(C::NT), 0, st, s, dr, q, k, v, dO, lse, ws.D, dq,
-                               ws.dq_part, n_splits);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-        }
-        {
-            using C = DkvCfg<T, D>;
-            dim3 grid((s.l_x + C::BKV - 1) / C::BKV, s.B * s.H);
-            TimedLaunch tl(K_DKV, st);
-            hipLaunchKernelGGL((bwd_dkv_kernel<T, D, DROP>), grid, dim3(C::NT), 0, st, s, dr, q, k, v, dO, lse, ws.D, dk_part,
-                               dv_part);
-            if ((e = hipGetLastError()) != hipSuccess) return e;
-        }
-        return hipSuccess;
+    auto rowdot = [&]() -> hipError_t {
+        const int64_t threads = (int64_t)s.B * s.l_s * s.H * 16;
+        TimedLaunch tl(K_ROWDOT, st);
+        hipLaunchKernelGGL((bwd_rowdot_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           s, out, dO, ws.D);
+        return hipGetLastError();
     };
-    if (dr.thr != 0) {          // dropout: the generic kernels, for both storage types
-        if ((e = generic(std::true_type{})) != hipSuccess) return e;
-    } else if constexpr (sizeof(T) == 2) {
-        // The dQ workgroups share their launch with the dK/dV ones and need not fill the chip alone:
-        // keys are split only so far that a dQ workgroup (64 key tiles at most) does not outlast the
-        // rest of the launch.  Never more splits than the workspace was sized for.
-        const int64_t kv_extent = s.causal ? (s.s0 + s.l_s < s.l_x ? s.s0 + s.l_s : (int64_t)s.l_x) : (int64_t)s.l_x;
-        const int want = (int)((kv_extent + 64 * 64 - 1) / (64 * 64));
-        if (want < n_splits) n_splits = want < 1 ? 1 : want;
-        if ((e = launch_bwd_bf16_main(s, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st)) != hipSuccess)
-            return e;
+    auto generic_dq = [&](auto drop) -> hipError_t {
+        using C = DqCfg<T, D>;
+        dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
+        TimedLaunch tl(K_DQ, st);
+        hipLaunchKernelGGL((bwd_dq_kernel<T, D, decltype(drop)::value>), grid, dim3(C::NT), 0, st, s, dr, q, k, v, dO, lse,
+                           ws.D, dq, ws.dq_part, n_splits);
+        return hipGetLastError();
+    };
+    auto generic_dkv = [&](auto drop) -> hipError_t {
+        using C = DkvCfg<T, D>;
+        dim3 grid((s.l_x + C::BKV - 1) / C::BKV, s.B * s.H);
+        TimedLaunch tl(K_DKV, st);
+        hipLaunchKernelGGL((bwd_dkv_kernel<T, D, decltype(drop)::value>), grid, dim3(C::NT), 0, st, s, dr, q, k, v, dO, lse,
+                           ws.D, dk_part, dv_part);
+        return hipGetLastError();
+    };
+    if constexpr (sizeof(T) == 2) {
+        if (dr.thr != 0) {
+            // dropout: the pipelined dQ workgroups (which take D from out and dO themselves), then the
+            // general dK/dV kernel with its row-dot kernel in front
+            if ((e = launch_bwd_bf16_main(s, dr, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st)) != hipSuccess) return e;
+            if ((e = rowdot()) != hipSuccess) return e;
+            if ((e = generic_dkv(std::true_type{})) != hipSuccess) return e;
+        } else {
+            // The dQ workgroups share their launch with the dK/dV ones and need not fill the chip alone:
+            // keys are split only so far that a dQ workgroup (64 key tiles at most) does not outlast the
+            // rest of the launch.  Never more splits than the workspace was sized for.
+            const int64_t kv_extent = s.causal ? (s.s0 + s.l_s < s.l_x ? s.s0 + s.l_s : (int64_t)s.l_x) : (int64_t)s.l_x;
+            const int want = (int)((kv_extent + 64 * 64 - 1) / (64 * 64));
+            if (want < n_splits) n_splits = want < 1 ? 1 : want;
+            if ((e = launch_bwd_bf16_main(s, dr, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st)) != hipSuccess)
+                return e;
+        }
     } else {
-        if ((e = generic(std::false_type{})) != hipSuccess) return e;
+        if ((e = rowdot()) != hipSuccess) return e;
+        if (dr.thr != 0) {
+            if ((e = generic_dq(std::true_type{})) != hipSuccess) return e;
+            if ((e = generic_dkv(std::true_type{})) != hipSuccess) return e;
+        } else {
+            if ((e = generic_dq(std::false_type{})) != hipSuccess) return e;
+            if ((e = generic_dkv(std::false_type{})) != hipSuccess) return e;
+        }
     }
     if (n_splits > 1) {
         const int64_t n4 = (int64_t)s.B * s.l_s * s.H * D / 4;

@@ -37,8 +37,10 @@ struct DqBf16Cfg {
 // instructions of A(g+1) and C(g-1) with the vector work of B(g) spread between them, over a ring
 // of three K/V tiles that are loaded global -> LDS directly, a full loop iteration ahead.
 // D = rowsum(dO * out) of the wavefront's own rows is computed here.
-template <int D>
-__device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const bf16_t *__restrict__ q,
+// DROP: dropout on the weights (mask M = keep / (1 - p), decided by drop_keep() of (seed,
+// batch*head, global row, key)): dS = P * (M dP - D).
+template <int D, bool DROP>
+__device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const DropArgs &dr, const bf16_t *__restrict__ q,
                                             const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
                                             const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO,
                                             const float *__restrict__ lse, bf16_t *__restrict__ dq,
@@ -136,10 +138,16 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
         };
         // B for elements [e0, e1): P = 2^(c * S - lse * log2 e), dS = P * (dP - D); finished pairs are
         // rounded to bf16 into the operand fragments of C
-        auto b_elems = [&](f32x16 &sc, f32x16 &dp, int e0, int e1, Frag<bf16_t> (&df)[2]) __attribute__((always_inline)) {
+        DropKeys drop = {0u, 0u};
+        if (DROP) drop = drop_row_keys(dr.seed_lo, dr.seed_hi, (uint32_t)bh, (uint32_t)(s.s0 + r));
+        auto b_elems = [&](f32x16 &sc, f32x16 &dp, int jb, int e0, int e1, Frag<bf16_t> (&df)[2]) __attribute__((always_inline)) {
 #pragma unroll
             for (int e = e0; e < e1; ++e) {
                 const float p = fast_exp2(sc[e] * c - L2);
+                if (DROP) {     // dp holds dP - D; element e of this lane is key jb + 8 (e / 4) + 4 hh + e % 4
+                    const uint32_t key = (uint32_t)(jb + 8 * (e >> 2) + 4 * hh + (e & 3));
+                    dp[e] = drop_keep(drop, key, dr.thr) ? (dp[e] + Dr) * dr.scale - Dr : -Dr;
+                }
                 dp[e] = p * dp[e];
                 if (e & 1) { df[e >> 3].v[(e & 7) - 1] = (bf16_t)dp[e - 1]; df[e >> 3].v[e & 7] = (bf16_t)dp[e]; }
             }
@@ -179,7 +187,7 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
                 if (HB) {
                     const int e0 = slot * 16 / NS, e1 = (slot + 1) * 16 / NS;
                     __builtin_amdgcn_sched_barrier(0);
-                    b_elems(sc_b, dp_b, e0, e1, df_b);
+                    b_elems(sc_b, dp_b, jb_b, e0, e1, df_b);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             };
@@ -646,9 +654,9 @@ __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(SegShape s, const bf
 // out in XCD order (xcd_item): an XCD works on one head at a time, whose workgroups share that
 // head's K, V, Q and dO in its L2; within a head the longest workgroups come first (last query
 // tiles; first key tiles, the zero-fill ones last).
-template <int D>
+template <int D, bool DROP>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
-    SegShape s, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    SegShape s, DropArgs dr, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO, const float *__restrict__ lse,
     const float *__restrict__ Ls, const float *__restrict__ Dn, bf16_t *__restrict__ dq, float *__restrict__ dq_part,
     float *__restrict__ dk_part, float *__restrict__ dv_part, int n_splits, int n_dq, int n_q_tiles, int n_key_tiles)
@@ -661,22 +669,32 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     const int id = blockIdx.x;
     int bh, inner;
     if (id >= n_dq) {
-        if (!xcd_item(id - n_dq, bhs, n_key_tiles, bh, inner)) return;
-        bwd_dkv_body<D>(smem, s, q, k, v, dO, Ls, Dn, dk_part, dv_part, bh, inner);
+        if constexpr (!DROP) {      // (with dropout the launch holds the dQ workgroups only)
+            if (!xcd_item(id - n_dq, bhs, n_key_tiles, bh, inner)) return;
+            bwd_dkv_body<D>(smem, s, q, k, v, dO, Ls, Dn, dk_part, dv_part, bh, inner);
+        }
     } else {
         if (!xcd_item(id, bhs, n_q_tiles * n_splits, bh, inner)) return;
-        bwd_dq_body<D>(smem, s, q, k, v, out, dO, lse, dq, dq_part, n_splits, inner % n_q_tiles, n_q_tiles, bh,
-                       inner / n_q_tiles);
+        bwd_dq_body<D, DROP>(smem, s, dr, q, k, v, out, dO, lse, dq, dq_part, n_splits, inner % n_q_tiles, n_q_tiles, bh,
+                             inner / n_q_tiles);
     }
 }
 
 template <int D>
-static hipError_t launch_bwd_bf16_d(const SegShape &s, const bf16_t *q, const bf16_t *k, const bf16_t *v,
-                                    const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq,
+static hipError_t launch_bwd_bf16_d(const SegShape &s, const DropArgs &drop, const bf16_t *q, const bf16_t *k,
+                                    const bf16_t *v, const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq,
                                     float *dk_part, float *dv_part, const Workspace &ws, int n_splits,
                                     hipStream_t st)
 {
     hipError_t e;
+    if (drop.thr != 0) {    // dropout: the pipelined dQ workgroups only; the caller runs the general dK/dV kernel
+        const int n_q_tiles = (s.l_s + DqBf16Cfg<D>::BR - 1) / DqBf16Cfg<D>::BR;
+        const int n_dq = xcd_grid(s.B * s.H, n_q_tiles * n_splits);
+        TimedLaunch tl(K_DQ, st);
+        hipLaunchKernelGGL((bwd_main_bf16_kernel<D, true>), dim3((unsigned)n_dq), dim3(256), 0, st, s, drop, q, k, v, out,
+                           dO, lse, ws.Ls, ws.D, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, 0);
+        return hipGetLastError();
+    }
     {
         const int64_t items = (int64_t)s.B * s.l_s * s.H * (D / 8);
         TimedLaunch tl(K_ROWDOT, st);
@@ -689,20 +707,21 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const bf16_t *q, const bf
         const int n_key_tiles = (s.l_x + DkvBf16Cfg<D>::BKV - 1) / DkvBf16Cfg<D>::BKV;
         const int n_dq = xcd_grid(s.B * s.H, n_q_tiles * n_splits), n_dkv = xcd_grid(s.B * s.H, n_key_tiles);
         TimedLaunch tl(K_BWD_MAIN, st);
-        hipLaunchKernelGGL((bwd_main_bf16_kernel<D>), dim3((unsigned)(n_dkv + n_dq)), dim3(256), 0, st, s, q, k, v, out, dO,
+        hipLaunchKernelGGL((bwd_main_bf16_kernel<D, false>), dim3((unsigned)(n_dkv + n_dq)), dim3(256), 0, st, s, drop, q, k, v, out, dO,
                            lse, ws.Ls, ws.D, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-// accumulator start values, then dQ and dK/dV in one launch; the caller runs the dQ split merge
-hipError_t launch_bwd_bf16_main(const SegShape &s, const bf16_t *q, const bf16_t *k, const bf16_t *v,
-                                const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq, float *dk_part,
-                                float *dv_part, const Workspace &ws, int n_splits, hipStream_t st)
+// accumulator start values, then dQ and dK/dV in one launch (with dropout: dQ only); the caller
+// runs the dQ split merge
+hipError_t launch_bwd_bf16_main(const SegShape &s, const DropArgs &drop, const bf16_t *q, const bf16_t *k,
+                                const bf16_t *v, const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq,
+                                float *dk_part, float *dv_part, const Workspace &ws, int n_splits, hipStream_t st)
 {
-    if (s.d == 64) return launch_bwd_bf16_d<64>(s, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st);
-    return launch_bwd_bf16_d<128>(s, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st);
+    if (s.d == 64) return launch_bwd_bf16_d<64>(s, drop, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st);
+    return launch_bwd_bf16_d<128>(s, drop, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st);
 }
 
 } // namespace lss

@@ -233,13 +233,13 @@ static hipError_t launch_fwd_d(const SegShape &s, const DropArgs &drop, const T 
     }
     hipError_t e;
     const dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
-    if (drop.thr != 0) {        // dropout: the generic kernel, for both storage types
+    if constexpr (sizeof(T) == 2) {
+        e = launch_fwd_bf16_main(s, drop, q, k, v, out, lse, ws, n_splits, st);
+    } else if (drop.thr != 0) {
         TimedLaunch tl(K_FWD, st);
         hipLaunchKernelGGL((fwd_kernel<T, D, true>), grid, dim3(C::NT), 0, st, s, drop, q, k, v, out, lse, ws.o_part,
                            ws.lse_part, n_splits);
         e = hipGetLastError();
-    } else if constexpr (sizeof(T) == 2) {
-        e = launch_fwd_bf16_main(s, q, k, v, out, lse, ws, n_splits, st);
     } else {
         TimedLaunch tl(K_FWD, st);
         hipLaunchKernelGGL((fwd_kernel<T, D, false>), grid, dim3(C::NT), 0, st, s, drop, q, k, v, out, lse, ws.o_part,

@@ -34,8 +34,11 @@ struct FwdBf16Cfg {
     static constexpr float kMaxBlockSum = 256.0f;       // 2^8: largest sum of a lane's weights of one block without a fix-up
 };
 
-template <int D>
-__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape s, const bf16_t *__restrict__ q,
+// DROP: dropout on the weights (Section 2.2): the weight that multiplies V is dropped or scaled by
+// 1 / (1 - p) according to drop_keep() of (seed, batch*head, global row, key); row sum and lse are
+// those of the softmax.
+template <int D, bool DROP>
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape s, DropArgs dr, const bf16_t *__restrict__ q,
                                                                        const bf16_t *__restrict__ k,
                                                                        const bf16_t *__restrict__ v,
                                                                        bf16_t *__restrict__ out, float *__restrict__ lse,
@@ -137,21 +140,29 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
         // and rounded to bf16 into the operand fragment of C.
         // A row that has seen no key yet (m = -inf) subtracts a huge negative number instead, so that
         // any real score gives weight +inf and forces the fix-up, while masked scores still give 0.
-        auto b_elems = [&](const f32x16 &sc, float m_sub, int e0, int e1, float &psum, Frag<bf16_t> (&pf)[2])
+        DropKeys drop = {0u, 0u};
+        if (DROP) drop = drop_row_keys(dr.seed_lo, dr.seed_hi, (uint32_t)bh, (uint32_t)(s.s0 + r));
+        auto b_elems = [&](const f32x16 &sc, float m_sub, int jb, int e0, int e1, float &psum, Frag<bf16_t> (&pf)[2])
             __attribute__((always_inline)) {
 #pragma unroll
             for (int e = e0; e < e1; e += 2) {
                 const float p0 = fast_exp2(sc[e] * c - m_sub), p1 = fast_exp2(sc[e + 1] * c - m_sub);
-                pf[e >> 3].v[e & 7] = (bf16_t)p0; pf[e >> 3].v[(e & 7) + 1] = (bf16_t)p1;
                 psum += p0;
                 psum += p1;
+                if (DROP) {     // element e of this lane is key jb + 8 (e / 4) + 4 hh + e % 4
+                    const uint32_t key = (uint32_t)(jb + 8 * (e >> 2) + 4 * hh + (e & 3));
+                    pf[e >> 3].v[e & 7] = (bf16_t)(drop_keep(drop, key, dr.thr) ? p0 * dr.scale : 0.f);
+                    pf[e >> 3].v[(e & 7) + 1] = (bf16_t)(drop_keep(drop, key + 1, dr.thr) ? p1 * dr.scale : 0.f);
+                } else {
+                    pf[e >> 3].v[e & 7] = (bf16_t)p0; pf[e >> 3].v[(e & 7) + 1] = (bf16_t)p1;
+                }
             }
         };
         auto m_sub_of = [](float mm) { return mm == -INFINITY ? -1e30f : mm; };
         // The fix-up: raise m to the exact maximum over what the row has seen including this block,
         // rescale what was accumulated under the old m (row sum l0 before this block; accumulator,
         // to which this block has not been added yet) and redo the block's weights.
-        auto fixup = [&](const f32x16 &sc, float l0, Frag<bf16_t> (&pf)[2]) __attribute__((always_inline)) {
+        auto fixup = [&](const f32x16 &sc, int jb, float l0, Frag<bf16_t> (&pf)[2]) __attribute__((always_inline)) {
             float mx = -INFINITY;
 #pragma unroll
             for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sc[e]);
@@ -164,7 +175,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
             for (int db = 0; db < D / 32; ++db)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
-            b_elems(sc, m_sub_of(m), 0, 16, l, pf);
+            b_elems(sc, m_sub_of(m), jb, 0, 16, l, pf);
         };
 
         // One pipeline step.  A: block (tile_a, kb2_a) into sc_a.  B: sc_b, first key jb_b, packing
@@ -188,7 +199,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
                 if (HB) {
                     const int e0 = 2 * (slot * 8 / NS), e1 = 2 * ((slot + 1) * 8 / NS);
                     __builtin_amdgcn_sched_barrier(0);
-                    b_elems(sc_b, m_sub, e0, e1, l, pf_b);
+                    b_elems(sc_b, m_sub, jb_b, e0, e1, l, pf_b);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             };
@@ -224,7 +235,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
             if (HB) {
                 // ... and its results through another one, so that it is not sunk below the step either
                 asm volatile("" : "+v"(pf_b[0].v), "+v"(pf_b[1].v), "+v"(l));
-                if (__any(!(l - l0 <= C::kMaxBlockSum))) fixup(sc_b, l0, pf_b);
+                if (__any(!(l - l0 <= C::kMaxBlockSum))) fixup(sc_b, jb_b, l0, pf_b);
             }
         };
         using std::true_type;
@@ -309,23 +320,27 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
 int fwd_bf16_rows_per_workgroup(int d) { return d == 64 ? FwdBf16Cfg<64>::BR : FwdBf16Cfg<128>::BR; }
 
 template <int D>
-static hipError_t launch_fwd_main(const SegShape &s, const bf16_t *q, const bf16_t *k, const bf16_t *v, bf16_t *out,
-                                  float *lse, const Workspace &ws, int n_splits, hipStream_t st)
+static hipError_t launch_fwd_main(const SegShape &s, const DropArgs &drop, const bf16_t *q, const bf16_t *k,
+                                  const bf16_t *v, bf16_t *out, float *lse, const Workspace &ws, int n_splits, hipStream_t st)
 {
     using C = FwdBf16Cfg<D>;
     const int n_q_tiles = (s.l_s + C::BR - 1) / C::BR;
     dim3 grid((unsigned)xcd_grid(s.B * s.H, n_q_tiles * n_splits));
     TimedLaunch tl(K_FWD, st);
-    hipLaunchKernelGGL((fwd_bf16_kernel<D>), grid, dim3(C::NT), 0, st, s, q, k, v, out, lse, ws.o_part, ws.lse_part,
-                       n_splits, n_q_tiles);
+    if (drop.thr != 0)
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, true>), grid, dim3(C::NT), 0, st, s, drop, q, k, v, out, lse, ws.o_part,
+                           ws.lse_part, n_splits, n_q_tiles);
+    else
+        hipLaunchKernelGGL((fwd_bf16_kernel<D, false>), grid, dim3(C::NT), 0, st, s, drop, q, k, v, out, lse, ws.o_part,
+                           ws.lse_part, n_splits, n_q_tiles);
     return hipGetLastError();
 }
 
-hipError_t launch_fwd_bf16_main(const SegShape &s, const bf16_t *q, const bf16_t *k, const bf16_t *v, bf16_t *out,
-                                float *lse, const Workspace &ws, int n_splits, hipStream_t st)
+hipError_t launch_fwd_bf16_main(const SegShape &s, const DropArgs &drop, const bf16_t *q, const bf16_t *k,
+                                const bf16_t *v, bf16_t *out, float *lse, const Workspace &ws, int n_splits, hipStream_t st)
 {
-    if (s.d == 64) return launch_fwd_main<64>(s, q, k, v, out, lse, ws, n_splits, st);
-    return launch_fwd_main<128>(s, q, k, v, out, lse, ws, n_splits, st);
+    if (s.d == 64) return launch_fwd_main<64>(s, drop, q, k, v, out, lse, ws, n_splits, st);
+    return launch_fwd_main<128>(s, drop, q, k, v, out, lse, ws, n_splits, st);
 }
 
 } // namespace lss

@@ -56,14 +56,14 @@ hipError_t launch_bwd(const SegShape &s, const DropArgs &drop, const T *q, const
 
 // tuned bf16 kernels (lss_fwd_bf16.hip)
 int fwd_bf16_rows_per_workgroup(int d);
-hipError_t launch_fwd_bf16_main(const SegShape &s, const bf16_t *q, const bf16_t *k, const bf16_t *v, bf16_t *out,
-                                float *lse, const Workspace &ws, int n_splits, hipStream_t st);
+hipError_t launch_fwd_bf16_main(const SegShape &s, const DropArgs &drop, const bf16_t *q, const bf16_t *k,
+                                const bf16_t *v, bf16_t *out, float *lse, const Workspace &ws, int n_splits, hipStream_t st);
 
 // tuned bf16 kernels (lss_bwd_bf16.hip): dQ kernel (also writes D = rowsum(dO * out)) then dK/dV kernel
 int dq_bf16_rows_per_workgroup(int d);
-hipError_t launch_bwd_bf16_main(const SegShape &s, const bf16_t *q, const bf16_t *k, const bf16_t *v,
-                                const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq, float *dk_part,
-                                float *dv_part, const Workspace &ws, int n_splits, hipStream_t st);
+hipError_t launch_bwd_bf16_main(const SegShape &s, const DropArgs &drop, const bf16_t *q, const bf16_t *k,
+                                const bf16_t *v, const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq,
+                                float *dk_part, float *dv_part, const Workspace &ws, int n_splits, hipStream_t st);
 
 // Optional per-kernel timing for benchmarks: when enabled, every launch site brackets its
 // kernel with a pair of HIP events on the launch stream.
