@@ -235,8 +235,13 @@ int lss_oracle_reduce_partials(const double *const *parts, int n, int64_t n_elem
  * outputs still concatenate to the full-sequence result (Section 3,
  * Principle 3).  It is a counter-based generator built from a published
  * 32-bit integer mixing function (two multiply-xorshift rounds), not a
- * stream: nothing depends on the order of evaluation.  The HIP library
- * implements the same function on its side.
+ * stream: nothing depends on the order of evaluation.  The random number of
+ * a weight is mix(row key + column key): the row key mixes the low half of
+ * the seed, the batch*head index and the row; the column key mixes the high
+ * half of the seed and the column.  (Separable on purpose: a kernel in which
+ * a lane owns a row keeps the row key in a register, one in which a lane owns
+ * a key keeps the column key.)  The HIP library implements the same function
+ * on its side.
  * ------------------------------------------------------------------------ */
 static uint32_t mix32(uint32_t x)
 {
@@ -245,22 +250,23 @@ static uint32_t mix32(uint32_t x)
     x ^= x >> 16;
     return x;
 }
-/* the two 32-bit keys of one (seed, batch*head, global row) */
-static void row_keys(uint64_t seed, uint32_t bh, uint32_t row, uint32_t *k1, uint32_t *k2)
+static uint32_t row_key(uint64_t seed, uint32_t bh, uint32_t row)
 {
-    const uint32_t a = mix32((uint32_t)seed + 0x9e3779b9U * (bh + 1U));
-    *k1 = mix32(a ^ row);
-    *k2 = mix32(*k1 + (uint32_t)(seed >> 32) + 0x85ebca6bU);
+    return mix32(mix32((uint32_t)seed + 0x9e3779b9U * (bh + 1U)) ^ row);
+}
+static uint32_t col_key(uint64_t seed, uint32_t col)
+{
+    return mix32(mix32((uint32_t)(seed >> 32) + 0x85ebca6bU) ^ col);
 }
 static uint32_t drop_threshold(double p)
 {
     const double t = floor(p * 4294967296.0 + 0.5);
     return t >= 4294967295.0 ? 4294967295U : (t <= 0.0 ? 0U : (uint32_t)t);
 }
-/* 1 if the weight at key position col is kept */
-static int keep(uint32_t k1, uint32_t k2, uint32_t col, uint32_t thr)
+/* 1 if the weight of (row key rk, key position col) is kept */
+static int keep(uint32_t rk, uint64_t seed, uint32_t col, uint32_t thr)
 {
-    return mix32(mix32(col ^ k1) + k2) >= thr;
+    return mix32(rk + col_key(seed, col)) >= thr;
 }
 
 /* keep mask of one segment: mask [B, H, l_s, l_x] bytes (1 = kept), all key positions */
@@ -271,9 +277,8 @@ int lss_oracle_dropout_mask(double p, uint64_t seed, int64_t s0, int64_t l_s, in
     const uint32_t thr = drop_threshold(p);
     for (int64_t bh = 0; bh < B * H; ++bh)
         for (int64_t r = 0; r < l_s; ++r) {
-            uint32_t k1, k2;
-            row_keys(seed, (uint32_t)bh, (uint32_t)(s0 + r), &k1, &k2);
-            for (int64_t j = 0; j < l_x; ++j) mask[(bh * l_s + r) * l_x + j] = (unsigned char)keep(k1, k2, (uint32_t)j, thr);
+            const uint32_t rk = row_key(seed, (uint32_t)bh, (uint32_t)(s0 + r));
+            for (int64_t j = 0; j < l_x; ++j) mask[(bh * l_s + r) * l_x + j] = (unsigned char)keep(rk, seed, (uint32_t)j, thr);
         }
     return 0;
 }
@@ -296,12 +301,11 @@ int lss_oracle_segment_fwd_dropout(const double *q_seg, const double *k, const d
             const int64_t nj = visible(s0, r, l_x, causal);
             const double *q_row = q_seg + IDX4(b, r, h, 0, l_s, H, d);
             lse[(b * H + h) * l_s + r] = row_softmax(q_row, k, b, h, l_x, H, d, nj, P);
-            uint32_t k1, k2;
-            row_keys(seed, (uint32_t)(b * H + h), (uint32_t)(s0 + r), &k1, &k2);
+            const uint32_t rk = row_key(seed, (uint32_t)(b * H + h), (uint32_t)(s0 + r));
             double *o_row = out + IDX4(b, r, h, 0, l_s, H, d);
             for (int64_t c = 0; c < d; ++c) o_row[c] = 0.0;
             for (int64_t j = 0; j < nj; ++j) {
-                if (!keep(k1, k2, (uint32_t)j, thr)) continue;
+                if (!keep(rk, seed, (uint32_t)j, thr)) continue;
                 const double w = P[j] * inv_keep;
                 const double *v_row = v + IDX4(b, j, h, 0, l_x, H, d);
                 for (int64_t c = 0; c < d; ++c) o_row[c] += w * v_row[c];
@@ -340,21 +344,20 @@ int lss_oracle_segment_bwd_dropout(const double *q_seg, const double *k, const d
                 const double *q_row = q_seg + IDX4(b, r, h, 0, l_s, H, d);
                 const double *do_row = dO + IDX4(b, r, h, 0, l_s, H, d);
                 row_softmax(q_row, k, b, h, l_x, H, d, nj, AM);     /* AM holds A for now */
-                uint32_t k1, k2;
-                row_keys(seed, (uint32_t)(b * H + h), (uint32_t)(s0 + r), &k1, &k2);
+                const uint32_t rk = row_key(seed, (uint32_t)(b * H + h), (uint32_t)(s0 + r));
                 double D = 0.0;
                 for (int64_t j = 0; j < nj; ++j) {
                     const double *v_row = v + IDX4(b, j, h, 0, l_x, H, d);
                     double dp = 0.0;
                     for (int64_t c = 0; c < d; ++c) dp += do_row[c] * v_row[c];
-                    const double mj = keep(k1, k2, (uint32_t)j, thr) ? inv_keep : 0.0;
+                    const double mj = keep(rk, seed, (uint32_t)j, thr) ? inv_keep : 0.0;
                     dS[j] = mj * dp;                                 /* dA[j] */
                     D += AM[j] * dS[j];
                 }
                 for (int64_t j = 0; j < nj; ++j) {
                     const double a = AM[j];
                     dS[j] = a * (dS[j] - D);
-                    AM[j] = keep(k1, k2, (uint32_t)j, thr) ? a * inv_keep : 0.0;
+                    AM[j] = keep(rk, seed, (uint32_t)j, thr) ? a * inv_keep : 0.0;
                 }
                 for (int64_t j = nj; j < l_x; ++j) { AM[j] = 0.0; dS[j] = 0.0; }
                 double *dq_row = dq + IDX4(b, r, h, 0, l_s, H, d);

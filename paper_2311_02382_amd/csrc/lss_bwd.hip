@@ -94,8 +94,8 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(SegShape s, DropArgs dr, co
     const float L2 = row_ok ? lse[(int64_t)bh * s.l_s + r] * kLog2e : INFINITY;
     const float Dr = row_ok ? Dv[(int64_t)bh * s.l_s + r] : 0.f;
     const float c = kLog2e / sqrtf((float)D);
-    DropKeys drop = {0u, 0u};
-    if (DROP) drop = drop_row_keys(dr.seed_lo, dr.seed_hi, (uint32_t)bh, (uint32_t)g);
+    uint32_t drop_rk = 0u, drop_cs = 0u;
+    if (DROP) { drop_rk = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)g); drop_cs = drop_col_seed(dr.seed_hi); }
 
     f32x16 acc[D / 32];
 #pragma unroll
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void bwd_dq_kernel(SegShape s, DropArgs dr, co
                 float dpe = dp[e];
                 if (DROP) {
                     const int key = j0 + kb2 * 32 + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    dpe = drop_keep(drop, (uint32_t)key, dr.thr) ? dpe * dr.scale : 0.f;
+                    dpe = drop_keep(drop_rk, drop_col_key(drop_cs, (uint32_t)key), dr.thr) ? dpe * dr.scale : 0.f;
                 }
                 ds[kb2][e] = p * (dpe - Dr);
             }
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, DropArgs dr, c
     __shared__ __attribute__((aligned(16))) T sGt[D * C::TP];
     __shared__ __attribute__((aligned(16))) float sL[C::BQ];
     __shared__ __attribute__((aligned(16))) float sD[C::BQ];
-    __shared__ __attribute__((aligned(16))) uint32_t sK1[DROP ? C::BQ : 4], sK2[DROP ? C::BQ : 4];   // dropout keys of the tile's rows
+    __shared__ __attribute__((aligned(16))) uint32_t sRK[DROP ? C::BQ : 4];     // dropout: row keys of the tile's rows
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int bh = blockIdx.y, b = bh / s.H, h = bh % s.H;
@@ -225,6 +225,8 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, DropArgs dr, c
     const bool key_ok = j < s.l_x;
     const int64_t ld = (int64_t)s.H * D;
     const int64_t kv_off = ((int64_t)b * s.l_x + j) * ld + (int64_t)h * D;
+
+    const uint32_t drop_ck = DROP ? drop_col_key(drop_col_seed(dr.seed_hi), (uint32_t)j) : 0u;   // dropout: this lane's column key
 
     // first query row that sees any key of this tile
     int rq_begin = 0;
@@ -262,11 +264,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, DropArgs dr, c
                 // rows past the segment: lse = +inf makes P (hence dS) exactly 0
                 sL[tid] = rr < s.l_s ? lse[(int64_t)bh * s.l_s + rr] * kLog2e : INFINITY;
                 sD[tid] = rr < s.l_s ? Dv[(int64_t)bh * s.l_s + rr] : 0.f;
-                if (DROP) {
-                    const DropKeys kk = drop_row_keys(dr.seed_lo, dr.seed_hi, (uint32_t)bh, (uint32_t)(s.s0 + rr));
-                    sK1[tid] = kk.k1;
-                    sK2[tid] = kk.k2;
-                }
+                if (DROP) sRK[tid] = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)(s.s0 + rr));
             }
             __syncthreads();
 
@@ -297,8 +295,7 @@ __global__ __launch_bounds__(256) void bwd_dkv_kernel(SegShape s, DropArgs dr, c
                         if (diag && (int64_t)j > s.s0 + rq0 + rl + i) p = 0.f;
                         float pv = p, dpe = dp[e];
                         if (DROP) {
-                            const DropKeys kk = {sK1[rl + i], sK2[rl + i]};
-                            const float mk = drop_keep(kk, (uint32_t)j, dr.thr) ? dr.scale : 0.f;
+                            const float mk = drop_keep(sRK[rl + i], drop_ck, dr.thr) ? dr.scale : 0.f;
                             pv = p * mk;
                             dpe *= mk;
                         }

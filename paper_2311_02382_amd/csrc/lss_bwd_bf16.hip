@@ -138,15 +138,15 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
         };
         // B for elements [e0, e1): P = 2^(c * S - lse * log2 e), dS = P * (dP - D); finished pairs are
         // rounded to bf16 into the operand fragments of C
-        DropKeys drop = {0u, 0u};
-        if (DROP) drop = drop_row_keys(dr.seed_lo, dr.seed_hi, (uint32_t)bh, (uint32_t)(s.s0 + r));
+        uint32_t drop_rk = 0u, drop_cs = 0u;            // dropout: this lane's row key; the column seed
+        if (DROP) { drop_rk = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)(s.s0 + r)); drop_cs = drop_col_seed(dr.seed_hi); }
         auto b_elems = [&](f32x16 &sc, f32x16 &dp, int jb, int e0, int e1, Frag<bf16_t> (&df)[2]) __attribute__((always_inline)) {
 #pragma unroll
             for (int e = e0; e < e1; ++e) {
                 const float p = fast_exp2(sc[e] * c - L2);
                 if (DROP) {     // dp holds dP - D; element e of this lane is key jb + 8 (e / 4) + 4 hh + e % 4
                     const uint32_t key = (uint32_t)(jb + 8 * (e >> 2) + 4 * hh + (e & 3));
-                    dp[e] = drop_keep(drop, key, dr.thr) ? (dp[e] + Dr) * dr.scale - Dr : -Dr;
+                    dp[e] = drop_keep(drop_rk, drop_col_key(drop_cs, key), dr.thr) ? (dp[e] + Dr) * dr.scale - Dr : -Dr;
                 }
                 dp[e] = p * dp[e];
                 if (e & 1) { df[e >> 3].v[(e & 7) - 1] = (bf16_t)dp[e - 1]; df[e >> 3].v[e & 7] = (bf16_t)dp[e]; }

@@ -104,27 +104,29 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 // Dropout on the attention weights (Section 2.2), decided per weight from its position in the whole
 // sequence, so that a segment drops what the sequential computation would drop there (Section 3,
-// Principle 3): the weight of (batch*head bh, global query row, key col) is kept when a 32-bit
-// number derived from (seed, bh, row, col) alone is >= the threshold round(p * 2^32).  The number
-// comes from a published 32-bit mixing function (xorshift-multiply, two rounds) applied to the
-// column under two keys of the row; no state, no stream.
-struct DropKeys { uint32_t k1, k2; };
+// Principle 3): the weight of (batch*head bh, global query row, key col) is kept when
+//     mix32(row key + column key) >= round(p * 2^32),
+// where the row key mixes (low half of the seed, bh, row) and the column key (high half of the seed,
+// col); mix32 is a published 32-bit mixing function (xorshift-multiply, two rounds).  No state, no
+// stream.  The split into a row and a column key is what a kernel needs: one whose lanes own query
+// rows keeps a row key per lane, one whose lanes own keys a column key per lane, and the other key
+// of a tile's 64 rows or columns is computed once per tile.
 __device__ __forceinline__ uint32_t mix32(uint32_t x)
 {
     x = (x ^ (x >> 16)) * 0x7feb352du;
     x = (x ^ (x >> 15)) * 0x846ca68bu;
     return x ^ (x >> 16);
 }
-__device__ __forceinline__ DropKeys drop_row_keys(uint32_t seed_lo, uint32_t seed_hi, uint32_t bh, uint32_t row)
+__device__ __forceinline__ uint32_t drop_row_key(uint32_t seed_lo, uint32_t bh, uint32_t row)
 {
-    DropKeys k;
-    k.k1 = mix32(mix32(seed_lo + 0x9e3779b9u * (bh + 1u)) ^ row);
-    k.k2 = mix32(k.k1 + seed_hi + 0x85ebca6bu);
-    return k;
+    return mix32(mix32(seed_lo + 0x9e3779b9u * (bh + 1u)) ^ row);
 }
-__device__ __forceinline__ bool drop_keep(DropKeys k, uint32_t col, uint32_t thr)
+// `cs` = drop_col_seed(seed_hi), the same for every column
+__device__ __forceinline__ uint32_t drop_col_seed(uint32_t seed_hi) { return mix32(seed_hi + 0x85ebca6bu); }
+__device__ __forceinline__ uint32_t drop_col_key(uint32_t cs, uint32_t col) { return mix32(cs ^ col); }
+__device__ __forceinline__ bool drop_keep(uint32_t row_key, uint32_t col_key, uint32_t thr)
 {
-    return mix32(mix32(col ^ k.k1) + k.k2) >= thr;
+    return mix32(row_key + col_key) >= thr;
 }
 
 template <typename T> struct Elems16 { static constexpr int n = 16 / sizeof(T); };

@@ -61,8 +61,8 @@ __global__ __launch_bounds__(256) void fwd_kernel(SegShape s, DropArgs dr, const
         for (int e = 0; e < 16; ++e) o[db][e] = 0.f;
     float m = -INFINITY, l = 0.f;               // running max (log2 domain) and sum, per query
     const float c = kLog2e / sqrtf((float)D);   // score -> log2 domain
-    DropKeys drop = {0u, 0u};                   // dropout: the keys of this lane's global row
-    if (DROP) drop = drop_row_keys(dr.seed_lo, dr.seed_hi, (uint32_t)bh, (uint32_t)g);
+    uint32_t drop_rk = 0u, drop_cs = 0u;        // dropout: the key of this lane's global row; the column seed
+    if (DROP) { drop_rk = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)g); drop_cs = drop_col_seed(dr.seed_hi); }
 
     const T *kbase = k + (int64_t)b * s.l_x * ld + (int64_t)h * D;
     const T *vbase = v + (int64_t)b * s.l_x * ld + (int64_t)h * D;
@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void fwd_kernel(SegShape s, DropArgs dr, const
                 psum += p;          // the row sum (hence lse and the normalisation) is that of the softmax
                 if (DROP) {         // the weight that multiplies V is dropped or scaled by 1 / (1 - p_drop)
                     const int key = j0 + kb2 * 32 + 8 * (e >> 2) + 4 * hh + (e & 3);
-                    sc[kb2][e] = drop_keep(drop, (uint32_t)key, dr.thr) ? p * dr.scale : 0.f;
+                    sc[kb2][e] = drop_keep(drop_rk, drop_col_key(drop_cs, (uint32_t)key), dr.thr) ? p * dr.scale : 0.f;
                 } else {
                     sc[kb2][e] = p;
                 }

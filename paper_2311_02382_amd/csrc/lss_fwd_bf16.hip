@@ -140,8 +140,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
         // and rounded to bf16 into the operand fragment of C.
         // A row that has seen no key yet (m = -inf) subtracts a huge negative number instead, so that
         // any real score gives weight +inf and forces the fix-up, while masked scores still give 0.
-        DropKeys drop = {0u, 0u};
-        if (DROP) drop = drop_row_keys(dr.seed_lo, dr.seed_hi, (uint32_t)bh, (uint32_t)(s.s0 + r));
+        uint32_t drop_rk = 0u, drop_cs = 0u;            // dropout: this lane's row key; the column seed
+        if (DROP) { drop_rk = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)(s.s0 + r)); drop_cs = drop_col_seed(dr.seed_hi); }
         auto b_elems = [&](const f32x16 &sc, float m_sub, int jb, int e0, int e1, float &psum, Frag<bf16_t> (&pf)[2])
             __attribute__((always_inline)) {
 #pragma unroll
@@ -151,8 +151,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape
                 psum += p1;
                 if (DROP) {     // element e of this lane is key jb + 8 (e / 4) + 4 hh + e % 4
                     const uint32_t key = (uint32_t)(jb + 8 * (e >> 2) + 4 * hh + (e & 3));
-                    pf[e >> 3].v[e & 7] = (bf16_t)(drop_keep(drop, key, dr.thr) ? p0 * dr.scale : 0.f);
-                    pf[e >> 3].v[(e & 7) + 1] = (bf16_t)(drop_keep(drop, key + 1, dr.thr) ? p1 * dr.scale : 0.f);
+                    pf[e >> 3].v[e & 7] = (bf16_t)(drop_keep(drop_rk, drop_col_key(drop_cs, key), dr.thr) ? p0 * dr.scale : 0.f);
+                    pf[e >> 3].v[(e & 7) + 1] = (bf16_t)(drop_keep(drop_rk, drop_col_key(drop_cs, key + 1), dr.thr) ? p1 * dr.scale : 0.f);
                 } else {
                     pf[e >> 3].v[e & 7] = (bf16_t)p0; pf[e >> 3].v[(e & 7) + 1] = (bf16_t)p1;
                 }
