@@ -232,8 +232,7 @@ def main() -> int:
     flops_fa = 14.0 * pairs * w.d
     # projections: 2 flops per multiply-add of Q_i, K, V and of dx_q, dx_partial (rows that hold data)
     proj_flops = {"proj_fwd_kernel": sum(2.0 * w.B * E * (2 * E * w.l_x + E * l_s) for _ in offs),
-                  "proj_bwd_kernel": sum(2.0 * w.B * E * 2 * E * rv for rv in rows_valid),
-                  "proj_bwd_q_kernel": sum(2.0 * w.B * E * E * l_s for _ in offs)}
+                  "proj_bwd_kernel": sum(2.0 * w.B * E * (2 * E * rv + E * l_s) for rv in rows_valid)}
     flops_proj = sum(proj_flops.values()) if args.projections else 0.0
     value = (flops_strict + flops_proj) / (ms_per_step * 1e-3) / 1e12
 

@@ -67,7 +67,7 @@ hipError_t launch_bwd_bf16_main(const SegShape &s, const DropArgs &drop, const b
 
 // Optional per-kernel timing for benchmarks: when enabled, every launch site brackets its
 // kernel with a pair of HIP events on the launch stream.
-enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_BWD_MAIN, K_PROJ_FWD, K_PROJ_BWD, K_PROJ_BWD_Q, K_COUNT };
+enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_BWD_MAIN, K_PROJ_FWD, K_PROJ_BWD, K_COUNT };
 void timing_begin(int id, hipStream_t st);
 void timing_end(int id, hipStream_t st);
 struct TimedLaunch {    // RAII bracket around one kernel launch

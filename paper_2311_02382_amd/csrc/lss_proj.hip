@@ -17,8 +17,9 @@
 //   W_TR   weights stored [k][n] (forward: W as given).  Their fragments come from the LDS tile
 //          by transposing reads; otherwise the weights are stored [n][k] (backward: W as given
 //          IS W'^T) and are read plainly.
-//   A_F32  A is float (the dK/dV partials): rounded to bf16 on the way into LDS, through
-//          registers; the contraction index runs over dK's columns, then dV's.
+//   A_ANY  a job's A may be float (the dK/dV partials; `a_f32` of the job): rounded to bf16 on the
+//          way into LDS, through registers; the contraction index runs over dK's columns, then
+//          dV's.  Jobs with bf16 A (dQ) share the launch.
 #include "lss_bf16.h"
 #include "lss_kernels.h"
 
@@ -41,6 +42,7 @@ struct ProjJob {
     int64_t a_batch_stride, c_batch_stride;     // elements
     int rows, rows_ok;          // rows per batch; leading rows of A that hold data (the rest count as 0)
     int batches, N, K, k_split, n_split, ldw;
+    int a_f32;                  // A is float (only in kernels compiled with A_ANY)
     int wg_begin, m_tiles, n_tiles;             // first workgroup id of the job, tiles per batch, column tiles
 };
 struct ProjArgs {
@@ -91,11 +93,11 @@ struct WTileTr {
     }
 };
 
-template <bool A_F32, bool W_TR>
+template <bool A_ANY, bool W_TR>
 __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    using OutT = typename std::conditional<A_F32 || !W_TR, float, bf16_t>::type;     // backward maps write float
+    using OutT = typename std::conditional<!W_TR, float, bf16_t>::type;     // backward maps write float
     constexpr bool OUT_F32 = std::is_same<OutT, float>::value;
 
     const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
@@ -189,12 +191,13 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
 
     // ---- tile loads
     uint32_t offA[ATile::NI], offW[W_TR ? WTileTr::NI : WTile::NI];
-    if constexpr (!A_F32) ATile::offsets(offA, args.lda, rows_data, wave, lane);
+    const bool a_f32 = A_ANY && J.a_f32 != 0;   // workgroup-uniform
+    ATile::offsets(offA, args.lda, rows_data, wave, lane);
     if constexpr (W_TR) WTileTr::offsets(offW, J.ldw, wave, lane, cols_here / 8);
     else WTile::offsets(offW, J.ldw, cols_here, wave, lane);
 
     const char *a0 = static_cast<const char *>(J.a0), *a1 = static_cast<const char *>(J.a1);
-    constexpr int AE = A_F32 ? 4 : 2;           // bytes per element of A
+    const int AE = a_f32 ? 4 : 2;               // bytes per element of A
     const int64_t a_tile0 = ((int64_t)batch * J.a_batch_stride + (int64_t)m0 * args.lda) * AE;
     auto a_src = [&](int t) -> const char * {   // first element of contraction tile t of this row tile
         return (t < t_split ? a0 + (int64_t)t * PK * AE : a1 + (int64_t)(t - t_split) * PK * AE) + a_tile0;
@@ -214,9 +217,9 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
     // float A: thread `tid` converts the 8-element chunks tid, tid + 512, ... of the tile
     // (chunk c is columns 8 (c % 8) .. + 7 of row c / 8) and writes them where the direct load would
     constexpr int FCH = PM * 8 / P_NT;          // chunks per thread
-    f32x4 stage[A_F32 ? 2 * FCH : 1];
+    f32x4 stage[A_ANY ? 2 * FCH : 1];
     auto fetch_a = [&](int t) {
-        if constexpr (A_F32) {
+        if constexpr (A_ANY) {
             const char *src = a_src(t);
 #pragma unroll
             for (int i = 0; i < FCH; ++i) {
@@ -228,7 +231,7 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
         }
     };
     auto stash_a = [&](int slot) {
-        if constexpr (A_F32) {
+        if constexpr (A_ANY) {
             char *dst = smem + slot * P_SLOT;
 #pragma unroll
             for (int i = 0; i < FCH; ++i) {
@@ -291,7 +294,7 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
 
     // ---- main loop: tile t is multiplied from slot t % 2 while tile t + 1 travels into the other slot
     // (last read during tile t - 1, which every wavefront left at the barrier)
-    if constexpr (A_F32) {
+    if (a_f32) {
         fetch_a(0);
         issue_w(0, 0);
         stash_a(0);
@@ -322,7 +325,7 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
     store_tiles(acc, true);
 }
 
-template <bool A_F32, bool W_TR>
+template <bool A_ANY, bool W_TR>
 hipError_t launch_proj(ProjArgs &args, int kernel_id, hipStream_t st)
 {
     int wgs = 0;
@@ -337,12 +340,12 @@ hipError_t launch_proj(ProjArgs &args, int kernel_id, hipStream_t st)
     static std::once_flag once;
     static hipError_t attr = hipSuccess;
     std::call_once(once, [] {
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(proj_gemm_kernel<A_F32, W_TR>),
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(proj_gemm_kernel<A_ANY, W_TR>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
     });
     if (attr != hipSuccess) return attr;
     TimedLaunch tl(kernel_id, st);
-    hipLaunchKernelGGL((proj_gemm_kernel<A_F32, W_TR>), dim3(wgs), dim3(P_NT), P_LDS, st, args);
+    hipLaunchKernelGGL((proj_gemm_kernel<A_ANY, W_TR>), dim3(wgs), dim3(P_NT), P_LDS, st, args);
     return hipGetLastError();
 }
 
@@ -377,33 +380,28 @@ hipError_t launch_project_bwd(const bf16_t *dq, const float *dk_part, const floa
                               const bf16_t *w_kv, int l_s, int l_x, int rows_valid, int B, int E, int skip_tail,
                               float *dx_q, float *dx_part, hipStream_t st)
 {
+    ProjArgs args{};
+    args.lda = args.ldc = E;
+    args.skip_tail = skip_tail;
+    int n = 0;
     {   // dx_partial = dK_part W_k^T + dV_part W_v^T: one contraction over the 2E columns of [dK | dV]
-        ProjArgs args{};
-        args.lda = args.ldc = E;
-        args.skip_tail = skip_tail;
-        ProjJob &J = args.job[0];
+        ProjJob &J = args.job[n++];
         J.a0 = dk_part; J.a1 = dv_part; J.w = w_kv; J.c0 = dx_part; J.c1 = nullptr;
         J.a_batch_stride = J.c_batch_stride = (int64_t)l_x * E;
         J.rows = l_x; J.rows_ok = rows_valid; J.batches = B;
         J.N = E; J.K = 2 * E; J.k_split = E; J.n_split = E; J.ldw = 2 * E;
-        args.n_jobs = 1;
-        const hipError_t e = launch_proj<true, false>(args, K_PROJ_BWD, st);
-        if (e != hipSuccess) return e;
+        J.a_f32 = 1;
     }
-    if (l_s > 0) {  // dx_q = dQ_i W_q^T
-        ProjArgs args{};
-        args.lda = args.ldc = E;
-        args.skip_tail = 0;
-        ProjJob &J = args.job[0];
+    if (l_s > 0) {  // dx_q = dQ_i W_q^T, in the same launch
+        ProjJob &J = args.job[n++];
         J.a0 = dq; J.a1 = nullptr; J.w = w_q; J.c0 = dx_q; J.c1 = nullptr;
         J.a_batch_stride = J.c_batch_stride = (int64_t)l_s * E;
         J.rows = J.rows_ok = l_s; J.batches = B;
         J.N = E; J.K = E; J.k_split = E; J.n_split = E; J.ldw = E;
-        args.n_jobs = 1;
-        const hipError_t e = launch_proj<false, false>(args, K_PROJ_BWD_Q, st);
-        if (e != hipSuccess) return e;
+        J.a_f32 = 0;
     }
-    return hipSuccess;
+    args.n_jobs = n;
+    return launch_proj<true, false>(args, K_PROJ_BWD, st);
 }
 
 } // namespace lss

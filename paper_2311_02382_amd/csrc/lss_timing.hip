@@ -22,7 +22,7 @@ int64_t g_count[K_COUNT] = {0};
 
 const char *const kNames[K_COUNT] = {"fwd_kernel", "fwd_merge_kernel", "bwd_rowdot_kernel", "bwd_dq_kernel",
                                      "bwd_dq_merge_kernel", "bwd_dkv_kernel", "reduce_partials_kernel",
-                                     "bwd_main_kernel", "proj_fwd_kernel", "proj_bwd_kernel", "proj_bwd_q_kernel"};
+                                     "bwd_main_kernel", "proj_fwd_kernel", "proj_bwd_kernel"};
 
 hipEvent_t get_event()
 {
