@@ -147,3 +147,23 @@ def test_dropout_argument_checks(lib):
                0x8000, 0x9000, None) == -5
     assert bwd(0x1000, 0x2000, 0x3000, 0, 128, 256, 1, 1, 64, 1, 0.5, 7, 2, 0x4000, 0x5000, 0x6000, 0x7000,
                0x8000, 0x9000, None) == -6
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    # no library, no result: the binding has no other path to fall back on
+    monkeypatch.setattr(lss, "_lib", None)
+    monkeypatch.setattr(lss, "LIB_PATH", tmp_path / "liblss_attn.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        lss.load()
+    with pytest.raises(RuntimeError):
+        lss.lss_version()
+
+
+def test_product_package_does_not_touch_the_oracle():
+    # the oracle is test infrastructure: nothing under the package imports it
+    pkg = ROOT / "paper_2311_02382_amd"
+    for path in pkg.rglob("*.py"):
+        text = path.read_text()
+        assert "import oracle" not in text and "from oracle" not in text, path
+    for path in (pkg / "csrc").iterdir():
+        assert "oracle" not in path.read_text().lower(), path
