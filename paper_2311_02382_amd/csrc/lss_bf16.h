@@ -61,34 +61,36 @@ struct DirectTile {
     // Issue the loads of two tensors' tiles with one set of offsets, the second tile following the
     // first in LDS (lds_tile + BYTES).  Base pointers, `lds_tile` and `wave` must be wavefront-uniform.
     // One assembly block (see lds_dma for why assembly), so that M0 is saved and restored once and
-    // merely stepped by 4 KB (four wavefronts x 1 KB) from load to load.
+    // merely stepped by WAVES KB (one KB per wavefront) from load to load.
     static __device__ __forceinline__ void issue_pair(const bf16_t *g0_uniform, const bf16_t *g1_uniform,
                                                       const uint32_t (&off)[NI], char *lds_tile, int wave)
     {
-        static_assert((NI == 2 || NI == 4) && WAVES == 4, "");
+        static_assert(NI == 2 || NI == 4, "");
+        constexpr int STEP = WAVES * 1024;              // between two load instructions of one wavefront
         const uint32_t lds_addr = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)(lds_tile + wave * 1024);
         uint32_t saved;
         if constexpr (NI == 2) {
             asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %2, %4\n\ts_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %3, %4\n\ts_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %2, %5\n\ts_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %2, %4\n\ts_add_u32 m0, m0, %6\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %3, %4\n\ts_add_u32 m0, m0, %6\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %2, %5\n\ts_add_u32 m0, m0, %6\n\ts_nop 0\n\t"
                          "global_load_lds_dwordx4 %3, %5\n\ts_mov_b32 m0, %0"
                          : "=&s"(saved)
-                         : "s"(lds_addr), "v"(off[0]), "v"(off[1]), "s"(g0_uniform), "s"(g1_uniform)
+                         : "s"(lds_addr), "v"(off[0]), "v"(off[1]), "s"(g0_uniform), "s"(g1_uniform), "i"(STEP)
                          : "memory", "scc");
         } else {
             asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %2, %6\n\ts_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %3, %6\n\ts_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %4, %6\n\ts_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %5, %6\n\ts_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %2, %7\n\ts_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %3, %7\n\ts_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %4, %7\n\ts_add_u32 m0, m0, 0x1000\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %2, %6\n\ts_add_u32 m0, m0, %8\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %3, %6\n\ts_add_u32 m0, m0, %8\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %4, %6\n\ts_add_u32 m0, m0, %8\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %5, %6\n\ts_add_u32 m0, m0, %8\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %2, %7\n\ts_add_u32 m0, m0, %8\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %3, %7\n\ts_add_u32 m0, m0, %8\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %4, %7\n\ts_add_u32 m0, m0, %8\n\ts_nop 0\n\t"
                          "global_load_lds_dwordx4 %5, %7\n\ts_mov_b32 m0, %0"
                          : "=&s"(saved)
-                         : "s"(lds_addr), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]), "s"(g0_uniform), "s"(g1_uniform)
+                         : "s"(lds_addr), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]), "s"(g0_uniform), "s"(g1_uniform),
+                           "i"(STEP)
                          : "memory", "scc");
         }
     }

@@ -25,11 +25,14 @@ namespace lss {
 
 template <int D>
 struct FwdBf16Cfg {
-    static constexpr int WAVES = 4, RW = 32;            // query rows per wavefront
-    static constexpr int BR = WAVES * RW, BC = 64, NT = 256;
+    // d = 64: four wavefronts, up to three workgroups per compute unit.  d = 128: the K/V ring alone
+    // takes 96 KB of LDS, so only one workgroup fits; it has eight wavefronts (two per SIMD, 256 query
+    // rows sharing the tiles) so that one wavefront's vector work hides behind another's matrix work.
+    static constexpr int WAVES = D == 64 ? 4 : 8, RW = 32;      // wavefronts; query rows per wavefront
+    static constexpr int BR = WAVES * RW, BC = 64, NT = 64 * WAVES;
     static constexpr int RING = 3;                      // K/V tiles resident in LDS
     static constexpr int NU = D / 16;                   // operand steps of the S^T product; same for O^T
-    using Tile = DirectTile<D, BC>;
+    using Tile = DirectTile<D, BC, WAVES>;
     static constexpr int OFF_V = Tile::BYTES, SLOT = 2 * Tile::BYTES;   // one ring slot: K tile, V tile
     static constexpr float kMaxBlockSum = 256.0f;       // 2^8: largest sum of a lane's weights of one block without a fix-up
 };
@@ -38,7 +41,7 @@ struct FwdBf16Cfg {
 // 1 / (1 - p) according to drop_keep() of (seed, batch*head, global row, key); row sum and lse are
 // those of the softmax.
 template <int D, bool DROP>
-__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape s, DropArgs dr, const bf16_t *__restrict__ q,
+__global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_kernel(SegShape s, DropArgs dr, const bf16_t *__restrict__ q,
                                                                        const bf16_t *__restrict__ k,
                                                                        const bf16_t *__restrict__ v,
                                                                        bf16_t *__restrict__ out, float *__restrict__ lse,
