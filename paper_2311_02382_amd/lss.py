@@ -96,7 +96,9 @@ def lss_workspace_bytes(l_s, l_x, B, H, d, elem_bytes=2) -> int:
 
 
 _ws = {}        # device index -> uint8 tensor currently handed to the library
-_ws_retired = []  # older buffers, kept alive: kernels in flight may still use them
+# Outgrown buffers are kept alive, because kernels in flight may still use them and nothing here
+# synchronises.  A buffer at least doubles when it grows, so together they stay below the current one.
+_ws_retired = []
 
 
 def lss_set_workspace(buf) -> None:
@@ -114,7 +116,8 @@ def _ensure_workspace(l_s, l_x, B, H, d, elem_bytes, device):
     if cur is None or cur.numel() < need:
         if cur is not None:
             _ws_retired.append(cur)
-        cur = torch.empty(max(need, 1 << 20), dtype=torch.uint8, device=device)
+        grown = 2 * cur.numel() if cur is not None else 1 << 20
+        cur = torch.empty(max(need, grown), dtype=torch.uint8, device=device)
         _ws[idx] = cur
     lss_set_workspace(cur)
 
