@@ -218,3 +218,83 @@ def project_bwd(dq, dk_partial, dv_partial, w_q, w_kv):
     dx_q = np.matmul(dq.reshape(B, l_s, E), w_q.T)
     dx_part = np.matmul(dk.reshape(B, l_x, E), w_kv[:, :E].T) + np.matmul(dv.reshape(B, l_x, E), w_kv[:, E:].T)
     return dx_q, dx_part
+
+
+# ---- the segment-local remainder of a layer (Section 3, Principles 1 and 2) ----------------------
+# Everything except the self-attention is computed independently per sequence segment: positional
+# embedding (a segment looks up only its own contiguous rows of the table), layer normalisation,
+# residual connections, and the feed-forward unit linear -> GeLU -> linear, whose matrix products
+# are row-distributed (Principle 1).  The paper names these operations without formulas; the
+# readings taken are the standard ones of the GPT models it trains (Section 5.1):
+#   layer normalisation over the E_m columns of a row with learned scale and shift,
+#       y = (x - mean) / sqrt(var + eps) * gamma + beta,  var the biased variance;
+#   GeLU(u) = u Phi(u) with the exact normal distribution function;
+#   feed-forward y = GeLU(h W_1) W_2, no bias (none is mentioned), D_inner columns in between.
+# Dropout inside these units is left out.  Plain numpy float64; nothing blocked or fused.
+
+def embed_pe(tok, pe_table, seg_offset: int):
+    """x_i = tok_i + PE[seg_offset : seg_offset + l_s]  (Principle 2).  tok [B,l_s,E], pe_table [l_x,E]."""
+    tok, pe_table = _f64(tok), _f64(pe_table)
+    l_s = tok.shape[1]
+    if not (0 <= seg_offset and seg_offset + l_s <= pe_table.shape[0]) or tok.shape[2] != pe_table.shape[1]:
+        raise ValueError("segment outside the table, or widths disagree")
+    return tok + pe_table[None, seg_offset:seg_offset + l_s, :]
+
+
+def embed_pe_bwd(dx):
+    """Gradient of the segment's rows of the table: the sum of dx over the batch, [l_s, E].
+    (The gradient of tok is dx itself.)"""
+    return _f64(dx).sum(axis=0)
+
+
+def layernorm_fwd(x, gamma, beta, eps: float = 1e-5):
+    """Row-wise layer normalisation.  x [..., E].  Returns (y, mean [...], rstd [...])."""
+    x, gamma, beta = _f64(x), _f64(gamma), _f64(beta)
+    mean = x.mean(axis=-1)
+    var = ((x - mean[..., None]) ** 2).mean(axis=-1)
+    rstd = 1.0 / np.sqrt(var + eps)
+    y = (x - mean[..., None]) * rstd[..., None] * gamma + beta
+    return y, mean, rstd
+
+
+def layernorm_bwd(x, gamma, dy, eps: float = 1e-5):
+    """Gradients of layernorm_fwd: (dx like x, dgamma [E], dbeta [E])."""
+    x, gamma, dy = _f64(x), _f64(gamma), _f64(dy)
+    E = x.shape[-1]
+    mean = x.mean(axis=-1, keepdims=True)
+    var = ((x - mean) ** 2).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + eps)
+    xh = (x - mean) * rstd
+    g = dy * gamma
+    dx = rstd * (g - g.mean(axis=-1, keepdims=True) - xh * (g * xh).mean(axis=-1, keepdims=True))
+    dgamma = (dy * xh).reshape(-1, E).sum(axis=0)
+    dbeta = dy.reshape(-1, E).sum(axis=0)
+    return dx, dgamma, dbeta
+
+
+def gelu(u):
+    """GeLU(u) = u Phi(u), Phi the standard normal distribution function."""
+    from math import erf
+    u = _f64(u)
+    return u * 0.5 * (1.0 + np.vectorize(erf)(u / np.sqrt(2.0)))
+
+
+def gelu_grad(u):
+    """d GeLU / du = Phi(u) + u phi(u)."""
+    from math import erf
+    u = _f64(u)
+    return 0.5 * (1.0 + np.vectorize(erf)(u / np.sqrt(2.0))) + u * np.exp(-0.5 * u * u) / np.sqrt(2.0 * np.pi)
+
+
+def ffn_fwd(h, w1, w2):
+    """Feed-forward unit on a segment's rows (Principle 1): u = h W_1, y = GeLU(u) W_2.
+    h [B,l_s,E], w1 [E,Di], w2 [Di,E].  Returns (y, u)."""
+    h, w1, w2 = _f64(h), _f64(w1), _f64(w2)
+    u = np.matmul(h, w1)
+    return np.matmul(gelu(u), w2), u
+
+
+def ffn_bwd(dy, u, w1, w2):
+    """Gradient of ffn_fwd with respect to h: dh = ((dy W_2^T) * GeLU'(u)) W_1^T."""
+    dy, u, w1, w2 = _f64(dy), _f64(u), _f64(w1), _f64(w2)
+    return np.matmul(np.matmul(dy, w2.T) * gelu_grad(u), w1.T)

@@ -1,0 +1,109 @@
+"""Pins for the oracle's segment-local operations (Section 3, Principles 1 and 2): closed forms,
+the segment/whole-sequence relations the principles state, finite differences, and torch's CPU
+float64 routines as a second opinion."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2311_02382_amd import synth
+
+
+def _rand(seed, *shape):
+    return synth.normal_f32(seed, int(np.prod(shape))).reshape(shape).astype(np.float64)
+
+
+def test_positional_embedding_is_a_row_slice_and_segments_concatenate():
+    B, l_x, E = 2, 12, 6
+    tok, pe = _rand(31, B, l_x, E), _rand(32, l_x, E)
+    full = oracle.embed_pe(tok, pe, 0)
+    assert np.array_equal(full, tok + pe[None])
+    for s0, l_s in ((0, 5), (5, 3), (8, 4)):
+        seg = oracle.embed_pe(tok[:, s0:s0 + l_s], pe, s0)
+        assert np.array_equal(seg, full[:, s0:s0 + l_s])        # Principle 2: only its own rows are looked up
+        for r in range(l_s):
+            assert np.array_equal(seg[:, r] - tok[:, s0 + r], np.broadcast_to(pe[s0 + r], (B, E)))
+    with pytest.raises(ValueError):
+        oracle.embed_pe(tok[:, :5], pe, 8)
+    dx = _rand(33, B, 4, E)
+    assert np.allclose(oracle.embed_pe_bwd(dx), dx[0] + dx[1])
+
+
+def test_layernorm_closed_forms_and_torch():
+    x, gamma, beta = _rand(34, 3, 7, 16), _rand(35, 16), _rand(36, 16)
+    y, mean, rstd = oracle.layernorm_fwd(x, np.ones(16), np.zeros(16), eps=0.0)
+    assert np.abs(y.mean(axis=-1)).max() < 1e-14 and np.abs((y ** 2).mean(axis=-1) - 1).max() < 1e-13
+    assert np.allclose(mean, x.mean(-1)) and np.allclose(rstd, 1 / x.std(-1))
+    # a row of equal entries normalises to beta; shifting a row changes nothing; scaling it neither (eps = 0)
+    const = np.full((1, 16), 3.25)
+    assert np.allclose(oracle.layernorm_fwd(const, gamma, beta)[0], beta)
+    assert np.allclose(oracle.layernorm_fwd(x + 5.0, gamma, beta, 0.0)[0], oracle.layernorm_fwd(x, gamma, beta, 0.0)[0])
+    assert np.allclose(oracle.layernorm_fwd(3.0 * x, gamma, beta, 0.0)[0], oracle.layernorm_fwd(x, gamma, beta, 0.0)[0])
+    xt = torch.tensor(x, requires_grad=True)
+    gt, bt = torch.tensor(gamma, requires_grad=True), torch.tensor(beta, requires_grad=True)
+    yt = torch.nn.functional.layer_norm(xt, (16,), gt, bt, eps=1e-5)
+    assert np.allclose(oracle.layernorm_fwd(x, gamma, beta)[0], yt.detach().numpy(), rtol=1e-12, atol=1e-12)
+    dy = _rand(37, 3, 7, 16)
+    yt.backward(torch.tensor(dy))
+    dx, dg, db = oracle.layernorm_bwd(x, gamma, dy)
+    assert np.allclose(dx, xt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    assert np.allclose(dg, gt.grad.numpy(), rtol=1e-10, atol=1e-12) and np.allclose(db, bt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    # rows are independent: a segment's rows normalise as they do in the whole sequence (Principle 1)
+    assert np.array_equal(oracle.layernorm_fwd(x[:, 2:5], gamma, beta)[0], oracle.layernorm_fwd(x, gamma, beta)[0][:, 2:5])
+
+
+def test_layernorm_gradient_by_finite_differences():
+    x, gamma, beta, dy = _rand(38, 2, 5), _rand(39, 5), _rand(40, 5), _rand(41, 2, 5)
+    dx, dg, db = oracle.layernorm_bwd(x, gamma, dy)
+    eps = 1e-6
+
+    def loss(xx, gg, bb):
+        return float((oracle.layernorm_fwd(xx, gg, bb)[0] * dy).sum())
+
+    for arr, grad, which in ((x, dx, 0), (gamma, dg, 1), (beta, db, 2)):
+        for idx in np.ndindex(*arr.shape):
+            args_hi, args_lo = [x, gamma, beta], [x, gamma, beta]
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += eps; lo[idx] -= eps
+            args_hi[which], args_lo[which] = hi, lo
+            fd = (loss(*args_hi) - loss(*args_lo)) / (2 * eps)
+            assert abs(fd - grad[idx]) <= 1e-7 * max(1.0, abs(fd)), (which, idx)
+
+
+def test_gelu_values_and_derivative():
+    u = np.array([-6.0, -1.0, 0.0, 0.5, 1.0, 6.0])
+    g = oracle.gelu(u)
+    assert g[2] == 0.0 and abs(g[4] - 0.8413447460685429) < 1e-15       # Phi(1) = 0.84134...
+    assert abs(g[5] - 6.0) < 1e-8 and abs(g[0]) < 1e-8                  # identity far right, zero far left
+    assert np.allclose(g - oracle.gelu(-u), u)                          # GeLU(u) - GeLU(-u) = u
+    assert np.allclose(g, torch.nn.functional.gelu(torch.tensor(u)).numpy(), rtol=1e-14, atol=1e-16)
+    eps = 1e-6
+    fd = (oracle.gelu(u + eps) - oracle.gelu(u - eps)) / (2 * eps)
+    assert np.allclose(oracle.gelu_grad(u), fd, rtol=1e-8, atol=1e-9)
+    assert oracle.gelu_grad(np.array([0.0]))[0] == 0.5
+
+
+def test_ffn_against_loops_torch_and_finite_differences():
+    B, l_s, E, Di = 2, 3, 4, 6
+    h, w1, w2, dy = _rand(42, B, l_s, E), _rand(43, E, Di), _rand(44, Di, E), _rand(45, B, l_s, E)
+    y, u = oracle.ffn_fwd(h, w1, w2)
+    for b in range(B):
+        for r in range(l_s):
+            uu = [sum(h[b, r, e] * w1[e, j] for e in range(E)) for j in range(Di)]
+            assert np.allclose(u[b, r], uu)
+            gg = oracle.gelu(np.array(uu))
+            assert np.allclose(y[b, r], [sum(gg[j] * w2[j, e] for j in range(Di)) for e in range(E)])
+    ht = torch.tensor(h, requires_grad=True)
+    yt = torch.nn.functional.gelu(ht @ torch.tensor(w1)) @ torch.tensor(w2)
+    assert np.allclose(y, yt.detach().numpy(), rtol=1e-12, atol=1e-12)
+    yt.backward(torch.tensor(dy))
+    dh = oracle.ffn_bwd(dy, u, w1, w2)
+    assert np.allclose(dh, ht.grad.numpy(), rtol=1e-10, atol=1e-12)
+    eps = 1e-6
+    for idx in np.ndindex(*h.shape):
+        hi, lo = h.copy(), h.copy()
+        hi[idx] += eps; lo[idx] -= eps
+        fd = float(((oracle.ffn_fwd(hi, w1, w2)[0] - oracle.ffn_fwd(lo, w1, w2)[0]) * dy).sum()) / (2 * eps)
+        assert abs(fd - dh[idx]) <= 1e-7 * max(1.0, abs(fd))
+    # row-distributed: a segment's rows give the rows of the whole (Principle 1)
+    assert np.array_equal(oracle.ffn_fwd(h[:, 1:3], w1, w2)[0], y[:, 1:3])
