@@ -230,6 +230,68 @@ int lss_project_bwd(const void *dq, const float *dk_partial, const float *dv_par
                     float *dx_q, float *dx_partial, void *stream);
 
 /*
+ * The segment-local remainder of a layer (Section 3, Principles 1 and 2): each of
+ * these works on the rows of one segment alone, with no communication.  bf16
+ * activations, fp32 arithmetic, one rounding to bf16 per output.  All pointers are
+ * DEVICE pointers, 16-byte aligned; E_m a multiple of 8.  None uses the workspace.
+ *
+ * Positional embedding (Principle 2): a segment adds only its own contiguous rows
+ * of the lookup table,
+ *     x[b, r, :] = tok[b, r, :] + pe_table[seg_offset + r, :],
+ * and the gradient of those table rows is the sum over the batch, b increasing:
+ *     dpe_rows[r, :] = sum_b dx[b, r, :].
+ *   tok, x, dx  [B, l_s, E_m] bf16;  pe_table [l_x, E_m] bf16;  dpe_rows [l_s, E_m] float
+ * 0 <= seg_offset, seg_offset + l_s <= l_x (LSS_ERR_RANGE otherwise).
+ */
+int lss_embed_pe_fwd(const void *tok, const void *pe_table, int64_t seg_offset,
+                     int64_t l_s, int64_t l_x, int64_t B, int64_t E_m,
+                     void *x, void *stream);
+int lss_embed_pe_bwd(const void *dx, int64_t l_s, int64_t B, int64_t E_m,
+                     float *dpe_rows, void *stream);
+
+/*
+ * Layer normalisation of each row over its E_m columns (the encoder/decoder blocks
+ * of Section 2.2; the paper gives no formula: the usual one, biased variance):
+ *     y = (x - mean) * rstd * gamma + beta,   rstd = 1 / sqrt(var + eps).
+ *   x, y    [rows, E_m] bf16;  gamma, beta [E_m] float;  mean, rstd [rows] float
+ *           (written by the forward, read by the backward)
+ * Backward: dx [rows, E_m] bf16, dgamma, dbeta [E_m] float; the sums over rows are
+ * taken in a fixed order (blocks of 32 rows, then the blocks in order), through
+ *   scratch  DEVICE buffer of lss_layernorm_bwd_scratch_bytes(rows, E_m) bytes,
+ *            caller-owned, overwritten.
+ * E_m <= 4096 (LSS_ERR_SHAPE otherwise); rows = 0 writes zeros to dgamma, dbeta.
+ */
+int lss_layernorm_fwd(const void *x, const float *gamma, const float *beta, double eps,
+                      int64_t rows, int64_t E_m, void *y, float *mean, float *rstd,
+                      void *stream);
+size_t lss_layernorm_bwd_scratch_bytes(int64_t rows, int64_t E_m);
+int lss_layernorm_bwd(const void *x, const float *gamma, const float *mean,
+                      const float *rstd, const void *dy, int64_t rows, int64_t E_m,
+                      void *dx, float *dgamma, float *dbeta,
+                      void *scratch, size_t scratch_bytes, void *stream);
+
+/*
+ * Feed-forward unit (Section 2.2), read as y = GeLU(h W1) W2 without biases, GeLU
+ * exact (u Phi(u)), built from three calls forward and three backward:
+ *     u = lss_linear_fwd(h, W1);  g = lss_gelu_fwd(u);  y = lss_linear_fwd(g, W2)
+ *     dg = lss_linear_bwd_input(dy, W2);  du = lss_gelu_bwd(u, dg);
+ *     dh = lss_linear_bwd_input(du, W1)
+ *   lss_linear_fwd        c[rows, N] = a[rows, K] w[K, N]
+ *   lss_linear_bwd_input  da[rows, K] = dc[rows, N] w[K, N]^T
+ *   lss_gelu_fwd / _bwd   elementwise over n elements, n a multiple of 8;
+ *                         du = dg * (Phi(u) + u phi(u))
+ * a, c, dc, da, u, g, dg, du bf16 row-major; w bf16 row-major.  K and N multiples of
+ * 128, at most 65536; rows < 2^31 (LSS_ERR_SHAPE otherwise).  bf16 matrix cores,
+ * fp32 accumulation.
+ */
+int lss_linear_fwd(const void *a, const void *w, int64_t rows, int64_t K, int64_t N,
+                   void *c, void *stream);
+int lss_linear_bwd_input(const void *dc, const void *w, int64_t rows, int64_t K, int64_t N,
+                         void *da, void *stream);
+int lss_gelu_fwd(const void *u, int64_t n, void *g, void *stream);
+int lss_gelu_bwd(const void *u, const void *dg, int64_t n, void *du, void *stream);
+
+/*
  * Per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every
  * kernel the library launches is bracketed by a pair of HIP events on its launch stream.
  *   lss_timing_enable(on)   switch recording on (1) or off (0) for every kernel; off by default

@@ -19,7 +19,7 @@ INCLUDE = PKG.parent / "include"
 LIB = PKG / "liblss_attn.so"
 OBJ_DIR = PKG / "_build"
 
-SOURCES = ["lss_fwd.hip", "lss_fwd_bf16.hip", "lss_bwd.hip", "lss_bwd_bf16.hip", "lss_reduce.hip", "lss_proj.hip", "lss_timing.hip", "lss_api.hip"]
+SOURCES = ["lss_fwd.hip", "lss_fwd_bf16.hip", "lss_bwd.hip", "lss_bwd_bf16.hip", "lss_reduce.hip", "lss_proj.hip", "lss_rows.hip", "lss_timing.hip", "lss_api.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
     # keep the compiler from forming packed-fp32 VALU ops

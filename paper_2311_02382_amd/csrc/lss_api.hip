@@ -319,6 +319,157 @@ int lss_project_bwd(const void *dq, const float *dk_partial, const float *dv_par
     return LSS_OK;
 }
 
+// ---- segment-local row operations (Section 3, Principles 1 and 2)
+
+int lss_embed_pe_fwd(const void *tok, const void *pe_table, int64_t seg_offset, int64_t l_s, int64_t l_x, int64_t B,
+                     int64_t E_m, void *x, void *stream)
+{
+    if (l_s < 0 || l_x < 1 || B < 0 || E_m < 8 || E_m % 8 != 0 || l_s > INT32_MAX || B > INT32_MAX || E_m > 65536)
+        return fail(LSS_ERR_SHAPE, "embed_pe: bad shape (l_s %lld, l_x %lld, B %lld, E_m %lld)", (long long)l_s,
+                    (long long)l_x, (long long)B, (long long)E_m);
+    if (seg_offset < 0 || seg_offset + l_s > l_x)
+        return fail(LSS_ERR_RANGE, "embed_pe: rows [%lld, %lld) outside the table of %lld rows", (long long)seg_offset,
+                    (long long)(seg_offset + l_s), (long long)l_x);
+    if (B == 0 || l_s == 0) return LSS_OK;
+    if (!tok || !pe_table || !x) return fail(LSS_ERR_NULL, "embed_pe: NULL tensor pointer");
+    if (misaligned(tok) || misaligned(pe_table) || misaligned(x))
+        return fail(LSS_ERR_ALIGN, "embed_pe: tensor pointers must be 16-byte aligned");
+    using lss::bf16_t;
+    const hipError_t e = lss::launch_embed_pe_fwd(static_cast<const bf16_t *>(tok), static_cast<const bf16_t *>(pe_table),
+                                                  seg_offset, (int)l_s, (int)B, (int)E_m, static_cast<bf16_t *>(x),
+                                                  static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "embed_pe launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+int lss_embed_pe_bwd(const void *dx, int64_t l_s, int64_t B, int64_t E_m, float *dpe_rows, void *stream)
+{
+    if (l_s < 0 || B < 0 || E_m < 8 || E_m % 8 != 0 || l_s > INT32_MAX || B > INT32_MAX || E_m > 65536)
+        return fail(LSS_ERR_SHAPE, "embed_pe_bwd: bad shape (l_s %lld, B %lld, E_m %lld)", (long long)l_s, (long long)B,
+                    (long long)E_m);
+    if (l_s == 0) return LSS_OK;
+    if (!dpe_rows || (B > 0 && !dx)) return fail(LSS_ERR_NULL, "embed_pe_bwd: NULL tensor pointer");
+    if (misaligned(dx) || misaligned(dpe_rows)) return fail(LSS_ERR_ALIGN, "embed_pe_bwd: tensor pointers must be 16-byte aligned");
+    const hipError_t e = lss::launch_embed_pe_bwd(static_cast<const lss::bf16_t *>(dx), (int)l_s, (int)B, (int)E_m, dpe_rows,
+                                                  static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "embed_pe_bwd launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+static int check_layernorm(const char *what, int64_t rows, int64_t E_m)
+{
+    if (rows < 0 || E_m < 8 || E_m % 8 != 0 || E_m > lss::layernorm_max_columns())
+        return fail(LSS_ERR_SHAPE, "%s: rows = %lld, E_m = %lld (need E_m a multiple of 8, at most %d)", what, (long long)rows,
+                    (long long)E_m, lss::layernorm_max_columns());
+    return LSS_OK;
+}
+
+int lss_layernorm_fwd(const void *x, const float *gamma, const float *beta, double eps, int64_t rows, int64_t E_m, void *y,
+                      float *mean, float *rstd, void *stream)
+{
+    if (int rc = check_layernorm("layernorm_fwd", rows, E_m)) return rc;
+    if (!(eps >= 0.0)) return fail(LSS_ERR_RANGE, "layernorm_fwd: eps = %g", eps);
+    if (rows == 0) return LSS_OK;
+    if (!x || !gamma || !beta || !y || !mean || !rstd) return fail(LSS_ERR_NULL, "layernorm_fwd: NULL tensor pointer");
+    if (misaligned(x) || misaligned(gamma) || misaligned(beta) || misaligned(y))
+        return fail(LSS_ERR_ALIGN, "layernorm_fwd: tensor pointers must be 16-byte aligned");
+    using lss::bf16_t;
+    const hipError_t e = lss::launch_layernorm_fwd(static_cast<const bf16_t *>(x), gamma, beta, (float)eps, rows, (int)E_m,
+                                                   static_cast<bf16_t *>(y), mean, rstd, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "layernorm_fwd launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+size_t lss_layernorm_bwd_scratch_bytes(int64_t rows, int64_t E_m)
+{
+    if (rows <= 0 || E_m <= 0 || E_m > lss::layernorm_max_columns()) return 0;
+    return lss::layernorm_bwd_scratch_bytes(rows, (int)E_m);
+}
+
+int lss_layernorm_bwd(const void *x, const float *gamma, const float *mean, const float *rstd, const void *dy, int64_t rows,
+                      int64_t E_m, void *dx, float *dgamma, float *dbeta, void *scratch, size_t scratch_bytes, void *stream)
+{
+    if (int rc = check_layernorm("layernorm_bwd", rows, E_m)) return rc;
+    if (!dgamma || !dbeta) return fail(LSS_ERR_NULL, "layernorm_bwd: NULL gradient pointer");
+    if (rows > 0) {
+        if (!x || !gamma || !mean || !rstd || !dy || !dx) return fail(LSS_ERR_NULL, "layernorm_bwd: NULL tensor pointer");
+        if (misaligned(x) || misaligned(gamma) || misaligned(dy) || misaligned(dx) || misaligned(scratch))
+            return fail(LSS_ERR_ALIGN, "layernorm_bwd: tensor pointers must be 16-byte aligned");
+        const size_t need = lss::layernorm_bwd_scratch_bytes(rows, (int)E_m);
+        if (!scratch || scratch_bytes < need)
+            return fail(LSS_ERR_WORKSPACE, "layernorm_bwd: scratch of %zu bytes, need %zu", scratch ? scratch_bytes : (size_t)0, need);
+    }
+    using lss::bf16_t;
+    const hipError_t e = lss::launch_layernorm_bwd(static_cast<const bf16_t *>(x), gamma, mean, rstd,
+                                                   static_cast<const bf16_t *>(dy), rows, (int)E_m, static_cast<bf16_t *>(dx),
+                                                   dgamma, dbeta, static_cast<float *>(scratch), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "layernorm_bwd launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+static int check_linear(const char *what, const void *a, const void *w, const void *c, int64_t rows, int64_t K, int64_t N)
+{
+    if (rows < 0 || rows > INT32_MAX || K < 128 || N < 128 || K % 128 != 0 || N % 128 != 0 || K > 65536 || N > 65536)
+        return fail(LSS_ERR_SHAPE, "%s: rows = %lld, K = %lld, N = %lld (K, N multiples of 128, at most 65536)", what,
+                    (long long)rows, (long long)K, (long long)N);
+    if (rows == 0) return LSS_OK;
+    if (!a || !w || !c) return fail(LSS_ERR_NULL, "%s: NULL tensor pointer", what);
+    if (misaligned(a) || misaligned(w) || misaligned(c)) return fail(LSS_ERR_ALIGN, "%s: tensor pointers must be 16-byte aligned", what);
+    return LSS_OK;
+}
+
+int lss_linear_fwd(const void *a, const void *w, int64_t rows, int64_t K, int64_t N, void *c, void *stream)
+{
+    if (int rc = check_linear("linear_fwd", a, w, c, rows, K, N)) return rc;
+    if (rows == 0) return LSS_OK;
+    using lss::bf16_t;
+    const hipError_t e = lss::launch_linear_fwd(static_cast<const bf16_t *>(a), static_cast<const bf16_t *>(w), (int)rows, (int)K,
+                                                (int)N, static_cast<bf16_t *>(c), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "linear_fwd launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+int lss_linear_bwd_input(const void *dc, const void *w, int64_t rows, int64_t K, int64_t N, void *da, void *stream)
+{
+    if (int rc = check_linear("linear_bwd_input", dc, w, da, rows, K, N)) return rc;
+    if (rows == 0) return LSS_OK;
+    using lss::bf16_t;
+    const hipError_t e = lss::launch_linear_bwd_input(static_cast<const bf16_t *>(dc), static_cast<const bf16_t *>(w), (int)rows,
+                                                      (int)K, (int)N, static_cast<bf16_t *>(da), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "linear_bwd_input launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+static int check_gelu(const char *what, int64_t n)
+{
+    if (n < 0 || n % 8 != 0) return fail(LSS_ERR_SHAPE, "%s: n = %lld is not a non-negative multiple of 8", what, (long long)n);
+    return LSS_OK;
+}
+
+int lss_gelu_fwd(const void *u, int64_t n, void *g, void *stream)
+{
+    if (int rc = check_gelu("gelu_fwd", n)) return rc;
+    if (n == 0) return LSS_OK;
+    if (!u || !g) return fail(LSS_ERR_NULL, "gelu_fwd: NULL tensor pointer");
+    if (misaligned(u) || misaligned(g)) return fail(LSS_ERR_ALIGN, "gelu_fwd: tensor pointers must be 16-byte aligned");
+    const hipError_t e = lss::launch_gelu_fwd(static_cast<const lss::bf16_t *>(u), n, static_cast<lss::bf16_t *>(g),
+                                              static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "gelu_fwd launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
+int lss_gelu_bwd(const void *u, const void *dg, int64_t n, void *du, void *stream)
+{
+    if (int rc = check_gelu("gelu_bwd", n)) return rc;
+    if (n == 0) return LSS_OK;
+    if (!u || !dg || !du) return fail(LSS_ERR_NULL, "gelu_bwd: NULL tensor pointer");
+    if (misaligned(u) || misaligned(dg) || misaligned(du)) return fail(LSS_ERR_ALIGN, "gelu_bwd: tensor pointers must be 16-byte aligned");
+    const hipError_t e = lss::launch_gelu_bwd(static_cast<const lss::bf16_t *>(u), static_cast<const lss::bf16_t *>(dg), n,
+                                              static_cast<lss::bf16_t *>(du), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "gelu_bwd launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
 int lss_reduce_partials(const float *const *parts, int n, const int64_t *rows_valid, int64_t l_x, int64_t B,
                         int64_t H, int64_t d, float *out, void *stream)
 {

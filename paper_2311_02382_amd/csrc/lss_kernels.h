@@ -67,7 +67,8 @@ hipError_t launch_bwd_bf16_main(const SegShape &s, const DropArgs &drop, const b
 
 // Optional per-kernel timing for benchmarks: when enabled, every launch site brackets its
 // kernel with a pair of HIP events on the launch stream.
-enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_BWD_MAIN, K_PROJ_FWD, K_PROJ_BWD, K_COUNT };
+enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_BWD_MAIN, K_PROJ_FWD, K_PROJ_BWD,
+                K_PE_FWD, K_PE_BWD, K_LN_FWD, K_LN_BWD, K_LN_PARAMS, K_GELU_FWD, K_GELU_BWD, K_LINEAR_FWD, K_LINEAR_BWD, K_COUNT };
 void timing_begin(int id, hipStream_t st);
 void timing_end(int id, hipStream_t st);
 struct TimedLaunch {    // RAII bracket around one kernel launch
@@ -86,5 +87,24 @@ hipError_t launch_project_qkv(const bf16_t *x, const bf16_t *w_q, const bf16_t *
 hipError_t launch_project_bwd(const bf16_t *dq, const float *dk_part, const float *dv_part, const bf16_t *w_q,
                               const bf16_t *w_kv, int l_s, int l_x, int rows_valid, int B, int E, int skip_tail,
                               float *dx_q, float *dx_part, hipStream_t st);
+
+
+// general bf16 linear maps with the same GEMM kernel (the feed-forward unit's two transforms):
+// c[rows, N] = a[rows, K] w[K, N]   and   da[rows, K] = dc[rows, N] w[K, N]^T;  K, N multiples of 128
+hipError_t launch_linear_fwd(const bf16_t *a, const bf16_t *w, int rows, int K, int N, bf16_t *c, hipStream_t st);
+hipError_t launch_linear_bwd_input(const bf16_t *dc, const bf16_t *w, int rows, int K, int N, bf16_t *da, hipStream_t st);
+
+// segment-local row operations (lss_rows.hip); E a multiple of 8
+hipError_t launch_embed_pe_fwd(const bf16_t *tok, const bf16_t *pe, int64_t s0, int l_s, int B, int E, bf16_t *x,
+                               hipStream_t st);
+hipError_t launch_embed_pe_bwd(const bf16_t *dx, int l_s, int B, int E, float *dpe, hipStream_t st);
+int layernorm_max_columns();
+size_t layernorm_bwd_scratch_bytes(int64_t rows, int E);
+hipError_t launch_layernorm_fwd(const bf16_t *x, const float *gamma, const float *beta, float eps, int64_t rows, int E,
+                                bf16_t *y, float *mean, float *rstd, hipStream_t st);
+hipError_t launch_layernorm_bwd(const bf16_t *x, const float *gamma, const float *mean, const float *rstd, const bf16_t *dy,
+                                int64_t rows, int E, bf16_t *dx, float *dgamma, float *dbeta, float *scratch, hipStream_t st);
+hipError_t launch_gelu_fwd(const bf16_t *u, int64_t n, bf16_t *g, hipStream_t st);
+hipError_t launch_gelu_bwd(const bf16_t *u, const bf16_t *dg, int64_t n, bf16_t *du, hipStream_t st);
 
 } // namespace lss

@@ -17,6 +17,8 @@
 //   W_TR   weights stored [k][n] (forward: W as given).  Their fragments come from the LDS tile
 //          by transposing reads; otherwise the weights are stored [n][k] (backward: W as given
 //          IS W'^T) and are read plainly.
+//   OUT_F32  C is written as float (the backward maps, whose results are summed over segments
+//          afterwards), else rounded once to bf16.
 //   A_ANY  a job's A may be float (the dK/dV partials; `a_f32` of the job): rounded to bf16 on the
 //          way into LDS, through registers; the contraction index runs over dK's columns, then
 //          dV's.  Jobs with bf16 A (dQ) share the launch.
@@ -93,12 +95,11 @@ struct WTileTr {
     }
 };
 
-template <bool A_ANY, bool W_TR>
+template <bool A_ANY, bool W_TR, bool OUT_F32>
 __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    using OutT = typename std::conditional<!W_TR, float, bf16_t>::type;     // backward maps write float
-    constexpr bool OUT_F32 = std::is_same<OutT, float>::value;
+    using OutT = typename std::conditional<OUT_F32, float, bf16_t>::type;
 
     const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -325,7 +326,7 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
     store_tiles(acc, true);
 }
 
-template <bool A_ANY, bool W_TR>
+template <bool A_ANY, bool W_TR, bool OUT_F32>
 hipError_t launch_proj(ProjArgs &args, int kernel_id, hipStream_t st)
 {
     int wgs = 0;
@@ -340,12 +341,12 @@ hipError_t launch_proj(ProjArgs &args, int kernel_id, hipStream_t st)
     static std::once_flag once;
     static hipError_t attr = hipSuccess;
     std::call_once(once, [] {
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(proj_gemm_kernel<A_ANY, W_TR>),
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(proj_gemm_kernel<A_ANY, W_TR, OUT_F32>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
     });
     if (attr != hipSuccess) return attr;
     TimedLaunch tl(kernel_id, st);
-    hipLaunchKernelGGL((proj_gemm_kernel<A_ANY, W_TR>), dim3(wgs), dim3(P_NT), P_LDS, st, args);
+    hipLaunchKernelGGL((proj_gemm_kernel<A_ANY, W_TR, OUT_F32>), dim3(wgs), dim3(P_NT), P_LDS, st, args);
     return hipGetLastError();
 }
 
@@ -373,7 +374,7 @@ hipError_t launch_project_qkv(const bf16_t *x, const bf16_t *w_q, const bf16_t *
         J.N = E; J.K = E; J.k_split = E; J.n_split = E; J.ldw = E;
     }
     args.n_jobs = n;
-    return launch_proj<false, true>(args, K_PROJ_FWD, st);
+    return launch_proj<false, true, false>(args, K_PROJ_FWD, st);
 }
 
 hipError_t launch_project_bwd(const bf16_t *dq, const float *dk_part, const float *dv_part, const bf16_t *w_q,
@@ -401,7 +402,33 @@ hipError_t launch_project_bwd(const bf16_t *dq, const float *dk_part, const floa
         J.a_f32 = 0;
     }
     args.n_jobs = n;
-    return launch_proj<true, false>(args, K_PROJ_BWD, st);
+    return launch_proj<true, false, true>(args, K_PROJ_BWD, st);
+}
+
+// c = a w for any row count: one job, one tall matrix
+hipError_t launch_linear_fwd(const bf16_t *a, const bf16_t *w, int rows, int K, int N, bf16_t *c, hipStream_t st)
+{
+    ProjArgs args{};
+    args.lda = K; args.ldc = N; args.skip_tail = 0; args.n_jobs = 1;
+    ProjJob &J = args.job[0];
+    J.a0 = a; J.a1 = nullptr; J.w = w; J.c0 = c; J.c1 = nullptr;
+    J.a_batch_stride = J.c_batch_stride = 0;
+    J.rows = J.rows_ok = rows; J.batches = 1;
+    J.N = N; J.K = K; J.k_split = K; J.n_split = N; J.ldw = N;
+    return launch_proj<false, true, false>(args, K_LINEAR_FWD, st);
+}
+
+// da = dc w^T: w as stored, [K][N], is the [output column][contraction index] layout read plainly
+hipError_t launch_linear_bwd_input(const bf16_t *dc, const bf16_t *w, int rows, int K, int N, bf16_t *da, hipStream_t st)
+{
+    ProjArgs args{};
+    args.lda = N; args.ldc = K; args.skip_tail = 0; args.n_jobs = 1;
+    ProjJob &J = args.job[0];
+    J.a0 = dc; J.a1 = nullptr; J.w = w; J.c0 = da; J.c1 = nullptr;
+    J.a_batch_stride = J.c_batch_stride = 0;
+    J.rows = J.rows_ok = rows; J.batches = 1;
+    J.N = K; J.K = N; J.k_split = N; J.n_split = K; J.ldw = N;
+    return launch_proj<false, false, false>(args, K_LINEAR_BWD, st);
 }
 
 } // namespace lss

@@ -22,7 +22,10 @@ int64_t g_count[K_COUNT] = {0};
 
 const char *const kNames[K_COUNT] = {"fwd_kernel", "fwd_merge_kernel", "bwd_rowdot_kernel", "bwd_dq_kernel",
                                      "bwd_dq_merge_kernel", "bwd_dkv_kernel", "reduce_partials_kernel",
-                                     "bwd_main_kernel", "proj_fwd_kernel", "proj_bwd_kernel"};
+                                     "bwd_main_kernel", "proj_fwd_kernel", "proj_bwd_kernel",
+                                     "embed_pe_fwd_kernel", "embed_pe_bwd_kernel", "layernorm_fwd_kernel",
+                                     "layernorm_bwd_kernel", "layernorm_bwd_params_kernel", "gelu_fwd_kernel",
+                                     "gelu_bwd_kernel", "linear_fwd_kernel", "linear_bwd_kernel"};
 
 hipEvent_t get_event()
 {

@@ -21,7 +21,10 @@ STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_E
 
 EXPORTS = ["lss_version", "lss_last_error", "lss_set_option", "lss_workspace_bytes", "lss_set_workspace",
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
-           "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd", "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
+           "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd",
+           "lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_layernorm_fwd", "lss_layernorm_bwd_scratch_bytes",
+           "lss_layernorm_bwd", "lss_linear_fwd", "lss_linear_bwd_input", "lss_gelu_fwd", "lss_gelu_bwd",
+           "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
            "lss_timing_read", "lss_timing_kernel_name"]
 
 
@@ -67,6 +70,19 @@ def load():
     lib.lss_project_qkv.restype = ci
     lib.lss_project_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, vp, vp]
     lib.lss_project_bwd.restype = ci
+    lib.lss_embed_pe_fwd.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp, vp]
+    lib.lss_embed_pe_bwd.argtypes = [vp, i64, i64, i64, vp, vp]
+    lib.lss_layernorm_fwd.argtypes = [vp, vp, vp, f64, i64, i64, vp, vp, vp, vp]
+    lib.lss_layernorm_bwd_scratch_bytes.argtypes = [i64, i64]
+    lib.lss_layernorm_bwd_scratch_bytes.restype = sz
+    lib.lss_layernorm_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
+    lib.lss_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    lib.lss_linear_bwd_input.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    lib.lss_gelu_fwd.argtypes = [vp, i64, vp, vp]
+    lib.lss_gelu_bwd.argtypes = [vp, vp, i64, vp, vp]
+    for name in ("lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_layernorm_fwd", "lss_layernorm_bwd", "lss_linear_fwd",
+                 "lss_linear_bwd_input", "lss_gelu_fwd", "lss_gelu_bwd"):
+        getattr(lib, name).restype = ci
     lib.lss_timing_enable.argtypes = [ci]
     lib.lss_timing_select.argtypes = [ctypes.c_uint]
     lib.lss_timing_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -274,6 +290,129 @@ def lss_project_bwd(dq, dk_partial, dv_partial, w_q, w_kv, rows_valid=None, dx_q
     _check(load().lss_project_bwd(_ptr(dq), _ptr(dk_partial), _ptr(dv_partial), _ptr(w_q), _ptr(w_kv), l_s, l_x,
                                   int(rows_valid), B, H, d, _ptr(dx_q), _ptr(dx_partial), _stream_ptr(stream)))
     return dx_q, dx_partial
+
+
+def _dev(t, dtype, what):
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype:
+        raise ValueError(f"{what} must be a contiguous {dtype} device tensor")
+
+
+def _out(t, shape, dtype, like):
+    if t is None:
+        return torch.empty(shape, dtype=dtype, device=like.device)
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"output has shape {tuple(t.shape)}, expected {tuple(shape)}")
+    _dev(t, dtype, "output")
+    return t
+
+
+def lss_embed_pe_fwd(tok, pe_table, seg_offset, x=None, stream=None):
+    """x[b, r] = tok[b, r] + pe_table[seg_offset + r].  tok [B,l_s,E] bf16, pe_table [l_x,E] bf16."""
+    if tok.dim() != 3 or pe_table.dim() != 2 or pe_table.shape[1] != tok.shape[2]:
+        raise ValueError("tok must be [B, l_s, E] and pe_table [l_x, E]")
+    B, l_s, E = tok.shape
+    _dev(tok, torch.bfloat16, "tok"); _dev(pe_table, torch.bfloat16, "pe_table")
+    x = _out(x, (B, l_s, E), torch.bfloat16, tok)
+    _check(load().lss_embed_pe_fwd(_ptr(tok), _ptr(pe_table), int(seg_offset), l_s, pe_table.shape[0], B, E, _ptr(x),
+                                   _stream_ptr(stream)))
+    return x
+
+
+def lss_embed_pe_bwd(dx, dpe_rows=None, stream=None):
+    """dpe_rows[r] = sum_b dx[b, r], float32 [l_s, E]: the gradient of the segment's rows of the table."""
+    if dx.dim() != 3:
+        raise ValueError("dx must be [B, l_s, E]")
+    B, l_s, E = dx.shape
+    _dev(dx, torch.bfloat16, "dx")
+    dpe_rows = _out(dpe_rows, (l_s, E), torch.float32, dx)
+    _check(load().lss_embed_pe_bwd(_ptr(dx), l_s, B, E, _ptr(dpe_rows), _stream_ptr(stream)))
+    return dpe_rows
+
+
+def lss_layernorm_fwd(x, gamma, beta, eps=1e-5, y=None, mean=None, rstd=None, stream=None):
+    """Row-wise layer normalisation of x [..., E] bf16; returns (y bf16, mean, rstd float32 [rows])."""
+    E = x.shape[-1]
+    rows = x.numel() // E if E else 0
+    _dev(x, torch.bfloat16, "x"); _dev(gamma, torch.float32, "gamma"); _dev(beta, torch.float32, "beta")
+    if gamma.numel() != E or beta.numel() != E:
+        raise ValueError("gamma and beta must have E elements")
+    y = _out(y, x.shape, torch.bfloat16, x)
+    mean = _out(mean, (rows,), torch.float32, x)
+    rstd = _out(rstd, (rows,), torch.float32, x)
+    _check(load().lss_layernorm_fwd(_ptr(x), _ptr(gamma), _ptr(beta), float(eps), rows, E, _ptr(y), _ptr(mean), _ptr(rstd),
+                                    _stream_ptr(stream)))
+    return y, mean, rstd
+
+
+def lss_layernorm_bwd_scratch_bytes(rows, E):
+    return int(load().lss_layernorm_bwd_scratch_bytes(int(rows), int(E)))
+
+
+def lss_layernorm_bwd(x, gamma, mean, rstd, dy, dx=None, dgamma=None, dbeta=None, scratch=None, stream=None):
+    """Backward of lss_layernorm_fwd: returns (dx bf16, dgamma, dbeta float32 [E]).
+
+    `scratch` is a uint8 device tensor of at least lss_layernorm_bwd_scratch_bytes(rows, E) bytes
+    (allocated here if absent).
+    """
+    E = x.shape[-1]
+    rows = x.numel() // E if E else 0
+    for t, dt, nm in ((x, torch.bfloat16, "x"), (dy, torch.bfloat16, "dy"), (gamma, torch.float32, "gamma"),
+                      (mean, torch.float32, "mean"), (rstd, torch.float32, "rstd")):
+        _dev(t, dt, nm)
+    if dy.shape != x.shape or gamma.numel() != E or mean.numel() != rows or rstd.numel() != rows:
+        raise ValueError("shapes disagree")
+    dx = _out(dx, x.shape, torch.bfloat16, x)
+    dgamma = _out(dgamma, (E,), torch.float32, x)
+    dbeta = _out(dbeta, (E,), torch.float32, x)
+    need = lss_layernorm_bwd_scratch_bytes(rows, E)
+    if scratch is None:
+        scratch = torch.empty((max(need, 16),), dtype=torch.uint8, device=x.device)
+    _dev(scratch, torch.uint8, "scratch")
+    _check(load().lss_layernorm_bwd(_ptr(x), _ptr(gamma), _ptr(mean), _ptr(rstd), _ptr(dy), rows, E, _ptr(dx), _ptr(dgamma),
+                                    _ptr(dbeta), _ptr(scratch), scratch.numel(), _stream_ptr(stream)))
+    return dx, dgamma, dbeta
+
+
+def lss_linear_fwd(a, w, c=None, stream=None):
+    """c = a w.  a [..., K] bf16, w [K, N] bf16 -> c [..., N] bf16."""
+    K, N = w.shape
+    if a.shape[-1] != K:
+        raise ValueError("a's last dimension must equal w's rows")
+    _dev(a, torch.bfloat16, "a"); _dev(w, torch.bfloat16, "w")
+    rows = a.numel() // K
+    c = _out(c, (*a.shape[:-1], N), torch.bfloat16, a)
+    _check(load().lss_linear_fwd(_ptr(a), _ptr(w), rows, K, N, _ptr(c), _stream_ptr(stream)))
+    return c
+
+
+def lss_linear_bwd_input(dc, w, da=None, stream=None):
+    """da = dc w^T.  dc [..., N] bf16, w [K, N] bf16 -> da [..., K] bf16."""
+    K, N = w.shape
+    if dc.shape[-1] != N:
+        raise ValueError("dc's last dimension must equal w's columns")
+    _dev(dc, torch.bfloat16, "dc"); _dev(w, torch.bfloat16, "w")
+    rows = dc.numel() // N
+    da = _out(da, (*dc.shape[:-1], K), torch.bfloat16, dc)
+    _check(load().lss_linear_bwd_input(_ptr(dc), _ptr(w), rows, K, N, _ptr(da), _stream_ptr(stream)))
+    return da
+
+
+def lss_gelu_fwd(u, g=None, stream=None):
+    """g = GeLU(u) = u Phi(u), elementwise, bf16."""
+    _dev(u, torch.bfloat16, "u")
+    g = _out(g, u.shape, torch.bfloat16, u)
+    _check(load().lss_gelu_fwd(_ptr(u), u.numel(), _ptr(g), _stream_ptr(stream)))
+    return g
+
+
+def lss_gelu_bwd(u, dg, du=None, stream=None):
+    """du = dg * GeLU'(u), elementwise, bf16."""
+    _dev(u, torch.bfloat16, "u"); _dev(dg, torch.bfloat16, "dg")
+    if dg.shape != u.shape:
+        raise ValueError("u and dg must have the same shape")
+    du = _out(du, u.shape, torch.bfloat16, u)
+    _check(load().lss_gelu_bwd(_ptr(u), _ptr(dg), u.numel(), _ptr(du), _stream_ptr(stream)))
+    return du
 
 
 def lss_timing_enable(on: bool) -> None:

@@ -103,6 +103,48 @@ def test_options(lib):
     assert b"option" in lib.lss_last_error()
 
 
+def test_layer_operation_argument_checks(lib):
+    pe = lib.lss_embed_pe_fwd
+
+    def f(tok=0x1000, table=0x2000, s0=0, l_s=128, l_x=256, B=1, E=64, x=0x3000):
+        return pe(tok, table, s0, l_s, l_x, B, E, x, None)
+
+    assert f(E=12) == -2 and f(E=0) == -2 and f(l_x=0) == -2 and f(l_s=-1) == -2
+    assert f(s0=129) == -5 and f(s0=-1) == -5
+    assert f(tok=0) == -1 and f(x=0) == -1 and f(table=0x2004) == -4
+    assert f(B=0) == 0 and f(l_s=0) == 0
+    assert lib.lss_embed_pe_bwd(0x1000, 128, 2, 12, 0x2000, None) == -2
+    assert lib.lss_embed_pe_bwd(0x1000, 128, 2, 64, None, None) == -1
+    assert lib.lss_embed_pe_bwd(None, 0, 2, 64, None, None) == 0
+
+    ln = lib.lss_layernorm_fwd
+    assert ln(0x1000, 0x2000, 0x3000, 1e-5, 4, 4104, 0x4000, 0x5000, 0x6000, None) == -2      # wider than 4096
+    assert b"4096" in lib.lss_last_error()
+    assert ln(0x1000, 0x2000, 0x3000, 1e-5, 4, 60, 0x4000, 0x5000, 0x6000, None) == -2
+    assert ln(0x1000, 0x2000, 0x3000, -1.0, 4, 64, 0x4000, 0x5000, 0x6000, None) == -5
+    assert ln(0x1000, None, 0x3000, 1e-5, 4, 64, 0x4000, 0x5000, 0x6000, None) == -1
+    assert ln(0x1000, 0x2000, 0x3000, 1e-5, 0, 64, 0x4000, 0x5000, 0x6000, None) == 0
+    assert lib.lss_layernorm_bwd_scratch_bytes(33, 512) == 2 * 2 * 512 * 4
+    assert lib.lss_layernorm_bwd_scratch_bytes(0, 512) == 0
+    lb = lib.lss_layernorm_bwd
+    assert lb(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 33, 512, 0x6000, 0x7000, 0x8000, 0x9000, 8191, None) == -6
+    assert lb(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 33, 512, 0x6000, 0x7000, 0x8000, None, 0, None) == -6
+    assert lb(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 33, 512, 0x6000, None, 0x8000, 0x9000, 8192, None) == -1
+
+    for fn in (lib.lss_linear_fwd, lib.lss_linear_bwd_input):
+        assert fn(0x1000, 0x2000, 16, 192, 256, 0x3000, None) == -2      # K not a multiple of 128
+        assert fn(0x1000, 0x2000, 16, 256, 64, 0x3000, None) == -2
+        assert fn(0x1000, 0x2000, -1, 256, 256, 0x3000, None) == -2
+        assert fn(0x1000, 0x2000, 2 ** 31, 256, 256, 0x3000, None) == -2
+        assert fn(0x1000, 0, 16, 256, 256, 0x3000, None) == -1
+        assert fn(0x1008, 0x2000, 16, 256, 256, 0x3000, None) == -4
+        assert fn(0, 0, 0, 256, 256, 0, None) == 0
+    assert lib.lss_gelu_fwd(0x1000, 12, 0x2000, None) == -2
+    assert lib.lss_gelu_fwd(0x1000, 16, None, None) == -1
+    assert lib.lss_gelu_bwd(0x1000, 0x2000, 16, 0x3004, None) == -4
+    assert lib.lss_gelu_bwd(None, None, 0, None, None) == 0
+
+
 def test_projection_argument_checks(lib):
     fwd, bwd = lib.lss_project_qkv, lib.lss_project_bwd
 
