@@ -6,7 +6,7 @@ segments of the sequence, forward then backward (Eq. 2 of Section 3 and its grad
 followed by the segment sum of the dK and dV partials (the arithmetic of the
 reduce-scatter of Fig. 2(v)).  Inputs are resident in HBM before the timed region.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lx8k] [--projections]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lx8k] [--projections | --layer-ops]
 
 With --projections every segment also runs the linear maps either side of the attention in
 the fused-communication form (Q_i, K, V from x before the forward; dx_q and dx_partial after
@@ -57,6 +57,162 @@ def measured_traffic(workload: str, kernel: str):
     return None
 
 
+def layer_ops(args, w) -> int:
+    """The segment-local remainder of a layer (Section 3, Principles 1 and 2) on the workload's shape:
+    per segment, x = tok + PE rows, LayerNorm, feed-forward unit (E_m -> 4 E_m -> E_m, exact GeLU),
+    then the same backwards.  `value` is the feed-forward unit's matrix flops (8 * rows * E_m * 4 E_m
+    per segment) over the time of the whole step, streaming kernels included."""
+    import numpy as np
+    import torch
+
+    from paper_2311_02382_amd import lss, synth
+
+    dev = torch.device("cuda:0")
+    E, F, l_s, offs = w.H * w.d, 4 * w.H * w.d, w.l_s, w.offsets()
+    rows = w.B * l_s
+
+    def stage(seed, shape, std=1.0, bf16=True):
+        a = (synth.normal_f32(seed, int(np.prod(shape))) * np.float32(std)).reshape(shape)
+        if not bf16:
+            return torch.from_numpy(a).to(dev), a.astype(np.float64)
+        bits = synth.f32_to_bf16_bits(a)
+        return (torch.from_numpy(bits.view(np.int16).reshape(shape)).to(dev).view(torch.bfloat16),
+                synth.bf16_bits_to_f64(bits).reshape(shape))
+
+    tok, tok_h = stage(w.seed + 20, (w.B, w.l_x, E))
+    pe, pe_h = stage(w.seed + 21, (w.l_x, E))
+    w1, w1_h = stage(w.seed + 22, (E, F), E ** -0.5)
+    w2, w2_h = stage(w.seed + 23, (F, E), F ** -0.5)
+    dy, dy_h = stage(w.seed + 24, (w.B, l_s, E))
+    gamma, gamma_h = stage(w.seed + 25, (E,), 0.1, bf16=False)
+    gamma += 1.0
+    gamma_h = gamma_h + 1.0
+    beta, beta_h = stage(w.seed + 26, (E,), 0.1, bf16=False)
+    tok_seg = [tok[:, s0:s0 + l_s].contiguous() for s0 in offs]
+    bf = dict(dtype=torch.bfloat16, device=dev)
+    x, h, dh, dx = (torch.empty((w.B, l_s, E), **bf) for _ in range(4))
+    u, g, dg, du = (torch.empty((w.B, l_s, F), **bf) for _ in range(4))
+    y = torch.empty((w.B, l_s, E), **bf)
+    mean, rstd = (torch.empty((rows,), dtype=torch.float32, device=dev) for _ in range(2))
+    dgamma, dbeta = (torch.empty((E,), dtype=torch.float32, device=dev) for _ in range(2))
+    dpe = torch.empty((l_s, E), dtype=torch.float32, device=dev)
+    scratch = torch.empty((max(16, lss.lss_layernorm_bwd_scratch_bytes(rows, E)),), dtype=torch.uint8, device=dev)
+
+    def step():
+        for i, s0 in enumerate(offs):
+            lss.lss_embed_pe_fwd(tok_seg[i], pe, s0, x=x)
+            lss.lss_layernorm_fwd(x, gamma, beta, y=h, mean=mean, rstd=rstd)
+            if args.fused_gelu:     # GeLU and its derivative in the GEMMs' epilogues: same bits, two launches fewer
+                lss.lss_linear_gelu_fwd(h, w1, u=u, g=g)
+                lss.lss_linear_fwd(g, w2, c=y)
+                lss.lss_linear_bwd_input_gelu(dy, w2, u, du=du)
+            else:
+                lss.lss_linear_fwd(h, w1, c=u)
+                lss.lss_gelu_fwd(u, g=g)
+                lss.lss_linear_fwd(g, w2, c=y)
+                lss.lss_linear_bwd_input(dy, w2, da=dg)
+                lss.lss_gelu_bwd(u, dg, du=du)
+            lss.lss_linear_bwd_input(du, w1, da=dh)
+            lss.lss_layernorm_bwd(x, gamma, mean, rstd, dh, dx=dx, dgamma=dgamma, dbeta=dbeta, scratch=scratch)
+            lss.lss_embed_pe_bwd(dx, dpe_rows=dpe)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    names, kid = {}, 0
+    while (name := lss.lss_timing_kernel_name(kid)) is not None:
+        names[kid] = name
+        kid += 1
+
+    def read_kernels(steps):
+        out_ = {}
+        for kid_, name_ in names.items():
+            ms, n = lss.lss_timing_read(kid_)
+            if n:
+                out_[name_] = {"launches_per_step": n / steps, "avg_us": 1e3 * ms / n, "ms_per_step": ms / steps}
+        return out_
+
+    lss.lss_timing_reset()
+    lss.lss_timing_enable(True)
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    lss.lss_timing_enable(False)
+    kernels = read_kernels(2)
+    dom = max(("linear_fwd_kernel", "linear_bwd_kernel"), key=lambda n_: kernels[n_]["ms_per_step"])
+    lss.lss_timing_reset()
+    lss.lss_timing_select([k_ for k_, n_ in names.items() if n_ == dom])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    lss.lss_timing_enable(False)
+    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+    timed = read_kernels(args.steps)
+    kernels[dom] = dict(timed[dom], timed_region=True)
+
+    lin_flops = 2.0 * rows * E * F                  # one linear map of one segment
+    flops_step = 4.0 * lin_flops * w.N
+    # algorithmic bytes per launch: every operand read once, every result written once
+    bytes_per_launch = {
+        "embed_pe_fwd_kernel": 4 * rows * E + 2 * l_s * E, "embed_pe_bwd_kernel": 2 * rows * E + 4 * l_s * E,
+        "layernorm_fwd_kernel": 4 * rows * E + 8 * rows + 8 * E,
+        "layernorm_bwd_kernel": 6 * rows * E + 8 * rows + 4 * E + 8 * E * ((rows + 31) // 32),
+        "layernorm_bwd_params_kernel": 8 * E * ((rows + 31) // 32) + 8 * E,
+        "gelu_fwd_kernel": 4 * rows * F, "gelu_bwd_kernel": 6 * rows * F,
+    }
+    for name, kk in kernels.items():
+        if name in bytes_per_launch:
+            kk["algorithmic_GBps"] = round(bytes_per_launch[name] / (kk["avg_us"] * 1e-6) / 1e9, 1)
+            kk["frac_of_hbm_peak"] = round(kk["algorithmic_GBps"] / PEAK_HBM_GBS, 4)
+        else:
+            kk["algorithmic_tflops"] = round(lin_flops / (kk["avg_us"] * 1e-6) / 1e12, 2)
+        kk["avg_us"] = round(kk["avg_us"], 2)
+        kk["ms_per_step"] = round(kk["ms_per_step"], 4)
+    achieved = lin_flops / (timed[dom]["avg_us"] * 1e-6) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_launch_us": round(timed[dom]["avg_us"], 2), "algorithmic_flops_per_launch": lin_flops}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n_s = min(l_s, max(1, int(2.0e11 / (8.0 * w.B * E * F))))      # about 2e11 fp64 flops of matrix work
+        t = time.perf_counter()
+        xs = oracle.embed_pe(tok_h[:, :n_s], pe_h, 0)
+        hs, _, _ = oracle.layernorm_fwd(xs, gamma_h, beta_h)
+        _, us = oracle.ffn_fwd(hs, w1_h, w2_h)
+        dhs = oracle.ffn_bwd(dy_h[:, :n_s], us, w1_h, w2_h)
+        dxs, _, _ = oracle.layernorm_bwd(xs, gamma_h, dhs)
+        oracle.embed_pe_bwd(dxs)
+        t_cpu = time.perf_counter() - t
+        from threadpoolctl import threadpool_info
+        blas_threads = max([p_["num_threads"] for p_ in threadpool_info() if p_.get("user_api") == "blas"] or [1])
+        cpu_baseline = {"value": round(8.0 * w.B * n_s * E * F / t_cpu / 1e12, 6), "unit": "TFLOP/s",
+                        "cores": blas_threads, "kind": "oracle",
+                        "sample": f"the first {n_s} rows of segment 0 for every batch entry, the same chain of "
+                                  f"operations, {t_cpu:.1f} s of fp64 CPU work, same flop count"}
+
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "segment-local layer operations fwd+bwd: feed-forward matrix TFLOP/s over the whole step on 1 MI355X",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name + "+layer-ops" + ("+fused-gelu" if args.fused_gelu else ""), "B": w.B, "l_x": w.l_x, "N": w.N, "l_s": l_s, "E_m": E, "F": F,
+                   "step": "per segment: x = tok + PE rows, LayerNorm, GeLU(h W1) W2, and the same backwards"},
+        "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "gpu_ms_per_step_events": round(gpu_ms / args.steps, 4),
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +226,11 @@ def main() -> int:
     ap.add_argument("--dropout", type=float, default=None, metavar="P",
                     help="run forward and backward with dropout probability P on the attention weights "
                          "(a further workload: the library's general kernels serve it)")
+    ap.add_argument("--layer-ops", action="store_true",
+                    help="a separate workload: the segment-local remainder of a layer (positional-embedding rows, "
+                         "layer normalisation, feed-forward unit), forward and backward, for every segment")
+    ap.add_argument("--fused-gelu", action="store_true",
+                    help="with --layer-ops: use the GEMM entry points that apply GeLU and its derivative in their epilogues")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device-to-device copy of this many MiB "
@@ -96,6 +257,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
 
     w = synth.WORKLOADS[args.workload]
+    if args.layer_ops:
+        return layer_ops(args, w)
     q, k, v, do = synth.workload_inputs(w)
 
     f32 = args.dtype == "f32"

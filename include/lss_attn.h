@@ -256,7 +256,7 @@ int lss_embed_pe_bwd(const void *dx, int64_t l_s, int64_t B, int64_t E_m,
  *   x, y    [rows, E_m] bf16;  gamma, beta [E_m] float;  mean, rstd [rows] float
  *           (written by the forward, read by the backward)
  * Backward: dx [rows, E_m] bf16, dgamma, dbeta [E_m] float; the sums over rows are
- * taken in a fixed order (blocks of 32 rows, then the blocks in order), through
+ * taken in a fixed order (within blocks of 32 rows, then over the blocks), through
  *   scratch  DEVICE buffer of lss_layernorm_bwd_scratch_bytes(rows, E_m) bytes,
  *            caller-owned, overwritten.
  * E_m <= 4096 (LSS_ERR_SHAPE otherwise); rows = 0 writes zeros to dgamma, dbeta.
@@ -283,11 +283,19 @@ int lss_layernorm_bwd(const void *x, const float *gamma, const float *mean,
  * a, c, dc, da, u, g, dg, du bf16 row-major; w bf16 row-major.  K and N multiples of
  * 128, at most 65536; rows < 2^31 (LSS_ERR_SHAPE otherwise).  bf16 matrix cores,
  * fp32 accumulation.
+ * Two fused forms save the GeLU's own passes over memory and give bit-identical
+ * results to the calls they replace:
+ *   lss_linear_gelu_fwd        u = a w  and  g = GeLU(u)   (u, g [rows, N])
+ *   lss_linear_bwd_input_gelu  du = (dc w^T) * GeLU'(u)    (u, du [rows, K])
  */
 int lss_linear_fwd(const void *a, const void *w, int64_t rows, int64_t K, int64_t N,
                    void *c, void *stream);
 int lss_linear_bwd_input(const void *dc, const void *w, int64_t rows, int64_t K, int64_t N,
                          void *da, void *stream);
+int lss_linear_gelu_fwd(const void *a, const void *w, int64_t rows, int64_t K, int64_t N,
+                        void *u, void *g, void *stream);
+int lss_linear_bwd_input_gelu(const void *dc, const void *w, const void *u,
+                              int64_t rows, int64_t K, int64_t N, void *du, void *stream);
 int lss_gelu_fwd(const void *u, int64_t n, void *g, void *stream);
 int lss_gelu_bwd(const void *u, const void *dg, int64_t n, void *du, void *stream);
 

@@ -418,26 +418,55 @@ static int check_linear(const char *what, const void *a, const void *w, const vo
     return LSS_OK;
 }
 
-int lss_linear_fwd(const void *a, const void *w, int64_t rows, int64_t K, int64_t N, void *c, void *stream)
+static int linear_fwd_impl(const char *what, const void *a, const void *w, int64_t rows, int64_t K, int64_t N, void *c,
+                           void *gelu_c, bool fused, void *stream)
 {
-    if (int rc = check_linear("linear_fwd", a, w, c, rows, K, N)) return rc;
+    if (int rc = check_linear(what, a, w, c, rows, K, N)) return rc;
     if (rows == 0) return LSS_OK;
+    if (fused && !gelu_c) return fail(LSS_ERR_NULL, "%s: NULL tensor pointer", what);
+    if (misaligned(gelu_c)) return fail(LSS_ERR_ALIGN, "%s: tensor pointers must be 16-byte aligned", what);
     using lss::bf16_t;
     const hipError_t e = lss::launch_linear_fwd(static_cast<const bf16_t *>(a), static_cast<const bf16_t *>(w), (int)rows, (int)K,
-                                                (int)N, static_cast<bf16_t *>(c), static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "linear_fwd launch failed: %s", hipGetErrorString(e));
+                                                (int)N, static_cast<bf16_t *>(c), static_cast<bf16_t *>(gelu_c),
+                                                static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "%s launch failed: %s", what, hipGetErrorString(e));
     return LSS_OK;
+}
+
+static int linear_bwd_impl(const char *what, const void *dc, const void *w, const void *gelu_u, bool fused, int64_t rows,
+                           int64_t K, int64_t N, void *da, void *stream)
+{
+    if (int rc = check_linear(what, dc, w, da, rows, K, N)) return rc;
+    if (rows == 0) return LSS_OK;
+    if (fused && !gelu_u) return fail(LSS_ERR_NULL, "%s: NULL tensor pointer", what);
+    if (misaligned(gelu_u)) return fail(LSS_ERR_ALIGN, "%s: tensor pointers must be 16-byte aligned", what);
+    using lss::bf16_t;
+    const hipError_t e = lss::launch_linear_bwd_input(static_cast<const bf16_t *>(dc), static_cast<const bf16_t *>(w),
+                                                      static_cast<const bf16_t *>(gelu_u), (int)rows, (int)K, (int)N,
+                                                      static_cast<bf16_t *>(da), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "%s launch failed: %s", what, hipGetErrorString(e));
+    return LSS_OK;
+}
+
+int lss_linear_fwd(const void *a, const void *w, int64_t rows, int64_t K, int64_t N, void *c, void *stream)
+{
+    return linear_fwd_impl("linear_fwd", a, w, rows, K, N, c, nullptr, false, stream);
+}
+
+int lss_linear_gelu_fwd(const void *a, const void *w, int64_t rows, int64_t K, int64_t N, void *u, void *g, void *stream)
+{
+    return linear_fwd_impl("linear_gelu_fwd", a, w, rows, K, N, u, g, true, stream);
 }
 
 int lss_linear_bwd_input(const void *dc, const void *w, int64_t rows, int64_t K, int64_t N, void *da, void *stream)
 {
-    if (int rc = check_linear("linear_bwd_input", dc, w, da, rows, K, N)) return rc;
-    if (rows == 0) return LSS_OK;
-    using lss::bf16_t;
-    const hipError_t e = lss::launch_linear_bwd_input(static_cast<const bf16_t *>(dc), static_cast<const bf16_t *>(w), (int)rows,
-                                                      (int)K, (int)N, static_cast<bf16_t *>(da), static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "linear_bwd_input launch failed: %s", hipGetErrorString(e));
-    return LSS_OK;
+    return linear_bwd_impl("linear_bwd_input", dc, w, nullptr, false, rows, K, N, da, stream);
+}
+
+int lss_linear_bwd_input_gelu(const void *dc, const void *w, const void *u, int64_t rows, int64_t K, int64_t N, void *du,
+                              void *stream)
+{
+    return linear_bwd_impl("linear_bwd_input_gelu", dc, w, u, true, rows, K, N, du, stream);
 }
 
 static int check_gelu(const char *what, int64_t n)

@@ -158,4 +158,12 @@ __device__ __forceinline__ void load_tile(const T *__restrict__ g, int64_t row_s
     }
 }
 
+// Exact GeLU, u Phi(u), and its derivative Phi(u) + u phi(u) (Phi, phi: the standard normal's
+// distribution function and density).
+__device__ __forceinline__ float gelu_value(float u) { return u * (0.5f * (1.0f + erff(u * 0.70710678118654752f))); }
+__device__ __forceinline__ float gelu_slope(float u)
+{
+    return 0.5f * (1.0f + erff(u * 0.70710678118654752f)) + u * 0.3989422804014327f * __expf(-0.5f * u * u);
+}
+
 } // namespace lss

@@ -91,8 +91,11 @@ hipError_t launch_project_bwd(const bf16_t *dq, const float *dk_part, const floa
 
 // general bf16 linear maps with the same GEMM kernel (the feed-forward unit's two transforms):
 // c[rows, N] = a[rows, K] w[K, N]   and   da[rows, K] = dc[rows, N] w[K, N]^T;  K, N multiples of 128
-hipError_t launch_linear_fwd(const bf16_t *a, const bf16_t *w, int rows, int K, int N, bf16_t *c, hipStream_t st);
-hipError_t launch_linear_bwd_input(const bf16_t *dc, const bf16_t *w, int rows, int K, int N, bf16_t *da, hipStream_t st);
+// with gelu_c: also gelu_c[rows, N] = GeLU(c);  with gelu_u [rows, K]: da = (dc w^T) * GeLU'(gelu_u)
+hipError_t launch_linear_fwd(const bf16_t *a, const bf16_t *w, int rows, int K, int N, bf16_t *c, bf16_t *gelu_c,
+                             hipStream_t st);
+hipError_t launch_linear_bwd_input(const bf16_t *dc, const bf16_t *w, const bf16_t *gelu_u, int rows, int K, int N,
+                                   bf16_t *da, hipStream_t st);
 
 // segment-local row operations (lss_rows.hip); E a multiple of 8
 hipError_t launch_embed_pe_fwd(const bf16_t *tok, const bf16_t *pe, int64_t s0, int l_s, int B, int E, bf16_t *x,

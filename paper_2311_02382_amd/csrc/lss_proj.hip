@@ -47,6 +47,12 @@ struct ProjJob {
     int a_f32;                  // A is float (only in kernels compiled with A_ANY)
     int wg_begin, m_tiles, n_tiles;             // first workgroup id of the job, tiles per batch, column tiles
 };
+// What happens to a finished bf16 tile on its way to memory (the feed-forward unit, whose GeLU
+// would otherwise be a pass over memory of its own):
+//   EPI_GELU       C is written to c0 and GeLU(C), of the rounded C, to c1 (same layout)
+//   EPI_GELU_BWD   C, rounded, is multiplied by GeLU'(U) before it is written; U = a1, laid out like C
+enum { EPI_NONE = 0, EPI_GELU = 1, EPI_GELU_BWD = 2 };
+
 struct ProjArgs {
     ProjJob job[2];
     int n_jobs, lda, ldc, skip_tail;
@@ -95,11 +101,12 @@ struct WTileTr {
     }
 };
 
-template <bool A_ANY, bool W_TR, bool OUT_F32>
+template <bool A_ANY, bool W_TR, bool OUT_F32, int EPI>
 __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     using OutT = typename std::conditional<OUT_F32, float, bf16_t>::type;
+    static_assert(EPI == EPI_NONE || !OUT_F32, "the GeLU epilogues work on bf16 results");
 
     const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -170,7 +177,23 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
                 const int m = i * 16 + (tid >> 5);
                 f32x4 raw = {0.f, 0.f, 0.f, 0.f};
                 if (from_acc) raw = *reinterpret_cast<const f32x4 *>(smem + m * 512 + ((c ^ (m & 31)) * 16));
-                if (col_ok && m < rows_here) *reinterpret_cast<f32x4 *>(dst + (int64_t)m * args.ldc) = raw;
+                if (col_ok && m < rows_here) {
+                    if constexpr (EPI == EPI_GELU_BWD) {
+                        const bf16_t *u = static_cast<const bf16_t *>(J.a1) + (int64_t)batch * J.c_batch_stride + (int64_t)(m0 + m) * args.ldc + n;
+                        const bf16x8 uu = *reinterpret_cast<const bf16x8 *>(u);
+                        bf16x8 cv = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) cv[e] = (bf16_t)((float)cv[e] * gelu_slope((float)uu[e]));
+                        raw = __builtin_bit_cast(f32x4, cv);
+                    }
+                    *reinterpret_cast<f32x4 *>(dst + (int64_t)m * args.ldc) = raw;
+                    if constexpr (EPI == EPI_GELU) {
+                        bf16x8 cv = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) cv[e] = (bf16_t)gelu_value((float)cv[e]);
+                        *reinterpret_cast<bf16x8 *>(c1 + n + (int64_t)m * args.ldc) = cv;
+                    }
+                }
             }
         }
     };
@@ -326,7 +349,7 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
     store_tiles(acc, true);
 }
 
-template <bool A_ANY, bool W_TR, bool OUT_F32>
+template <bool A_ANY, bool W_TR, bool OUT_F32, int EPI = EPI_NONE>
 hipError_t launch_proj(ProjArgs &args, int kernel_id, hipStream_t st)
 {
     int wgs = 0;
@@ -341,12 +364,12 @@ hipError_t launch_proj(ProjArgs &args, int kernel_id, hipStream_t st)
     static std::once_flag once;
     static hipError_t attr = hipSuccess;
     std::call_once(once, [] {
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(proj_gemm_kernel<A_ANY, W_TR, OUT_F32>),
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(proj_gemm_kernel<A_ANY, W_TR, OUT_F32, EPI>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
     });
     if (attr != hipSuccess) return attr;
     TimedLaunch tl(kernel_id, st);
-    hipLaunchKernelGGL((proj_gemm_kernel<A_ANY, W_TR, OUT_F32>), dim3(wgs), dim3(P_NT), P_LDS, st, args);
+    hipLaunchKernelGGL((proj_gemm_kernel<A_ANY, W_TR, OUT_F32, EPI>), dim3(wgs), dim3(P_NT), P_LDS, st, args);
     return hipGetLastError();
 }
 
@@ -405,29 +428,34 @@ hipError_t launch_project_bwd(const bf16_t *dq, const float *dk_part, const floa
     return launch_proj<true, false, true>(args, K_PROJ_BWD, st);
 }
 
-// c = a w for any row count: one job, one tall matrix
-hipError_t launch_linear_fwd(const bf16_t *a, const bf16_t *w, int rows, int K, int N, bf16_t *c, hipStream_t st)
+// c = a w for any row count: one job, one tall matrix; with gelu_c also gelu_c = GeLU(c)
+hipError_t launch_linear_fwd(const bf16_t *a, const bf16_t *w, int rows, int K, int N, bf16_t *c, bf16_t *gelu_c,
+                             hipStream_t st)
 {
     ProjArgs args{};
     args.lda = K; args.ldc = N; args.skip_tail = 0; args.n_jobs = 1;
     ProjJob &J = args.job[0];
-    J.a0 = a; J.a1 = nullptr; J.w = w; J.c0 = c; J.c1 = nullptr;
+    J.a0 = a; J.a1 = nullptr; J.w = w; J.c0 = c; J.c1 = gelu_c;
     J.a_batch_stride = J.c_batch_stride = 0;
     J.rows = J.rows_ok = rows; J.batches = 1;
     J.N = N; J.K = K; J.k_split = K; J.n_split = N; J.ldw = N;
+    if (gelu_c) return launch_proj<false, true, false, EPI_GELU>(args, K_LINEAR_FWD, st);
     return launch_proj<false, true, false>(args, K_LINEAR_FWD, st);
 }
 
-// da = dc w^T: w as stored, [K][N], is the [output column][contraction index] layout read plainly
-hipError_t launch_linear_bwd_input(const bf16_t *dc, const bf16_t *w, int rows, int K, int N, bf16_t *da, hipStream_t st)
+// da = dc w^T: w as stored, [K][N], is the [output column][contraction index] layout read plainly;
+// with gelu_u, da = (dc w^T) * GeLU'(gelu_u)
+hipError_t launch_linear_bwd_input(const bf16_t *dc, const bf16_t *w, const bf16_t *gelu_u, int rows, int K, int N,
+                                   bf16_t *da, hipStream_t st)
 {
     ProjArgs args{};
     args.lda = N; args.ldc = K; args.skip_tail = 0; args.n_jobs = 1;
     ProjJob &J = args.job[0];
-    J.a0 = dc; J.a1 = nullptr; J.w = w; J.c0 = da; J.c1 = nullptr;
+    J.a0 = dc; J.a1 = gelu_u; J.w = w; J.c0 = da; J.c1 = nullptr;
     J.a_batch_stride = J.c_batch_stride = 0;
     J.rows = J.rows_ok = rows; J.batches = 1;
     J.N = K; J.K = N; J.k_split = N; J.n_split = K; J.ldw = N;
+    if (gelu_u) return launch_proj<false, false, false, EPI_GELU_BWD>(args, K_LINEAR_BWD, st);
     return launch_proj<false, false, false>(args, K_LINEAR_BWD, st);
 }
 

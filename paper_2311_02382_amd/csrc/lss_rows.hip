@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t *__rest
 // fourth of them: dx of a row needs two row sums; the contributions to dgamma and dbeta stay in the
 // lane that owns the columns and are added up over the wavefront's rows in row order, then over the
 // four wavefronts in wavefront order (through LDS) into part[workgroup] -- a second kernel adds
-// the workgroups' parts in workgroup order.
+// the workgroups' parts in a fixed order.
 constexpr int LN_ROWS = 32;
 template <int NCH>
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t *__restrict__ x, const float *__restrict__ gamma,
@@ -193,19 +193,27 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t *__rest
         part[((int64_t)blockIdx.x * 2 + which) * E + cc] = acc;
     }
 }
+// 64 columns x 16 groups of parts per workgroup: thread (group pg, chunk cc) adds parts pg, pg + 16, ...
+// of its four columns in increasing order, then the 16 group sums are added in group order.
 __global__ __launch_bounds__(256) void layernorm_bwd_params_kernel(const float *__restrict__ part, int n_parts, int E,
                                                                    float *__restrict__ dgamma, float *__restrict__ dbeta)
 {
-    const int col = blockIdx.x * blockDim.x + threadIdx.x;      // [0, 2E)
-    if (col >= 2 * E) return;
-    const int which = col / E, cc = col % E;
-    float acc = 0.f;
-    for (int p = 0; p < n_parts; ++p) acc += part[((int64_t)p * 2 + which) * E + cc];
-    (which == 0 ? dgamma : dbeta)[cc] = acc;
+    __shared__ f32x4 red[16][16];
+    const int cc = threadIdx.x & 15, pg = threadIdx.x >> 4;
+    const int col = (blockIdx.x * 16 + cc) * 4;         // [0, 2E): dgamma's columns, then dbeta's
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (col < 2 * E)
+        for (int p = pg; p < n_parts; p += 16) acc += *reinterpret_cast<const f32x4 *>(part + (int64_t)p * 2 * E + col);
+    red[pg][cc] = acc;
+    __syncthreads();
+    if (pg == 0 && col < 2 * E) {
+#pragma unroll
+        for (int j = 1; j < 16; ++j) acc += red[j][cc];
+        *reinterpret_cast<f32x4 *>(col < E ? dgamma + col : dbeta + (col - E)) = acc;
+    }
 }
 
 // g = GeLU(u) = u Phi(u);  du = dg * (Phi(u) + u phi(u)).  One 16-byte chunk per thread.
-__device__ __forceinline__ float norm_cdf(float u) { return 0.5f * (1.0f + erff(u * 0.70710678118654752f)); }
 __global__ __launch_bounds__(256) void gelu_fwd_kernel(const bf16_t *__restrict__ u, int64_t n_chunks, bf16_t *__restrict__ g)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -213,7 +221,7 @@ __global__ __launch_bounds__(256) void gelu_fwd_kernel(const bf16_t *__restrict_
     float a[8];
     unpack8(*reinterpret_cast<const bf16x8 *>(u + i * 8), a);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) a[e] = a[e] * norm_cdf(a[e]);
+    for (int e = 0; e < 8; ++e) a[e] = gelu_value(a[e]);
     *reinterpret_cast<bf16x8 *>(g + i * 8) = pack8(a);
 }
 __global__ __launch_bounds__(256) void gelu_bwd_kernel(const bf16_t *__restrict__ u, const bf16_t *__restrict__ dg,
@@ -225,8 +233,7 @@ __global__ __launch_bounds__(256) void gelu_bwd_kernel(const bf16_t *__restrict_
     unpack8(*reinterpret_cast<const bf16x8 *>(u + i * 8), a);
     unpack8(*reinterpret_cast<const bf16x8 *>(dg + i * 8), d);
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-        d[e] *= norm_cdf(a[e]) + a[e] * 0.3989422804014327f * __expf(-0.5f * a[e] * a[e]);
+    for (int e = 0; e < 8; ++e) d[e] *= gelu_slope(a[e]);
     *reinterpret_cast<bf16x8 *>(du + i * 8) = pack8(d);
 }
 
@@ -293,7 +300,7 @@ hipError_t launch_layernorm_bwd(const bf16_t *x, const float *gamma, const float
         if (e != hipSuccess) return e;
     }
     TimedLaunch tl(K_LN_PARAMS, st);
-    hipLaunchKernelGGL(layernorm_bwd_params_kernel, dim3(blocks_for(2 * (int64_t)E)), dim3(256), 0, st, scratch, n_parts, E,
+    hipLaunchKernelGGL(layernorm_bwd_params_kernel, dim3((unsigned)((2 * E + 63) / 64)), dim3(256), 0, st, scratch, n_parts, E,
                        dgamma, dbeta);
     return hipGetLastError();
 }

@@ -23,7 +23,8 @@ EXPORTS = ["lss_version", "lss_last_error", "lss_set_option", "lss_workspace_byt
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
            "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd",
            "lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_layernorm_fwd", "lss_layernorm_bwd_scratch_bytes",
-           "lss_layernorm_bwd", "lss_linear_fwd", "lss_linear_bwd_input", "lss_gelu_fwd", "lss_gelu_bwd",
+           "lss_layernorm_bwd", "lss_linear_fwd", "lss_linear_bwd_input", "lss_linear_gelu_fwd",
+           "lss_linear_bwd_input_gelu", "lss_gelu_fwd", "lss_gelu_bwd",
            "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
            "lss_timing_read", "lss_timing_kernel_name"]
 
@@ -78,10 +79,12 @@ def load():
     lib.lss_layernorm_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
     lib.lss_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     lib.lss_linear_bwd_input.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    lib.lss_linear_gelu_fwd.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp]
+    lib.lss_linear_bwd_input_gelu.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
     lib.lss_gelu_fwd.argtypes = [vp, i64, vp, vp]
     lib.lss_gelu_bwd.argtypes = [vp, vp, i64, vp, vp]
     for name in ("lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_layernorm_fwd", "lss_layernorm_bwd", "lss_linear_fwd",
-                 "lss_linear_bwd_input", "lss_gelu_fwd", "lss_gelu_bwd"):
+                 "lss_linear_bwd_input", "lss_linear_gelu_fwd", "lss_linear_bwd_input_gelu", "lss_gelu_fwd", "lss_gelu_bwd"):
         getattr(lib, name).restype = ci
     lib.lss_timing_enable.argtypes = [ci]
     lib.lss_timing_select.argtypes = [ctypes.c_uint]
@@ -395,6 +398,30 @@ def lss_linear_bwd_input(dc, w, da=None, stream=None):
     da = _out(da, (*dc.shape[:-1], K), torch.bfloat16, dc)
     _check(load().lss_linear_bwd_input(_ptr(dc), _ptr(w), rows, K, N, _ptr(da), _stream_ptr(stream)))
     return da
+
+
+def lss_linear_gelu_fwd(a, w, u=None, g=None, stream=None):
+    """u = a w and g = GeLU(u) in one kernel; returns (u, g), both [..., N] bf16."""
+    K, N = w.shape
+    if a.shape[-1] != K:
+        raise ValueError("a's last dimension must equal w's rows")
+    _dev(a, torch.bfloat16, "a"); _dev(w, torch.bfloat16, "w")
+    u = _out(u, (*a.shape[:-1], N), torch.bfloat16, a)
+    g = _out(g, (*a.shape[:-1], N), torch.bfloat16, a)
+    _check(load().lss_linear_gelu_fwd(_ptr(a), _ptr(w), a.numel() // K, K, N, _ptr(u), _ptr(g), _stream_ptr(stream)))
+    return u, g
+
+
+def lss_linear_bwd_input_gelu(dc, w, u, du=None, stream=None):
+    """du = (dc w^T) * GeLU'(u) in one kernel.  dc [..., N], w [K, N], u [..., K] -> du [..., K], bf16."""
+    K, N = w.shape
+    if dc.shape[-1] != N or u.shape[-1] != K or u.numel() // K != dc.numel() // N:
+        raise ValueError("shapes disagree")
+    for t, nm in ((dc, "dc"), (w, "w"), (u, "u")):
+        _dev(t, torch.bfloat16, nm)
+    du = _out(du, u.shape, torch.bfloat16, u)
+    _check(load().lss_linear_bwd_input_gelu(_ptr(dc), _ptr(w), _ptr(u), dc.numel() // N, K, N, _ptr(du), _stream_ptr(stream)))
+    return du
 
 
 def lss_gelu_fwd(u, g=None, stream=None):

@@ -139,6 +139,12 @@ def test_layer_operation_argument_checks(lib):
         assert fn(0x1000, 0, 16, 256, 256, 0x3000, None) == -1
         assert fn(0x1008, 0x2000, 16, 256, 256, 0x3000, None) == -4
         assert fn(0, 0, 0, 256, 256, 0, None) == 0
+    assert lib.lss_linear_gelu_fwd(0x1000, 0x2000, 16, 256, 256, 0x3000, None, None) == -1
+    assert lib.lss_linear_gelu_fwd(0x1000, 0x2000, 16, 256, 256, 0x3000, 0x4008, None) == -4
+    assert lib.lss_linear_gelu_fwd(0x1000, 0x2000, 16, 256, 200, 0x3000, 0x4000, None) == -2
+    assert lib.lss_linear_bwd_input_gelu(0x1000, 0x2000, None, 16, 256, 256, 0x3000, None) == -1
+    assert lib.lss_linear_bwd_input_gelu(0x1000, 0x2000, 0x4004, 16, 256, 256, 0x3000, None) == -4
+    assert lib.lss_linear_bwd_input_gelu(None, None, None, 0, 256, 256, None, None) == 0
     assert lib.lss_gelu_fwd(0x1000, 12, 0x2000, None) == -2
     assert lib.lss_gelu_fwd(0x1000, 16, None, None) == -1
     assert lib.lss_gelu_bwd(0x1000, 0x2000, 16, 0x3004, None) == -4

@@ -153,6 +153,26 @@ def test_ffn_matches_oracle(rows, E, F):
     assert rel_err(to_np(dh), rdh) <= TOL["bf16"]["t"]
 
 
+@pytest.mark.parametrize("rows,E,F", FFN_SHAPES)
+def test_fused_gelu_forms_equal_the_separate_calls(rows, E, F):
+    Hh = staged(7600 + rows, (rows, E))
+    W1, W2 = staged(7601 + rows, (E, F), std=E ** -0.5), staged(7602 + rows, (F, E), std=F ** -0.5)
+    DY = staged(7603 + rows, (rows, E))
+    u = lss.lss_linear_fwd(Hh.dev, W1.dev)
+    g = lss.lss_gelu_fwd(u)
+    u2, g2 = lss.lss_linear_gelu_fwd(Hh.dev, W1.dev)
+    assert torch.equal(u, u2) and torch.equal(g, g2)
+    du = lss.lss_gelu_bwd(u, lss.lss_linear_bwd_input(DY.dev, W2.dev))
+    du2 = lss.lss_linear_bwd_input_gelu(DY.dev, W2.dev, u)
+    assert torch.equal(du, du2)
+    # and the fused chain against the oracle, end to end
+    y = lss.lss_linear_fwd(g2, W2.dev)
+    dh = lss.lss_linear_bwd_input(du2, W1.dev)
+    ry, _ = oracle.ffn_fwd(Hh.f64, W1.f64, W2.f64)
+    assert rel_err(to_np(y), ry) <= TOL["bf16"]["t"]
+    assert rel_err(to_np(dh), oracle.ffn_bwd(DY.f64, to_np(u), W1.f64, W2.f64)) <= TOL["bf16"]["t"]
+
+
 def test_linear_outputs_preallocated_and_on_a_side_stream():
     rows, E, F = 600, 256, 512
     A, W = staged(7500, (rows, E)), staged(7501, (E, F), std=E ** -0.5)
