@@ -51,7 +51,9 @@ def _load():
         lib.lss_oracle_segment_fwd_dropout.argtypes = [dp, dp, dp, i64, i64, i64, i64, i64, i64, ci, f64, u64, dp, dp]
         lib.lss_oracle_segment_bwd_dropout.argtypes = [dp, dp, dp, i64, i64, i64, i64, i64, i64, ci, f64, u64, dp, dp, dp, dp]
         lib.lss_oracle_dropout_mask.argtypes = [f64, u64, i64, i64, i64, i64, i64, dp]
-        for f in (lib.lss_oracle_segment_fwd_dropout, lib.lss_oracle_segment_bwd_dropout, lib.lss_oracle_dropout_mask):
+        lib.lss_oracle_activation_keep.argtypes = [f64, u64, i64, i64, i64, i64, dp]
+        for f in (lib.lss_oracle_segment_fwd_dropout, lib.lss_oracle_segment_bwd_dropout, lib.lss_oracle_dropout_mask,
+                  lib.lss_oracle_activation_keep):
             f.restype = ci
         for f in (lib.lss_oracle_segment_fwd, lib.lss_oracle_segment_bwd,
                   lib.lss_oracle_segment_weights, lib.lss_oracle_reduce_partials,
@@ -230,7 +232,12 @@ def project_bwd(dq, dk_partial, dv_partial, w_q, w_kv):
 #       y = (x - mean) / sqrt(var + eps) * gamma + beta,  var the biased variance;
 #   GeLU(u) = u Phi(u) with the exact normal distribution function;
 #   feed-forward y = GeLU(h W_1) W_2, no bias (none is mentioned), D_inner columns in between.
-# Dropout inside these units is left out.  Plain numpy float64; nothing blocked or fused.
+#   residual connection with dropout on the branch (Principle 1 lists dropout among the operations
+#       that act on segments independently): out = x + dropout(delta), inverted dropout as for the
+#       attention weights, the keep decision of element (batch b, global row g, column c) drawn by
+#       the same generator with (batch*head, row, key) := (b, g, c) -- a function of the position in
+#       the whole sequence, so the segments' results concatenate to the sequential one.
+# Plain numpy float64; nothing blocked or fused.
 
 def embed_pe(tok, pe_table, seg_offset: int):
     """x_i = tok_i + PE[seg_offset : seg_offset + l_s]  (Principle 2).  tok [B,l_s,E], pe_table [l_x,E]."""
@@ -245,6 +252,19 @@ def embed_pe_bwd(dx):
     """Gradient of the segment's rows of the table: the sum of dx over the batch, [l_s, E].
     (The gradient of tok is dx itself.)"""
     return _f64(dx).sum(axis=0)
+
+
+def residual_dropout_add(x, delta, seg_offset: int, p: float = 0.0, seed: int = 0):
+    """out = x + dropout(delta) on a segment's rows [B, l_s, E] (x may be None: the dropout alone).
+    Being linear and diagonal in delta, the same call maps d out to d delta."""
+    delta = _f64(delta)
+    B, l_s, E = delta.shape
+    keep = np.empty((B, l_s, E), dtype=np.uint8)
+    rc = _load().lss_oracle_activation_keep(float(p), int(seed), int(seg_offset), l_s, E, B, _p(keep))
+    if rc != 0:
+        raise ValueError(f"lss_oracle_activation_keep rejected the arguments (rc={rc})")
+    y = delta * keep / (1.0 - p)
+    return y if x is None else _f64(x, delta.shape) + y
 
 
 def layernorm_fwd(x, gamma, beta, eps: float = 1e-5):

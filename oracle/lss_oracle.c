@@ -283,6 +283,21 @@ int lss_oracle_dropout_mask(double p, uint64_t seed, int64_t s0, int64_t l_s, in
     return 0;
 }
 
+/* keep mask for dropout on a segment's activations [B, l_s, E] (the residual branches of a layer):
+ * element (b, r, c) is decided as the weight of (batch*head b, global row s0 + r, key c) would be */
+int lss_oracle_activation_keep(double p, uint64_t seed, int64_t s0, int64_t l_s, int64_t E, int64_t B,
+                               unsigned char *mask)
+{
+    if (l_s < 0 || E < 1 || s0 < 0 || B < 0 || !(p >= 0.0 && p < 1.0)) return -1;
+    const uint32_t thr = drop_threshold(p);
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t r = 0; r < l_s; ++r) {
+            const uint32_t rk = row_key(seed, (uint32_t)b, (uint32_t)(s0 + r));
+            for (int64_t c = 0; c < E; ++c) mask[(b * l_s + r) * E + c] = (unsigned char)keep(rk, seed, (uint32_t)c, thr);
+        }
+    return 0;
+}
+
 /* Forward with dropout: as lss_oracle_segment_fwd, with out = sum_j keep_j P[j] / (1 - p) v[j]. */
 int lss_oracle_segment_fwd_dropout(const double *q_seg, const double *k, const double *v,
                                    int64_t s0, int64_t l_s, int64_t l_x, int64_t B, int64_t H,

@@ -107,3 +107,40 @@ def test_ffn_against_loops_torch_and_finite_differences():
         assert abs(fd - dh[idx]) <= 1e-7 * max(1.0, abs(fd))
     # row-distributed: a segment's rows give the rows of the whole (Principle 1)
     assert np.array_equal(oracle.ffn_fwd(h[:, 1:3], w1, w2)[0], y[:, 1:3])
+
+
+def test_residual_dropout_add_pins():
+    B, l_x, E = 2, 24, 40
+    x, delta = _rand(61, B, l_x, E), _rand(62, B, l_x, E)
+    # p = 0 is the plain residual connection
+    assert np.array_equal(oracle.residual_dropout_add(x, delta, 0, 0.0, 7), x + delta)
+    p, seed = 0.25, 0x1234_5678_9ABC
+    full = oracle.residual_dropout_add(x, delta, 0, p, seed)
+    # every element is either untouched (dropped) or moved by delta / (1 - p) (kept): nothing else
+    moved = full - x
+    kept = np.isclose(moved, delta / (1 - p))
+    assert np.all(kept | (moved == 0.0))
+    # Principle 1: decided by the position in the whole sequence, so segments concatenate
+    for s0, l_s in ((0, 7), (7, 9), (16, 8)):
+        seg = oracle.residual_dropout_add(x[:, s0:s0 + l_s], delta[:, s0:s0 + l_s], s0, p, seed)
+        assert np.array_equal(seg, full[:, s0:s0 + l_s])
+    # ... and a segment evaluated at the wrong offset gets another mask
+    assert not np.array_equal(oracle.residual_dropout_add(x[:, 8:16], delta[:, 8:16], 0, p, seed), full[:, 8:16])
+    # the decisions are those of the attention generator for (batch*head, row, key) = (b, g, c)
+    ref = oracle.dropout_mask(p, seed, 0, l_x, max(E, l_x), B, 1)[:, 0, :, :E].astype(bool)
+    assert np.array_equal(kept, ref)
+    # batch entries, seeds and rows draw different masks; the keep rate is 1 - p within coin-flip noise
+    big = oracle.residual_dropout_add(None, np.ones((4, 200, 256)), 1000, p, seed)
+    rate = (big != 0).mean()
+    n = big.size
+    assert abs(rate - (1 - p)) < 5 * np.sqrt(p * (1 - p) / n)
+    assert not np.array_equal(big[0], big[1])
+    assert not np.array_equal(big, oracle.residual_dropout_add(None, np.ones((4, 200, 256)), 1000, p, seed + 1))
+    assert np.all((big == 0) | np.isclose(big, 1 / (1 - p)))
+    # expectation over seeds is the identity (inverted dropout is unbiased)
+    mean = np.mean([oracle.residual_dropout_add(None, np.ones((1, 8, 64)), 3, p, s) for s in range(400)], axis=0)
+    assert abs(mean.mean() - 1.0) < 0.01
+    # backward: the map delta -> out is linear and diagonal, so it is its own adjoint
+    dout = _rand(63, B, l_x, E)
+    ddelta = oracle.residual_dropout_add(None, dout, 0, p, seed)
+    assert np.isclose((dout * (full - x)).sum(), (ddelta * delta).sum())
