@@ -60,7 +60,7 @@ def measured_traffic(workload: str, kernel: str):
 def layer_ops(args, w) -> int:
     """The segment-local remainder of a layer (Section 3, Principles 1 and 2) on the workload's shape:
     per segment, x = tok + PE rows, LayerNorm, feed-forward unit (E_m -> 4 E_m -> E_m, exact GeLU),
-    then the same backwards.  `value` is the feed-forward unit's matrix flops (8 * rows * E_m * 4 E_m
+    residual connection with dropout 0.1 on the branch, then the same backwards.  `value` is the feed-forward unit's matrix flops (8 * rows * E_m * 4 E_m
     per segment) over the time of the whole step, streaming kernels included."""
     import numpy as np
     import torch
@@ -90,7 +90,8 @@ def layer_ops(args, w) -> int:
     beta, beta_h = stage(w.seed + 26, (E,), 0.1, bf16=False)
     tok_seg = [tok[:, s0:s0 + l_s].contiguous() for s0 in offs]
     bf = dict(dtype=torch.bfloat16, device=dev)
-    x, h, dh, dx = (torch.empty((w.B, l_s, E), **bf) for _ in range(4))
+    P_HIDDEN = 0.1      # dropout on the feed-forward branch of the residual connection
+    x, h, dh, dx, x2, dyb = (torch.empty((w.B, l_s, E), **bf) for _ in range(6))
     u, g, dg, du = (torch.empty((w.B, l_s, F), **bf) for _ in range(4))
     y = torch.empty((w.B, l_s, E), **bf)
     mean, rstd = (torch.empty((rows,), dtype=torch.float32, device=dev) for _ in range(2))
@@ -104,16 +105,20 @@ def layer_ops(args, w) -> int:
             lss.lss_layernorm_fwd(x, gamma, beta, y=h, mean=mean, rstd=rstd)
             if args.fused_gelu:     # GeLU and its derivative in the GEMMs' epilogues: same bits, two launches fewer
                 lss.lss_linear_gelu_fwd(h, w1, u=u, g=g)
-                lss.lss_linear_fwd(g, w2, c=y)
-                lss.lss_linear_bwd_input_gelu(dy, w2, u, du=du)
             else:
                 lss.lss_linear_fwd(h, w1, c=u)
                 lss.lss_gelu_fwd(u, g=g)
-                lss.lss_linear_fwd(g, w2, c=y)
-                lss.lss_linear_bwd_input(dy, w2, da=dg)
+            lss.lss_linear_fwd(g, w2, c=y)
+            lss.lss_residual_dropout_add(x, y, s0, P_HIDDEN, w.seed, out=x2)          # x2 = x + dropout(y)
+            lss.lss_residual_dropout_add(None, dy, s0, P_HIDDEN, w.seed, out=dyb)       # gradient entering the branch
+            if args.fused_gelu:
+                lss.lss_linear_bwd_input_gelu(dyb, w2, u, du=du)
+            else:
+                lss.lss_linear_bwd_input(dyb, w2, da=dg)
                 lss.lss_gelu_bwd(u, dg, du=du)
             lss.lss_linear_bwd_input(du, w1, da=dh)
             lss.lss_layernorm_bwd(x, gamma, mean, rstd, dh, dx=dx, dgamma=dgamma, dbeta=dbeta, scratch=scratch)
+            lss.lss_residual_dropout_add(dy, dx, s0, 0.0, 0, out=dx)                    # + the gradient on the skip path
             lss.lss_embed_pe_bwd(dx, dpe_rows=dpe)
 
     for _ in range(args.warmup):
@@ -166,6 +171,7 @@ def layer_ops(args, w) -> int:
         "layernorm_bwd_kernel": 6 * rows * E + 8 * rows + 4 * E + 8 * E * ((rows + 31) // 32),
         "layernorm_bwd_params_kernel": 8 * E * ((rows + 31) // 32) + 8 * E,
         "gelu_fwd_kernel": 4 * rows * F, "gelu_bwd_kernel": 6 * rows * F,
+        "residual_add_kernel": 16 * rows * E / 3.0,        # three launches: 3, 2 and 3 tensors of rows * E bf16
     }
     for name, kk in kernels.items():
         if name in bytes_per_launch:
@@ -187,10 +193,12 @@ def layer_ops(args, w) -> int:
         t = time.perf_counter()
         xs = oracle.embed_pe(tok_h[:, :n_s], pe_h, 0)
         hs, _, _ = oracle.layernorm_fwd(xs, gamma_h, beta_h)
-        _, us = oracle.ffn_fwd(hs, w1_h, w2_h)
-        dhs = oracle.ffn_bwd(dy_h[:, :n_s], us, w1_h, w2_h)
+        ys, us = oracle.ffn_fwd(hs, w1_h, w2_h)
+        oracle.residual_dropout_add(xs, ys, 0, P_HIDDEN, w.seed)
+        dybs = oracle.residual_dropout_add(None, dy_h[:, :n_s], 0, P_HIDDEN, w.seed)
+        dhs = oracle.ffn_bwd(dybs, us, w1_h, w2_h)
         dxs, _, _ = oracle.layernorm_bwd(xs, gamma_h, dhs)
-        oracle.embed_pe_bwd(dxs)
+        oracle.embed_pe_bwd(dy_h[:, :n_s] + dxs)
         t_cpu = time.perf_counter() - t
         from threadpoolctl import threadpool_info
         blas_threads = max([p_["num_threads"] for p_ in threadpool_info() if p_.get("user_api") == "blas"] or [1])
@@ -206,7 +214,7 @@ def layer_ops(args, w) -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name + "+layer-ops" + ("+fused-gelu" if args.fused_gelu else ""), "B": w.B, "l_x": w.l_x, "N": w.N, "l_s": l_s, "E_m": E, "F": F,
-                   "step": "per segment: x = tok + PE rows, LayerNorm, GeLU(h W1) W2, and the same backwards"},
+                   "step": "per segment: x = tok + PE rows, LayerNorm, GeLU(h W1) W2, x + dropout(.), and the same backwards"},
         "frac_of_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "gpu_ms_per_step_events": round(gpu_ms / args.steps, 4),
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels}))

@@ -250,6 +250,24 @@ int lss_embed_pe_bwd(const void *dx, int64_t l_s, int64_t B, int64_t E_m,
                      float *dpe_rows, void *stream);
 
 /*
+ * Residual connection with dropout on the branch (Principle 1 counts dropout among
+ * the operations that act on each segment independently):
+ *     out = x + dropout(delta),   dropout: keep with probability 1 - p_drop, kept
+ *                                 elements times 1 / (1 - p_drop).
+ * Element (b, r, c) is decided by the generator of lss_segment_attn_fwd_dropout with
+ * (batch*head, row, key) := (b, seg_offset + r, c): a function of the position in
+ * the whole sequence, so the segments' results concatenate to the sequential one.
+ * The backward of the branch is the same call on the gradient: d delta =
+ * lss_residual_dropout_add(NULL, d out, ...) with the same seg_offset, p_drop, seed.
+ *   x      [B, l_s, E_m] bf16, or NULL (taken as zeros)
+ *   delta, out  [B, l_s, E_m] bf16; out may alias x or delta
+ * p_drop in [0, 1) (LSS_ERR_RANGE otherwise); 0 is the plain sum.
+ */
+int lss_residual_dropout_add(const void *x, const void *delta, int64_t seg_offset,
+                             int64_t l_s, int64_t B, int64_t E_m,
+                             double p_drop, uint64_t seed, void *out, void *stream);
+
+/*
  * Layer normalisation of each row over its E_m columns (the encoder/decoder blocks
  * of Section 2.2; the paper gives no formula: the usual one, biased variance):
  *     y = (x - mean) * rstd * gamma + beta,   rstd = 1 / sqrt(var + eps).

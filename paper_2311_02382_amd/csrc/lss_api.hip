@@ -356,6 +356,27 @@ int lss_embed_pe_bwd(const void *dx, int64_t l_s, int64_t B, int64_t E_m, float 
     return LSS_OK;
 }
 
+int lss_residual_dropout_add(const void *x, const void *delta, int64_t seg_offset, int64_t l_s, int64_t B, int64_t E_m,
+                             double p_drop, uint64_t seed, void *out, void *stream)
+{
+    if (l_s < 0 || B < 0 || E_m < 8 || E_m % 8 != 0 || l_s > INT32_MAX || B > INT32_MAX || E_m > 65536)
+        return fail(LSS_ERR_SHAPE, "residual_dropout_add: bad shape (l_s %lld, B %lld, E_m %lld)", (long long)l_s, (long long)B,
+                    (long long)E_m);
+    if (seg_offset < 0 || seg_offset + l_s > (int64_t)UINT32_MAX)
+        return fail(LSS_ERR_RANGE, "residual_dropout_add: seg_offset = %lld", (long long)seg_offset);
+    if (int rc = check_dropout(p_drop)) return rc;
+    if (B == 0 || l_s == 0) return LSS_OK;
+    if (!delta || !out) return fail(LSS_ERR_NULL, "residual_dropout_add: NULL tensor pointer");
+    if (misaligned(x) || misaligned(delta) || misaligned(out))
+        return fail(LSS_ERR_ALIGN, "residual_dropout_add: tensor pointers must be 16-byte aligned");
+    using lss::bf16_t;
+    const hipError_t e = lss::launch_residual_add(static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(delta),
+                                                  dropout_args(p_drop, seed), seg_offset, (int)l_s, (int)B, (int)E_m,
+                                                  static_cast<bf16_t *>(out), static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "residual_dropout_add launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
 static int check_layernorm(const char *what, int64_t rows, int64_t E_m)
 {
     if (rows < 0 || E_m < 8 || E_m % 8 != 0 || E_m > lss::layernorm_max_columns())

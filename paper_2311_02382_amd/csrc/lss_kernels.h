@@ -68,7 +68,7 @@ hipError_t launch_bwd_bf16_main(const SegShape &s, const DropArgs &drop, const b
 // Optional per-kernel timing for benchmarks: when enabled, every launch site brackets its
 // kernel with a pair of HIP events on the launch stream.
 enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_BWD_MAIN, K_PROJ_FWD, K_PROJ_BWD,
-                K_PE_FWD, K_PE_BWD, K_LN_FWD, K_LN_BWD, K_LN_PARAMS, K_GELU_FWD, K_GELU_BWD, K_LINEAR_FWD, K_LINEAR_BWD, K_COUNT };
+                K_PE_FWD, K_PE_BWD, K_LN_FWD, K_LN_BWD, K_LN_PARAMS, K_GELU_FWD, K_GELU_BWD, K_LINEAR_FWD, K_LINEAR_BWD, K_RESIDUAL, K_COUNT };
 void timing_begin(int id, hipStream_t st);
 void timing_end(int id, hipStream_t st);
 struct TimedLaunch {    // RAII bracket around one kernel launch
@@ -101,6 +101,8 @@ hipError_t launch_linear_bwd_input(const bf16_t *dc, const bf16_t *w, const bf16
 hipError_t launch_embed_pe_fwd(const bf16_t *tok, const bf16_t *pe, int64_t s0, int l_s, int B, int E, bf16_t *x,
                                hipStream_t st);
 hipError_t launch_embed_pe_bwd(const bf16_t *dx, int l_s, int B, int E, float *dpe, hipStream_t st);
+hipError_t launch_residual_add(const bf16_t *x, const bf16_t *delta, const DropArgs &drop, int64_t s0, int l_s, int B, int E,
+                               bf16_t *out, hipStream_t st);
 int layernorm_max_columns();
 size_t layernorm_bwd_scratch_bytes(int64_t rows, int E);
 hipError_t launch_layernorm_fwd(const bf16_t *x, const float *gamma, const float *beta, float eps, int64_t rows, int E,

@@ -68,6 +68,30 @@ __global__ __launch_bounds__(256) void embed_pe_bwd_kernel(const bf16_t *__restr
     *reinterpret_cast<f32x4 *>(dpe + i * 8 + 4) = f32x4{acc[4], acc[5], acc[6], acc[7]};
 }
 
+// out = x + dropout(delta) (x may be null: the dropout alone); element (b, r, c) is decided like the
+// attention weight of (batch*head b, global row s0 + r, key c).  One 16-byte chunk per thread.
+template <bool DROP>
+__global__ __launch_bounds__(256) void residual_add_kernel(const bf16_t *x, const bf16_t *delta, DropArgs dr, int64_t s0,
+                                                           int l_s, int64_t n_chunks, int cpr, bf16_t *out)    // out may alias x or delta
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_chunks) return;
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, dl[8];
+    if (x) unpack8(*reinterpret_cast<const bf16x8 *>(x + i * 8), a);
+    unpack8(*reinterpret_cast<const bf16x8 *>(delta + i * 8), dl);
+    if constexpr (DROP) {
+        const int64_t row = i / cpr;
+        const uint32_t c0 = (uint32_t)(i % cpr) * 8u;
+        const uint32_t rk = drop_row_key(dr.seed_lo, (uint32_t)(row / l_s), (uint32_t)(s0 + row % l_s));
+        const uint32_t cs = drop_col_seed(dr.seed_hi);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dl[e] = drop_keep(rk, drop_col_key(cs, c0 + e), dr.thr) ? dl[e] * dr.scale : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] += dl[e];
+    *reinterpret_cast<bf16x8 *>(out + i * 8) = pack8(a);
+}
+
 constexpr int LN_MAXC = 8;      // 16-byte chunks a lane may hold: rows of up to 64 * 8 * 8 = 4096 columns
 
 // One wavefront per row: the row is read once into registers (lane l holds chunks l, l + 64, ...
@@ -256,6 +280,18 @@ hipError_t launch_embed_pe_bwd(const bf16_t *dx, int l_s, int B, int E, float *d
     if (n == 0) return hipSuccess;
     TimedLaunch tl(K_PE_BWD, st);
     hipLaunchKernelGGL(embed_pe_bwd_kernel, dim3(blocks_for(n)), dim3(256), 0, st, dx, B, l_s, E / 8, dpe);
+    return hipGetLastError();
+}
+hipError_t launch_residual_add(const bf16_t *x, const bf16_t *delta, const DropArgs &drop, int64_t s0, int l_s, int B, int E,
+                               bf16_t *out, hipStream_t st)
+{
+    const int64_t n = (int64_t)B * l_s * (E / 8);
+    if (n == 0) return hipSuccess;
+    TimedLaunch tl(K_RESIDUAL, st);
+    if (drop.thr != 0)
+        hipLaunchKernelGGL(residual_add_kernel<true>, dim3(blocks_for(n)), dim3(256), 0, st, x, delta, drop, s0, l_s, n, E / 8, out);
+    else
+        hipLaunchKernelGGL(residual_add_kernel<false>, dim3(blocks_for(n)), dim3(256), 0, st, x, delta, drop, s0, l_s, n, E / 8, out);
     return hipGetLastError();
 }
 int layernorm_max_columns() { return 64 * LN_MAXC * 8; }

@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_E
 EXPORTS = ["lss_version", "lss_last_error", "lss_set_option", "lss_workspace_bytes", "lss_set_workspace",
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
            "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd",
-           "lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_layernorm_fwd", "lss_layernorm_bwd_scratch_bytes",
+           "lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_residual_dropout_add", "lss_layernorm_fwd", "lss_layernorm_bwd_scratch_bytes",
            "lss_layernorm_bwd", "lss_linear_fwd", "lss_linear_bwd_input", "lss_linear_gelu_fwd",
            "lss_linear_bwd_input_gelu", "lss_gelu_fwd", "lss_gelu_bwd",
            "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
@@ -73,6 +73,8 @@ def load():
     lib.lss_project_bwd.restype = ci
     lib.lss_embed_pe_fwd.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp, vp]
     lib.lss_embed_pe_bwd.argtypes = [vp, i64, i64, i64, vp, vp]
+    lib.lss_residual_dropout_add.argtypes = [vp, vp, i64, i64, i64, i64, f64, u64, vp, vp]
+    lib.lss_residual_dropout_add.restype = ci
     lib.lss_layernorm_fwd.argtypes = [vp, vp, vp, f64, i64, i64, vp, vp, vp, vp]
     lib.lss_layernorm_bwd_scratch_bytes.argtypes = [i64, i64]
     lib.lss_layernorm_bwd_scratch_bytes.restype = sz
@@ -83,7 +85,7 @@ def load():
     lib.lss_linear_bwd_input_gelu.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
     lib.lss_gelu_fwd.argtypes = [vp, i64, vp, vp]
     lib.lss_gelu_bwd.argtypes = [vp, vp, i64, vp, vp]
-    for name in ("lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_layernorm_fwd", "lss_layernorm_bwd", "lss_linear_fwd",
+    for name in ("lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_residual_dropout_add", "lss_layernorm_fwd", "lss_layernorm_bwd", "lss_linear_fwd",
                  "lss_linear_bwd_input", "lss_linear_gelu_fwd", "lss_linear_bwd_input_gelu", "lss_gelu_fwd", "lss_gelu_bwd"):
         getattr(lib, name).restype = ci
     lib.lss_timing_enable.argtypes = [ci]
@@ -330,6 +332,20 @@ def lss_embed_pe_bwd(dx, dpe_rows=None, stream=None):
     dpe_rows = _out(dpe_rows, (l_s, E), torch.float32, dx)
     _check(load().lss_embed_pe_bwd(_ptr(dx), l_s, B, E, _ptr(dpe_rows), _stream_ptr(stream)))
     return dpe_rows
+
+
+def lss_residual_dropout_add(x, delta, seg_offset, p_drop=0.0, seed=0, out=None, stream=None):
+    """out = x + dropout(delta) on a segment's rows [B, l_s, E] bf16; x may be None (zeros)."""
+    if delta.dim() != 3 or (x is not None and x.shape != delta.shape):
+        raise ValueError("delta must be [B, l_s, E] and x, if given, of the same shape")
+    B, l_s, E = delta.shape
+    _dev(delta, torch.bfloat16, "delta")
+    if x is not None:
+        _dev(x, torch.bfloat16, "x")
+    out = _out(out, delta.shape, torch.bfloat16, delta)
+    _check(load().lss_residual_dropout_add(_ptr(x) if x is not None else None, _ptr(delta), int(seg_offset), l_s, B, E,
+                                           float(p_drop), int(seed), _ptr(out), _stream_ptr(stream)))
+    return out
 
 
 def lss_layernorm_fwd(x, gamma, beta, eps=1e-5, y=None, mean=None, rstd=None, stream=None):

@@ -117,6 +117,13 @@ def test_layer_operation_argument_checks(lib):
     assert lib.lss_embed_pe_bwd(0x1000, 128, 2, 64, None, None) == -1
     assert lib.lss_embed_pe_bwd(None, 0, 2, 64, None, None) == 0
 
+    ra = lib.lss_residual_dropout_add
+    assert ra(0x1000, 0x2000, 0, 16, 2, 60, 0.1, 5, 0x3000, None) == -2
+    assert ra(0x1000, 0x2000, -1, 16, 2, 64, 0.1, 5, 0x3000, None) == -5
+    assert ra(0x1000, 0x2000, 0, 16, 2, 64, 1.0, 5, 0x3000, None) == -5
+    assert ra(0x1000, None, 0, 16, 2, 64, 0.1, 5, 0x3000, None) == -1
+    assert ra(0x1004, 0x2000, 0, 16, 2, 64, 0.1, 5, 0x3000, None) == -4
+    assert ra(None, None, 0, 0, 2, 64, 0.1, 5, None, None) == 0
     ln = lib.lss_layernorm_fwd
     assert ln(0x1000, 0x2000, 0x3000, 1e-5, 4, 4104, 0x4000, 0x5000, 0x6000, None) == -2      # wider than 4096
     assert b"4096" in lib.lss_last_error()

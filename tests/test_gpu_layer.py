@@ -61,6 +61,26 @@ def test_embed_pe_segments_tile_the_table():
         assert torch.equal(part, whole[:, i * l_s:(i + 1) * l_s])
 
 
+@pytest.mark.parametrize("B,l_s,E,s0,p", [(2, 300, 512, 437, 0.1), (1, 1, 8, 50111, 0.5), (3, 77, 1024, 0, 0.25),
+                                          (2, 129, 136, 1000, 0.0)])
+def test_residual_dropout_add_matches_oracle(B, l_s, E, s0, p):
+    X, DL = staged(7150 + l_s, (B, l_s, E)), staged(7151 + l_s, (B, l_s, E))
+    seed = 0xABCD_0000_1234 + l_s
+    out = lss.lss_residual_dropout_add(X.dev, DL.dev, s0, p, seed)
+    ref = oracle.residual_dropout_add(X.f64, DL.f64, s0, p, seed)
+    assert_rounded(to_np(out), ref, f"residual {B, l_s, E, s0, p}", slack=1e-6)
+    # the keep decisions are exactly the oracle's: where it dropped, out is x itself
+    dropped = oracle.residual_dropout_add(None, np.ones((B, l_s, E)), s0, p, seed) == 0
+    assert np.array_equal(to_np(out)[dropped], X.f64[dropped])
+    # the branch alone (x absent), which is also the backward of the branch; in place
+    alone = lss.lss_residual_dropout_add(None, DL.dev, s0, p, seed)
+    assert_rounded(to_np(alone), oracle.residual_dropout_add(None, DL.f64, s0, p, seed), "branch alone", slack=1e-6)
+    assert np.array_equal(to_np(alone) == 0, dropped | (DL.f64 == 0))
+    buf = X.dev.clone()
+    lss.lss_residual_dropout_add(buf, DL.dev, s0, p, seed, out=buf)
+    assert torch.equal(buf, out)
+
+
 LN_SHAPES = [  # rows, E
     (256, 256), (1000, 512), (1, 1024), (333, 2048), (67, 4096), (129, 8), (35, 520), (4100, 128),
 ]
