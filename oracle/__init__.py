@@ -318,3 +318,14 @@ def ffn_bwd(dy, u, w1, w2):
     """Gradient of ffn_fwd with respect to h: dh = ((dy W_2^T) * GeLU'(u)) W_1^T."""
     dy, u, w1, w2 = _f64(dy), _f64(u), _f64(w1), _f64(w2)
     return np.matmul(np.matmul(dy, w2.T) * gelu_grad(u), w1.T)
+
+
+def linear_bwd_weight(a, dc):
+    """Gradient of c = a w with respect to w, summed over every row of the segment (and batch):
+    dw[k, n] = sum_rows a[row, k] dc[row, n].  a [..., K], dc [..., N] -> dw [K, N].  This is one
+    segment's contribution; the paper's gradient averaging over the sequence-parallel group (Section 4)
+    adds the segments' contributions."""
+    a, dc = _f64(a), _f64(dc)
+    if a.shape[:-1] != dc.shape[:-1]:
+        raise ValueError("a and dc must have the same rows")
+    return np.matmul(a.reshape(-1, a.shape[-1]).T, dc.reshape(-1, dc.shape[-1]))

@@ -144,3 +144,33 @@ def test_residual_dropout_add_pins():
     dout = _rand(63, B, l_x, E)
     ddelta = oracle.residual_dropout_add(None, dout, 0, p, seed)
     assert np.isclose((dout * (full - x)).sum(), (ddelta * delta).sum())
+
+
+def test_linear_weight_gradient_pins():
+    B, l_x, E, F = 2, 9, 5, 7
+    h, w1, w2, dy = _rand(71, B, l_x, E), _rand(72, E, F), _rand(73, F, E), _rand(74, B, l_x, E)
+    y, u = oracle.ffn_fwd(h, w1, w2)
+    g = oracle.gelu(u)
+    dw2 = oracle.linear_bwd_weight(g, dy)
+    dw1 = oracle.linear_bwd_weight(h, np.matmul(dy, w2.T) * oracle.gelu_grad(u))
+    # the definition, element by element
+    k, n = 3, 4
+    assert np.isclose(dw2[k, n], sum(g[b, r, k] * dy[b, r, n] for b in range(B) for r in range(l_x)))
+    # central differences of <dy, ffn(h; w1, w2)> in single weights
+    eps = 1e-6
+    for (W, dW, idx) in ((w1, dw1, (2, 5)), (w1, dw1, (0, 0)), (w2, dw2, (6, 1)), (w2, dw2, (3, 3))):
+        Wp, Wm = W.copy(), W.copy()
+        Wp[idx] += eps
+        Wm[idx] -= eps
+        f = lambda a1, a2: (dy * oracle.ffn_fwd(h, a1, a2)[0]).sum()
+        fd = (f(Wp, w2) - f(Wm, w2)) if W is w1 else (f(w1, Wp) - f(w1, Wm))
+        assert np.isclose(fd / (2 * eps), dW[idx], rtol=1e-6, atol=1e-8)
+    # torch float64 autograd as a second opinion
+    th, tw1, tw2 = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (h, w1, w2))
+    (torch.nn.functional.gelu(th @ tw1) @ tw2 * torch.tensor(dy)).sum().backward()
+    assert np.allclose(tw1.grad.numpy(), dw1) and np.allclose(tw2.grad.numpy(), dw2)
+    # Section 4: the segments' contributions add up to the gradient of the whole sequence
+    parts = [oracle.linear_bwd_weight(g[:, s:e], dy[:, s:e]) for s, e in ((0, 4), (4, 5), (5, 9))]
+    assert np.allclose(sum(parts), dw2)
+    with pytest.raises(ValueError):
+        oracle.linear_bwd_weight(h, dy[:, :3])
