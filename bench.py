@@ -60,8 +60,8 @@ def measured_traffic(workload: str, kernel: str):
 def layer_ops(args, w) -> int:
     """The segment-local remainder of a layer (Section 3, Principles 1 and 2) on the workload's shape:
     per segment, x = tok + PE rows, LayerNorm, feed-forward unit (E_m -> 4 E_m -> E_m, exact GeLU),
-    residual connection with dropout 0.1 on the branch, then the same backwards.  `value` is the feed-forward unit's matrix flops (8 * rows * E_m * 4 E_m
-    per segment) over the time of the whole step, streaming kernels included."""
+    residual connection with dropout 0.1 on the branch, then the same backwards, weight gradients of the two maps included.  `value` is the feed-forward
+    unit's matrix flops (12 * rows * E_m * 4 E_m per segment) over the time of the whole step, streaming kernels included."""
     import numpy as np
     import torch
 
@@ -98,6 +98,10 @@ def layer_ops(args, w) -> int:
     dgamma, dbeta = (torch.empty((E,), dtype=torch.float32, device=dev) for _ in range(2))
     dpe = torch.empty((l_s, E), dtype=torch.float32, device=dev)
     scratch = torch.empty((max(16, lss.lss_layernorm_bwd_scratch_bytes(rows, E)),), dtype=torch.uint8, device=dev)
+    dw1 = torch.empty((E, F), dtype=torch.float32, device=dev)
+    dw2 = torch.empty((F, E), dtype=torch.float32, device=dev)
+    wscratch = torch.empty((max(16, lss.lss_linear_bwd_weight_scratch_bytes(rows, E, F),
+                            lss.lss_linear_bwd_weight_scratch_bytes(rows, F, E)),), dtype=torch.uint8, device=dev)
 
     def step():
         for i, s0 in enumerate(offs):
@@ -117,6 +121,8 @@ def layer_ops(args, w) -> int:
                 lss.lss_linear_bwd_input(dyb, w2, da=dg)
                 lss.lss_gelu_bwd(u, dg, du=du)
             lss.lss_linear_bwd_input(du, w1, da=dh)
+            lss.lss_linear_bwd_weight(g, dyb, dw=dw2, scratch=wscratch)      # this segment's share of dW2 and dW1
+            lss.lss_linear_bwd_weight(h, du, dw=dw1, scratch=wscratch)
             lss.lss_layernorm_bwd(x, gamma, mean, rstd, dh, dx=dx, dgamma=dgamma, dbeta=dbeta, scratch=scratch)
             lss.lss_residual_dropout_add(dy, dx, s0, 0.0, 0, out=dx)                    # + the gradient on the skip path
             lss.lss_embed_pe_bwd(dx, dpe_rows=dpe)
@@ -163,7 +169,7 @@ def layer_ops(args, w) -> int:
     kernels[dom] = dict(timed[dom], timed_region=True)
 
     lin_flops = 2.0 * rows * E * F                  # one linear map of one segment
-    flops_step = 4.0 * lin_flops * w.N
+    flops_step = 6.0 * lin_flops * w.N             # two maps forward, their input and weight gradients backward
     # algorithmic bytes per launch: every operand read once, every result written once
     bytes_per_launch = {
         "embed_pe_fwd_kernel": 4 * rows * E + 2 * l_s * E, "embed_pe_bwd_kernel": 2 * rows * E + 4 * l_s * E,
@@ -177,7 +183,7 @@ def layer_ops(args, w) -> int:
         if name in bytes_per_launch:
             kk["algorithmic_GBps"] = round(bytes_per_launch[name] / (kk["avg_us"] * 1e-6) / 1e9, 1)
             kk["frac_of_hbm_peak"] = round(kk["algorithmic_GBps"] / PEAK_HBM_GBS, 4)
-        else:
+        elif name.startswith("linear_"):
             kk["algorithmic_tflops"] = round(lin_flops / (kk["avg_us"] * 1e-6) / 1e12, 2)
         kk["avg_us"] = round(kk["avg_us"], 2)
         kk["ms_per_step"] = round(kk["ms_per_step"], 4)
@@ -189,7 +195,7 @@ def layer_ops(args, w) -> int:
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
-        n_s = min(l_s, max(1, int(2.0e11 / (8.0 * w.B * E * F))))      # about 2e11 fp64 flops of matrix work
+        n_s = min(l_s, max(1, int(2.0e11 / (12.0 * w.B * E * F))))     # about 2e11 fp64 flops of matrix work
         t = time.perf_counter()
         xs = oracle.embed_pe(tok_h[:, :n_s], pe_h, 0)
         hs, _, _ = oracle.layernorm_fwd(xs, gamma_h, beta_h)
@@ -197,12 +203,14 @@ def layer_ops(args, w) -> int:
         oracle.residual_dropout_add(xs, ys, 0, P_HIDDEN, w.seed)
         dybs = oracle.residual_dropout_add(None, dy_h[:, :n_s], 0, P_HIDDEN, w.seed)
         dhs = oracle.ffn_bwd(dybs, us, w1_h, w2_h)
+        oracle.linear_bwd_weight(oracle.gelu(us), dybs)
+        oracle.linear_bwd_weight(hs, np.matmul(dybs, w2_h.T) * oracle.gelu_grad(us))
         dxs, _, _ = oracle.layernorm_bwd(xs, gamma_h, dhs)
         oracle.embed_pe_bwd(dy_h[:, :n_s] + dxs)
         t_cpu = time.perf_counter() - t
         from threadpoolctl import threadpool_info
         blas_threads = max([p_["num_threads"] for p_ in threadpool_info() if p_.get("user_api") == "blas"] or [1])
-        cpu_baseline = {"value": round(8.0 * w.B * n_s * E * F / t_cpu / 1e12, 6), "unit": "TFLOP/s",
+        cpu_baseline = {"value": round(12.0 * w.B * n_s * E * F / t_cpu / 1e12, 6), "unit": "TFLOP/s",
                         "cores": blas_threads, "kind": "oracle",
                         "sample": f"the first {n_s} rows of segment 0 for every batch entry, the same chain of "
                                   f"operations, {t_cpu:.1f} s of fp64 CPU work, same flop count"}

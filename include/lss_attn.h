@@ -301,6 +301,13 @@ int lss_layernorm_bwd(const void *x, const float *gamma, const float *mean,
  * a, c, dc, da, u, g, dg, du bf16 row-major; w bf16 row-major.  K and N multiples of
  * 128, at most 65536; rows < 2^31 (LSS_ERR_SHAPE otherwise).  bf16 matrix cores,
  * fp32 accumulation.
+ * Weight gradient over a segment's rows (one segment's contribution: the gradient
+ * averaging over the sequence-parallel group, Section 4, adds the segments'):
+ *   lss_linear_bwd_weight  dw[K, N] = a[rows, K]^T dc[rows, N], float (written)
+ *     scratch  DEVICE buffer of lss_linear_bwd_weight_scratch_bytes(rows, K, N)
+ *              bytes (0 for few rows: may then be NULL), caller-owned, overwritten.
+ *              Rows are divided into chunks whose partial results are added in
+ *              chunk order: bit-reproducible, no atomics.  rows = 0 writes zeros.
  * Two fused forms save the GeLU's own passes over memory and give bit-identical
  * results to the calls they replace:
  *   lss_linear_gelu_fwd        u = a w  and  g = GeLU(u)   (u, g [rows, N])
@@ -310,6 +317,9 @@ int lss_linear_fwd(const void *a, const void *w, int64_t rows, int64_t K, int64_
                    void *c, void *stream);
 int lss_linear_bwd_input(const void *dc, const void *w, int64_t rows, int64_t K, int64_t N,
                          void *da, void *stream);
+size_t lss_linear_bwd_weight_scratch_bytes(int64_t rows, int64_t K, int64_t N);
+int lss_linear_bwd_weight(const void *a, const void *dc, int64_t rows, int64_t K, int64_t N,
+                          float *dw, void *scratch, size_t scratch_bytes, void *stream);
 int lss_linear_gelu_fwd(const void *a, const void *w, int64_t rows, int64_t K, int64_t N,
                         void *u, void *g, void *stream);
 int lss_linear_bwd_input_gelu(const void *dc, const void *w, const void *u,

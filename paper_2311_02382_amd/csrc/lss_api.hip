@@ -490,6 +490,41 @@ int lss_linear_bwd_input_gelu(const void *dc, const void *w, const void *u, int6
     return linear_bwd_impl("linear_bwd_input_gelu", dc, w, u, true, rows, K, N, du, stream);
 }
 
+size_t lss_linear_bwd_weight_scratch_bytes(int64_t rows, int64_t K, int64_t N)
+{
+    if (rows < 1 || rows > INT32_MAX || K < 128 || N < 128 || K % 128 != 0 || N % 128 != 0 || K > 65536 || N > 65536) return 0;
+    return lss::linear_bwd_weight_scratch_bytes((int)rows, (int)K, (int)N);
+}
+
+int lss_linear_bwd_weight(const void *a, const void *dc, int64_t rows, int64_t K, int64_t N, float *dw, void *scratch,
+                          size_t scratch_bytes, void *stream)
+{
+    if (rows < 0 || rows > INT32_MAX || K < 128 || N < 128 || K % 128 != 0 || N % 128 != 0 || K > 65536 || N > 65536)
+        return fail(LSS_ERR_SHAPE, "linear_bwd_weight: rows = %lld, K = %lld, N = %lld (K, N multiples of 128, at most 65536)",
+                    (long long)rows, (long long)K, (long long)N);
+    if (!dw) return fail(LSS_ERR_NULL, "linear_bwd_weight: NULL tensor pointer");
+    if (misaligned(dw)) return fail(LSS_ERR_ALIGN, "linear_bwd_weight: tensor pointers must be 16-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (rows == 0) {    // no rows: the gradient is zero (written by the sum kernel over one part without valid rows)
+        const int64_t none = 0;
+        const float *part = dw;
+        const hipError_t e = lss::launch_reduce(&part, 1, &none, K, 1, 1, N, dw, st);
+        if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "linear_bwd_weight launch failed: %s", hipGetErrorString(e));
+        return LSS_OK;
+    }
+    if (!a || !dc) return fail(LSS_ERR_NULL, "linear_bwd_weight: NULL tensor pointer");
+    if (misaligned(a) || misaligned(dc) || misaligned(scratch))
+        return fail(LSS_ERR_ALIGN, "linear_bwd_weight: tensor pointers must be 16-byte aligned");
+    const size_t need = lss::linear_bwd_weight_scratch_bytes((int)rows, (int)K, (int)N);
+    if (need > 0 && (!scratch || scratch_bytes < need))
+        return fail(LSS_ERR_WORKSPACE, "linear_bwd_weight: scratch of %zu bytes, need %zu", scratch ? scratch_bytes : (size_t)0, need);
+    using lss::bf16_t;
+    const hipError_t e = lss::launch_linear_bwd_weight(static_cast<const bf16_t *>(a), static_cast<const bf16_t *>(dc), (int)rows,
+                                                       (int)K, (int)N, dw, static_cast<float *>(scratch), st);
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "linear_bwd_weight launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
 static int check_gelu(const char *what, int64_t n)
 {
     if (n < 0 || n % 8 != 0) return fail(LSS_ERR_SHAPE, "%s: n = %lld is not a non-negative multiple of 8", what, (long long)n);

@@ -68,7 +68,7 @@ hipError_t launch_bwd_bf16_main(const SegShape &s, const DropArgs &drop, const b
 // Optional per-kernel timing for benchmarks: when enabled, every launch site brackets its
 // kernel with a pair of HIP events on the launch stream.
 enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_BWD_MAIN, K_PROJ_FWD, K_PROJ_BWD,
-                K_PE_FWD, K_PE_BWD, K_LN_FWD, K_LN_BWD, K_LN_PARAMS, K_GELU_FWD, K_GELU_BWD, K_LINEAR_FWD, K_LINEAR_BWD, K_RESIDUAL, K_COUNT };
+                K_PE_FWD, K_PE_BWD, K_LN_FWD, K_LN_BWD, K_LN_PARAMS, K_GELU_FWD, K_GELU_BWD, K_LINEAR_FWD, K_LINEAR_BWD, K_RESIDUAL, K_LINEAR_WGRAD, K_COUNT };
 void timing_begin(int id, hipStream_t st);
 void timing_end(int id, hipStream_t st);
 struct TimedLaunch {    // RAII bracket around one kernel launch
@@ -96,6 +96,11 @@ hipError_t launch_linear_fwd(const bf16_t *a, const bf16_t *w, int rows, int K, 
                              hipStream_t st);
 hipError_t launch_linear_bwd_input(const bf16_t *dc, const bf16_t *w, const bf16_t *gelu_u, int rows, int K, int N,
                                    bf16_t *da, hipStream_t st);
+
+// dw[K, N] (float) = a[rows, K]^T dc[rows, N]; rows >= 1; scratch of linear_bwd_weight_scratch_bytes() bytes
+size_t linear_bwd_weight_scratch_bytes(int rows, int K, int N);
+hipError_t launch_linear_bwd_weight(const bf16_t *a, const bf16_t *dc, int rows, int K, int N, float *dw, float *scratch,
+                                    hipStream_t st);
 
 // segment-local row operations (lss_rows.hip); E a multiple of 8
 hipError_t launch_embed_pe_fwd(const bf16_t *tok, const bf16_t *pe, int64_t s0, int l_s, int B, int E, bf16_t *x,

@@ -67,14 +67,16 @@ using WTile = DirectTile<PK, PN, P_WAVES>;      // weights [256 n][64 k]
 // evenly over the banks.
 struct WTileTr {
     static constexpr int NI = PK * (PN / 8) / 64 / P_WAVES;     // load instructions per wavefront (2 rows each)
-    // chunks >= chunks_ok (columns past the matrix) re-read chunk chunks_ok - 1; chunks_ok is a multiple of 8
-    static __device__ __forceinline__ void offsets(uint32_t (&off)[NI], int ldw, int wave, int lane, int chunks_ok)
+    // chunks >= chunks_ok (columns past the matrix) re-read chunk chunks_ok - 1; chunks_ok is a multiple of 8;
+    // rows >= rows_ok re-read row rows_ok - 1
+    static __device__ __forceinline__ void offsets(uint32_t (&off)[NI], int ldw, int wave, int lane, int chunks_ok,
+                                                   int rows_ok = PK)
     {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int row = (i * P_WAVES + wave) * 2 + lane / 32, pos = lane % 32;
             const int chunk = min(pos ^ (4 * (row & 3)), chunks_ok - 1);
-            off[i] = ((uint32_t)row * (uint32_t)ldw + (uint32_t)chunk * 8u) * 2u;
+            off[i] = ((uint32_t)min(row, rows_ok - 1) * (uint32_t)ldw + (uint32_t)chunk * 8u) * 2u;
         }
     }
     // Transposing reads (see load_frag_tr_sw for the instruction's lane mapping): within its group
@@ -349,6 +351,155 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
     store_tiles(acc, true);
 }
 
+
+// Weight gradient of a linear map: dW[k, n] = sum_r A[r, k] dC[r, n], the contraction running over
+// the rows of both operands.  Both are therefore loaded as [64 rows][256 columns] tiles and read
+// through transposing LDS reads (WTileTr); a workgroup owns a 256 (k) x 256 (n) tile of dW for one
+// chunk of rows and writes it in fp32, to dW itself when there is a single chunk, else to that
+// chunk's partial result, which a fixed-order sum adds up afterwards.  Same wavefront layout,
+// two-slot ring and LDS-staged stores as proj_gemm_kernel.
+struct WgradArgs {
+    const bf16_t *a, *dc;       // [rows][K], [rows][N]
+    float *out;                 // [splits][K][N]
+    int rows, K, N;
+    int chunk_rows;             // rows per split, a multiple of 64
+    int splits, m_tiles, n_tiles;
+};
+
+__global__ __launch_bounds__(P_NT, 1) void wgrad_gemm_kernel(WgradArgs g)
+{
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave & 1, wn = wave >> 1;
+
+    // consecutive ids go to consecutive XCDs; an XCD walks the output tiles of one chunk of rows, so
+    // that chunk's rows of A and dC are read from HBM once per XCD
+    const int tiles = g.m_tiles * g.n_tiles;
+    const int x = blockIdx.x % kXcds, rest = blockIdx.x / kXcds;
+    const int tile = rest % tiles, split = x + kXcds * (rest / tiles);
+    if (split >= g.splits) return;
+    const int m0 = (tile / g.n_tiles) * PM, n0 = (tile % g.n_tiles) * PN;
+    const int r0 = split * g.chunk_rows, r1 = min(r0 + g.chunk_rows, g.rows);
+    const int T = (r1 - r0 + PK - 1) / PK;          // >= 1: the host sizes the splits so
+    const int tail = (r1 - r0) - (T - 1) * PK;      // rows of the last tile, 1 .. 64
+    const int cols_m = min(g.K - m0, PM), cols_n = min(g.N - n0, PN);
+
+    uint32_t offA[WTileTr::NI], offW[WTileTr::NI], offA_last[WTileTr::NI], offW_last[WTileTr::NI];
+    WTileTr::offsets(offA, g.K, wave, lane, cols_m / 8);
+    WTileTr::offsets(offW, g.N, wave, lane, cols_n / 8);
+    WTileTr::offsets(offA_last, g.K, wave, lane, cols_m / 8, tail);
+    WTileTr::offsets(offW_last, g.N, wave, lane, cols_n / 8, tail);
+    auto issue = [&](int t, int slot) {
+        char *dst = smem + slot * P_SLOT;
+        const bf16_t *pa = g.a + (int64_t)(r0 + t * PK) * g.K + m0, *pw = g.dc + (int64_t)(r0 + t * PK) * g.N + n0;
+        const bool last = t == T - 1;
+#pragma unroll
+        for (int i = 0; i < WTileTr::NI; ++i) {
+            lds_dma<16>(pa, last ? offA_last[i] : offA[i], dst + (i * P_WAVES + wave) * 1024);
+            lds_dma<16>(pw, last ? offW_last[i] : offW[i], dst + P_ABYTES + (i * P_WAVES + wave) * 1024);
+        }
+    };
+    // Rows past the end of the chunk re-read its last row; their copies in both tiles are replaced
+    // by zeros, each lane clearing exactly the 16 bytes its own loads wrote (after waiting for them).
+    auto clear_tail = [&](int slot) {
+        if (tail == PK) return;
+        char *dst = smem + slot * P_SLOT;
+#pragma unroll
+        for (int i = 0; i < WTileTr::NI; ++i) {
+            const int row = (i * P_WAVES + wave) * 2 + lane / 32;
+            if (row >= tail) {
+                *reinterpret_cast<f32x4 *>(dst + (i * P_WAVES + wave) * 1024 + lane * 16) = f32x4{0.f, 0.f, 0.f, 0.f};
+                *reinterpret_cast<f32x4 *>(dst + P_ABYTES + (i * P_WAVES + wave) * 1024 + lane * 16) = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+    };
+
+    int at_off[4], wt_off[2];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb) at_off[mb] = WTileTr::lane_offset(lane, 4 * wm + mb);
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) wt_off[nb] = WTileTr::lane_offset(lane, 2 * wn + nb);
+
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = zero16;
+
+    struct Frags { Frag<bf16_t> fb[4], fw[2]; };
+    auto load_frags = [&](const char *at, const char *wt, int ks, Frags &f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) f.fw[nb] = WTileTr::load_frag(wt, ks, wt_off[nb]);
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) f.fb[mb] = WTileTr::load_frag(at, ks, at_off[mb]);
+    };
+    auto compute = [&](int slot) {
+        const char *at = smem + slot * P_SLOT, *wt = at + P_ABYTES;
+        Frags f[2];
+        load_frags(at, wt, 0, f[0]);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (ks + 1 < 4) load_frags(at, wt, ks + 1, f[(ks + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mma(f[ks & 1].fw[nb], f[ks & 1].fb[mb], acc[mb][nb]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    issue(0, 0);
+    wait_vmem_all();
+    if (T == 1) clear_tail(0);
+    __syncthreads();
+    for (int t = 0; t < T; ++t) {
+        const int slot = t & 1;
+        if (t + 1 < T) issue(t + 1, slot ^ 1);
+        compute(slot);
+        wait_vmem_all();
+        if (t + 1 == T - 1) clear_tail(slot ^ 1);
+        __syncthreads();
+    }
+
+    // ---- the finished tile -> memory through LDS (whole rows written), 128 columns per pass; see
+    // proj_gemm_kernel for the layout: element v of accumulator (mb, nb) is row 128 wm + 32 mb + lq,
+    // column 64 wn + 32 nb + 8 (v / 4) + 4 hh + v % 4
+    float *out = g.out + (int64_t)split * g.K * g.N + (int64_t)m0 * g.N + n0;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        if (pass) __syncthreads();
+        if ((wn >> 1) == pass) {
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+                const int m = 128 * wm + 32 * mb + lq;
+                char *row = smem + m * 512;
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int c = 16 * (wn & 1) + 8 * nb + 2 * q + hh;
+                        *reinterpret_cast<f32x4 *>(row + ((c ^ (m & 31)) * 16)) =
+                            f32x4{acc[mb][nb][4 * q], acc[mb][nb][4 * q + 1], acc[mb][nb][4 * q + 2], acc[mb][nb][4 * q + 3]};
+                    }
+            }
+        }
+        __syncthreads();
+        const int c = tid & 31;
+        if (pass * 128 + c * 4 < cols_n) {
+#pragma unroll
+            for (int i = 0; i < PM / 16; ++i) {
+                const int m = i * 16 + (tid >> 5);
+                if (m < cols_m)
+                    *reinterpret_cast<f32x4 *>(out + (int64_t)m * g.N + pass * 128 + c * 4) =
+                        *reinterpret_cast<const f32x4 *>(smem + m * 512 + ((c ^ (m & 31)) * 16));
+            }
+        }
+    }
+}
+
 template <bool A_ANY, bool W_TR, bool OUT_F32, int EPI = EPI_NONE>
 hipError_t launch_proj(ProjArgs &args, int kernel_id, hipStream_t st)
 {
@@ -457,6 +608,58 @@ hipError_t launch_linear_bwd_input(const bf16_t *dc, const bf16_t *w, const bf16
     J.N = K; J.K = N; J.k_split = N; J.n_split = K; J.ldw = N;
     if (gelu_u) return launch_proj<false, false, false, EPI_GELU_BWD>(args, K_LINEAR_BWD, st);
     return launch_proj<false, false, false>(args, K_LINEAR_BWD, st);
+}
+
+// How the rows are split for the weight gradient: about two workgroups per compute unit, at least
+// eight 64-row tiles per workgroup, at most kMaxReduceParts chunks.  Shape-only, deterministic.
+static void wgrad_plan(int rows, int K, int N, int &splits, int &chunk_rows)
+{
+    const int tiles = ((K + PM - 1) / PM) * ((N + PN - 1) / PN);
+    const int R = (rows + PK - 1) / PK;
+    int want = (512 + tiles - 1) / tiles;
+    if (want > kMaxReduceParts) want = kMaxReduceParts;
+    int chunk_tiles = (R + want - 1) / want;
+    if (chunk_tiles < 8) chunk_tiles = R < 8 ? R : 8;
+    if (chunk_tiles < 1) chunk_tiles = 1;
+    splits = (R + chunk_tiles - 1) / chunk_tiles;
+    if (splits < 1) splits = 1;
+    chunk_rows = chunk_tiles * PK;
+}
+
+size_t linear_bwd_weight_scratch_bytes(int rows, int K, int N)
+{
+    int splits, chunk_rows;
+    wgrad_plan(rows, K, N, splits, chunk_rows);
+    return splits > 1 ? (size_t)splits * K * N * sizeof(float) : 0;
+}
+
+// dw = a^T dc.  rows >= 1.
+hipError_t launch_linear_bwd_weight(const bf16_t *a, const bf16_t *dc, int rows, int K, int N, float *dw, float *scratch,
+                                    hipStream_t st)
+{
+    WgradArgs g{};
+    wgrad_plan(rows, K, N, g.splits, g.chunk_rows);
+    g.a = a; g.dc = dc; g.rows = rows; g.K = K; g.N = N;
+    g.out = g.splits > 1 ? scratch : dw;
+    g.m_tiles = (K + PM - 1) / PM;
+    g.n_tiles = (N + PN - 1) / PN;
+    static std::once_flag once;
+    static hipError_t attr = hipSuccess;
+    std::call_once(once, [] {
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   P_LDS);
+    });
+    if (attr != hipSuccess) return attr;
+    {
+        TimedLaunch tl(K_LINEAR_WGRAD, st);
+        hipLaunchKernelGGL(wgrad_gemm_kernel, dim3(xcd_grid(g.splits, g.m_tiles * g.n_tiles)), dim3(P_NT), P_LDS, st, g);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (g.splits == 1) return hipSuccess;
+    const float *parts[kMaxReduceParts];
+    for (int i = 0; i < g.splits; ++i) parts[i] = scratch + (size_t)i * K * N;
+    return launch_reduce(parts, g.splits, nullptr, K, 1, 1, N, dw, st);      // chunk 0 + chunk 1 + ..., in that order
 }
 
 } // namespace lss

@@ -25,7 +25,8 @@ const char *const kNames[K_COUNT] = {"fwd_kernel", "fwd_merge_kernel", "bwd_rowd
                                      "bwd_main_kernel", "proj_fwd_kernel", "proj_bwd_kernel",
                                      "embed_pe_fwd_kernel", "embed_pe_bwd_kernel", "layernorm_fwd_kernel",
                                      "layernorm_bwd_kernel", "layernorm_bwd_params_kernel", "gelu_fwd_kernel",
-                                     "gelu_bwd_kernel", "linear_fwd_kernel", "linear_bwd_kernel", "residual_add_kernel"};
+                                     "gelu_bwd_kernel", "linear_fwd_kernel", "linear_bwd_kernel", "residual_add_kernel",
+                                     "linear_wgrad_kernel"};
 
 hipEvent_t get_event()
 {

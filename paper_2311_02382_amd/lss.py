@@ -23,7 +23,8 @@ EXPORTS = ["lss_version", "lss_last_error", "lss_set_option", "lss_workspace_byt
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
            "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd",
            "lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_residual_dropout_add", "lss_layernorm_fwd", "lss_layernorm_bwd_scratch_bytes",
-           "lss_layernorm_bwd", "lss_linear_fwd", "lss_linear_bwd_input", "lss_linear_gelu_fwd",
+           "lss_layernorm_bwd", "lss_linear_fwd", "lss_linear_bwd_input", "lss_linear_bwd_weight_scratch_bytes", "lss_linear_bwd_weight",
+           "lss_linear_gelu_fwd",
            "lss_linear_bwd_input_gelu", "lss_gelu_fwd", "lss_gelu_bwd",
            "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
            "lss_timing_read", "lss_timing_kernel_name"]
@@ -81,6 +82,10 @@ def load():
     lib.lss_layernorm_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, sz, vp]
     lib.lss_linear_fwd.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     lib.lss_linear_bwd_input.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    lib.lss_linear_bwd_weight_scratch_bytes.argtypes = [i64, i64, i64]
+    lib.lss_linear_bwd_weight_scratch_bytes.restype = sz
+    lib.lss_linear_bwd_weight.argtypes = [vp, vp, i64, i64, i64, vp, vp, sz, vp]
+    lib.lss_linear_bwd_weight.restype = ci
     lib.lss_linear_gelu_fwd.argtypes = [vp, vp, i64, i64, i64, vp, vp, vp]
     lib.lss_linear_bwd_input_gelu.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp]
     lib.lss_gelu_fwd.argtypes = [vp, i64, vp, vp]
@@ -414,6 +419,30 @@ def lss_linear_bwd_input(dc, w, da=None, stream=None):
     da = _out(da, (*dc.shape[:-1], K), torch.bfloat16, dc)
     _check(load().lss_linear_bwd_input(_ptr(dc), _ptr(w), rows, K, N, _ptr(da), _stream_ptr(stream)))
     return da
+
+
+def lss_linear_bwd_weight_scratch_bytes(rows, K, N):
+    return int(load().lss_linear_bwd_weight_scratch_bytes(int(rows), int(K), int(N)))
+
+
+def lss_linear_bwd_weight(a, dc, dw=None, scratch=None, stream=None):
+    """dw = a^T dc over every row.  a [..., K], dc [..., N] bf16 -> dw [K, N] float32.
+
+    `scratch` is a uint8 device tensor of at least lss_linear_bwd_weight_scratch_bytes(rows, K, N)
+    bytes (allocated here if absent)."""
+    K, N = a.shape[-1], dc.shape[-1]
+    if a.shape[:-1] != dc.shape[:-1]:
+        raise ValueError("a and dc must have the same rows")
+    _dev(a, torch.bfloat16, "a"); _dev(dc, torch.bfloat16, "dc")
+    rows = a.numel() // K if K else 0
+    dw = _out(dw, (K, N), torch.float32, a)
+    need = lss_linear_bwd_weight_scratch_bytes(rows, K, N)
+    if scratch is None:
+        scratch = torch.empty((max(need, 16),), dtype=torch.uint8, device=a.device)
+    _dev(scratch, torch.uint8, "scratch")
+    _check(load().lss_linear_bwd_weight(_ptr(a), _ptr(dc), rows, K, N, _ptr(dw), _ptr(scratch), scratch.numel(),
+                                        _stream_ptr(stream)))
+    return dw
 
 
 def lss_linear_gelu_fwd(a, w, u=None, g=None, stream=None):

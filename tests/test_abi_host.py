@@ -146,6 +146,16 @@ def test_layer_operation_argument_checks(lib):
         assert fn(0x1000, 0, 16, 256, 256, 0x3000, None) == -1
         assert fn(0x1008, 0x2000, 16, 256, 256, 0x3000, None) == -4
         assert fn(0, 0, 0, 256, 256, 0, None) == 0
+    wg = lib.lss_linear_bwd_weight
+    assert lib.lss_linear_bwd_weight_scratch_bytes(64, 128, 128) == 0               # one chunk: written in place
+    assert lib.lss_linear_bwd_weight_scratch_bytes(5000, 128, 128) == 10 * 128 * 128 * 4
+    assert lib.lss_linear_bwd_weight_scratch_bytes(5000, 100, 128) == 0
+    assert wg(0x1000, 0x2000, 64, 128, 192, 0x3000, None, 0, None) == -2
+    assert wg(0x1000, 0x2000, 64, 128, 128, None, None, 0, None) == -1
+    assert wg(None, 0x2000, 64, 128, 128, 0x3000, None, 0, None) == -1
+    assert wg(0x1000, 0x2008, 64, 128, 128, 0x3000, None, 0, None) == -4
+    assert wg(0x1000, 0x2000, 5000, 128, 128, 0x3000, None, 0, None) == -6
+    assert wg(0x1000, 0x2000, 5000, 128, 128, 0x3000, 0x4000, 10 * 128 * 128 * 4 - 1, None) == -6
     assert lib.lss_linear_gelu_fwd(0x1000, 0x2000, 16, 256, 256, 0x3000, None, None) == -1
     assert lib.lss_linear_gelu_fwd(0x1000, 0x2000, 16, 256, 256, 0x3000, 0x4008, None) == -4
     assert lib.lss_linear_gelu_fwd(0x1000, 0x2000, 16, 256, 200, 0x3000, 0x4000, None) == -2

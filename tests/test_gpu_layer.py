@@ -193,6 +193,59 @@ def test_fused_gelu_forms_equal_the_separate_calls(rows, E, F):
     assert rel_err(to_np(dh), oracle.ffn_bwd(DY.f64, to_np(u), W1.f64, W2.f64)) <= TOL["bf16"]["t"]
 
 
+WGRAD_SHAPES = [  # rows, K, N
+    (1, 128, 128), (63, 128, 256), (64, 256, 128), (65, 384, 128), (1000, 256, 1024), (2300, 512, 2048),
+    (5000, 128, 128),       # one output tile: the rows are split into many chunks
+    (4097, 1024, 384),
+]
+
+
+@pytest.mark.parametrize("rows,K,N", WGRAD_SHAPES)
+def test_linear_weight_gradient_matches_oracle(rows, K, N):
+    A, DC = staged(7700 + rows, (rows, K)), staged(7701 + rows, (rows, N))
+    need = lss.lss_linear_bwd_weight_scratch_bytes(rows, K, N)
+    scratch = torch.full((max(need, 16),), 0xFF, dtype=torch.uint8, device="cuda")     # NaN patterns: must be overwritten
+    dw = lss.lss_linear_bwd_weight(A.dev, DC.dev, scratch=scratch)
+    assert dw.dtype == torch.float32 and tuple(dw.shape) == (K, N)
+    assert rel_err(to_np(dw), oracle.linear_bwd_weight(A.f64, DC.f64)) <= TOL["f32"]["t"]
+    again = lss.lss_linear_bwd_weight(A.dev, DC.dev)
+    assert torch.equal(dw, again)                       # fixed-order sum of the chunks: bit-reproducible
+    if need:
+        with pytest.raises(lss.LssError) as e:
+            lss.lss_linear_bwd_weight(A.dev, DC.dev, scratch=scratch[: need - 16])
+        assert e.value.code == -6
+
+
+def test_linear_weight_gradient_sums_over_segments_and_handles_no_rows():
+    # Section 4: the segments' contributions add up to the whole sequence's gradient
+    B, l_x, K, N, n_seg = 2, 900, 256, 384, 3
+    A, DC = staged(7710, (B, l_x, K)), staged(7711, (B, l_x, N))
+    whole = oracle.linear_bwd_weight(A.f64, DC.f64)
+    l_s = l_x // n_seg
+    total = sum(to_np(lss.lss_linear_bwd_weight(A.dev[:, i * l_s:(i + 1) * l_s].contiguous(),
+                                                DC.dev[:, i * l_s:(i + 1) * l_s].contiguous())) for i in range(n_seg))
+    assert rel_err(total, whole) <= TOL["f32"]["t"]
+    none = torch.empty((0, K), dtype=torch.bfloat16, device="cuda")
+    dw = lss.lss_linear_bwd_weight(none, torch.empty((0, N), dtype=torch.bfloat16, device="cuda"),
+                                   dw=torch.full((K, N), 5.0, device="cuda"))
+    assert not dw.any()
+
+
+def test_ffn_weight_gradients_match_oracle():
+    rows, E, F = 700, 256, 1024
+    Hh, DY = staged(7720, (rows, E)), staged(7721, (rows, E))
+    W1, W2 = staged(7722, (E, F), std=E ** -0.5), staged(7723, (F, E), std=F ** -0.5)
+    u, g = lss.lss_linear_gelu_fwd(Hh.dev, W1.dev)
+    du = lss.lss_linear_bwd_input_gelu(DY.dev, W2.dev, u)
+    dw2 = lss.lss_linear_bwd_weight(g, DY.dev)
+    dw1 = lss.lss_linear_bwd_weight(Hh.dev, du)
+    ru = to_np(u)       # the device's own pre-activation, as the other operand the oracle's
+    rg = oracle.gelu(ru)
+    assert rel_err(to_np(dw2), oracle.linear_bwd_weight(rg, DY.f64)) <= TOL["bf16"]["t"]
+    rdu = (DY.f64 @ W2.f64.T) * oracle.gelu_grad(ru)
+    assert rel_err(to_np(dw1), oracle.linear_bwd_weight(Hh.f64, rdu)) <= TOL["bf16"]["t"]
+
+
 def test_linear_outputs_preallocated_and_on_a_side_stream():
     rows, E, F = 600, 256, 512
     A, W = staged(7500, (rows, E)), staged(7501, (E, F), std=E ** -0.5)
