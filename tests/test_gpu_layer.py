@@ -257,3 +257,68 @@ def test_linear_outputs_preallocated_and_on_a_side_stream():
         lss.lss_linear_fwd(A.dev, W.dev, c=c, stream=st)
     st.synchronize()
     assert torch.equal(c, ref)
+
+
+def test_layer_operations_at_the_lx24k_segment_size():
+    """One lx24k segment (16384 rows, E_m = 1024, inner width 4096) through the calls bench.py --layer-ops
+    times; sampled rows against the oracle (every operation here but the weight gradient acts row by
+    row), sampled columns of the weight gradients against the oracle's full sum over rows."""
+    B, l_s, l_x, E, F, s0 = 4, 4096, 24576, 1024, 4096, 5 * 4096
+    rows = B * l_s
+    TOKS, PE = staged(7800, (B, l_s, E)), staged(7801, (l_x, E))
+    G, Bt = staged(7802, (E,), "f32", std=0.1, shift=1.0), staged(7803, (E,), "f32", std=0.1)
+    W1, W2 = staged(7804, (E, F), std=E ** -0.5), staged(7805, (F, E), std=F ** -0.5)
+    DY = staged(7806, (B, l_s, E))
+    p, seed = 0.1, 3000
+    x = lss.lss_embed_pe_fwd(TOKS.dev, PE.dev, s0)
+    h, mean, rstd = lss.lss_layernorm_fwd(x, G.dev, Bt.dev)
+    u = lss.lss_linear_fwd(h, W1.dev)
+    g = lss.lss_gelu_fwd(u)
+    y = lss.lss_linear_fwd(g, W2.dev)
+    x2 = lss.lss_residual_dropout_add(x, y, s0, p, seed)
+    dyb = lss.lss_residual_dropout_add(None, DY.dev, s0, p, seed)
+    dg = lss.lss_linear_bwd_input(dyb, W2.dev)
+    du = lss.lss_gelu_bwd(u, dg)
+    dh = lss.lss_linear_bwd_input(du, W1.dev)
+    dw2 = lss.lss_linear_bwd_weight(g, dyb)
+    dw1 = lss.lss_linear_bwd_weight(h, du)
+    dx, dgam, dbet = lss.lss_layernorm_bwd(x, G.dev, mean, rstd, dh)
+    dx = lss.lss_residual_dropout_add(DY.dev, dx, s0)
+    dpe = lss.lss_embed_pe_bwd(dx)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(7)
+    rs = np.unique(np.concatenate([[0, l_s - 1, 255, 256], rng.integers(0, l_s, 12)]))
+    t = TOL["bf16"]["t"]
+    for b in (0, B - 1):
+        sel = lambda a: to_np(a[b, rs])
+        # forward chain on the sampled rows, each stage from the device's own input to it
+        rx = oracle.embed_pe(TOKS.f64[b:b + 1, rs], PE.f64[s0 + rs], 0)[0]
+        assert_rounded(sel(x), rx, "x", slack=0.0)
+        rh, rmean, _ = oracle.layernorm_fwd(sel(x), G.f64, Bt.f64)
+        assert_rounded(sel(h), rh, "h")
+        assert rel_err(to_np(mean.view(B, l_s)[b, rs]), rmean, floor=1.0) <= 1e-5
+        ry, ru = oracle.ffn_fwd(sel(h), W1.f64, W2.f64)
+        assert_rounded(sel(u), ru, "u")
+        assert rel_err(sel(y), ry) <= t
+        for j, r in enumerate(rs):      # the residual's keep decisions are those of global row s0 + r
+            # (batch entry b keys the generator: the oracle is evaluated with b entries of padding in front)
+            pad = np.zeros((b + 1, 1, E))
+            pad[b] = sel(y)[j]
+            ref = oracle.residual_dropout_add(None, pad, s0 + int(r), p, seed)[b, 0] + sel(x)[j]
+            assert_rounded(sel(x2)[j], ref, "x2", slack=1e-6)
+        # backward chain
+        assert_rounded(sel(dg), sel(dyb) @ W2.f64.T, "dg")
+        assert_rounded(sel(du), sel(dg) * oracle.gelu_grad(sel(u)), "du", slack=1e-6)
+        assert_rounded(sel(dh), sel(du) @ W1.f64.T, "dh")
+    # weight gradients: eight sampled columns, the full sum over 16384 rows
+    cols = rng.integers(0, E, 8)
+    ref = oracle.linear_bwd_weight(to_np(g.view(rows, F)), to_np(dyb.view(rows, E))[:, cols])
+    assert rel_err(to_np(dw2[:, cols]), ref) <= TOL["f32"]["t"]
+    cols = rng.integers(0, F, 8)
+    ref = oracle.linear_bwd_weight(to_np(h.view(rows, E)), to_np(du.view(rows, F))[:, cols])
+    assert rel_err(to_np(dw1[:, cols]), ref) <= TOL["f32"]["t"]
+    # sums over all rows: parameter gradients of the layer normalisation, and the table rows
+    rdx, rdg, rdb = oracle.layernorm_bwd(to_np(x), G.f64, to_np(dh))
+    assert rel_err(to_np(dgam), rdg) <= 1e-4 and rel_err(to_np(dbet), rdb) <= 1e-4
+    assert rel_err(to_np(dpe), oracle.embed_pe_bwd(to_np(dx))) <= 1e-6
