@@ -222,6 +222,27 @@ def project_bwd(dq, dk_partial, dv_partial, w_q, w_kv):
     return dx_q, dx_part
 
 
+def project_bwd_weight(x, dq, dk_partial, dv_partial, seg_offset: int):
+    """One segment's contribution to the gradients of the projection weights:
+    dW_q [E,E] = sum_b x_i^T dQ_i and dW_kv [E,2E] = sum_b x^T [dK_part | dV_part] (the segment
+    projects K and V of the whole gathered x itself, Fig. 2(ii), so its share of dW_k, dW_v runs over
+    all l_x rows).  The gradient averaging over the sequence-parallel group (Section 4) adds the
+    segments' contributions."""
+    x, dq, dk, dv = _f64(x), _f64(dq), _f64(dk_partial), _f64(dv_partial)
+    B, l_s, H, d = dq.shape
+    E = H * d
+    l_x = x.shape[1]
+    if x.shape != (B, l_x, E) or dk.shape != (B, l_x, H, d) or dv.shape != dk.shape:
+        raise ValueError("shapes disagree")
+    if not (0 <= seg_offset and seg_offset + l_s <= l_x):
+        raise ValueError("segment outside the sequence")
+    x_i = x[:, seg_offset:seg_offset + l_s, :].reshape(B * l_s, E)
+    dw_q = np.matmul(x_i.T, dq.reshape(B * l_s, E))
+    xf = x.reshape(B * l_x, E)
+    dw_kv = np.concatenate([np.matmul(xf.T, dk.reshape(B * l_x, E)), np.matmul(xf.T, dv.reshape(B * l_x, E))], axis=1)
+    return dw_q, dw_kv
+
+
 # ---- the segment-local remainder of a layer (Section 3, Principles 1 and 2) ----------------------
 # Everything except the self-attention is computed independently per sequence segment: positional
 # embedding (a segment looks up only its own contiguous rows of the table), layer normalisation,

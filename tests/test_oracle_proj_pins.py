@@ -139,3 +139,44 @@ def test_segment_sum_of_dx_equals_unsegmented_gradient():
         assert not np.any(p[:, s0 + 6:])            # causal: later rows get nothing from this segment
     assert np.allclose(oracle.reduce_partials(parts), dxp_full, rtol=1e-12, atol=1e-12)
     assert np.allclose(dxq, dxq_full, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_weight_gradients_by_finite_differences(causal):
+    # loss(W_q, W_kv) = sum_i <dO_i, E_i>; its gradient is the sum over segments of each segment's
+    # contribution (Section 4); compared with central differences in single weights.
+    B, l_x, H, d = 2, 8, 2, 2
+    E = H * d
+    cuts = [0, 3, 5, 8]
+    x, w_q, w_kv = _inputs(B, l_x, H, d, 17)
+    w_q, w_kv = 3.0 * w_q, 3.0 * w_kv
+    do = np.random.default_rng(8).standard_normal((B, l_x, H, d))
+
+    def loss(wq, wkv):
+        tot = 0.0
+        for a, b in zip(cuts, cuts[1:]):
+            q, k, v = oracle.project_qkv(x, wq, wkv, a, b - a, H)
+            out, _ = oracle.segment_fwd(q, k, v, a, causal)
+            tot += float((out * do[:, a:b]).sum())
+        return tot
+
+    g_q, g_kv = np.zeros((E, E)), np.zeros((E, 2 * E))
+    for a, b in zip(cuts, cuts[1:]):
+        q, k, v = oracle.project_qkv(x, w_q, w_kv, a, b - a, H)
+        dq, dk, dv = oracle.segment_bwd(q, k, v, do[:, a:b], a, causal)
+        dwq, dwkv = oracle.project_bwd_weight(x, dq, dk, dv, a)
+        # the definition, one element each
+        assert np.isclose(dwq[1, 2], sum(x[bb, a + r, 1] * dq.reshape(B, b - a, E)[bb, r, 2] for bb in range(B) for r in range(b - a)))
+        assert np.isclose(dwkv[3, E + 1], sum(x[bb, r, 3] * dv.reshape(B, l_x, E)[bb, r, 1] for bb in range(B) for r in range(l_x)))
+        g_q += dwq
+        g_kv += dwkv
+    eps = 1e-6
+    for idx in np.ndindex(E, E):
+        wp, wm = w_q.copy(), w_q.copy()
+        wp[idx] += eps; wm[idx] -= eps
+        assert np.isclose((loss(wp, w_kv) - loss(wm, w_kv)) / (2 * eps), g_q[idx], rtol=1e-6, atol=1e-7)
+    for idx in np.ndindex(E, 2 * E):
+        wp, wm = w_kv.copy(), w_kv.copy()
+        wp[idx] += eps; wm[idx] -= eps
+        assert np.isclose((loss(w_q, wp) - loss(w_q, wm)) / (2 * eps), g_kv[idx], rtol=1e-6, atol=1e-7)
+    assert np.abs(g_q).max() > 1e-3 and np.abs(g_kv).max() > 1e-3
