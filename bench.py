@@ -237,6 +237,8 @@ def main() -> int:
     ap.add_argument("--workload", default="lx8k")
     ap.add_argument("--projections", action="store_true",
                     help="also run the Q/K/V projections and their backward around every segment")
+    ap.add_argument("--weight-grads", action="store_true",
+                    help="with --projections: every segment also computes its share of dW_q and dW_kv")
     ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16",
                     help="storage type: bf16 (the benchmark) or f32 (the single-precision twins of the entry points)")
     ap.add_argument("--dropout", type=float, default=None, metavar="P",
@@ -320,6 +322,11 @@ def main() -> int:
         dx_q = [torch.empty((w.B, l_s, E), dtype=torch.float32, device=dev) for _ in offs]
         dx_part = [torch.empty((w.B, w.l_x, 1, E), dtype=torch.float32, device=dev) for _ in offs]
         dX = torch.empty((w.B, w.l_x, 1, E), dtype=torch.float32, device=dev)
+        if args.weight_grads:
+            dw_q = torch.empty((E, E), dtype=torch.float32, device=dev)
+            dw_kv = torch.empty((E, 2 * E), dtype=torch.float32, device=dev)
+            wg_scratch = torch.empty((max(16, lss.lss_project_bwd_weight_scratch_bytes(l_s, w.l_x, w.B, w.H, w.d)),),
+                                     dtype=torch.uint8, device=dev)
     else:
         dk_part = [torch.empty(kd.shape, dtype=torch.float32, device=dev) for _ in offs]
         dv_part = [torch.empty(kd.shape, dtype=torch.float32, device=dev) for _ in offs]
@@ -347,6 +354,9 @@ def main() -> int:
                                      dq=dq[i], dk_partial=dk_one, dv_partial=dv_one, **drop)
             lss.lss_project_bwd(dq[i], dk_one, dv_one, wqd, wkvd, rows_valid[i], dx_q=dx_q[i],
                                 dx_partial=dx_part[i].view(w.B, w.l_x, E))
+            if args.weight_grads:
+                lss.lss_project_bwd_weight(xd, dq[i], dk_one, dv_one, s0, rows_valid[i], dw_q=dw_q, dw_kv=dw_kv,
+                                           scratch=wg_scratch)
         lss.lss_reduce_partials(dx_part, rows_valid, out=dX)
 
     step = step_with_projections if args.projections else step_attention
@@ -412,6 +422,8 @@ def main() -> int:
     # projections: 2 flops per multiply-add of Q_i, K, V and of dx_q, dx_partial (rows that hold data)
     proj_flops = {"proj_fwd_kernel": sum(2.0 * w.B * E * (2 * E * w.l_x + E * l_s) for _ in offs),
                   "proj_bwd_kernel": sum(2.0 * w.B * E * (2 * E * rv + E * l_s) for rv in rows_valid)}
+    if args.projections and args.weight_grads:      # same products as the backward maps, contracted over rows instead
+        proj_flops["linear_wgrad_kernel"] = proj_flops["proj_bwd_kernel"]
     flops_proj = sum(proj_flops.values()) if args.projections else 0.0
     value = (flops_strict + flops_proj) / (ms_per_step * 1e-3) / 1e12
 
@@ -437,7 +449,7 @@ def main() -> int:
                 kk["algorithmic_tflops"] = round(proj_flops[name] / (kk["ms_per_step"] * 1e-3) / 1e12, 2)
             kk["avg_us"] = round(kk["avg_us"], 2)
             kk["ms_per_step"] = round(kk["ms_per_step"], 4)
-        if "reduce_partials_kernel" in kernels:
+        if "reduce_partials_kernel" in kernels and not (args.projections and args.weight_grads):   # (there it also adds row chunks)
             # algorithmic bytes of the segment sum: valid rows of every part read once, l_x rows written
             row_bytes = w.B * w.H * w.d * 4
             byts = (1 if args.projections else 2) * (sum(rows_valid) + w.l_x) * row_bytes
@@ -515,6 +527,7 @@ def main() -> int:
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": w.name + ("+projections" if args.projections else "")
+                               + ("+weight-grads" if args.projections and args.weight_grads else "")
                                + (f"+dropout{args.dropout}" if args.dropout is not None else "")
                                + ("+f32" if f32 else ""), "B": w.B, "l_x": w.l_x,
                    "N": w.N, "l_s": l_s, "H": w.H, "d": w.d, "causal": w.causal,

@@ -230,6 +230,33 @@ int lss_project_bwd(const void *dq, const float *dk_partial, const float *dv_par
                     float *dx_q, float *dx_partial, void *stream);
 
 /*
+ * One segment's share of the gradients of the projection weights (the gradient
+ * averaging over the sequence-parallel group, Section 4, adds the segments'):
+ *     dw_q  [E_m, E_m]   = sum_b x_i^T dQ_i                        float (written)
+ *     dw_kv [E_m, 2 E_m] = sum_b x^T [dK_part | dV_part]           float (written)
+ * the second over the leading rows_valid rows of every batch entry (the segment
+ * projected K and V of the whole gathered x itself, Fig. 2(ii)).
+ *   x           [B, l_x, E_m] bf16;  dq [B, l_s, H, d] bf16
+ *   dk_partial, dv_partial  [B, l_x, H, d] float as lss_segment_attn_bwd wrote them;
+ *               rows >= rows_valid are not read.  Rounded to bf16 as matrix-core
+ *               operands; accumulation and results are fp32.
+ *   scratch     DEVICE buffer of lss_project_bwd_weight_scratch_bytes(l_s, l_x, B, H, d)
+ *               bytes (enough for any rows_valid), caller-owned, overwritten.  Rows are
+ *               divided into chunks whose partial results are added in chunk
+ *               order: bit-reproducible, no atomics.
+ * Same restrictions as lss_project_qkv.  l_s = 0 or rows_valid = 0 writes zeros to
+ * the gradient concerned.
+ */
+size_t lss_project_bwd_weight_scratch_bytes(int64_t l_s, int64_t l_x, int64_t B,
+                                            int64_t H, int64_t d);
+int lss_project_bwd_weight(const void *x, const void *dq, const float *dk_partial,
+                           const float *dv_partial, int64_t seg_offset,
+                           int64_t l_s, int64_t l_x, int64_t rows_valid,
+                           int64_t B, int64_t H, int64_t d,
+                           float *dw_q, float *dw_kv,
+                           void *scratch, size_t scratch_bytes, void *stream);
+
+/*
  * The segment-local remainder of a layer (Section 3, Principles 1 and 2): each of
  * these works on the rows of one segment alone, with no communication.  bf16
  * activations, fp32 arithmetic, one rounding to bf16 per output.  All pointers are

@@ -555,6 +555,54 @@ int lss_gelu_bwd(const void *u, const void *dg, int64_t n, void *du, void *strea
     return LSS_OK;
 }
 
+size_t lss_project_bwd_weight_scratch_bytes(int64_t l_s, int64_t l_x, int64_t B, int64_t H, int64_t d)
+{
+    const int64_t E = H * d;
+    if (l_s < 0 || l_x < 1 || B < 1 || H < 1 || d < 1 || l_s > l_x || l_x > INT32_MAX || B > INT32_MAX || E % 128 != 0 || E > 65536)
+        return 0;
+    return lss::project_bwd_weight_scratch_bytes((int)l_s, (int)l_x, (int)B, (int)E);
+}
+
+int lss_project_bwd_weight(const void *x, const void *dq, const float *dk_partial, const float *dv_partial, int64_t seg_offset,
+                           int64_t l_s, int64_t l_x, int64_t rows_valid, int64_t B, int64_t H, int64_t d, float *dw_q,
+                           float *dw_kv, void *scratch, size_t scratch_bytes, void *stream)
+{
+    if (int rc = check_shape(seg_offset, l_s, l_x, B, H, d)) return rc;
+    const int64_t E = H * d;
+    if (E % 128 != 0 || E > 65536)
+        return fail(LSS_ERR_SHAPE, "projections: E_m = H*d = %lld is not a multiple of 128 or exceeds 65536", (long long)E);
+    if (rows_valid < 0 || rows_valid > l_x)
+        return fail(LSS_ERR_RANGE, "project_bwd_weight: rows_valid = %lld outside [0, %lld]", (long long)rows_valid, (long long)l_x);
+    if (!dw_q || !dw_kv) return fail(LSS_ERR_NULL, "project_bwd_weight: NULL gradient pointer");
+    if (misaligned(dw_q) || misaligned(dw_kv)) return fail(LSS_ERR_ALIGN, "project_bwd_weight: tensor pointers must be 16-byte aligned");
+    const bool has_q = B > 0 && l_s > 0, has_kv = B > 0 && rows_valid > 0;
+    if ((has_q && (!x || !dq)) || (has_kv && (!x || !dk_partial || !dv_partial)))
+        return fail(LSS_ERR_NULL, "project_bwd_weight: NULL tensor pointer");
+    if (misaligned(x) || misaligned(dq) || misaligned(dk_partial) || misaligned(dv_partial) || misaligned(scratch))
+        return fail(LSS_ERR_ALIGN, "project_bwd_weight: tensor pointers must be 16-byte aligned");
+    const size_t need = B > 0 ? lss::project_bwd_weight_scratch_needed(has_q ? (int)l_s : 0, has_kv ? (int)rows_valid : 0, (int)B, (int)E) : 0;
+    if (need > 0 && (!scratch || scratch_bytes < need))
+        return fail(LSS_ERR_WORKSPACE, "project_bwd_weight: scratch of %zu bytes, need %zu", scratch ? scratch_bytes : (size_t)0, need);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    const int64_t none = 0;     // a gradient without rows is zero: written by the sum kernel over one part without valid rows
+    if (!has_q) {
+        const float *part = dw_q;
+        e = lss::launch_reduce(&part, 1, &none, E, 1, 1, E, dw_q, st);
+    }
+    if (e == hipSuccess && !has_kv) {
+        const float *part = dw_kv;
+        e = lss::launch_reduce(&part, 1, &none, E, 1, 1, 2 * E, dw_kv, st);
+    }
+    using lss::bf16_t;
+    if (e == hipSuccess && (has_q || has_kv))
+        e = lss::launch_project_bwd_weight(static_cast<const bf16_t *>(x), static_cast<const bf16_t *>(dq), dk_partial, dv_partial,
+                                           seg_offset, has_q ? (int)l_s : 0, (int)l_x, has_kv ? (int)rows_valid : 0, (int)B, (int)E,
+                                           dw_q, dw_kv, static_cast<float *>(scratch), st);
+    if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "project_bwd_weight launch failed: %s", hipGetErrorString(e));
+    return LSS_OK;
+}
+
 int lss_reduce_partials(const float *const *parts, int n, const int64_t *rows_valid, int64_t l_x, int64_t B,
                         int64_t H, int64_t d, float *out, void *stream)
 {

@@ -102,6 +102,13 @@ size_t linear_bwd_weight_scratch_bytes(int rows, int K, int N);
 hipError_t launch_linear_bwd_weight(const bf16_t *a, const bf16_t *dc, int rows, int K, int N, float *dw, float *scratch,
                                     hipStream_t st);
 
+// one segment's share of the projection weights' gradients: dw_q [E][E], dw_kv [E][2E] (float)
+size_t project_bwd_weight_scratch_bytes(int l_s, int l_x, int B, int E);        // for any rows_valid <= l_x
+size_t project_bwd_weight_scratch_needed(int l_s, int rows_valid, int B, int E); // what one call uses
+hipError_t launch_project_bwd_weight(const bf16_t *x, const bf16_t *dq, const float *dk_part, const float *dv_part, int64_t s0,
+                                     int l_s, int l_x, int rows_valid, int B, int E, float *dw_q, float *dw_kv, float *scratch,
+                                     hipStream_t st);
+
 // segment-local row operations (lss_rows.hip); E a multiple of 8
 hipError_t launch_embed_pe_fwd(const bf16_t *tok, const bf16_t *pe, int64_t s0, int l_s, int B, int E, bf16_t *x,
                                hipStream_t st);

@@ -27,6 +27,7 @@
 
 #include <mutex>
 #include <type_traits>
+#include <vector>
 
 namespace lss {
 
@@ -355,17 +356,24 @@ __global__ __launch_bounds__(P_NT, 1) void proj_gemm_kernel(ProjArgs args)
 // Weight gradient of a linear map: dW[k, n] = sum_r A[r, k] dC[r, n], the contraction running over
 // the rows of both operands.  Both are therefore loaded as [64 rows][256 columns] tiles and read
 // through transposing LDS reads (WTileTr); a workgroup owns a 256 (k) x 256 (n) tile of dW for one
-// chunk of rows and writes it in fp32, to dW itself when there is a single chunk, else to that
-// chunk's partial result, which a fixed-order sum adds up afterwards.  Same wavefront layout,
-// two-slot ring and LDS-staged stores as proj_gemm_kernel.
+// chunk of rows of one batch entry and writes it in fp32, to dW itself when there is a single chunk,
+// else to that chunk's partial result, which a fixed-order sum adds up afterwards.  Same wavefront
+// layout, two-slot ring and LDS-staged stores as proj_gemm_kernel.
+//   DC_F32  dC is float and may come from two tensors side by side (the dK and dV partials): it is
+//           rounded to bf16 on its way into LDS, through registers, as proj_gemm_kernel does for a
+//           float A.
 struct WgradArgs {
-    const bf16_t *a, *dc;       // [rows][K], [rows][N]
+    const bf16_t *a;            // batch b, row r: a + b * a_batch_stride + r * lda  (K columns)
+    const void *dc0, *dc1;      // dC: columns < n_split from dc0, the others from dc1 (column n - n_split); row stride ldc
+    int64_t a_batch_stride, dc_batch_stride;    // elements
     float *out;                 // [splits][K][N]
-    int rows, K, N;
+    int rows;                   // rows of every batch entry
+    int batches, K, N, n_split, lda, ldc;
     int chunk_rows;             // rows per split, a multiple of 64
-    int splits, m_tiles, n_tiles;
+    int splits_per_batch, m_tiles, n_tiles;
 };
 
+template <bool DC_F32>
 __global__ __launch_bounds__(P_NT, 1) void wgrad_gemm_kernel(WgradArgs g)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -375,32 +383,39 @@ __global__ __launch_bounds__(P_NT, 1) void wgrad_gemm_kernel(WgradArgs g)
 
     // consecutive ids go to consecutive XCDs; an XCD walks the output tiles of one chunk of rows, so
     // that chunk's rows of A and dC are read from HBM once per XCD
-    const int tiles = g.m_tiles * g.n_tiles;
+    const int tiles = g.m_tiles * g.n_tiles, splits = g.batches * g.splits_per_batch;
     const int x = blockIdx.x % kXcds, rest = blockIdx.x / kXcds;
     const int tile = rest % tiles, split = x + kXcds * (rest / tiles);
-    if (split >= g.splits) return;
+    if (split >= splits) return;
+    const int batch = split / g.splits_per_batch;
     const int m0 = (tile / g.n_tiles) * PM, n0 = (tile % g.n_tiles) * PN;
-    const int r0 = split * g.chunk_rows, r1 = min(r0 + g.chunk_rows, g.rows);
+    const int r0 = (split % g.splits_per_batch) * g.chunk_rows, r1 = min(r0 + g.chunk_rows, g.rows);
     const int T = (r1 - r0 + PK - 1) / PK;          // >= 1: the host sizes the splits so
     const int tail = (r1 - r0) - (T - 1) * PK;      // rows of the last tile, 1 .. 64
     const int cols_m = min(g.K - m0, PM), cols_n = min(g.N - n0, PN);
 
-    uint32_t offA[WTileTr::NI], offW[WTileTr::NI], offA_last[WTileTr::NI], offW_last[WTileTr::NI];
-    WTileTr::offsets(offA, g.K, wave, lane, cols_m / 8);
-    WTileTr::offsets(offW, g.N, wave, lane, cols_n / 8);
-    WTileTr::offsets(offA_last, g.K, wave, lane, cols_m / 8, tail);
-    WTileTr::offsets(offW_last, g.N, wave, lane, cols_n / 8, tail);
+    uint32_t offA[WTileTr::NI], offA_last[WTileTr::NI], offW[DC_F32 ? 1 : WTileTr::NI], offW_last[DC_F32 ? 1 : WTileTr::NI];
+    WTileTr::offsets(offA, g.lda, wave, lane, cols_m / 8);
+    WTileTr::offsets(offA_last, g.lda, wave, lane, cols_m / 8, tail);
+    if constexpr (!DC_F32) {
+        WTileTr::offsets(offW, g.ldc, wave, lane, cols_n / 8);
+        WTileTr::offsets(offW_last, g.ldc, wave, lane, cols_n / 8, tail);
+    }
+    const bf16_t *a_base = g.a + (int64_t)batch * g.a_batch_stride + (int64_t)r0 * g.lda + m0;
     auto issue = [&](int t, int slot) {
         char *dst = smem + slot * P_SLOT;
-        const bf16_t *pa = g.a + (int64_t)(r0 + t * PK) * g.K + m0, *pw = g.dc + (int64_t)(r0 + t * PK) * g.N + n0;
+        const bf16_t *pa = a_base + (int64_t)t * PK * g.lda;
         const bool last = t == T - 1;
 #pragma unroll
-        for (int i = 0; i < WTileTr::NI; ++i) {
-            lds_dma<16>(pa, last ? offA_last[i] : offA[i], dst + (i * P_WAVES + wave) * 1024);
-            lds_dma<16>(pw, last ? offW_last[i] : offW[i], dst + P_ABYTES + (i * P_WAVES + wave) * 1024);
+        for (int i = 0; i < WTileTr::NI; ++i) lds_dma<16>(pa, last ? offA_last[i] : offA[i], dst + (i * P_WAVES + wave) * 1024);
+        if constexpr (!DC_F32) {
+            const bf16_t *pw = static_cast<const bf16_t *>(g.dc0) + (int64_t)batch * g.dc_batch_stride + (int64_t)(r0 + t * PK) * g.ldc + n0;
+#pragma unroll
+            for (int i = 0; i < WTileTr::NI; ++i)
+                lds_dma<16>(pw, last ? offW_last[i] : offW[i], dst + P_ABYTES + (i * P_WAVES + wave) * 1024);
         }
     };
-    // Rows past the end of the chunk re-read its last row; their copies in both tiles are replaced
+    // Rows past the end of the chunk re-read its last row; their copies in the tiles are replaced
     // by zeros, each lane clearing exactly the 16 bytes its own loads wrote (after waiting for them).
     auto clear_tail = [&](int slot) {
         if (tail == PK) return;
@@ -410,7 +425,44 @@ __global__ __launch_bounds__(P_NT, 1) void wgrad_gemm_kernel(WgradArgs g)
             const int row = (i * P_WAVES + wave) * 2 + lane / 32;
             if (row >= tail) {
                 *reinterpret_cast<f32x4 *>(dst + (i * P_WAVES + wave) * 1024 + lane * 16) = f32x4{0.f, 0.f, 0.f, 0.f};
-                *reinterpret_cast<f32x4 *>(dst + P_ABYTES + (i * P_WAVES + wave) * 1024 + lane * 16) = f32x4{0.f, 0.f, 0.f, 0.f};
+                if constexpr (!DC_F32)
+                    *reinterpret_cast<f32x4 *>(dst + P_ABYTES + (i * P_WAVES + wave) * 1024 + lane * 16) = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+    };
+    // float dC: thread `tid` converts the 8-column chunks tid, tid + 512, ... of the [64][256] tile
+    // (chunk c is columns 8 (c % 32) .. + 7 of row c / 32) and writes them where the direct load would;
+    // rows past the end of the chunk are written as zeros
+    constexpr int FCH = PK * (PN / 8) / P_NT;       // chunks per thread
+    f32x4 stage[DC_F32 ? 2 * FCH : 1];
+    auto fetch_w = [&](int t) {
+        if constexpr (DC_F32) {
+            const int rows_here = t == T - 1 ? tail : PK;
+#pragma unroll
+            for (int i = 0; i < FCH; ++i) {
+                const int c = i * P_NT + tid, row = min(c >> 5, rows_here - 1), col = min(c & 31, cols_n / 8 - 1);
+                const int n = n0 + col * 8;
+                const float *src = n < g.n_split ? static_cast<const float *>(g.dc0) + n : static_cast<const float *>(g.dc1) + (n - g.n_split);
+                const f32x4 *p = reinterpret_cast<const f32x4 *>(src + (int64_t)batch * g.dc_batch_stride + (int64_t)(r0 + t * PK + row) * g.ldc);
+                stage[2 * i] = p[0];
+                stage[2 * i + 1] = p[1];
+            }
+        }
+    };
+    auto stash_w = [&](int t, int slot) {
+        if constexpr (DC_F32) {
+            const int rows_here = t == T - 1 ? tail : PK;
+            char *dst = smem + slot * P_SLOT + P_ABYTES;
+#pragma unroll
+            for (int i = 0; i < FCH; ++i) {
+                const int c = i * P_NT + tid, row = c >> 5, col = c & 31;
+                bf16x8 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    v[e] = row < rows_here ? (bf16_t)stage[2 * i][e] : (bf16_t)0.f;
+                    v[4 + e] = row < rows_here ? (bf16_t)stage[2 * i + 1][e] : (bf16_t)0.f;
+                }
+                *reinterpret_cast<bf16x8 *>(dst + row * (PN * 2) + ((col ^ (4 * (row & 3))) * 16)) = v;
             }
         }
     };
@@ -451,7 +503,12 @@ __global__ __launch_bounds__(P_NT, 1) void wgrad_gemm_kernel(WgradArgs g)
         }
     };
 
+    // tile t is multiplied from slot t % 2 while tile t + 1 travels into the other slot; a float
+    // dC tile is fetched into registers two tiles ahead and written to LDS one tile ahead
+    fetch_w(0);
     issue(0, 0);
+    stash_w(0, 0);
+    if (T > 1) fetch_w(1);
     wait_vmem_all();
     if (T == 1) clear_tail(0);
     __syncthreads();
@@ -459,8 +516,10 @@ __global__ __launch_bounds__(P_NT, 1) void wgrad_gemm_kernel(WgradArgs g)
         const int slot = t & 1;
         if (t + 1 < T) issue(t + 1, slot ^ 1);
         compute(slot);
+        if (t + 1 < T) stash_w(t + 1, slot ^ 1);
         wait_vmem_all();
         if (t + 1 == T - 1) clear_tail(slot ^ 1);
+        if (t + 2 < T) fetch_w(t + 2);
         __syncthreads();
     }
 
@@ -611,55 +670,109 @@ hipError_t launch_linear_bwd_input(const bf16_t *dc, const bf16_t *w, const bf16
 }
 
 // How the rows are split for the weight gradient: about two workgroups per compute unit, at least
-// eight 64-row tiles per workgroup, at most kMaxReduceParts chunks.  Shape-only, deterministic.
-static void wgrad_plan(int rows, int K, int N, int &splits, int &chunk_rows)
+// eight 64-row tiles per workgroup; a chunk never crosses batch entries.  Shape-only, deterministic.
+static int wgrad_want(int batches, int K, int N)       // chunks per batch entry aimed at; never exceeded
 {
     const int tiles = ((K + PM - 1) / PM) * ((N + PN - 1) / PN);
+    const int want = ((512 + tiles - 1) / tiles + batches - 1) / batches;
+    return want < 1 ? 1 : want;
+}
+static void wgrad_plan(int rows, int batches, int K, int N, int &splits_per_batch, int &chunk_rows)
+{
     const int R = (rows + PK - 1) / PK;
-    int want = (512 + tiles - 1) / tiles;
-    if (want > kMaxReduceParts) want = kMaxReduceParts;
+    const int want = wgrad_want(batches, K, N);
     int chunk_tiles = (R + want - 1) / want;
     if (chunk_tiles < 8) chunk_tiles = R < 8 ? R : 8;
     if (chunk_tiles < 1) chunk_tiles = 1;
-    splits = (R + chunk_tiles - 1) / chunk_tiles;
-    if (splits < 1) splits = 1;
+    splits_per_batch = (R + chunk_tiles - 1) / chunk_tiles;
+    if (splits_per_batch < 1) splits_per_batch = 1;
     chunk_rows = chunk_tiles * PK;
 }
 
-size_t linear_bwd_weight_scratch_bytes(int rows, int K, int N)
+static size_t wgrad_scratch_bytes(int rows, int batches, int K, int N)
 {
-    int splits, chunk_rows;
-    wgrad_plan(rows, K, N, splits, chunk_rows);
-    return splits > 1 ? (size_t)splits * K * N * sizeof(float) : 0;
+    int spb, chunk_rows;
+    wgrad_plan(rows, batches, K, N, spb, chunk_rows);
+    return batches * spb > 1 ? (size_t)batches * spb * K * N * sizeof(float) : 0;
 }
+
+// g: operands, rows, batches, K, N, strides filled in; dw [K][N]; rows >= 1, batches >= 1
+template <bool DC_F32>
+static hipError_t launch_wgrad(WgradArgs &g, float *dw, float *scratch, hipStream_t st)
+{
+    wgrad_plan(g.rows, g.batches, g.K, g.N, g.splits_per_batch, g.chunk_rows);
+    const int splits = g.batches * g.splits_per_batch;
+    g.out = splits > 1 ? scratch : dw;
+    g.m_tiles = (g.K + PM - 1) / PM;
+    g.n_tiles = (g.N + PN - 1) / PN;
+    static std::once_flag once;
+    static hipError_t attr = hipSuccess;
+    std::call_once(once, [] {
+        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_gemm_kernel<DC_F32>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, P_LDS);
+    });
+    if (attr != hipSuccess) return attr;
+    {
+        TimedLaunch tl(K_LINEAR_WGRAD, st);
+        hipLaunchKernelGGL(wgrad_gemm_kernel<DC_F32>, dim3(xcd_grid(splits, g.m_tiles * g.n_tiles)), dim3(P_NT), P_LDS, st, g);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (splits == 1) return hipSuccess;
+    std::vector<const float *> parts(splits);
+    for (int i = 0; i < splits; ++i) parts[i] = scratch + (size_t)i * g.K * g.N;
+    return launch_reduce(parts.data(), splits, nullptr, g.K, 1, 1, g.N, dw, st);   // chunk 0 + chunk 1 + ..., in that order
+}
+
+size_t linear_bwd_weight_scratch_bytes(int rows, int K, int N) { return wgrad_scratch_bytes(rows, 1, K, N); }
 
 // dw = a^T dc.  rows >= 1.
 hipError_t launch_linear_bwd_weight(const bf16_t *a, const bf16_t *dc, int rows, int K, int N, float *dw, float *scratch,
                                     hipStream_t st)
 {
     WgradArgs g{};
-    wgrad_plan(rows, K, N, g.splits, g.chunk_rows);
-    g.a = a; g.dc = dc; g.rows = rows; g.K = K; g.N = N;
-    g.out = g.splits > 1 ? scratch : dw;
-    g.m_tiles = (K + PM - 1) / PM;
-    g.n_tiles = (N + PN - 1) / PN;
-    static std::once_flag once;
-    static hipError_t attr = hipSuccess;
-    std::call_once(once, [] {
-        attr = hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_gemm_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   P_LDS);
-    });
-    if (attr != hipSuccess) return attr;
-    {
-        TimedLaunch tl(K_LINEAR_WGRAD, st);
-        hipLaunchKernelGGL(wgrad_gemm_kernel, dim3(xcd_grid(g.splits, g.m_tiles * g.n_tiles)), dim3(P_NT), P_LDS, st, g);
-        const hipError_t e = hipGetLastError();
+    g.a = a; g.dc0 = dc; g.dc1 = nullptr;
+    g.rows = rows; g.batches = 1; g.K = K; g.N = N; g.n_split = N; g.lda = K; g.ldc = N;
+    return launch_wgrad<false>(g, dw, scratch, st);
+}
+
+// enough for any rows_valid <= l_x: a plan never has more chunks per batch entry than wgrad_want()
+size_t project_bwd_weight_scratch_bytes(int l_s, int l_x, int B, int E)
+{
+    (void)l_x;
+    const size_t q = l_s > 0 ? wgrad_scratch_bytes(l_s, B, E, E) : 0;
+    const size_t kv = (size_t)B * wgrad_want(B, E, 2 * E) * E * 2 * E * sizeof(float);
+    return q > kv ? q : kv;
+}
+size_t project_bwd_weight_scratch_needed(int l_s, int rows_valid, int B, int E)
+{
+    const size_t q = l_s > 0 ? wgrad_scratch_bytes(l_s, B, E, E) : 0;
+    const size_t kv = rows_valid > 0 ? wgrad_scratch_bytes(rows_valid, B, E, 2 * E) : 0;
+    return q > kv ? q : kv;
+}
+
+// dw_q = sum_b x_i^T dQ_i (l_s >= 1) and dw_kv = sum_b x[:rows_valid]^T [dK_part | dV_part][:rows_valid] (rows_valid >= 1);
+// either is skipped when its row count is 0 (the caller writes the zeros)
+hipError_t launch_project_bwd_weight(const bf16_t *x, const bf16_t *dq, const float *dk_part, const float *dv_part, int64_t s0,
+                                     int l_s, int l_x, int rows_valid, int B, int E, float *dw_q, float *dw_kv, float *scratch,
+                                     hipStream_t st)
+{
+    if (l_s > 0) {
+        WgradArgs g{};
+        g.a = x + s0 * E; g.a_batch_stride = (int64_t)l_x * E; g.lda = E;
+        g.dc0 = dq; g.dc1 = nullptr; g.dc_batch_stride = (int64_t)l_s * E; g.ldc = E;
+        g.rows = l_s; g.batches = B; g.K = E; g.N = E; g.n_split = E;
+        const hipError_t e = launch_wgrad<false>(g, dw_q, scratch, st);
         if (e != hipSuccess) return e;
     }
-    if (g.splits == 1) return hipSuccess;
-    const float *parts[kMaxReduceParts];
-    for (int i = 0; i < g.splits; ++i) parts[i] = scratch + (size_t)i * K * N;
-    return launch_reduce(parts, g.splits, nullptr, K, 1, 1, N, dw, st);      // chunk 0 + chunk 1 + ..., in that order
+    if (rows_valid > 0) {
+        WgradArgs g{};
+        g.a = x; g.a_batch_stride = (int64_t)l_x * E; g.lda = E;
+        g.dc0 = dk_part; g.dc1 = dv_part; g.dc_batch_stride = (int64_t)l_x * E; g.ldc = E;
+        g.rows = rows_valid; g.batches = B; g.K = E; g.N = 2 * E; g.n_split = E;
+        return launch_wgrad<true>(g, dw_kv, scratch, st);
+    }
+    return hipSuccess;
 }
 
 } // namespace lss

@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_E
 
 EXPORTS = ["lss_version", "lss_last_error", "lss_set_option", "lss_workspace_bytes", "lss_set_workspace",
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
-           "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd",
+           "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd", "lss_project_bwd_weight_scratch_bytes", "lss_project_bwd_weight",
            "lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_residual_dropout_add", "lss_layernorm_fwd", "lss_layernorm_bwd_scratch_bytes",
            "lss_layernorm_bwd", "lss_linear_fwd", "lss_linear_bwd_input", "lss_linear_bwd_weight_scratch_bytes", "lss_linear_bwd_weight",
            "lss_linear_gelu_fwd",
@@ -72,6 +72,10 @@ def load():
     lib.lss_project_qkv.restype = ci
     lib.lss_project_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, vp, vp]
     lib.lss_project_bwd.restype = ci
+    lib.lss_project_bwd_weight_scratch_bytes.argtypes = [i64, i64, i64, i64, i64]
+    lib.lss_project_bwd_weight_scratch_bytes.restype = sz
+    lib.lss_project_bwd_weight.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp, vp, vp, sz, vp]
+    lib.lss_project_bwd_weight.restype = ci
     lib.lss_embed_pe_fwd.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp, vp]
     lib.lss_embed_pe_bwd.argtypes = [vp, i64, i64, i64, vp, vp]
     lib.lss_residual_dropout_add.argtypes = [vp, vp, i64, i64, i64, i64, f64, u64, vp, vp]
@@ -300,6 +304,38 @@ def lss_project_bwd(dq, dk_partial, dv_partial, w_q, w_kv, rows_valid=None, dx_q
     _check(load().lss_project_bwd(_ptr(dq), _ptr(dk_partial), _ptr(dv_partial), _ptr(w_q), _ptr(w_kv), l_s, l_x,
                                   int(rows_valid), B, H, d, _ptr(dx_q), _ptr(dx_partial), _stream_ptr(stream)))
     return dx_q, dx_partial
+
+
+def lss_project_bwd_weight_scratch_bytes(l_s, l_x, B, H, d):
+    return int(load().lss_project_bwd_weight_scratch_bytes(int(l_s), int(l_x), int(B), int(H), int(d)))
+
+
+def lss_project_bwd_weight(x, dq, dk_partial, dv_partial, seg_offset, rows_valid=None, dw_q=None, dw_kv=None,
+                           scratch=None, stream=None):
+    """One segment's share of dW_q [E,E] = sum_b x_i^T dQ_i and dW_kv [E,2E] = sum_b x^T [dK_part | dV_part], float32."""
+    if x.dim() != 3 or dq.dim() != 4 or dk_partial.dim() != 4 or dk_partial.shape != dv_partial.shape:
+        raise ValueError("x must be [B,l_x,E]; dq [B,l_s,H,d]; partials [B,l_x,H,d]")
+    B, l_s, H, d = dq.shape
+    l_x, E = x.shape[1], H * d
+    if tuple(x.shape) != (B, l_x, E) or tuple(dk_partial.shape) != (B, l_x, H, d):
+        raise ValueError("shapes disagree")
+    if rows_valid is None:
+        rows_valid = l_x
+    for t, dt in ((x, torch.bfloat16), (dq, torch.bfloat16), (dk_partial, torch.float32), (dv_partial, torch.float32)):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != dt:
+            raise ValueError("tensors must be contiguous device tensors of the documented types")
+    if dw_q is None:
+        dw_q = torch.empty((E, E), dtype=torch.float32, device=x.device)
+    if dw_kv is None:
+        dw_kv = torch.empty((E, 2 * E), dtype=torch.float32, device=x.device)
+    if tuple(dw_q.shape) != (E, E) or tuple(dw_kv.shape) != (E, 2 * E) or dw_q.dtype != torch.float32 or dw_kv.dtype != torch.float32:
+        raise ValueError("dw_q must be float32 [E, E] and dw_kv float32 [E, 2E]")
+    if scratch is None:
+        scratch = torch.empty((max(16, lss_project_bwd_weight_scratch_bytes(l_s, l_x, B, H, d)),), dtype=torch.uint8, device=x.device)
+    _check(load().lss_project_bwd_weight(_ptr(x), _ptr(dq), _ptr(dk_partial), _ptr(dv_partial), int(seg_offset), l_s, l_x,
+                                         int(rows_valid), B, H, d, _ptr(dw_q), _ptr(dw_kv), _ptr(scratch), scratch.numel(),
+                                         _stream_ptr(stream)))
+    return dw_q, dw_kv
 
 
 def _dev(t, dtype, what):

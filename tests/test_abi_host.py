@@ -103,6 +103,24 @@ def test_options(lib):
     assert b"option" in lib.lss_last_error()
 
 
+def test_projection_weight_gradient_argument_checks(lib):
+    f = lib.lss_project_bwd_weight
+
+    def g(x=0x1000, dq=0x2000, dk=0x3000, dv=0x4000, s0=0, l_s=128, l_x=256, rv=256, B=1, H=2, d=64, dwq=0x5000, dwkv=0x6000,
+          scratch=0x7000, nbytes=1 << 30):
+        return f(x, dq, dk, dv, s0, l_s, l_x, rv, B, H, d, dwq, dwkv, scratch, nbytes, None)
+
+    assert g(H=1) == -2 and g(d=32) == -3 and g(s0=200) == -5
+    assert g(rv=257) == -5 and g(rv=-1) == -5
+    assert g(dwq=0) == -1 and g(x=0) == -1 and g(dk=0) == -1 and g(dq=0) == -1
+    assert g(dv=0x4004) == -4
+    need = lib.lss_project_bwd_weight_scratch_bytes(4096, 24576, 4, 16, 64)
+    assert need == 4 * 4 * 1024 * 2048 * 4
+    assert g(l_s=4096, l_x=24576, rv=24576, B=4, H=16, scratch=0, nbytes=0) == -6
+    assert g(l_s=4096, l_x=24576, rv=24576, B=4, H=16, nbytes=need - 1) == -6
+    assert lib.lss_project_bwd_weight_scratch_bytes(128, 256, 1, 1, 64) == 0     # E_m = 64: unsupported
+
+
 def test_layer_operation_argument_checks(lib):
     pe = lib.lss_embed_pe_fwd
 

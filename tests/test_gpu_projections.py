@@ -249,3 +249,61 @@ def test_projections_and_dropout_record_into_a_graph():
         for i, (a, b) in enumerate(zip(got, results)):
             assert torch.equal(a, b), f"seed {sd}: result {i} differs between replay and eager"
         assert all(torch.isfinite(t).all() for t in got)
+
+
+@pytest.mark.parametrize("B,l_x,H,d,s0,l_s", SHAPES)
+def test_project_bwd_weight_matches_oracle(B, l_x, H, d, s0, l_s):
+    X, _, _ = stage_proj(B, l_x, H, d, 9600 + l_x)
+    E = H * d
+    n = B * l_x * E
+    dk = synth.normal_f32(9601, n).reshape(B, l_x, H, d)
+    dv = synth.normal_f32(9602, n).reshape(B, l_x, H, d)
+    DQ = Staged(synth.normal_f32(9603, B * l_s * E).reshape(B, l_s, H, d), "bf16")
+    rows_valid = s0 + l_s
+    dk[:, rows_valid:] = 0.0
+    dv[:, rows_valid:] = 0.0
+    rq, rkv = oracle.project_bwd_weight(X.f64, DQ.f64, dk, dv, s0)
+    # the device copies carry NaN where the library must not read
+    dk_dev, dv_dev = torch.from_numpy(dk).cuda(), torch.from_numpy(dv).cuda()
+    dk_dev[:, rows_valid:] = float("nan")
+    dv_dev[:, rows_valid:] = float("nan")
+    need = lss.lss_project_bwd_weight_scratch_bytes(l_s, l_x, B, H, d)
+    scratch = torch.full((max(need, 16),), 0xFF, dtype=torch.uint8, device="cuda")
+    dwq, dwkv = lss.lss_project_bwd_weight(X.dev, DQ.dev, dk_dev, dv_dev, s0, rows_valid, scratch=scratch)
+    # fp32 sums of products of bf16-rounded operands: the partials' rounding (2^-9 each, independent)
+    # averages out over the rows, the bound is the single-stage one
+    assert rel_err(to_np(dwq), rq) <= TOL["bf16"]["t"]
+    assert rel_err(to_np(dwkv), rkv) <= TOL["bf16"]["t"]
+    # against the oracle fed the same bf16-rounded partials the matrix cores see: fp32 accumulation only
+    rdk = to_np(torch.from_numpy(dk).cuda().to(torch.bfloat16))
+    rdv = to_np(torch.from_numpy(dv).cuda().to(torch.bfloat16))
+    _, rkv_r = oracle.project_bwd_weight(X.f64, DQ.f64, rdk, rdv, s0)
+    assert rel_err(to_np(dwq), rq) <= TOL["f32"]["t"] and rel_err(to_np(dwkv), rkv_r) <= TOL["f32"]["t"]
+    again = lss.lss_project_bwd_weight(X.dev, DQ.dev, dk_dev, dv_dev, s0, rows_valid)
+    assert torch.equal(again[0], dwq) and torch.equal(again[1], dwkv)
+
+
+def test_project_bwd_weight_sums_over_segments_and_empty_cases():
+    B, l_x, H, d, N = 2, 640, 2, 64, 4
+    X, WQ, WKV = stage_proj(B, l_x, H, d, 9700)
+    E, l_s = H * d, l_x // N
+    DO = Staged(synth.normal_f32(9701, B * l_x * E).reshape(B, l_x, H, d), "bf16")
+    tot_q, tot_kv = np.zeros((E, E)), np.zeros((E, 2 * E))
+    for i in range(N):
+        s0 = i * l_s
+        q, k, v = lss.lss_project_qkv(X.dev, WQ.dev, WKV.dev, s0, l_s, H)
+        out, lse = lss.lss_segment_attn_fwd(q, k, v, s0, True)
+        dq, dkp, dvp = lss.lss_segment_attn_bwd(q, k, v, s0, out, lse, DO.dev[:, s0:s0 + l_s].contiguous(), True)
+        a, b_ = lss.lss_project_bwd_weight(X.dev, dq, dkp, dvp, s0, s0 + l_s)
+        tot_q += to_np(a)
+        tot_kv += to_np(b_)
+    # the oracle's chain on the whole sequence as one segment (Section 4: the contributions add up)
+    rq_, rk_, rv_ = oracle.project_qkv(X.f64, WQ.f64, WKV.f64, 0, l_x, H)
+    rdq, rdk, rdv = oracle.segment_bwd(rq_, rk_, rv_, DO.f64, 0, True)
+    ref_q, ref_kv = oracle.project_bwd_weight(X.f64, rdq, rdk, rdv, 0)
+    assert rel_err(tot_q, ref_q) <= 2 * TOL["bf16"]["t"] and rel_err(tot_kv, ref_kv) <= 2 * TOL["bf16"]["t"]
+    # no query rows / no valid rows: zeros
+    dq0 = torch.empty((B, 0, H, d), dtype=torch.bfloat16, device="cuda")
+    a, b_ = lss.lss_project_bwd_weight(X.dev, dq0, dkp, dvp, 0, 0, dw_q=torch.full((E, E), 2.0, device="cuda"),
+                                       dw_kv=torch.full((E, 2 * E), 2.0, device="cuda"))
+    assert not a.any() and not b_.any()
