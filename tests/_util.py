@@ -23,6 +23,15 @@ def rel_err(got, ref, floor=1e-30):
     return float(np.abs(got - ref).max() / max(np.abs(ref).max(), floor))
 
 
+def fro_err(got, ref, floor=1e-30):
+    """Second metric: ||got - ref||_F / max(||ref||_F, floor)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    return float(np.linalg.norm((got - ref).ravel()) / max(np.linalg.norm(ref.ravel()), floor))
+
+
 def lse_err(got, ref):
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)

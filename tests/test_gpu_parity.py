@@ -6,7 +6,7 @@ import torch
 
 import oracle
 from paper_2311_02382_amd import lss, synth
-from _util import TOL, Staged, lse_err, rel_err, stage_all, to_np
+from _util import TOL, Staged, fro_err, lse_err, rel_err, stage_all, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -21,6 +21,7 @@ def run_segment(Q, K, V, DO, s0, l_s, causal, kind, check_bwd=True, tag="", floo
     ref_o, ref_l = oracle.segment_fwd(Q.f64[:, sl], K.f64, V.f64, s0, causal)
     e_o, e_l = rel_err(to_np(out), ref_o), lse_err(to_np(lse), ref_l)
     assert e_o <= tol["t"], f"{tag} out err {e_o}"
+    assert fro_err(to_np(out), ref_o) <= tol["t"], f"{tag} out: Frobenius error"
     assert e_l <= tol["lse"], f"{tag} lse err {e_l}"
     if not check_bwd:
         return None
@@ -29,6 +30,8 @@ def run_segment(Q, K, V, DO, s0, l_s, causal, kind, check_bwd=True, tag="", floo
     for name, got, ref in (("dq", dq, rdq), ("dk", dk, rdk), ("dv", dv, rdv)):
         e = rel_err(to_np(got), ref, floor)
         assert e <= tol["t"], f"{tag} {name} err {e}"
+        if floor <= 1e-30:      # (a case whose exact result is 0 has no norm to compare with)
+            assert fro_err(to_np(got), ref) <= tol["t"], f"{tag} {name}: Frobenius error"
     if causal:  # rows no query of the segment sees are exactly zero
         assert torch.count_nonzero(dk[:, s0 + l_s:]) == 0 and torch.count_nonzero(dv[:, s0 + l_s:]) == 0
     return dk, dv, rdk, rdv
