@@ -17,6 +17,13 @@
  * segments is the full gradient -- the arithmetic of the reduce-scatter that is
  * the backward of the all-gather (Section 3, Principle 4, Fig. 2(v)).
  *
+ * Around that operation the header also declares, further down, the rest of a
+ * layer as one GPU computes it for its segment: the projections in the
+ * fused-communication form with their input and weight gradients (Principle 3,
+ * Fig. 2(ii)), and the operations that act on a segment's rows alone
+ * (Principles 1 and 2): positional-embedding rows, residual connection with
+ * dropout, layer normalisation, GeLU and general linear maps.
+ *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library
  *     neither frees nor retains them.  They must be 16-byte aligned.
