@@ -404,17 +404,24 @@ def main() -> int:
         lss.lss_timing_reset()
         lss.lss_timing_select([k_ for k_, n_ in names.items() if n_ == dom])
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps - 1)]    # step boundaries, for median and min
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0.record()
-    for _ in range(args.steps):
+    for i_ in range(args.steps):
         step()
+        if i_ < args.steps - 1:
+            marks[i_].record()
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     gpu_ms = e0.elapsed_time(e1)
     lss.lss_timing_enable(False)
     ms_per_step = max(wall_ms, gpu_ms) / args.steps
+    bounds = [e0] + marks + [e1]
+    per_step = sorted(a_.elapsed_time(b_) for a_, b_ in zip(bounds, bounds[1:]))
+    step_stats = {"median_ms": round(per_step[len(per_step) // 2], 4), "min_ms": round(per_step[0], 4),
+                  "max_ms": round(per_step[-1], 4), "note": "GPU time between step boundaries inside the timed region"}
 
     pairs = w.pairs()                       # unmasked (query, key) pairs x B x H, whole sequence
     flops_strict = 12.0 * pairs * w.d
@@ -535,7 +542,7 @@ def main() -> int:
                             if args.projections else "fwd+bwd of all N segments, then segment sum of dK and dV")},
         ("frac_of_f32_peak" if f32 else "frac_of_bf16_peak"): round(value / peak, 4),
         "tflops_with_recompute_count_14Pd": round(flops_fa / (ms_per_step * 1e-3) / 1e12, 2),
-        "gpu_ms_per_step_events": round(gpu_ms / args.steps, 4),
+        "gpu_ms_per_step_events": round(gpu_ms / args.steps, 4), "step_stats": step_stats,
         "roofline": roofline, "cpu_baseline": cpu_baseline, "rates": rates, "kernels": kernels,
     }
     print(json.dumps(line))
