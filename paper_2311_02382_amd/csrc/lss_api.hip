@@ -31,7 +31,7 @@ int choose_splits(int l_s, int l_x, int B, int H, int rows_per_wg)
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-struct WsLayout { size_t o_part, lse_part, D, Ls, dq_part, total; };
+struct WsLayout { size_t o_part, lse_part, D, Ls, dq_part, row_key, total; };
 static WsLayout ws_layout(int l_s, int l_x, int B, int H, int d, int elem_bytes)
 {
     // forward and dQ kernels may use different tile heights, hence different split counts
@@ -46,6 +46,7 @@ static WsLayout ws_layout(int l_s, int l_x, int B, int H, int d, int elem_bytes)
     w.D = off;        off += align256(rows * sizeof(float));
     w.Ls = off;       off += align256(rows * sizeof(float));
     w.dq_part = off;  off += align256(sp > 1 ? sp * rows * d * sizeof(float) : 0);
+    w.row_key = off;  off += align256(rows * sizeof(uint32_t));
     w.total = off;
     return w;
 }
@@ -63,6 +64,7 @@ Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d, int
     ws.D = reinterpret_cast<float *>(p + w.D);
     ws.Ls = reinterpret_cast<float *>(p + w.Ls);
     ws.dq_part = reinterpret_cast<float *>(p + w.dq_part);
+    ws.row_key = reinterpret_cast<uint32_t *>(p + w.row_key);
     return ws;
 }
 

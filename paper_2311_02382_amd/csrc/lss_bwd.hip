@@ -366,22 +366,15 @@ static hipError_t launch_bwd_d(const SegShape &s, const DropArgs &dr, const T *q
         return hipGetLastError();
     };
     if constexpr (sizeof(T) == 2) {
-        if (dr.thr != 0) {
-            // dropout: the pipelined dQ workgroups (which take D from out and dO themselves), then the
-            // general dK/dV kernel with its row-dot kernel in front
-            if ((e = launch_bwd_bf16_main(s, dr, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st)) != hipSuccess) return e;
-            if ((e = rowdot()) != hipSuccess) return e;
-            if ((e = generic_dkv(std::true_type{})) != hipSuccess) return e;
-        } else {
-            // The dQ workgroups share their launch with the dK/dV ones and need not fill the chip alone:
-            // keys are split only so far that a dQ workgroup (64 key tiles at most) does not outlast the
-            // rest of the launch.  Never more splits than the workspace was sized for.
-            const int64_t kv_extent = s.causal ? (s.s0 + s.l_s < s.l_x ? s.s0 + s.l_s : (int64_t)s.l_x) : (int64_t)s.l_x;
-            const int want = (int)((kv_extent + 64 * 64 - 1) / (64 * 64));
-            if (want < n_splits) n_splits = want < 1 ? 1 : want;
-            if ((e = launch_bwd_bf16_main(s, dr, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st)) != hipSuccess)
-                return e;
-        }
+        // The dQ workgroups share their launch with the dK/dV ones and need not fill the chip alone:
+        // keys are split only so far that a dQ workgroup (64 key tiles at most) does not outlast the
+        // rest of the launch.  Never more splits than the workspace was sized for.  (Dropout runs
+        // the same launch with the kernels' dropout variants.)
+        const int64_t kv_extent = s.causal ? (s.s0 + s.l_s < s.l_x ? s.s0 + s.l_s : (int64_t)s.l_x) : (int64_t)s.l_x;
+        const int want = (int)((kv_extent + 64 * 64 - 1) / (64 * 64));
+        if (want < n_splits) n_splits = want < 1 ? 1 : want;
+        if ((e = launch_bwd_bf16_main(s, dr, q, k, v, out, lse, dO, dq, dk_part, dv_part, ws, n_splits, st)) != hipSuccess)
+            return e;
     } else {
         if ((e = rowdot()) != hipSuccess) return e;
         if (dr.thr != 0) {

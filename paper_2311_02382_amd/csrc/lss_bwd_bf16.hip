@@ -304,7 +304,7 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
-template <int D>
+template <int D, bool DROP = false>
 struct DkvBf16Cfg {
     // One 32-row key block per wavefront.  Two blocks would halve the LDS traffic per flop but
     // their accumulators leave room for only one wavefront per SIMD, which measures slower.
@@ -314,8 +314,9 @@ struct DkvBf16Cfg {
     static constexpr int NU = D / 16;                   // operand steps of the S/dP products; same for dV/dK
     using Tile = DirectTile<D, BQ>;
     // one ring slot: Q tile, dO tile, 64 S-accumulator start values, 64 dP-accumulator start values
-    static constexpr int OFF_G = Tile::BYTES, OFF_L = 2 * Tile::BYTES, OFF_D = OFF_L + BQ * 4;
-    static constexpr int SLOT = OFF_D + BQ * 4;
+    // (with dropout also the 64 rows' generator keys)
+    static constexpr int OFF_G = Tile::BYTES, OFF_L = 2 * Tile::BYTES, OFF_D = OFF_L + BQ * 4, OFF_R = OFF_D + BQ * 4;
+    static constexpr int SLOT = OFF_R + (DROP ? BQ * 4 : 0);
 };
 
 // The query rows are walked in blocks of 32 (two per 64-row Q/dO tile).  Per block g three stages:
@@ -326,14 +327,20 @@ struct DkvBf16Cfg {
 // A(g+1) and C(g-1) with the vector work of B(g) spread between them, one element per matrix
 // instruction.  Block g+1 may belong to the next tile and block g-1 to the previous one, hence a
 // ring of three tiles in LDS; tiles travel global -> LDS directly, a full loop iteration ahead.
-template <int D>
-__device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, const bf16_t *__restrict__ q,
+//
+// With dropout (DROP) the weight that enters dV is A = P * M (M = 1 / (1 - p) where the weight is
+// kept, else 0) and dS = A * dP - P * D; the dP accumulator still starts at -D, so with acc = dP - D
+// this is dS = A * acc + (P - A) * (-D).  The keep decision of an element needs its row's key
+// (precomputed per query row, travelling with the tile like the start values) and this lane's
+// column key; -D of the element's row is read from the tile's start values a second time.
+template <int D, bool DROP>
+__device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, const DropArgs &dr, const bf16_t *__restrict__ q,
                                              const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
                                              const bf16_t *__restrict__ dO, const float *__restrict__ Ls,
-                                             const float *__restrict__ Dn, float *__restrict__ dk_part,
-                                             float *__restrict__ dv_part, int bh, int key_tile)
+                                             const float *__restrict__ Dn, const uint32_t *__restrict__ row_key,
+                                             float *__restrict__ dk_part, float *__restrict__ dv_part, int bh, int key_tile)
 {
-    using C = DkvBf16Cfg<D>;
+    using C = DkvBf16Cfg<D, DROP>;
     using Tile = typename C::Tile;
     constexpr int NU = C::NU;
 
@@ -394,6 +401,8 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
     const bf16_t *qbase = q + (int64_t)b * s.l_s * ld + (int64_t)h * D;
     const bf16_t *gbase = dO + (int64_t)b * s.l_s * ld + (int64_t)h * D;
     const float *lbase = Ls + (int64_t)bh * s.l_s, *dbase = Dn + (int64_t)bh * s.l_s;
+    const uint32_t *rbase = DROP ? row_key + (int64_t)bh * s.l_s : nullptr;
+    const uint32_t drop_ck = DROP ? drop_col_key(drop_col_seed(dr.seed_hi), (uint32_t)j) : 0u;  // this lane's key
 
     // ---- tile loads: all four wavefronts move Q and dO; wavefronts 0 and 1 also the 64 start values
     uint32_t offF[Tile::NI];                            // this lane's global offsets within a full tile
@@ -412,6 +421,7 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
             const uint32_t ro = (uint32_t)min(lane, rows_ok - 1) * 4u;
             lds_dma<4>(src, ro, dst + (wave == 0 ? C::OFF_L : C::OFF_D));
         }
+        if (DROP && wave == 2) lds_dma<4>(rbase + rq0, (uint32_t)min(lane, rows_ok - 1) * 4u, dst + C::OFF_R);
     };
 
     // ---- per-lane LDS offsets (bytes, within a tile)
@@ -462,13 +472,27 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
     };
     // B for elements [e0, e1): P = 2^(c * (S - lse*sqrt(d))), dS = P * (dP - D); finished pairs are
     // rounded to bf16 into the operand fragments of C
-    auto b_elems = [&](f32x16 &sc, f32x16 &dp, int e0, int e1, Frag<bf16_t> (&pf)[2], Frag<bf16_t> (&df)[2])
-        __attribute__((always_inline)) {
+    // (dropout: `tile_b`, `qb_b` name B's block; the row keys and -D of four elements are read when
+    // the first of them is due)
+    u32x4 rk4;
+    f32x4 nd4;
+    auto b_elems = [&](const char *tile_b, int qb_b, f32x16 &sc, f32x16 &dp, int e0, int e1, Frag<bf16_t> (&pf)[2],
+                       Frag<bf16_t> (&df)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int e = e0; e < e1; ++e) {
             const float p = fast_exp2(sc[e] * c);
-            sc[e] = p;
-            dp[e] = p * dp[e];
+            if constexpr (DROP) {
+                if ((e & 3) == 0) {
+                    rk4 = *reinterpret_cast<const u32x4 *>(tile_b + C::OFF_R + (qb_b * 32 + 8 * (e >> 2) + 4 * hh) * 4);
+                    nd4 = *reinterpret_cast<const f32x4 *>(tile_b + C::OFF_D + (qb_b * 32 + 8 * (e >> 2) + 4 * hh) * 4);
+                }
+                const float a = drop_keep(rk4[e & 3], drop_ck, dr.thr) ? p * dr.scale : 0.f;
+                sc[e] = a;
+                dp[e] = a * dp[e] + (p - a) * nd4[e & 3];
+            } else {
+                sc[e] = p;
+                dp[e] = p * dp[e];
+            }
             if (e & 1) {
                 pf[e >> 3].v[(e & 7) - 1] = (bf16_t)sc[e - 1]; pf[e >> 3].v[e & 7] = (bf16_t)sc[e];
                 df[e >> 3].v[(e & 7) - 1] = (bf16_t)dp[e - 1]; df[e >> 3].v[e & 7] = (bf16_t)dp[e];
@@ -488,9 +512,9 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
     // the barrier publishes.
     Frag<bf16_t> cq[2], cg[2];
     auto step = [&](auto has_a, auto has_b, auto has_c, auto pre, const char *tile_a, int qb_a, int r0_a, f32x16 &sc_a,
-                    f32x16 &dp_a, f32x16 &sc_b, f32x16 &dp_b, Frag<bf16_t> (&pf_b)[2], Frag<bf16_t> (&df_b)[2],
-                    const char *tile_c, int qb_c, Frag<bf16_t> (&pf_c)[2], Frag<bf16_t> (&df_c)[2], const char *tile_an,
-                    int qb_an, const char *tile_cn, int qb_cn, auto &&mid) __attribute__((always_inline)) {
+                    f32x16 &dp_a, const char *tile_b, int qb_b, f32x16 &sc_b, f32x16 &dp_b, Frag<bf16_t> (&pf_b)[2],
+                    Frag<bf16_t> (&df_b)[2], const char *tile_c, int qb_c, Frag<bf16_t> (&pf_c)[2], Frag<bf16_t> (&df_c)[2],
+                    const char *tile_an, int qb_an, const char *tile_cn, int qb_cn, auto &&mid) __attribute__((always_inline)) {
         constexpr bool HA = decltype(has_a)::value, HB = decltype(has_b)::value, HC = decltype(has_c)::value;
         constexpr bool PRE = decltype(pre)::value;
         constexpr int NS = 4 * NU;                      // slots; 16 elements of B spread over them
@@ -499,7 +523,7 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
             if (HB) {
                 const int e0 = slot * 16 / NS, e1 = (slot + 1) * 16 / NS;
                 __builtin_amdgcn_sched_barrier(0);
-                b_elems(sc_b, dp_b, e0, e1, pf_b, df_b);
+                b_elems(tile_b, qb_b, sc_b, dp_b, e0, e1, pf_b, df_b);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
@@ -562,8 +586,8 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
     // step -1: A(0) alone (leaves the first loop step's C operands in cq[0], cg[0]).  That step has
     // no C(-1): it multiplies zeros with tile 0 instead.
     auto nothing = [] {};
-    step(true_type{}, false_type{}, false_type{}, false_type{}, smem, 0, rq_begin, sc0, dp0, sc1, dp1, pf0, df0, smem, 0, pf1,
-         df1, smem, 1, smem, 1, nothing);
+    step(true_type{}, false_type{}, false_type{}, false_type{}, smem, 0, rq_begin, sc0, dp0, smem, 0, sc1, dp1, pf0, df0, smem, 0,
+         pf1, df1, smem, 1, smem, 1, nothing);
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
@@ -580,7 +604,7 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
         // Before its last requests (which may touch tile t+1): tile t+1's loads, issued one iteration
         // ago, have landed for this wavefront; after the barrier for all, and every wavefront has
         // requested its last operands from tile t-1, whose slot takes tile t+2.
-        step(true_type{}, true_type{}, true_type{}, true_type{}, t_cur, 1, r0 + 32, sc1, dp1, sc0, dp0, pf0, df0,
+        step(true_type{}, true_type{}, true_type{}, true_type{}, t_cur, 1, r0 + 32, sc1, dp1, t_cur, 0, sc0, dp0, pf0, df0,
              t > 0 ? t_prv : t_cur, 1, pf1, df1, t_a2, 0, t_cur, 0, [&] {
                  wait_vmem_all();
                  __syncthreads();
@@ -588,15 +612,15 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
              });
         // odd step g = 2t+1: A(2t+2) [tile t+1, first half; past the end result unused], B(2t+1),
         // C(2t) [tile t, first half]
-        step(true_type{}, true_type{}, true_type{}, true_type{}, t_a2, 0, r0 + C::BQ, sc0, dp0, sc1, dp1, pf1, df1, t_cur, 0, pf0,
-             df0, t_a2, 1, t_cur, 1, nothing);
+        step(true_type{}, true_type{}, true_type{}, true_type{}, t_a2, 0, r0 + C::BQ, sc0, dp0, t_cur, 1, sc1, dp1, pf1, df1, t_cur,
+             0, pf0, df0, t_a2, 1, t_cur, 1, nothing);
         cur = nxt;
     }
     // step 2T: C(2T-1) [tile T-1, second half] alone
     {
         const char *t_last = smem + (cur == 0 ? C::RING - 1 : cur - 1) * C::SLOT;
-        step(false_type{}, false_type{}, true_type{}, false_type{}, smem, 0, 0, sc0, dp0, sc0, dp0, pf0, df0, t_last, 1, pf1, df1,
-             smem, 0, t_last, 1, nothing);
+        step(false_type{}, false_type{}, true_type{}, false_type{}, smem, 0, 0, sc0, dp0, smem, 0, sc0, dp0, pf0, df0, t_last, 1, pf1,
+             df1, smem, 0, t_last, 1, nothing);
     }
 
     if (key_ok) {
@@ -621,10 +645,12 @@ int dq_bf16_rows_per_workgroup(int d) { return d == 64 ? DqBf16Cfg<64>::BR : DqB
 // ------------------------------------------------------------------------------------------ launch
 // Start values of the dK/dV accumulators, per query row: -D = -rowsum(dO * out) and -lse * sqrt(d).
 // One 16-byte chunk of a row per thread, D/8 consecutive lanes per row.
-template <int D>
-__global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(SegShape s, const bf16_t *__restrict__ out,
+// (dropout: also the generator's key of the row, for the dK/dV workgroups.)
+template <int D, bool DROP>
+__global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(SegShape s, DropArgs dr, const bf16_t *__restrict__ out,
                                                             const bf16_t *__restrict__ dO, const float *__restrict__ lse,
-                                                            float *__restrict__ Dn, float *__restrict__ Ls)
+                                                            float *__restrict__ Dn, float *__restrict__ Ls,
+                                                            uint32_t *__restrict__ row_key)
 {
     constexpr int CPR = D / 8;
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -643,6 +669,7 @@ __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(SegShape s, const bf
         const int64_t o_idx = ((int64_t)b * s.H + h) * s.l_s + r;
         Dn[o_idx] = -dsum;
         Ls[o_idx] = -lse[o_idx] * sqrtf((float)D);
+        if constexpr (DROP) row_key[o_idx] = drop_row_key(dr.seed_lo, (uint32_t)(b * s.H + h), (uint32_t)(s.s0 + r));
     }
 }
 
@@ -658,21 +685,21 @@ template <int D, bool DROP>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     SegShape s, DropArgs dr, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO, const float *__restrict__ lse,
-    const float *__restrict__ Ls, const float *__restrict__ Dn, bf16_t *__restrict__ dq, float *__restrict__ dq_part,
-    float *__restrict__ dk_part, float *__restrict__ dv_part, int n_splits, int n_dq, int n_q_tiles, int n_key_tiles)
+    const float *__restrict__ Ls, const float *__restrict__ Dn, const uint32_t *__restrict__ row_key, bf16_t *__restrict__ dq,
+    float *__restrict__ dq_part, float *__restrict__ dk_part, float *__restrict__ dv_part, int n_splits, int n_dq, int n_q_tiles,
+    int n_key_tiles)
 {
-    constexpr int SMEM = DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT > DkvBf16Cfg<D>::RING * DkvBf16Cfg<D>::SLOT
+    using DkvC = DkvBf16Cfg<D, DROP>;
+    constexpr int SMEM = DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT > DkvC::RING * DkvC::SLOT
                              ? DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT
-                             : DkvBf16Cfg<D>::RING * DkvBf16Cfg<D>::SLOT;
+                             : DkvC::RING * DkvC::SLOT;
     __shared__ __attribute__((aligned(1024))) char smem[SMEM];
     const int bhs = s.B * s.H;
     const int id = blockIdx.x;
     int bh, inner;
     if (id >= n_dq) {
-        if constexpr (!DROP) {      // (with dropout the launch holds the dQ workgroups only)
-            if (!xcd_item(id - n_dq, bhs, n_key_tiles, bh, inner)) return;
-            bwd_dkv_body<D>(smem, s, q, k, v, dO, Ls, Dn, dk_part, dv_part, bh, inner);
-        }
+        if (!xcd_item(id - n_dq, bhs, n_key_tiles, bh, inner)) return;
+        bwd_dkv_body<D, DROP>(smem, s, dr, q, k, v, dO, Ls, Dn, row_key, dk_part, dv_part, bh, inner);
     } else {
         if (!xcd_item(id, bhs, n_q_tiles * n_splits, bh, inner)) return;
         bwd_dq_body<D, DROP>(smem, s, dr, q, k, v, out, dO, lse, dq, dq_part, n_splits, inner % n_q_tiles, n_q_tiles, bh,
@@ -687,35 +714,36 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const DropArgs &drop, con
                                     hipStream_t st)
 {
     hipError_t e;
-    if (drop.thr != 0) {    // dropout: the pipelined dQ workgroups only; the caller runs the general dK/dV kernel
-        const int n_q_tiles = (s.l_s + DqBf16Cfg<D>::BR - 1) / DqBf16Cfg<D>::BR;
-        const int n_dq = xcd_grid(s.B * s.H, n_q_tiles * n_splits);
-        TimedLaunch tl(K_DQ, st);
-        hipLaunchKernelGGL((bwd_main_bf16_kernel<D, true>), dim3((unsigned)n_dq), dim3(256), 0, st, s, drop, q, k, v, out,
-                           dO, lse, ws.Ls, ws.D, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, 0);
-        return hipGetLastError();
-    }
+    const bool with_drop = drop.thr != 0;
     {
         const int64_t items = (int64_t)s.B * s.l_s * s.H * (D / 8);
+        const dim3 grid((unsigned)((items + 255) / 256));
         TimedLaunch tl(K_ROWDOT, st);
-        hipLaunchKernelGGL((bwd_prep_bf16_kernel<D>), dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, s, out, dO,
-                           lse, ws.D, ws.Ls);
+        if (with_drop)
+            hipLaunchKernelGGL((bwd_prep_bf16_kernel<D, true>), grid, dim3(256), 0, st, s, drop, out, dO, lse, ws.D, ws.Ls, ws.row_key);
+        else
+            hipLaunchKernelGGL((bwd_prep_bf16_kernel<D, false>), grid, dim3(256), 0, st, s, drop, out, dO, lse, ws.D, ws.Ls, ws.row_key);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     {
         const int n_q_tiles = (s.l_s + DqBf16Cfg<D>::BR - 1) / DqBf16Cfg<D>::BR;
         const int n_key_tiles = (s.l_x + DkvBf16Cfg<D>::BKV - 1) / DkvBf16Cfg<D>::BKV;
         const int n_dq = xcd_grid(s.B * s.H, n_q_tiles * n_splits), n_dkv = xcd_grid(s.B * s.H, n_key_tiles);
+        const dim3 grid((unsigned)(n_dkv + n_dq));
         TimedLaunch tl(K_BWD_MAIN, st);
-        hipLaunchKernelGGL((bwd_main_bf16_kernel<D, false>), dim3((unsigned)(n_dkv + n_dq)), dim3(256), 0, st, s, drop, q, k, v, out, dO,
-                           lse, ws.Ls, ws.D, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);
+        if (with_drop)
+            hipLaunchKernelGGL((bwd_main_bf16_kernel<D, true>), grid, dim3(256), 0, st, s, drop, q, k, v, out, dO, lse, ws.Ls, ws.D,
+                               ws.row_key, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);
+        else
+            hipLaunchKernelGGL((bwd_main_bf16_kernel<D, false>), grid, dim3(256), 0, st, s, drop, q, k, v, out, dO, lse, ws.Ls, ws.D,
+                               ws.row_key, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-// accumulator start values, then dQ and dK/dV in one launch (with dropout: dQ only); the caller
-// runs the dQ split merge
+// accumulator start values (with dropout also the rows' generator keys), then dQ and dK/dV in one
+// launch; the caller runs the dQ split merge
 hipError_t launch_bwd_bf16_main(const SegShape &s, const DropArgs &drop, const bf16_t *q, const bf16_t *k,
                                 const bf16_t *v, const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq,
                                 float *dk_part, float *dv_part, const Workspace &ws, int n_splits, hipStream_t st)

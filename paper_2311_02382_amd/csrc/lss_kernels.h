@@ -41,6 +41,7 @@ struct Workspace {
     float *D;         // [B*H, l_s]      rowsum(dO * out)   (bf16 kernels: its negative)
     float *Ls;        // [B*H, l_s]      bf16 kernels: -lse * sqrt(d), start value of the S accumulators
     float *dq_part;   // [splits, B, l_s, H, d]
+    uint32_t *row_key; // [B*H, l_s]      dropout in the bf16 dK/dV workgroups: the generator's key of every query row
 };
 size_t workspace_bytes(int l_s, int l_x, int B, int H, int d, int elem_bytes);
 Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d, int elem_bytes);
