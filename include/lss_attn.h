@@ -161,9 +161,8 @@ int lss_segment_attn_bwd_f32(const void *q_seg, const void *k, const void *v,
  *   seed        any 64-bit value
  *   elem_bytes  2: q_seg, k, v, out, dO, dq are bf16;  4: float
  * All other arguments as in lss_segment_attn_fwd / lss_segment_attn_bwd.
- * With p_drop > 0 the bf16 forward and dQ run on dropout variants of the tuned
- * kernels; the dK/dV partials, and everything in the float case, come from the
- * library's general kernels.
+ * With p_drop > 0 the bf16 calls run dropout variants of the tuned kernels; the
+ * float case uses the library's general kernels.
  */
 int lss_segment_attn_fwd_dropout(const void *q_seg, const void *k, const void *v,
                                  int64_t seg_offset, int64_t l_s, int64_t l_x,
