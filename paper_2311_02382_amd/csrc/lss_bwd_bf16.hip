@@ -105,6 +105,13 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
         const bf16_t *kbase = k + (int64_t)b * s.l_x * ld + (int64_t)h * D;
         const bf16_t *vbase = v + (int64_t)b * s.l_x * ld + (int64_t)h * D;
 
+        // dropout: this lane's row key; the column seed; the column keys of tile t (global tile index)
+        // are computed once, by one wavefront when the tile's loads are issued, into quarter t % 4 of
+        // a small ring behind the tiles -- published by the same barrier as the tile
+        uint32_t drop_rk = 0u, drop_cs = 0u;
+        if (DROP) { drop_rk = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)(s.s0 + r)); drop_cs = drop_col_seed(dr.seed_hi); }
+        char *const ck_ring = smem + C::RING * C::SLOT;
+
         // ---- tile loads, by all four wavefronts
         uint32_t offF[Tile::NI];                        // this lane's global offsets within a full tile
         Tile::offsets(offF, ld, C::BC, wave, lane);
@@ -116,6 +123,8 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
             if (rows_ok < C::BC) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
             static_assert(C::OFF_V == Tile::BYTES, "V tile follows K tile");
             Tile::issue_pair(kbase + (int64_t)j0 * ld, vbase + (int64_t)j0 * ld, off, smem + slot * C::SLOT, wave);
+            if (DROP && wave == 0)
+                reinterpret_cast<uint32_t *>(ck_ring)[(t & 3) * C::BC + lane] = drop_col_key(drop_cs, (uint32_t)(j0 + lane));
         };
 
         // ---- per-lane LDS offsets (bytes, within a tile)
@@ -138,15 +147,15 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
         };
         // B for elements [e0, e1): P = 2^(c * S - lse * log2 e), dS = P * (dP - D); finished pairs are
         // rounded to bf16 into the operand fragments of C
-        uint32_t drop_rk = 0u, drop_cs = 0u;            // dropout: this lane's row key; the column seed
-        if (DROP) { drop_rk = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)(s.s0 + r)); drop_cs = drop_col_seed(dr.seed_hi); }
+        u32x4 ck4;      // dropout: the column keys of four consecutive elements, read when the first is due
         auto b_elems = [&](f32x16 &sc, f32x16 &dp, int jb, int e0, int e1, Frag<bf16_t> (&df)[2]) __attribute__((always_inline)) {
 #pragma unroll
             for (int e = e0; e < e1; ++e) {
                 const float p = fast_exp2(sc[e] * c - L2);
                 if (DROP) {     // dp holds dP - D; element e of this lane is key jb + 8 (e / 4) + 4 hh + e % 4
-                    const uint32_t key = (uint32_t)(jb + 8 * (e >> 2) + 4 * hh + (e & 3));
-                    dp[e] = drop_keep(drop_rk, drop_col_key(drop_cs, key), dr.thr) ? (dp[e] + Dr) * dr.scale - Dr : -Dr;
+                    if ((e & 3) == 0)
+                        ck4 = *reinterpret_cast<const u32x4 *>(ck_ring + (((jb >> 6) & 3) * C::BC + (jb & 63) + 8 * (e >> 2) + 4 * hh) * 4);
+                    dp[e] = drop_keep(drop_rk, ck4[e & 3], dr.thr) ? (dp[e] + Dr) * dr.scale - Dr : -Dr;
                 }
                 dp[e] = p * dp[e];
                 if (e & 1) { df[e >> 3].v[(e & 7) - 1] = (bf16_t)dp[e - 1]; df[e >> 3].v[e & 7] = (bf16_t)dp[e]; }
@@ -690,9 +699,9 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     int n_key_tiles)
 {
     using DkvC = DkvBf16Cfg<D, DROP>;
-    constexpr int SMEM = DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT > DkvC::RING * DkvC::SLOT
-                             ? DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT
-                             : DkvC::RING * DkvC::SLOT;
+    // (dropout: the dQ workgroups keep a ring of column keys, 4 x 64, behind their tiles)
+    constexpr int SMEM_DQ = DqBf16Cfg<D>::RING * DqBf16Cfg<D>::SLOT + (DROP ? 4 * DqBf16Cfg<D>::BC * 4 : 0);
+    constexpr int SMEM = SMEM_DQ > DkvC::RING * DkvC::SLOT ? SMEM_DQ : DkvC::RING * DkvC::SLOT;
     __shared__ __attribute__((aligned(1024))) char smem[SMEM];
     const int bhs = s.B * s.H;
     const int id = blockIdx.x;

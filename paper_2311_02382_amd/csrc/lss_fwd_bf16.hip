@@ -51,7 +51,8 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
     using C = FwdBf16Cfg<D>;
     using Tile = typename C::Tile;
     constexpr int NU = C::NU;
-    __shared__ __attribute__((aligned(1024))) char smem[C::RING * C::SLOT];
+    // (dropout: behind the ring, the column keys of the last four tiles issued, 64 each)
+    __shared__ __attribute__((aligned(1024))) char smem[C::RING * C::SLOT + (DROP ? 4 * C::BC * 4 : 0)];
 
     const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -96,6 +97,13 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
         const bf16_t *kbase = k + (int64_t)b * s.l_x * ld + (int64_t)h * D;
         const bf16_t *vbase = v + (int64_t)b * s.l_x * ld + (int64_t)h * D;
 
+        // dropout: this lane's row key; the column seed; the column keys of tile t (global tile index)
+        // are computed once, by one wavefront when the tile's loads are issued, into quarter t % 4 of
+        // a small ring behind the tiles -- published by the same barrier as the tile
+        uint32_t drop_rk = 0u, drop_cs = 0u;
+        if (DROP) { drop_rk = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)(s.s0 + r)); drop_cs = drop_col_seed(dr.seed_hi); }
+        char *const ck_ring = smem + C::RING * C::SLOT;
+
         // ---- tile loads, by all four wavefronts
         uint32_t offF[Tile::NI];                        // this lane's global offsets within a full tile
         Tile::offsets(offF, ld, C::BC, wave, lane);
@@ -107,6 +115,8 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
             if (rows_ok < C::BC) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
             static_assert(C::OFF_V == Tile::BYTES, "V tile follows K tile");
             Tile::issue_pair(kbase + (int64_t)j0 * ld, vbase + (int64_t)j0 * ld, off, smem + slot * C::SLOT, wave);
+            if (DROP && wave == 0)
+                reinterpret_cast<uint32_t *>(ck_ring)[(t & 3) * C::BC + lane] = drop_col_key(drop_cs, (uint32_t)(j0 + lane));
         };
 
         // ---- per-lane LDS offsets (bytes, within a tile)
@@ -143,8 +153,7 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
         // and rounded to bf16 into the operand fragment of C.
         // A row that has seen no key yet (m = -inf) subtracts a huge negative number instead, so that
         // any real score gives weight +inf and forces the fix-up, while masked scores still give 0.
-        uint32_t drop_rk = 0u, drop_cs = 0u;            // dropout: this lane's row key; the column seed
-        if (DROP) { drop_rk = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)(s.s0 + r)); drop_cs = drop_col_seed(dr.seed_hi); }
+        u32x4 ck4;      // dropout: the column keys of four consecutive elements, read when the first is due
         auto b_elems = [&](const f32x16 &sc, float m_sub, int jb, int e0, int e1, float &psum, Frag<bf16_t> (&pf)[2])
             __attribute__((always_inline)) {
 #pragma unroll
@@ -153,9 +162,10 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
                 psum += p0;
                 psum += p1;
                 if (DROP) {     // element e of this lane is key jb + 8 (e / 4) + 4 hh + e % 4
-                    const uint32_t key = (uint32_t)(jb + 8 * (e >> 2) + 4 * hh + (e & 3));
-                    pf[e >> 3].v[e & 7] = (bf16_t)(drop_keep(drop_rk, drop_col_key(drop_cs, key), dr.thr) ? p0 * dr.scale : 0.f);
-                    pf[e >> 3].v[(e & 7) + 1] = (bf16_t)(drop_keep(drop_rk, drop_col_key(drop_cs, key + 1), dr.thr) ? p1 * dr.scale : 0.f);
+                    if ((e & 3) == 0)
+                        ck4 = *reinterpret_cast<const u32x4 *>(ck_ring + (((jb >> 6) & 3) * C::BC + (jb & 63) + 8 * (e >> 2) + 4 * hh) * 4);
+                    pf[e >> 3].v[e & 7] = (bf16_t)(drop_keep(drop_rk, ck4[e & 3], dr.thr) ? p0 * dr.scale : 0.f);
+                    pf[e >> 3].v[(e & 7) + 1] = (bf16_t)(drop_keep(drop_rk, ck4[(e & 3) + 1], dr.thr) ? p1 * dr.scale : 0.f);
                 } else {
                     pf[e >> 3].v[e & 7] = (bf16_t)p0; pf[e >> 3].v[(e & 7) + 1] = (bf16_t)p1;
                 }
