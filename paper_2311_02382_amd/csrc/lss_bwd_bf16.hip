@@ -313,6 +313,34 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
 }
 
 // ------------------------------------------------------------------------------------------ dK, dV
+// A wavefront's finished [32 keys][D] tile (accumulator layout: lane = key lq, element e of block db =
+// column 32 db + 8 (e / 4) + 4 hh + e % 4) goes to memory through a wavefront-private LDS buffer of
+// 32 * D * 4 bytes, so that every store instruction writes whole rows (1 KB contiguous per four or
+// two keys) instead of 32-byte pieces of 32 rows.  16-byte chunk c of key row r sits at chunk
+// position c ^ (r % chunks per row).  `rows_ok` keys of the block exist.
+template <int D>
+__device__ __forceinline__ void store_key_rows(char *buf, const f32x16 (&acc)[D / 32], float scale, float *__restrict__ dst,
+                                               int64_t ld, int rows_ok, int lane)
+{
+    constexpr int CH = D / 4;                           // 16-byte chunks per row
+    const int lq = lane & 31, hh = lane >> 5;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            const int c = db * 8 + 2 * e4 + hh;
+            *reinterpret_cast<f32x4 *>(buf + lq * (D * 4) + ((c ^ (lq & (CH - 1))) * 16)) =
+                f32x4{acc[db][4 * e4] * scale, acc[db][4 * e4 + 1] * scale, acc[db][4 * e4 + 2] * scale, acc[db][4 * e4 + 3] * scale};
+        }
+    constexpr int RPI = 64 / CH;                        // rows per store instruction
+#pragma unroll
+    for (int i = 0; i < 32 / RPI; ++i) {
+        const int row = i * RPI + lane / CH, c = lane % CH;
+        const f32x4 val = *reinterpret_cast<const f32x4 *>(buf + row * (D * 4) + ((c ^ (row & (CH - 1))) * 16));
+        if (row < rows_ok) *reinterpret_cast<f32x4 *>(dst + (int64_t)row * ld + c * 4) = val;
+    }
+}
+
 template <int D, bool DROP = false>
 struct DkvBf16Cfg {
     // One 32-row key block per wavefront.  Two blocks would halve the LDS traffic per flop but
@@ -388,7 +416,6 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
     // this lane's key (column of the S tile); keys past the sequence re-read its last row
     // (unconditional loads), take part in all the arithmetic and are never stored
     const int j = jw0 + lq;
-    const bool key_ok = j < s.l_x;
     Frag<bf16_t> kf[NU], vf[NU];
     {
         const int64_t off = kv_base + (int64_t)min(j, s.l_x - 1) * ld + hh * 8;
@@ -632,20 +659,170 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
              df1, smem, 0, t_last, 1, nothing);
     }
 
-    if (key_ok) {
-        const float scale = 1.f / sqrt_d;
-        const int64_t off = kv_base + (int64_t)j * ld;
+    // the ring is free once every wavefront has made its last reads
+    __syncthreads();
+    {
+        char *buf = smem + wave * (32 * D * 4);
+        const int64_t off = kv_base + (int64_t)jw0 * ld;
+        const int rows_ok = min(s.l_x - jw0, C::KW);
+        store_key_rows<D>(buf, dk, 1.f / sqrt_d, dk_part + off, ld, rows_ok, lane);
+        store_key_rows<D>(buf, dv, 1.f, dv_part + off, ld, rows_ok, lane);
+    }
+}
+
+// dK/dV for a segment of at most 64 query rows (the segment length the paper's largest runs leave
+// one GPU): every key tile then meets ONE Q/dO tile, and the pipeline above would spend most of its
+// steps on its start and its end.  Here a workgroup loads that tile once and walks KT_PER_WG key tiles
+// with it, one 32-key block per wavefront as above: both 32-row blocks' S and dP, then their weights,
+// then dV^T and dK^T, in program order; the next key tile's K and V rows are requested from memory
+// before the current one is computed.  After the first barrier the wavefronts never meet again.
+constexpr int kSkinnyRows = 64, kSkinnyTilesPerWg = 4;
+template <int D>
+__device__ __forceinline__ void bwd_dkv_skinny_body(char *smem, const SegShape &s, const bf16_t *__restrict__ q,
+                                                    const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+                                                    const bf16_t *__restrict__ dO, const float *__restrict__ Ls,
+                                                    const float *__restrict__ Dn, float *__restrict__ dk_part,
+                                                    float *__restrict__ dv_part, int bh, int tile_group)
+{
+    using C = DkvBf16Cfg<D>;
+    using Tile = typename C::Tile;
+    constexpr int NU = C::NU;
+    static_assert(C::BQ == kSkinnyRows, "one Q/dO tile holds the whole segment");
+
+    const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b = bh / s.H, h = bh % s.H;
+    const int64_t ld = (int64_t)s.H * D;
+    const int64_t kv_base = (int64_t)b * s.l_x * ld + (int64_t)h * D;
+    const int n_key_tiles = (s.l_x + C::BKV - 1) / C::BKV;
+    const int kt0 = tile_group * kSkinnyTilesPerWg, kt1 = min(kt0 + kSkinnyTilesPerWg, n_key_tiles);
+    // key tiles from kt_vis on are seen by no query of the segment
+    const int kt_vis = s.causal ? (int)min<int64_t>((s.s0 + s.l_s + C::BKV - 1) / C::BKV, n_key_tiles) : n_key_tiles;
+
+    // ---- the segment's Q/dO tile and start values (slot 0), by all four wavefronts
+    if (kt0 < kt_vis) {
+        uint32_t off[Tile::NI];
+        Tile::offsets(off, ld, s.l_s, wave, lane);
+        const bf16_t *qbase = q + (int64_t)b * s.l_s * ld + (int64_t)h * D;
+        const bf16_t *gbase = dO + (int64_t)b * s.l_s * ld + (int64_t)h * D;
+        Tile::issue_pair(qbase, gbase, off, smem, wave);
+        if (wave < 2) {
+            const float *src = (wave == 0 ? Ls : Dn) + (int64_t)bh * s.l_s;
+            lds_dma<4>(src, (uint32_t)min(lane, s.l_s - 1) * 4u, smem + (wave == 0 ? C::OFF_L : C::OFF_D));
+        }
+    }
+    auto load_kv = [&](int kt, Frag<bf16_t> (&kf)[NU], Frag<bf16_t> (&vf)[NU]) __attribute__((always_inline)) {
+        const int jj = kt * C::BKV + wave * C::KW + lq;
+        const int64_t off = kv_base + (int64_t)min(jj, s.l_x - 1) * ld + hh * 8;
+#pragma unroll
+        for (int kb = 0; kb < NU; ++kb) {
+            kf[kb] = load_frag<bf16_t>(k + off + kb * 16);
+            vf[kb] = load_frag<bf16_t>(v + off + kb * 16);
+        }
+    };
+    Frag<bf16_t> kf[NU], vf[NU], kf_n[NU], vf_n[NU];
+    if (kt0 < kt_vis) load_kv(kt0, kf, vf);
+    wait_vmem_all();
+    __syncthreads();
+
+    int a_off[NU], t_off[D / 32];
+#pragma unroll
+    for (int kb = 0; kb < NU; ++kb) a_off[kb] = Tile::chunk_offset(lq, 2 * kb + hh);
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) t_off[db] = tr_lane_offset_sw<D>(lane, db);
+    const float sqrt_d = sqrtf((float)D);
+    const float c = kLog2e / sqrt_d, scale = 1.f / sqrt_d;
+    const int n_blocks = s.l_s > 32 ? 2 : 1;            // 32-row blocks that hold rows of the segment
+
+    for (int kt = kt0; kt < kt1; ++kt) {
+        const int j0 = kt * C::BKV;
+        if (kt >= kt_vis) {
+            // no query of the segment sees this tile: its partial rows are zero, or stay unwritten
+            if (s.skip_tail) return;
+            constexpr int F4 = D / 4;
+            const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+            for (int i = tid; i < C::BKV * F4; i += C::NT) {
+                const int row = j0 + i / F4, c4 = (i % F4) * 4;
+                if (row < s.l_x) {
+                    *reinterpret_cast<f32x4 *>(dk_part + kv_base + (int64_t)row * ld + c4) = z;
+                    *reinterpret_cast<f32x4 *>(dv_part + kv_base + (int64_t)row * ld + c4) = z;
+                }
+            }
+            continue;
+        }
+        const bool more = kt + 1 < kt1 && kt + 1 < kt_vis;
+        if (more) load_kv(kt + 1, kf_n, vf_n);          // in flight while this tile is computed
+
+        const int jw0 = j0 + wave * C::KW, j = jw0 + lq;
+        f32x16 dk[D / 32], dv[D / 32];
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                f32x4 a, bq;
+            for (int e = 0; e < 16; ++e) { dk[db][e] = 0.f; dv[db][e] = 0.f; }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { a[i] = dk[db][4 * e4 + i] * scale; bq[i] = dv[db][4 * e4 + i]; }
-                const int col = db * 32 + 8 * e4 + 4 * hh;
-                *reinterpret_cast<f32x4 *>(dk_part + off + col) = a;
-                *reinterpret_cast<f32x4 *>(dv_part + off + col) = bq;
+        for (int qb = 0; qb < 2; ++qb) {
+            if (qb < n_blocks) {
+                const int r0 = 32 * qb;
+                // S and dP of the block, accumulators starting at -lse*sqrt(d) and -D of their rows (element
+                // e of this lane is row 8*(e/4) + 4*hh + e%4), masked elements at -inf
+                f32x16 sc, dp;
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const f32x4 l4 = *reinterpret_cast<const f32x4 *>(smem + C::OFF_L + (r0 + 8 * e4 + 4 * hh) * 4);
+                    const f32x4 d4 = *reinterpret_cast<const f32x4 *>(smem + C::OFF_D + (r0 + 8 * e4 + 4 * hh) * 4);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) { sc[4 * e4 + i] = l4[i]; dp[4 * e4 + i] = d4[i]; }
+                }
+                {
+                    const bool diag = s.causal && ((int64_t)jw0 + C::KW - 1 > s.s0 + r0);
+                    if (diag || r0 + 32 > s.l_s) {
+                        const int first = diag ? (int)max<int64_t>(min<int64_t>((int64_t)j - s.s0 - r0 - 4 * hh, 64), 0) : 0;
+                        const int end = min(s.l_s - r0, 32) - 4 * hh;
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const int rr = 8 * (e >> 2) + (e & 3);
+                            if (rr < first || rr >= end) sc[e] = -INFINITY;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int kb = 0; kb < NU; ++kb) {
+                    const char *p = smem + r0 * (D * 2) + a_off[kb];
+                    const Frag<bf16_t> fq = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(p));
+                    const Frag<bf16_t> fg = load_frag<bf16_t>(reinterpret_cast<const bf16_t *>(p + C::OFF_G));
+                    sc = mma(fq, kf[kb], sc);
+                    dp = mma(fg, vf[kb], dp);
+                }
+                // weights: P = 2^(c * (S - lse*sqrt(d))), dS = P * (dP - D), rounded to bf16 operands
+                Frag<bf16_t> pf[2], df[2];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float pw = fast_exp2(sc[e] * c);
+                    pf[e >> 3].v[e & 7] = (bf16_t)pw;
+                    df[e >> 3].v[e & 7] = (bf16_t)(pw * dp[e]);
+                }
+                // dV^T += dO^T P, dK^T += Q^T dS
+#pragma unroll
+                for (int u = 0; u < NU; ++u) {
+                    const int half = u / (D / 32), db = u % (D / 32);
+                    const Frag<bf16_t> fq = load_frag_tr_sw<D>(smem, (qb * 2 + half) * 16, t_off[db]);
+                    const Frag<bf16_t> fg = load_frag_tr_sw<D>(smem + C::OFF_G, (qb * 2 + half) * 16, t_off[db]);
+                    dv[db] = mma(fg, pf[half], dv[db]);
+                    dk[db] = mma(fq, df[half], dk[db]);
+                }
             }
+        }
+        {   // (slots 1 and 2 of the ring are never used here: a staging buffer per wavefront)
+            char *buf = smem + C::SLOT + wave * (32 * D * 4);
+            const int64_t off = kv_base + (int64_t)jw0 * ld;
+            const int rows_ok = min(s.l_x - jw0, C::KW);
+            store_key_rows<D>(buf, dk, scale, dk_part + off, ld, rows_ok, lane);
+            store_key_rows<D>(buf, dv, 1.f, dv_part + off, ld, rows_ok, lane);
+        }
+        if (more) {
+#pragma unroll
+            for (int kb = 0; kb < NU; ++kb) { kf[kb] = kf_n[kb]; vf[kb] = vf_n[kb]; }
+        }
     }
 }
 
@@ -690,7 +867,9 @@ __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(SegShape s, DropArgs
 // out in XCD order (xcd_item): an XCD works on one head at a time, whose workgroups share that
 // head's K, V, Q and dO in its L2; within a head the longest workgroups come first (last query
 // tiles; first key tiles, the zero-fill ones last).
-template <int D, bool DROP>
+// SKINNY: segments of at most 64 rows, whose dK/dV workgroups take kSkinnyTilesPerWg key tiles each
+// (n_key_tiles then counts those groups).
+template <int D, bool DROP, bool SKINNY = false>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     SegShape s, DropArgs dr, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO, const float *__restrict__ lse,
@@ -708,7 +887,8 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     int bh, inner;
     if (id >= n_dq) {
         if (!xcd_item(id - n_dq, bhs, n_key_tiles, bh, inner)) return;
-        bwd_dkv_body<D, DROP>(smem, s, dr, q, k, v, dO, Ls, Dn, row_key, dk_part, dv_part, bh, inner);
+        if constexpr (SKINNY) bwd_dkv_skinny_body<D>(smem, s, q, k, v, dO, Ls, Dn, dk_part, dv_part, bh, inner);
+        else bwd_dkv_body<D, DROP>(smem, s, dr, q, k, v, dO, Ls, Dn, row_key, dk_part, dv_part, bh, inner);
     } else {
         if (!xcd_item(id, bhs, n_q_tiles * n_splits, bh, inner)) return;
         bwd_dq_body<D, DROP>(smem, s, dr, q, k, v, out, dO, lse, dq, dq_part, n_splits, inner % n_q_tiles, n_q_tiles, bh,
@@ -736,11 +916,16 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const DropArgs &drop, con
     }
     {
         const int n_q_tiles = (s.l_s + DqBf16Cfg<D>::BR - 1) / DqBf16Cfg<D>::BR;
-        const int n_key_tiles = (s.l_x + DkvBf16Cfg<D>::BKV - 1) / DkvBf16Cfg<D>::BKV;
+        const bool skinny = !with_drop && s.l_s <= kSkinnyRows;
+        int n_key_tiles = (s.l_x + DkvBf16Cfg<D>::BKV - 1) / DkvBf16Cfg<D>::BKV;
+        if (skinny) n_key_tiles = (n_key_tiles + kSkinnyTilesPerWg - 1) / kSkinnyTilesPerWg;      // groups of key tiles
         const int n_dq = xcd_grid(s.B * s.H, n_q_tiles * n_splits), n_dkv = xcd_grid(s.B * s.H, n_key_tiles);
         const dim3 grid((unsigned)(n_dkv + n_dq));
         TimedLaunch tl(K_BWD_MAIN, st);
-        if (with_drop)
+        if (skinny)
+            hipLaunchKernelGGL((bwd_main_bf16_kernel<D, false, true>), grid, dim3(256), 0, st, s, drop, q, k, v, out, dO, lse, ws.Ls,
+                               ws.D, ws.row_key, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);
+        else if (with_drop)
             hipLaunchKernelGGL((bwd_main_bf16_kernel<D, true>), grid, dim3(256), 0, st, s, drop, q, k, v, out, dO, lse, ws.Ls, ws.D,
                                ws.row_key, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);
         else
