@@ -245,6 +245,20 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
         wait_vmem_all();
         __syncthreads();
 
+        if (rw0 >= s.l_s) {
+            // None of this wavefront's rows exists (a partly filled last query tile; half the workgroup for
+            // a segment of at most 64 rows): it only keeps moving tiles and meeting the loop's barriers.
+            int cur = 0;
+            for (int t = 0; t < T; ++t) {
+                const int prv = cur == 0 ? C::RING - 1 : cur - 1;
+                wait_vmem_all();
+                __syncthreads();
+                if (t + 2 < T) issue_tile(t_begin + t + 2, prv);
+                cur = cur == C::RING - 1 ? 0 : cur + 1;
+            }
+            return;
+        }
+
         f32x16 sc0, dp0, sc1, dp1;                      // even / odd blocks
         Frag<bf16_t> df0[2], df1[2];
         // step -1: A(0) alone.  The first loop step has no C(-1): it multiplies zeros with tile 0 instead.

@@ -260,6 +260,20 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
         wait_vmem_all();
         __syncthreads();
 
+        if (rw0 >= s.l_s) {
+            // None of this wavefront's rows exists (a partly filled last query tile): it only keeps moving
+            // tiles and meeting the loop's barriers.
+            int cur = 0;
+            for (int t = 0; t < T; ++t) {
+                const int prv = cur == 0 ? C::RING - 1 : cur - 1;
+                wait_vmem_all();
+                __syncthreads();
+                if (t + 2 < T) issue_tile(t_begin + t + 2, prv);
+                cur = cur == C::RING - 1 ? 0 : cur + 1;
+            }
+            return;
+        }
+
         f32x16 sc0, sc1;                                // even / odd blocks
         Frag<bf16_t> pf0[2], pf1[2];
         // step -1: A(0) alone.  The first loop step has no C(-1): it multiplies zeros with tile 0 instead.
