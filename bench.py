@@ -525,6 +525,7 @@ def main() -> int:
         what = "all batches and heads" if slices is None else f"(batch, head) slices {slices}"
         cpu_baseline = {"value": round(flops_cpu / t_cpu / 1e12, 6), "unit": "TFLOP/s",
                         "cores": oracle.threads(), "kind": "oracle",
+                        "whole_step_extrapolated_s": round((flops_strict + flops_proj) / (flops_cpu / t_cpu), 1),
                         "sample": f"segments {sample} of {w.N} (fwd+bwd, {what}), "
                                   f"{t_cpu:.1f} s of fp64 CPU work, same strict flop count"}
 

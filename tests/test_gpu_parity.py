@@ -325,3 +325,17 @@ def test_random_skinny_shapes_sweep():
         Q, K, V, DO = stage_all(B, l_x, H, d, 6000 + case, "bf16")
         run_segment(Q, K, V, DO, s0, l_s, causal, "bf16", tag=f"case {case}: {(B, l_x, H, d, s0, l_s, causal)}",
                     floor=1e-2)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("l_s", [1, 5, 31, 32, 33, 58, 61, 64])
+def test_segments_of_at_most_64_rows(l_s, d):
+    # the segment lengths of the paper's runs (5 to 61 rows per GPU, Section 5): these take the dK/dV
+    # workgroups that walk four key tiles with one Q/dO tile.  1,300 keys = 10 key tiles and 20 keys, so the
+    # last group of four is partly filled; offsets put the diagonal at the start, inside and at the end
+    # of a group, with groups and tiles that no query sees behind it.
+    B, l_x, H = 2, 1300, 2
+    Q, K, V, DO = stage_all(B, l_x, H, d, 7000 + l_s, "bf16")
+    for s0 in (0, 517, l_x - l_s):
+        run_segment(Q, K, V, DO, s0, l_s, True, "bf16", tag=f"l_s={l_s} s0={s0} causal", floor=1e-2)
+    run_segment(Q, K, V, DO, 700, l_s, False, "bf16", tag=f"l_s={l_s} non-causal")
