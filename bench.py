@@ -249,6 +249,9 @@ def main() -> int:
                          "layer normalisation, feed-forward unit), forward and backward, for every segment")
     ap.add_argument("--fused-gelu", action="store_true",
                     help="with --layer-ops: use the GEMM entry points that apply GeLU and its derivative in their epilogues")
+    ap.add_argument("--segments", default=None, metavar="I,J,...",
+                    help="run only these segments of the workload (for workloads whose N segments' partials do not "
+                         "fit in memory at once, e.g. lx50k_skinny); the segment sum then adds these segments' partials")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device-to-device copy of this many MiB "
@@ -305,7 +308,14 @@ def main() -> int:
 
     (qd, qb), (kd, kb), (vd, vb), (dod, dob) = map(stage, (q, k, v, do))
     del q, k, v, do
-    offs, l_s = w.offsets(), w.l_s
+    seg_ids = list(range(w.N)) if args.segments is None else sorted({int(t_) for t_ in args.segments.split(",")})
+    if not seg_ids or seg_ids[0] < 0 or seg_ids[-1] >= w.N:
+        print(f"bench.py: --segments must name segments in [0, {w.N})", file=sys.stderr)
+        return 2
+    if args.segments is not None and args.projections:
+        print("bench.py: --segments cannot be combined with --projections", file=sys.stderr)
+        return 2
+    offs, l_s = [w.offsets()[i_] for i_ in seg_ids], w.l_s
     E = w.H * w.d
     q_seg = [qd[:, s0:s0 + l_s].contiguous() for s0 in offs]
     do_seg = [dod[:, s0:s0 + l_s].contiguous() for s0 in offs]
@@ -423,7 +433,8 @@ def main() -> int:
     step_stats = {"median_ms": round(per_step[len(per_step) // 2], 4), "min_ms": round(per_step[0], 4),
                   "max_ms": round(per_step[-1], 4), "note": "GPU time between step boundaries inside the timed region"}
 
-    pairs = w.pairs()                       # unmasked (query, key) pairs x B x H, whole sequence
+    # unmasked (query, key) pairs x B x H: the whole sequence, or the listed segments
+    pairs = w.pairs() if args.segments is None else sum(w.segment_pairs(i_) for i_ in seg_ids)
     flops_strict = 12.0 * pairs * w.d
     flops_fa = 14.0 * pairs * w.d
     # projections: 2 flops per multiply-add of Q_i, K, V and of dx_q, dx_partial (rows that hold data)
@@ -449,6 +460,22 @@ def main() -> int:
                         "avg_launch_us": round(mfma[dom]["avg_us"], 2),
                         "algorithmic_flops_per_launch": per_launch,
                         "executed_over_algorithmic": EXEC_PRODUCTS[dom] / ALGO_PRODUCTS[dom]}
+            # Algorithmic bytes of that kernel per launch (averaged over the segments run): every operand read
+            # once, every result written once.  Below the machine's balance point the launch is bound by
+            # memory, and the roofline is reported against the HBM peak instead.
+            eb, bh = (4 if f32 else 2), w.B * w.H
+            def alg_bytes(kv):
+                if dom == "fwd_kernel":
+                    return bh * (eb * w.d * (2 * l_s + 2 * kv) + 4 * l_s)
+                return bh * (eb * w.d * (4 * l_s + 2 * kv) + 8 * l_s + 8 * w.d * kv)    # backward: also the fp32 partials
+            if dom in ("fwd_kernel", "bwd_main_kernel"):
+                byts = sum(alg_bytes(rv) for rv in rows_valid) / len(rows_valid)
+                roofline["algorithmic_bytes_per_launch"] = byts
+                roofline["flop_per_byte"] = round(per_launch / byts, 1)
+                if per_launch / byts < peak * 1e12 / (PEAK_HBM_GBS * 1e9):
+                    gbs = byts / (mfma[dom]["avg_us"] * 1e-6) / 1e9
+                    roofline.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                     "frac": round(gbs / PEAK_HBM_GBS, 4), "achieved_tflops": round(achieved, 2)})
         for name, kk in kernels.items():
             if name in ALGO_PRODUCTS:
                 kk["algorithmic_tflops"] = round(ALGO_PRODUCTS[name] * 2.0 * w.d * pairs / (kk["ms_per_step"] * 1e-3) / 1e12, 2)
@@ -483,11 +510,11 @@ def main() -> int:
         # complete, smaller problem of the same shape.  (With projections the slices cannot be cut
         # out of x, so the sample is then whole segments.)
         budget = 1.0e12
-        seg_flops = [12.0 * w.segment_pairs(i) * w.d for i in range(w.N)]
-        if sum(seg_flops) <= budget:
-            sample, slices = list(range(w.N)), None
+        seg_flops = {i: 12.0 * w.segment_pairs(i) * w.d for i in seg_ids}
+        if sum(seg_flops.values()) <= budget:
+            sample, slices = list(seg_ids), None
         else:
-            sample = sorted({w.N // 2 - 1, w.N - 1})
+            sample = sorted({seg_ids[max(len(seg_ids) // 2 - 1, 0)], seg_ids[-1]})
             slices = None if args.projections or sum(seg_flops[i] for i in sample) <= budget else \
                 sorted({(0, 0), (w.B - 1, w.H - 1)})
         kh, vh = kb.f64(), vb.f64()
@@ -503,7 +530,7 @@ def main() -> int:
             return oracle.segment_bwd_dropout(qh, kh_, vh_, doh, s0, w.causal, args.dropout, w.seed)
 
         for i in sample:
-            s0 = offs[i]
+            s0 = w.offsets()[i]
             qh, doh = qb[:, s0:s0 + l_s].f64(), dob[:, s0:s0 + l_s].f64()
             if slices is None:
                 t = time.perf_counter()
@@ -512,7 +539,7 @@ def main() -> int:
                 g_ = oracle_segment(qh, kh, vh, doh, s0)
                 if args.projections:
                     oracle.project_bwd(g_[0], g_[1], g_[2], wqh, wkvh)
-                    flops_cpu += 2.0 * w.B * E * (2 * E * w.l_x + E * l_s) + 2.0 * w.B * E * (2 * E * rows_valid[i] + E * l_s)
+                    flops_cpu += 2.0 * w.B * E * (2 * E * w.l_x + E * l_s) + 2.0 * w.B * E * (2 * E * rows_valid[seg_ids.index(i)] + E * l_s)
                 t_cpu += time.perf_counter() - t
                 flops_cpu += seg_flops[i]
             else:
@@ -537,10 +564,13 @@ def main() -> int:
         "config": {"workload": w.name + ("+projections" if args.projections else "")
                                + ("+weight-grads" if args.projections and args.weight_grads else "")
                                + (f"+dropout{args.dropout}" if args.dropout is not None else "")
-                               + ("+f32" if f32 else ""), "B": w.B, "l_x": w.l_x,
+                               + ("+f32" if f32 else "")
+                               + (f"+segments{seg_ids}" if args.segments is not None else ""), "B": w.B, "l_x": w.l_x,
                    "N": w.N, "l_s": l_s, "H": w.H, "d": w.d, "causal": w.causal,
                    "step": ("per segment: Q_i, K, V from x, fwd, bwd, dx_q and dx_partial; then segment sum of dx"
-                            if args.projections else "fwd+bwd of all N segments, then segment sum of dK and dV")},
+                            if args.projections else
+                            "fwd+bwd of the listed segments, then the sum of their dK and dV partials" if args.segments is not None
+                            else "fwd+bwd of all N segments, then segment sum of dK and dV")},
         ("frac_of_f32_peak" if f32 else "frac_of_bf16_peak"): round(value / peak, 4),
         "tflops_with_recompute_count_14Pd": round(flops_fa / (ms_per_step * 1e-3) / 1e12, 2),
         "gpu_ms_per_step_events": round(gpu_ms / args.steps, 4), "step_stats": step_stats,
