@@ -13,11 +13,16 @@ the fused-communication form (Q_i, K, V from x before the forward; dx_q and dx_p
 the backward; Fig. 2(ii), (v)), the segment sum then runs on the dx partials, and `value`
 counts the projections' flops as well: a second workload, not the headline one.
 
+With --segments I,J,... only the listed segments run (and the sum of their partials): for workloads whose
+N partial buffers do not fit in memory at once.  --layer-ops, --dropout P and --dtype f32 are further workloads
+(see their help texts).
+
 Prints ONE JSON line.  `value` is the strict-count rate: 12*d flops per unmasked
 (query, key) pair and head (six matrix products: S, PV, dV, dP, dQ, dK), recomputation not
 counted.  The line also carries the dominant kernel's roofline figures (timed with HIP
 events on the launch stream, inside the timed region; the other kernels' averages come from
-an untimed survey pass just before it) and the fp64 oracle's rate on the host cores for a
+an untimed survey pass just before it; against the matrix peak, or against the HBM peak when
+the kernel's algorithmic flops per algorithmic byte are below the machine's balance point) and the fp64 oracle's rate on the host cores for a
 bounded sample of the same workload.
 """
 from __future__ import annotations
