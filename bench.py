@@ -6,7 +6,11 @@ segments of the sequence, forward then backward (Eq. 2 of Section 3 and its grad
 followed by the segment sum of the dK and dV partials (the arithmetic of the
 reduce-scatter of Fig. 2(v)).  Inputs are resident in HBM before the timed region.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lx8k] [--projections | --layer-ops]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload lx24k] [--projections | --layer-ops]
+
+The default workload is lx24k (B=4, l_x=24576, 6 segments of 4096 rows, 16 heads of width 64, causal): the
+largest configuration with d = 64 and l_s >= 1024.  Run without --workload, the line also carries `extra`: the
+other four configurations (tiny, lx8k, lx32k_d128, lx50k), each timed the same way over a few steps.
 
 With --projections every segment also runs the linear maps either side of the attention in
 the fused-communication form (Q_i, K, V from x before the forward; dx_q and dx_partial after
@@ -19,11 +23,15 @@ N partial buffers do not fit in memory at once.  --layer-ops, --dropout P and --
 
 Prints ONE JSON line.  `value` is the strict-count rate: 12*d flops per unmasked
 (query, key) pair and head (six matrix products: S, PV, dV, dP, dQ, dK), recomputation not
-counted.  The line also carries the dominant kernel's roofline figures (timed with HIP
-events on the launch stream, inside the timed region; the other kernels' averages come from
-an untimed survey pass just before it; against the matrix peak, or against the HBM peak when
-the kernel's algorithmic flops per algorithmic byte are below the machine's balance point) and the fp64 oracle's rate on the host cores for a
-bounded sample of the same workload.
+counted, over a timed region that holds the library's calls and nothing else.  The region is then run a
+second time with the dominant kernel bracketed by HIP events on its launch stream (`roofline`: against the
+matrix peak, or against the HBM peak when the kernel's algorithmic flops per algorithmic byte are below the
+machine's balance point); the other kernels' averages come from an untimed survey pass.  `cpu_baseline` is
+the fp64 oracle's rate on the host cores for a bounded sample of the same workload.
+
+Contract timed: the backward calls pass LSS_FLAG_SKIP_MASKED_TAIL (lss_segment_attn_bwd_ex), because the only
+reader of the partials here is the segment sum, which is told how many rows of each part hold data;
+--default-contract times lss_segment_attn_bwd as it is (every row of the partials written).
 """
 from __future__ import annotations
 
@@ -45,8 +53,13 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E peak (published)
 # fwd: S and PV.  The backward's main kernel holds two kinds of workgroup: dQ (dP and dQ; it also
 # recomputes S) and dK/dV (dV and dK; it also recomputes S and dP).  Together the six products of
 # the 12*d count.  (bwd_dq_kernel / bwd_dkv_kernel: the fp32 path, which launches them separately.)
-ALGO_PRODUCTS = {"fwd_kernel": 2, "bwd_main_kernel": 4, "bwd_dq_kernel": 2, "bwd_dkv_kernel": 2}
-EXEC_PRODUCTS = {"fwd_kernel": 2, "bwd_main_kernel": 7, "bwd_dq_kernel": 3, "bwd_dkv_kernel": 4}
+# Names are those of the __global__ functions, as a profiler prints them (bf16: the tuned kernels; fwd_kernel,
+# bwd_dq_kernel, bwd_dkv_kernel: the general kernels that serve --dtype f32, launched separately).
+ALGO_PRODUCTS = {"fwd_bf16_kernel": 2, "bwd_main_bf16_kernel": 4, "fwd_kernel": 2, "bwd_dq_kernel": 2, "bwd_dkv_kernel": 2}
+EXEC_PRODUCTS = {"fwd_bf16_kernel": 2, "bwd_main_bf16_kernel": 7, "fwd_kernel": 2, "bwd_dq_kernel": 3, "bwd_dkv_kernel": 4}
+FWD_KERNELS = ("fwd_bf16_kernel", "fwd_kernel", "fwd_merge_kernel")
+BWD_KERNELS = ("bwd_prep_bf16_kernel", "bwd_rowdot_kernel", "bwd_main_bf16_kernel", "bwd_dq_kernel", "bwd_dkv_kernel",
+               "bwd_dq_merge_kernel")
 
 
 def measured_traffic(workload: str, kernel: str):
@@ -70,7 +83,7 @@ def layer_ops(args, w) -> int:
     import numpy as np
     import torch
 
-    from paper_2311_02382_amd import lss, synth
+    from paper_2311_02382_amd import lss, synth, timing
 
     dev = torch.device("cuda:0")
     E, F, l_s, offs = w.H * w.d, 4 * w.H * w.d, w.l_s, w.offsets()
@@ -135,29 +148,26 @@ def layer_ops(args, w) -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    names, kid = {}, 0
-    while (name := lss.lss_timing_kernel_name(kid)) is not None:
-        names[kid] = name
-        kid += 1
+    names = timing.kernel_names()
 
     def read_kernels(steps):
         out_ = {}
         for kid_, name_ in names.items():
-            ms, n = lss.lss_timing_read(kid_)
+            ms, n = timing.read(kid_)
             if n:
                 out_[name_] = {"launches_per_step": n / steps, "avg_us": 1e3 * ms / n, "ms_per_step": ms / steps}
         return out_
 
-    lss.lss_timing_reset()
-    lss.lss_timing_enable(True)
+    timing.reset()
+    timing.enable(True)
     for _ in range(2):
         step()
     torch.cuda.synchronize()
-    lss.lss_timing_enable(False)
+    timing.enable(False)
     kernels = read_kernels(2)
-    dom = max(("linear_fwd_kernel", "linear_bwd_kernel"), key=lambda n_: kernels[n_]["ms_per_step"])
-    lss.lss_timing_reset()
-    lss.lss_timing_select([k_ for k_, n_ in names.items() if n_ == dom])
+    dom = max(("proj_gemm_kernel:linear_fwd", "proj_gemm_kernel:linear_bwd_input"), key=lambda n_: kernels[n_]["ms_per_step"])
+    timing.reset()
+    timing.select([k_ for k_, n_ in names.items() if n_ == dom])
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -168,7 +178,7 @@ def layer_ops(args, w) -> int:
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     gpu_ms = e0.elapsed_time(e1)
-    lss.lss_timing_enable(False)
+    timing.enable(False)
     ms_per_step = max(wall_ms, gpu_ms) / args.steps
     timed = read_kernels(args.steps)
     kernels[dom] = dict(timed[dom], timed_region=True)
@@ -188,7 +198,7 @@ def layer_ops(args, w) -> int:
         if name in bytes_per_launch:
             kk["algorithmic_GBps"] = round(bytes_per_launch[name] / (kk["avg_us"] * 1e-6) / 1e9, 1)
             kk["frac_of_hbm_peak"] = round(kk["algorithmic_GBps"] / PEAK_HBM_GBS, 4)
-        elif name.startswith("linear_"):
+        elif name.startswith("proj_gemm_kernel:linear_") or name == "wgrad_gemm_kernel":
             kk["algorithmic_tflops"] = round(lin_flops / (kk["avg_us"] * 1e-6) / 1e12, 2)
         kk["avg_us"] = round(kk["avg_us"], 2)
         kk["ms_per_step"] = round(kk["ms_per_step"], 4)
@@ -234,63 +244,17 @@ def layer_ops(args, w) -> int:
     return 0
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="lx8k")
-    ap.add_argument("--projections", action="store_true",
-                    help="also run the Q/K/V projections and their backward around every segment")
-    ap.add_argument("--weight-grads", action="store_true",
-                    help="with --projections: every segment also computes its share of dW_q and dW_kv")
-    ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16",
-                    help="storage type: bf16 (the benchmark) or f32 (the single-precision twins of the entry points)")
-    ap.add_argument("--dropout", type=float, default=None, metavar="P",
-                    help="run forward and backward with dropout probability P on the attention weights "
-                         "(a further workload: the library's general kernels serve it)")
-    ap.add_argument("--layer-ops", action="store_true",
-                    help="a separate workload: the segment-local remainder of a layer (positional-embedding rows, "
-                         "layer normalisation, feed-forward unit), forward and backward, for every segment")
-    ap.add_argument("--fused-gelu", action="store_true",
-                    help="with --layer-ops: use the GEMM entry points that apply GeLU and its derivative in their epilogues")
-    ap.add_argument("--segments", default=None, metavar="I,J,...",
-                    help="run only these segments of the workload (for workloads whose N segments' partials do not "
-                         "fit in memory at once, e.g. lx50k_skinny); the segment sum then adds these segments' partials")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--calib-copy-mib", type=int, default=0,
-                    help="before the timed region, run one plain device-to-device copy of this many MiB "
-                         "(a kernel of known traffic, to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--no-kernel-timing", action="store_true",
-                    help="leave the per-kernel HIP events out of the timed region (roofline becomes null)")
-    args = ap.parse_args()
-
-    if args.gpus != 1:
-        print(f"bench.py: this build is one GPU's share of the path; --gpus {args.gpus} is not supported "
-              "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
-        return 2
-
+def attention(args, w, steps, warmup, with_cpu_baseline):
+    """Times `steps` steps of workload `w` and returns the JSON line as a dict."""
     import numpy as np
     import torch
 
-    from paper_2311_02382_amd import lss, synth
+    from paper_2311_02382_amd import lss, synth, timing
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 3
-    lss.load()      # fails loudly if the HIP library has not been built
-    torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-
-    w = synth.WORKLOADS[args.workload]
-    if args.layer_ops:
-        return layer_ops(args, w)
     q, k, v, do = synth.workload_inputs(w)
 
     f32 = args.dtype == "f32"
-    if f32 and args.projections:
-        print("bench.py: the projections are bf16 only; --dtype f32 cannot be combined with --projections", file=sys.stderr)
-        return 2
     peak = PEAK_F32_TFLOPS if f32 else PEAK_BF16_TFLOPS
 
     class HostCopy:
@@ -315,11 +279,7 @@ def main() -> int:
     del q, k, v, do
     seg_ids = list(range(w.N)) if args.segments is None else sorted({int(t_) for t_ in args.segments.split(",")})
     if not seg_ids or seg_ids[0] < 0 or seg_ids[-1] >= w.N:
-        print(f"bench.py: --segments must name segments in [0, {w.N})", file=sys.stderr)
-        return 2
-    if args.segments is not None and args.projections:
-        print("bench.py: --segments cannot be combined with --projections", file=sys.stderr)
-        return 2
+        raise SystemExit(f"bench.py: --segments must name segments in [0, {w.N})")
     offs, l_s = [w.offsets()[i_] for i_ in seg_ids], w.l_s
     E = w.H * w.d
     q_seg = [qd[:, s0:s0 + l_s].contiguous() for s0 in offs]
@@ -347,9 +307,9 @@ def main() -> int:
         dv_part = [torch.empty(kd.shape, dtype=torch.float32, device=dev) for _ in offs]
         dK = torch.empty(kd.shape, dtype=torch.float32, device=dev)
         dV = torch.empty(kd.shape, dtype=torch.float32, device=dev)
-    # the partials' only consumer here is the segment sum, which is told how many rows of each are
-    # valid: key tiles no query of a segment sees need not be filled with zeros
-    lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, 1)
+    # The partials' only consumer here is the segment sum, which is told how many rows of each are valid: key
+    # tiles no query of a segment sees need not be filled with zeros (a flag of the call; --default-contract: off)
+    skip = not args.default_contract
 
     drop = {} if args.dropout is None else {"p_drop": args.dropout, "seed": w.seed}
 
@@ -357,7 +317,7 @@ def main() -> int:
         for i, s0 in enumerate(offs):
             lss.lss_segment_attn_fwd(q_seg[i], kd, vd, s0, w.causal, out=out[i], lse=lse[i], **drop)
             lss.lss_segment_attn_bwd(q_seg[i], kd, vd, s0, out[i], lse[i], do_seg[i], w.causal,
-                                     dq=dq[i], dk_partial=dk_part[i], dv_partial=dv_part[i], **drop)
+                                     dq=dq[i], dk_partial=dk_part[i], dv_partial=dv_part[i], skip_masked_tail=skip, **drop)
         lss.lss_reduce_partials(dk_part, rows_valid, out=dK)
         lss.lss_reduce_partials(dv_part, rows_valid, out=dV)
 
@@ -366,9 +326,9 @@ def main() -> int:
             lss.lss_project_qkv(xd, wqd, wkvd, s0, l_s, w.H, q_seg=q_seg[i], k=kd, v=vd)
             lss.lss_segment_attn_fwd(q_seg[i], kd, vd, s0, w.causal, out=out[i], lse=lse[i], **drop)
             lss.lss_segment_attn_bwd(q_seg[i], kd, vd, s0, out[i], lse[i], do_seg[i], w.causal,
-                                     dq=dq[i], dk_partial=dk_one, dv_partial=dv_one, **drop)
+                                     dq=dq[i], dk_partial=dk_one, dv_partial=dv_one, skip_masked_tail=skip, **drop)
             lss.lss_project_bwd(dq[i], dk_one, dv_one, wqd, wkvd, rows_valid[i], dx_q=dx_q[i],
-                                dx_partial=dx_part[i].view(w.B, w.l_x, E))
+                                dx_partial=dx_part[i].view(w.B, w.l_x, E), skip_masked_tail=skip)
             if args.weight_grads:
                 lss.lss_project_bwd_weight(xd, dq[i], dk_one, dv_one, s0, rows_valid[i], dw_q=dw_q, dw_kv=dw_kv,
                                            scratch=wg_scratch)
@@ -376,7 +336,7 @@ def main() -> int:
 
     step = step_with_projections if args.projections else step_attention
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     if args.calib_copy_mib > 0:
@@ -387,100 +347,102 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    timing = not args.no_kernel_timing
-    names = {}
-    kid = 0
-    while (name := lss.lss_timing_kernel_name(kid)) is not None:
-        names[kid] = name
-        kid += 1
+    use_events = not args.no_kernel_timing
+    names = timing.kernel_names()
 
-    def read_kernels(steps):
+    def read_kernels(n_steps):
         out_ = {}
         for kid_, name_ in names.items():
-            ms, n = lss.lss_timing_read(kid_)
+            ms, n = timing.read(kid_)
             if n:
-                out_[name_] = {"launches_per_step": n / steps, "avg_us": 1e3 * ms / n, "ms_per_step": ms / steps}
+                out_[name_] = {"launches_per_step": n / n_steps, "avg_us": 1e3 * ms / n, "ms_per_step": ms / n_steps}
         return out_
 
-    # survey pass (untimed): every kernel bracketed by events, to find the one with the largest
-    # share of a step and to report the others.  The timed region then brackets only that kernel,
-    # which keeps the event overhead out of `value`.
-    survey, dom = {}, None
-    if timing:
-        lss.lss_timing_reset()
-        lss.lss_timing_enable(True)
+    def timed_region():
+        """`steps` steps between two events; returns (ms per step, per-step GPU times)."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps - 1)]    # step boundaries, for median and min
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for i_ in range(steps):
+            step()
+            if i_ < steps - 1:
+                marks[i_].record()
+        e1.record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        gpu_ms = e0.elapsed_time(e1)
+        bounds = [e0] + marks + [e1]
+        return max(wall_ms, gpu_ms) / steps, gpu_ms / steps, sorted(a_.elapsed_time(b_) for a_, b_ in zip(bounds, bounds[1:]))
+
+    # 1. the timed region proper: the library's calls and nothing else
+    timing.enable(False)
+    ms_per_step, gpu_ms_per_step, per_step = timed_region()
+    step_stats = {"median_ms": round(per_step[len(per_step) // 2], 4), "min_ms": round(per_step[0], 4),
+                  "max_ms": round(per_step[-1], 4), "note": "GPU time between step boundaries inside the timed region"}
+
+    # 2. survey pass: every kernel bracketed by events, to find the one with the largest share of a step and to
+    # report the others.  3. the timed region again, with that one kernel bracketed: its average launch duration
+    # under the same back-to-back conditions, for the roofline.
+    survey, dom, ms_per_step_events = {}, None, None
+    if use_events:
+        timing.reset()
+        timing.enable(True)
         for _ in range(2):
             step()
         torch.cuda.synchronize()
-        lss.lss_timing_enable(False)
+        timing.enable(False)
         survey = read_kernels(2)
         cand = {n_: k_ for n_, k_ in survey.items() if n_ in ALGO_PRODUCTS}
         dom = max(cand, key=lambda n_: cand[n_]["ms_per_step"])
-        lss.lss_timing_reset()
-        lss.lss_timing_select([k_ for k_, n_ in names.items() if n_ == dom])
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps - 1)]    # step boundaries, for median and min
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0.record()
-    for i_ in range(args.steps):
-        step()
-        if i_ < args.steps - 1:
-            marks[i_].record()
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    gpu_ms = e0.elapsed_time(e1)
-    lss.lss_timing_enable(False)
-    ms_per_step = max(wall_ms, gpu_ms) / args.steps
-    bounds = [e0] + marks + [e1]
-    per_step = sorted(a_.elapsed_time(b_) for a_, b_ in zip(bounds, bounds[1:]))
-    step_stats = {"median_ms": round(per_step[len(per_step) // 2], 4), "min_ms": round(per_step[0], 4),
-                  "max_ms": round(per_step[-1], 4), "note": "GPU time between step boundaries inside the timed region"}
+        timing.reset()
+        timing.select([k_ for k_, n_ in names.items() if n_ == dom])
+        ms_per_step_events, _, _ = timed_region()
+        timing.enable(False)
 
     # unmasked (query, key) pairs x B x H: the whole sequence, or the listed segments
     pairs = w.pairs() if args.segments is None else sum(w.segment_pairs(i_) for i_ in seg_ids)
     flops_strict = 12.0 * pairs * w.d
     flops_fa = 14.0 * pairs * w.d
     # projections: 2 flops per multiply-add of Q_i, K, V and of dx_q, dx_partial (rows that hold data)
-    proj_flops = {"proj_fwd_kernel": sum(2.0 * w.B * E * (2 * E * w.l_x + E * l_s) for _ in offs),
-                  "proj_bwd_kernel": sum(2.0 * w.B * E * (2 * E * rv + E * l_s) for rv in rows_valid)}
+    proj_flops = {"proj_gemm_kernel:project_qkv": sum(2.0 * w.B * E * (2 * E * w.l_x + E * l_s) for _ in offs),
+                  "proj_gemm_kernel:project_bwd": sum(2.0 * w.B * E * (2 * E * rv + E * l_s) for rv in rows_valid)}
     if args.projections and args.weight_grads:      # same products as the backward maps, contracted over rows instead
-        proj_flops["linear_wgrad_kernel"] = proj_flops["proj_bwd_kernel"]
+        proj_flops["wgrad_gemm_kernel"] = proj_flops["proj_gemm_kernel:project_bwd"]
     flops_proj = sum(proj_flops.values()) if args.projections else 0.0
     value = (flops_strict + flops_proj) / (ms_per_step * 1e-3) / 1e12
 
     kernels, roofline = {}, None
-    if timing:
+    if use_events:
         kernels = survey
-        timed = read_kernels(args.steps)        # the dominant kernel, inside the timed region
+        timed = read_kernels(steps)        # the dominant kernel, inside the second timed region
         kernels[dom] = dict(timed[dom], timed_region=True)
-        mfma = {dom: timed[dom]}
-        if mfma:
-            per_launch = ALGO_PRODUCTS[dom] * 2.0 * w.d * pairs / mfma[dom]["launches_per_step"]
-            achieved = per_launch / (mfma[dom]["avg_us"] * 1e-6) / 1e12
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
-                        "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                        "traffic": measured_traffic(w.name, dom),
-                        "avg_launch_us": round(mfma[dom]["avg_us"], 2),
-                        "algorithmic_flops_per_launch": per_launch,
-                        "executed_over_algorithmic": EXEC_PRODUCTS[dom] / ALGO_PRODUCTS[dom]}
-            # Algorithmic bytes of that kernel per launch (averaged over the segments run): every operand read
-            # once, every result written once.  Below the machine's balance point the launch is bound by
-            # memory, and the roofline is reported against the HBM peak instead.
-            eb, bh = (4 if f32 else 2), w.B * w.H
-            def alg_bytes(kv):
-                if dom == "fwd_kernel":
-                    return bh * (eb * w.d * (2 * l_s + 2 * kv) + 4 * l_s)
-                return bh * (eb * w.d * (4 * l_s + 2 * kv) + 8 * l_s + 8 * w.d * kv)    # backward: also the fp32 partials
-            if dom in ("fwd_kernel", "bwd_main_kernel"):
-                byts = sum(alg_bytes(rv) for rv in rows_valid) / len(rows_valid)
-                roofline["algorithmic_bytes_per_launch"] = byts
-                roofline["flop_per_byte"] = round(per_launch / byts, 1)
-                if per_launch / byts < peak * 1e12 / (PEAK_HBM_GBS * 1e9):
-                    gbs = byts / (mfma[dom]["avg_us"] * 1e-6) / 1e9
-                    roofline.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                     "frac": round(gbs / PEAK_HBM_GBS, 4), "achieved_tflops": round(achieved, 2)})
+        per_launch = ALGO_PRODUCTS[dom] * 2.0 * w.d * pairs / timed[dom]["launches_per_step"]
+        achieved = per_launch / (timed[dom]["avg_us"] * 1e-6) / 1e12
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": peak,
+                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                    "traffic": measured_traffic(w.name, dom),
+                    "avg_launch_us": round(timed[dom]["avg_us"], 2),
+                    "algorithmic_flops_per_launch": per_launch,
+                    "executed_over_algorithmic": EXEC_PRODUCTS[dom] / ALGO_PRODUCTS[dom],
+                    "ms_per_step_with_events": round(ms_per_step_events, 4)}
+        # Algorithmic bytes of that kernel per launch (averaged over the segments run): every operand read
+        # once, every result written once.  Below the machine's balance point the launch is bound by
+        # memory, and the roofline is reported against the HBM peak instead.
+        eb, bh = (4 if f32 else 2), w.B * w.H
+        def alg_bytes(kv):
+            if dom in ("fwd_kernel", "fwd_bf16_kernel"):
+                return bh * (eb * w.d * (2 * l_s + 2 * kv) + 4 * l_s)
+            return bh * (eb * w.d * (4 * l_s + 2 * kv) + 8 * l_s + 8 * w.d * kv)    # backward: also the fp32 partials
+        if dom in ("fwd_kernel", "fwd_bf16_kernel", "bwd_main_bf16_kernel"):
+            byts = sum(alg_bytes(rv) for rv in rows_valid) / len(rows_valid)
+            roofline["algorithmic_bytes_per_launch"] = byts
+            roofline["flop_per_byte"] = round(per_launch / byts, 1)
+            if per_launch / byts < peak * 1e12 / (PEAK_HBM_GBS * 1e9):
+                gbs = byts / (timed[dom]["avg_us"] * 1e-6) / 1e9
+                roofline.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                 "frac": round(gbs / PEAK_HBM_GBS, 4), "achieved_tflops": round(achieved, 2)})
         for name, kk in kernels.items():
             if name in ALGO_PRODUCTS:
                 kk["algorithmic_tflops"] = round(ALGO_PRODUCTS[name] * 2.0 * w.d * pairs / (kk["ms_per_step"] * 1e-3) / 1e12, 2)
@@ -498,21 +460,20 @@ def main() -> int:
     # forward-only and backward-only rates from the survey pass (kernel times, launch gaps not included)
     rates = None
     if kernels:
-        t_f = sum(kernels[n_]["ms_per_step"] for n_ in ("fwd_kernel", "fwd_merge_kernel") if n_ in kernels)
-        t_b = sum(kernels[n_]["ms_per_step"] for n_ in ("bwd_rowdot_kernel", "bwd_main_kernel", "bwd_dq_kernel",
-                                                        "bwd_dkv_kernel", "bwd_dq_merge_kernel") if n_ in kernels)
+        t_f = sum(kernels[n_]["ms_per_step"] for n_ in FWD_KERNELS if n_ in kernels)
+        t_b = sum(kernels[n_]["ms_per_step"] for n_ in BWD_KERNELS if n_ in kernels)
         if t_f > 0 and t_b > 0:
             rates = {"fwd_only_tflops": round(4.0 * pairs * w.d / (t_f * 1e-3) / 1e12, 2),
                      "bwd_only_tflops": round(8.0 * pairs * w.d / (t_b * 1e-3) / 1e12, 2),
                      "note": "strict counts 4*P*d and 8*P*d over the summed kernel times of one step"}
 
     cpu_baseline = None
-    if not args.no_cpu_baseline:
+    if with_cpu_baseline:
         import oracle
         # A bounded sample of the same workload: about 1e12 fp64 flops (10-30 s on the machine's cores).  The
         # whole workload if it is that small; otherwise the middle and the last segment, and of those
-        # only the (batch, head) slices (0, 0) and (B-1, H-1) -- heads are independent, so a slice is a
-        # complete, smaller problem of the same shape.  (With projections the slices cannot be cut
+        # only some (batch, head) slices, (0, 0) and (B-1, H-1) among them -- heads are independent, so a
+        # slice is a complete, smaller problem of the same shape.  (With projections the slices cannot be cut
         # out of x, so the sample is then whole segments.)
         budget = 1.0e12
         seg_flops = {i: 12.0 * w.segment_pairs(i) * w.d for i in seg_ids}
@@ -520,8 +481,13 @@ def main() -> int:
             sample, slices = list(seg_ids), None
         else:
             sample = sorted({seg_ids[max(len(seg_ids) // 2 - 1, 0)], seg_ids[-1]})
-            slices = None if args.projections or sum(seg_flops[i] for i in sample) <= budget else \
-                sorted({(0, 0), (w.B - 1, w.H - 1)})
+            slices = None
+            if not args.projections and sum(seg_flops[i] for i in sample) > budget:
+                # (0, 0), (B-1, H-1) and as many evenly spaced (batch, head) pairs as the budget allows
+                bh = w.B * w.H
+                n_sl = int(min(bh, max(2, budget // (sum(seg_flops[i] for i in sample) / bh))))
+                picks = sorted({round(j_ * (bh - 1) / (n_sl - 1)) for j_ in range(n_sl)})
+                slices = [(x_ // w.H, x_ % w.H) for x_ in picks]
         kh, vh = kb.f64(), vb.f64()
         if args.projections:
             xh, wqh, wkvh = (b_.f64() for b_ in (xb, wqb, wkvb))
@@ -561,9 +527,9 @@ def main() -> int:
                         "sample": f"segments {sample} of {w.N} (fwd+bwd, {what}), "
                                   f"{t_cpu:.1f} s of fp64 CPU work, same strict flop count"}
 
-    line = {
+    return {
         "metric": "segment-attention fwd+bwd TFLOP/s on 1 MI355X; % of bf16 MFMA peak",
-        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": w.name + ("+projections" if args.projections else "")
@@ -575,12 +541,90 @@ def main() -> int:
                    "step": ("per segment: Q_i, K, V from x, fwd, bwd, dx_q and dx_partial; then segment sum of dx"
                             if args.projections else
                             "fwd+bwd of the listed segments, then the sum of their dK and dV partials" if args.segments is not None
-                            else "fwd+bwd of all N segments, then segment sum of dK and dV")},
+                            else "fwd+bwd of all N segments, then segment sum of dK and dV"),
+                   "partials_contract": ("every row of the partials written (lss_segment_attn_bwd)" if args.default_contract else
+                                         "LSS_FLAG_SKIP_MASKED_TAIL: key tiles no query of a causal segment sees stay unwritten; "
+                                         "the segment sum is given rows_valid")},
         ("frac_of_f32_peak" if f32 else "frac_of_bf16_peak"): round(value / peak, 4),
         "tflops_with_recompute_count_14Pd": round(flops_fa / (ms_per_step * 1e-3) / 1e12, 2),
-        "gpu_ms_per_step_events": round(gpu_ms / args.steps, 4), "step_stats": step_stats,
+        "gpu_ms_per_step_events": round(gpu_ms_per_step, 4), "step_stats": step_stats,
         "roofline": roofline, "cpu_baseline": cpu_baseline, "rates": rates, "kernels": kernels,
     }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=None,
+                    help="one of synth.WORKLOADS; default lx24k, and then the other configurations are reported in `extra`")
+    ap.add_argument("--projections", action="store_true",
+                    help="also run the Q/K/V projections and their backward around every segment")
+    ap.add_argument("--weight-grads", action="store_true",
+                    help="with --projections: every segment also computes its share of dW_q and dW_kv")
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default="bf16",
+                    help="storage type: bf16 (the benchmark) or f32 (the single-precision twins of the entry points)")
+    ap.add_argument("--dropout", type=float, default=None, metavar="P",
+                    help="run forward and backward with dropout probability P on the attention weights")
+    ap.add_argument("--layer-ops", action="store_true",
+                    help="a separate workload: the segment-local remainder of a layer (positional-embedding rows, "
+                         "layer normalisation, feed-forward unit), forward and backward, for every segment")
+    ap.add_argument("--fused-gelu", action="store_true",
+                    help="with --layer-ops: use the GEMM entry points that apply GeLU and its derivative in their epilogues")
+    ap.add_argument("--segments", default=None, metavar="I,J,...",
+                    help="run only these segments of the workload (for workloads whose N segments' partials do not "
+                         "fit in memory at once, e.g. lx50k_skinny); the segment sum then adds these segments' partials")
+    ap.add_argument("--default-contract", action="store_true",
+                    help="time the backward with every row of the partials written (no LSS_FLAG_SKIP_MASKED_TAIL)")
+    ap.add_argument("--no-extra", action="store_true", help="leave out the other configurations' figures")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="before the timed region, run one plain device-to-device copy of this many MiB "
+                         "(a kernel of known traffic, to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="no survey pass and no second, event-bracketed timed region (roofline becomes null)")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print(f"bench.py: this build is one GPU's share of the path; --gpus {args.gpus} is not supported "
+              "(no collectives, no second GPU). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    from paper_2311_02382_amd import lss, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    lss.load()      # fails loudly if the HIP library has not been built
+    torch.cuda.set_device(0)
+
+    headline = args.workload is None
+    w = synth.WORKLOADS[args.workload or "lx24k"]
+    if args.layer_ops:
+        return layer_ops(args, w)
+    if args.dtype == "f32" and args.projections:
+        print("bench.py: the projections are bf16 only; --dtype f32 cannot be combined with --projections", file=sys.stderr)
+        return 2
+    if args.segments is not None and args.projections:
+        print("bench.py: --segments cannot be combined with --projections", file=sys.stderr)
+        return 2
+
+    line = attention(args, w, args.steps, args.warmup, not args.no_cpu_baseline)
+    plain = not (args.projections or args.dropout is not None or args.segments is not None or args.dtype == "f32")
+    if headline and plain and not args.no_extra:
+        # the other configurations, same step, same timing, a few steps each
+        extra = []
+        for name in ("tiny", "lx8k", "lx32k_d128", "lx50k"):
+            torch.cuda.empty_cache()
+            e = attention(args, synth.WORKLOADS[name], min(args.steps, 5), min(args.warmup, 2), False)
+            extra.append({"workload": name, "value": e["value"], "unit": e["unit"], "ms_per_step": e["ms_per_step"],
+                          "steps": e["steps"], "frac_of_bf16_peak": e["frac_of_bf16_peak"],
+                          "config": {k_: e["config"][k_] for k_ in ("B", "l_x", "N", "l_s", "H", "d", "causal")},
+                          "roofline": e["roofline"], "rates": e["rates"]})
+        line["extra"] = extra
     print(json.dumps(line))
     return 0
 

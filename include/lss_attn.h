@@ -38,9 +38,11 @@
  *     is enqueued on it; no call synchronises with the host.
  *   - Return value: LSS_OK (0) or a negative lss_status.  On error nothing has
  *     been launched and no output was touched; lss_last_error() describes it.
- *   - Scratch memory comes from the caller through lss_set_workspace(); kernels
- *     launched by one call use it until they finish, so calls that overlap in
- *     time (different streams) must not share one workspace.
+ *   - Scratch memory comes from the caller: lss_set_workspace() registers one
+ *     buffer per GPU, which every call made with that GPU current uses; the *_ex
+ *     entry points take a buffer of their own instead.  Kernels launched by one
+ *     call use the buffer until they finish, so calls that overlap in time on one
+ *     GPU (different streams) must be given different buffers through *_ex.
  *   - Results are bit-reproducible run to run: no atomics, every reduction has a
  *     fixed order.
  */
@@ -72,25 +74,6 @@ int lss_version(void);
 const char *lss_last_error(void);
 
 /*
- * Process-wide options, all 0 by default.
- *
- * LSS_OPT_SKIP_MASKED_TAIL: with a value != 0, causal backward calls leave
- * UNWRITTEN the 128-row key tiles of dk_partial / dv_partial that lie entirely
- * at or beyond row seg_offset + l_s (keys no query of the segment sees; by
- * default they are filled with zeros).  For callers whose only use of the
- * partials is lss_reduce_partials() with rows_valid[i] = seg_offset + l_s,
- * which never reads those rows: short segments of long sequences then stop
- * paying for writing l_x rows of zeros per call.  (The segment sum of Section
- * 3, Principle 3 only needs the rows a segment contributes to.)
- *
- * Returns LSS_OK, or LSS_ERR_RANGE for an unknown option.
- */
-typedef enum {
-    LSS_OPT_SKIP_MASKED_TAIL = 1
-} lss_option;
-int lss_set_option(int option, int value);
-
-/*
  * Bytes of device scratch that one forward or backward call of this shape may use
  * (split-KV partial outputs, the row terms D = rowsum(dO * out), partial dQ).
  * Depends on the shape only, not on seg_offset or causal.  Returns 0 for an
@@ -100,9 +83,10 @@ size_t lss_workspace_bytes(int64_t l_s, int64_t l_x, int64_t B, int64_t H, int64
 
 /*
  * Hands the library a device buffer (16-byte aligned) to use as scratch from now
- * on, for calls from any thread.  The caller keeps ownership and must keep it
- * alive until the last call that uses it has finished on the GPU.  (NULL, 0)
- * clears it.
+ * on by calls made, from any thread, while the GPU that is current now is current.
+ * One registration per GPU (at most 64 GPUs).  The caller keeps ownership and
+ * must keep the buffer alive until the last call that uses it has finished on the
+ * GPU.  (NULL, 0) clears this GPU's registration.
  */
 int lss_set_workspace(void *device_ptr, size_t bytes);
 
@@ -123,8 +107,7 @@ int lss_segment_attn_fwd(const void *q_seg, const void *k, const void *v,
  *   out, lse: what the forward call wrote;  dO [B, l_s, H, d] bf16
  *   dq [B, l_s, H, d] bf16 (written)
  *   dk_partial, dv_partial [B, l_x, H, d] float (every row written; with
- *   causal != 0 the rows >= seg_offset + l_s are exactly 0 -- but see
- *   LSS_OPT_SKIP_MASKED_TAIL)
+ *   causal != 0 the rows >= seg_offset + l_s are exactly 0)
  */
 int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v,
                          int64_t seg_offset, int64_t l_s, int64_t l_x,
@@ -147,9 +130,9 @@ int lss_segment_attn_bwd_f32(const void *q_seg, const void *k, const void *v,
                              void *dq, float *dk_partial, float *dv_partial, void *stream);
 
 /*
- * Forward and backward with dropout on the attention weights.  Section 2.2 has
- * the scores "normalized by a dropout and a SoftMax"; read as: the softmax row
- * A_w is computed, each weight is kept with probability 1 - p_drop and kept
+ * Forward and backward with dropout on the attention weights.  Section 2.2 names
+ * a dropout next to the softmax in the normalisation of the scores; read as: the
+ * softmax row A_w is computed, each weight is kept with probability 1 - p_drop and kept
  * weights are divided by 1 - p_drop, and E_i = dropout(A_w) V.  lse is still the
  * logsumexp of the scores.  The keep decision of a weight depends only on
  * (seed, batch*head, GLOBAL query position seg_offset + r, key position): a
@@ -177,6 +160,39 @@ int lss_segment_attn_bwd_dropout(const void *q_seg, const void *k, const void *v
                                  void *dq, float *dk_partial, float *dv_partial, void *stream);
 
 /*
+ * General forms of the forward and backward calls: everything the entry points
+ * above take, plus per-call flags and a per-call scratch buffer.  With flags = 0,
+ * workspace = NULL they are lss_segment_attn_fwd_dropout / _bwd_dropout.
+ *   flags      LSS_FLAG_SKIP_MASKED_TAIL (backward, causal != 0): the 128-row key
+ *              tiles of dk_partial / dv_partial that lie entirely at or beyond row
+ *              seg_offset + l_s -- keys no query of the segment sees, by default
+ *              filled with zeros -- are left UNWRITTEN.  For callers whose only use
+ *              of the partials is lss_reduce_partials() with rows_valid[i] =
+ *              seg_offset + l_s, which never reads those rows: short segments of
+ *              long sequences then stop paying for l_x rows of zeros per call (the
+ *              segment sum of Section 3, Principle 4 only needs the rows a segment
+ *              contributes to).  Other bits must be 0 (LSS_ERR_RANGE).
+ *   workspace  DEVICE buffer of at least lss_workspace_bytes() bytes, 16-byte
+ *              aligned, used instead of the one registered with lss_set_workspace();
+ *              NULL: the registered one.  Calls that overlap in time on one GPU
+ *              need a buffer each.
+ */
+#define LSS_FLAG_SKIP_MASKED_TAIL 1u
+int lss_segment_attn_fwd_ex(const void *q_seg, const void *k, const void *v,
+                            int64_t seg_offset, int64_t l_s, int64_t l_x,
+                            int64_t B, int64_t H, int64_t d, int causal,
+                            double p_drop, uint64_t seed, int elem_bytes, unsigned flags,
+                            void *workspace, size_t workspace_bytes,
+                            void *out, float *lse, void *stream);
+int lss_segment_attn_bwd_ex(const void *q_seg, const void *k, const void *v,
+                            int64_t seg_offset, int64_t l_s, int64_t l_x,
+                            int64_t B, int64_t H, int64_t d, int causal,
+                            double p_drop, uint64_t seed, int elem_bytes, unsigned flags,
+                            void *workspace, size_t workspace_bytes,
+                            const void *out, const float *lse, const void *dO,
+                            void *dq, float *dk_partial, float *dv_partial, void *stream);
+
+/*
  * Segment sum of partials (Fig. 2(v): what the reduce-scatter adds up):
  *     out = parts[0] + parts[1] + ... + parts[n-1]   elementwise, in that order.
  *   parts       HOST array of n DEVICE pointers, each [B, l_x, H, d] float
@@ -195,8 +211,8 @@ int lss_reduce_partials(const float *const *parts, int n, const int64_t *rows_va
  * (Section 3, Principle 3; Fig. 2(ii), (iii)): a segment computes its query from
  * its own rows of the layer input, and key and value from the gathered sequence,
  *     Q_i = x_i W_q,    K = x W_k,    V = x W_v.
- * Section 2.2 only says that x is linearly transformed into Q, K and V of the
- * size of x: read here as square E_m x E_m weights (E_m = H*d) and no bias.
+ * Section 2.2 gives Q, K and V as linear maps of x with the shape of x: read
+ * here as square E_m x E_m weights (E_m = H*d) and no bias.
  *   x      [B, l_x, E_m] bf16, the gathered sequence; x_i is its rows
  *          seg_offset .. seg_offset + l_s - 1
  *   w_q    [E_m, E_m] bf16 row-major;  w_kv [E_m, 2 E_m] bf16 row-major holds
@@ -223,9 +239,10 @@ int lss_project_qkv(const void *x, const void *w_q, const void *w_kv,
  *               as lss_segment_attn_bwd wrote them
  *   rows_valid  leading rows (per batch entry) of the partials that hold data:
  *               l_x, or seg_offset + l_s for a causal segment.  Later rows are not
- *               read; those rows of dx_partial are written as zeros (with
- *               LSS_OPT_SKIP_MASKED_TAIL, 256-row tiles entirely past rows_valid
- *               are left unwritten instead).
+ *               read; those rows of dx_partial are written as zeros
+ *               (lss_project_bwd_ex with LSS_FLAG_SKIP_MASKED_TAIL: 256-row tiles
+ *               entirely past rows_valid are left unwritten instead; other flag
+ *               bits must be 0).
  * The partials are rounded to bf16 as matrix-core operands; accumulation is fp32.
  * Same restrictions as lss_project_qkv.
  */
@@ -234,6 +251,11 @@ int lss_project_bwd(const void *dq, const float *dk_partial, const float *dv_par
                     int64_t l_s, int64_t l_x, int64_t rows_valid,
                     int64_t B, int64_t H, int64_t d,
                     float *dx_q, float *dx_partial, void *stream);
+int lss_project_bwd_ex(const void *dq, const float *dk_partial, const float *dv_partial,
+                       const void *w_q, const void *w_kv,
+                       int64_t l_s, int64_t l_x, int64_t rows_valid,
+                       int64_t B, int64_t H, int64_t d, unsigned flags,
+                       float *dx_q, float *dx_partial, void *stream);
 
 /*
  * One segment's share of the gradients of the projection weights (the gradient
@@ -359,25 +381,6 @@ int lss_linear_bwd_input_gelu(const void *dc, const void *w, const void *u,
                               int64_t rows, int64_t K, int64_t N, void *du, void *stream);
 int lss_gelu_fwd(const void *u, int64_t n, void *g, void *stream);
 int lss_gelu_bwd(const void *u, const void *dg, int64_t n, void *du, void *stream);
-
-/*
- * Per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every
- * kernel the library launches is bracketed by a pair of HIP events on its launch stream.
- *   lss_timing_enable(on)   switch recording on (1) or off (0) for every kernel; off by default
- *   lss_timing_select(mask) record only the kernels whose id bit is set in `mask` (0 = none)
- *   lss_timing_reset()      wait for outstanding events and zero the totals
- *   lss_timing_read(id, &total_ms, &launches)
- *                           wait for outstanding events (blocks the host until those kernels
- *                           are done), then return the summed duration and launch count of
- *                           kernel `id` since the last reset; host pointers
- *   lss_timing_kernel_name(id)  name of kernel `id` (0, 1, ...), NULL past the last one
- * Not thread-safe against concurrent reads; returns LSS_OK or a negative lss_status.
- */
-int lss_timing_enable(int on);
-int lss_timing_select(unsigned kernel_mask);
-int lss_timing_reset(void);
-int lss_timing_read(int kernel_id, double *total_ms, int64_t *launches);
-const char *lss_timing_kernel_name(int kernel_id);
 
 #ifdef __cplusplus
 }

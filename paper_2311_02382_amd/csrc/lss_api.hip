@@ -73,10 +73,11 @@ Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d, int
 namespace {
 
 thread_local char g_err[256] = "";
-std::atomic<int> g_skip_masked_tail{0};
+// the scratch buffer registered for each GPU (lss_set_workspace), indexed by HIP device id
+constexpr int kMaxDevices = 64;
 std::mutex g_ws_mutex;
-void *g_ws_ptr = nullptr;
-size_t g_ws_bytes = 0;
+void *g_ws_ptr[kMaxDevices] = {};
+size_t g_ws_bytes[kMaxDevices] = {};
 
 int fail(int code, const char *fmt, ...)
 {
@@ -116,28 +117,58 @@ int check_dropout(double p)
     return LSS_OK;
 }
 
-int get_workspace(int l_s, int l_x, int B, int H, int d, int elem_bytes, lss::Workspace *ws)
+int current_device(int *dev)
+{
+    if (hipGetDevice(dev) != hipSuccess) {      // a host without a GPU: argument checks still work, against slot 0
+        (void)hipGetLastError();
+        *dev = 0;
+    }
+    if (*dev < 0 || *dev >= kMaxDevices) return fail(LSS_ERR_WORKSPACE, "device id %d is not below %d", *dev, kMaxDevices);
+    return LSS_OK;
+}
+
+// The scratch of one call: the caller's own buffer (`own`, `own_bytes`) if given, else the one
+// registered for the current GPU.
+int get_workspace(int l_s, int l_x, int B, int H, int d, int elem_bytes, void *own, size_t own_bytes, lss::Workspace *ws)
 {
     const size_t need = lss::workspace_bytes(l_s, l_x, B, H, d, elem_bytes);
-    std::lock_guard<std::mutex> lock(g_ws_mutex);
-    if (need > 0 && (g_ws_ptr == nullptr || g_ws_bytes < need))
-        return fail(LSS_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu set (lss_set_workspace)", need, g_ws_bytes);
-    *ws = lss::carve_workspace(g_ws_ptr, l_s, l_x, B, H, d, elem_bytes);
+    void *base = own;
+    size_t have = own_bytes;
+    if (own == nullptr) {
+        int dev = 0;
+        if (int rc = current_device(&dev)) return rc;
+        std::lock_guard<std::mutex> lock(g_ws_mutex);
+        base = g_ws_ptr[dev];
+        have = g_ws_bytes[dev];
+    }
+    if (need > 0 && (base == nullptr || have < need))
+        return fail(LSS_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu %s", need, base ? have : (size_t)0,
+                    own ? "passed" : "registered for this GPU (lss_set_workspace)");
+    *ws = lss::carve_workspace(base, l_s, l_x, B, H, d, elem_bytes);
+    return LSS_OK;
+}
+
+int check_flags(unsigned flags)
+{
+    if (flags & ~LSS_FLAG_SKIP_MASKED_TAIL) return fail(LSS_ERR_RANGE, "unknown flag bits 0x%x", flags & ~LSS_FLAG_SKIP_MASKED_TAIL);
     return LSS_OK;
 }
 
 template <typename T>
 int fwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_s, int64_t l_x, int64_t B,
-             int64_t H, int64_t d, int causal, double p_drop, uint64_t seed, void *out, float *lse, void *stream)
+             int64_t H, int64_t d, int causal, double p_drop, uint64_t seed, unsigned flags, void *wsp, size_t wsp_bytes,
+             void *out, float *lse, void *stream)
 {
     if (int rc = check_shape(s0, l_s, l_x, B, H, d)) return rc;
     if (int rc = check_dropout(p_drop)) return rc;
+    if (int rc = check_flags(flags)) return rc;
+    if (misaligned(wsp)) return fail(LSS_ERR_ALIGN, "forward: workspace must be 16-byte aligned");
     if (l_s == 0 || B == 0) return LSS_OK;
     if (!q || !k || !v || !out || !lse) return fail(LSS_ERR_NULL, "forward: NULL tensor pointer");
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out) || misaligned(lse))
         return fail(LSS_ERR_ALIGN, "forward: tensor pointers must be 16-byte aligned");
     lss::Workspace ws;
-    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), &ws)) return rc;
+    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), wsp, wsp_bytes, &ws)) return rc;
     const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0, 0};
     const lss::DropArgs drop = dropout_args(p_drop, seed);
     const hipError_t e = lss::launch_fwd<T>(s, drop, static_cast<const T *>(q), static_cast<const T *>(k),
@@ -149,11 +180,13 @@ int fwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
 
 template <typename T>
 int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_s, int64_t l_x, int64_t B,
-             int64_t H, int64_t d, int causal, double p_drop, uint64_t seed, const void *out, const float *lse,
-             const void *dO, void *dq, float *dk_part, float *dv_part, void *stream)
+             int64_t H, int64_t d, int causal, double p_drop, uint64_t seed, unsigned flags, void *wsp, size_t wsp_bytes,
+             const void *out, const float *lse, const void *dO, void *dq, float *dk_part, float *dv_part, void *stream)
 {
     if (int rc = check_shape(s0, l_s, l_x, B, H, d)) return rc;
     if (int rc = check_dropout(p_drop)) return rc;
+    if (int rc = check_flags(flags)) return rc;
+    if (misaligned(wsp)) return fail(LSS_ERR_ALIGN, "backward: workspace must be 16-byte aligned");
     if (B == 0) return LSS_OK;
     if (!k || !v || !dk_part || !dv_part) return fail(LSS_ERR_NULL, "backward: NULL tensor pointer");
     if (l_s > 0 && (!q || !out || !lse || !dO || !dq)) return fail(LSS_ERR_NULL, "backward: NULL tensor pointer");
@@ -173,9 +206,9 @@ int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
         return LSS_OK;
     }
     lss::Workspace ws;
-    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), &ws)) return rc;
+    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), wsp, wsp_bytes, &ws)) return rc;
     const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0,
-                          g_skip_masked_tail.load(std::memory_order_relaxed)};
+                          (flags & LSS_FLAG_SKIP_MASKED_TAIL) ? 1 : 0};
     const lss::DropArgs drop = dropout_args(p_drop, seed);
     const hipError_t e = lss::launch_bwd<T>(s, drop, static_cast<const T *>(q), static_cast<const T *>(k),
                                             static_cast<const T *>(v), static_cast<const T *>(out), lse,
@@ -190,15 +223,6 @@ extern "C" {
 
 int lss_version(void) { return 100; }
 
-int lss_set_option(int option, int value)
-{
-    if (option == LSS_OPT_SKIP_MASKED_TAIL) {
-        g_skip_masked_tail.store(value != 0 ? 1 : 0);
-        return LSS_OK;
-    }
-    return fail(LSS_ERR_RANGE, "unknown option %d", option);
-}
-
 const char *lss_last_error(void) { return g_err; }
 
 size_t lss_workspace_bytes(int64_t l_s, int64_t l_x, int64_t B, int64_t H, int64_t d, int elem_bytes)
@@ -212,9 +236,11 @@ int lss_set_workspace(void *device_ptr, size_t bytes)
 {
     if (device_ptr == nullptr && bytes != 0) return fail(LSS_ERR_NULL, "workspace pointer is NULL but bytes = %zu", bytes);
     if (misaligned(device_ptr)) return fail(LSS_ERR_ALIGN, "workspace must be 16-byte aligned");
+    int dev = 0;
+    if (int rc = current_device(&dev)) return rc;
     std::lock_guard<std::mutex> lock(g_ws_mutex);
-    g_ws_ptr = device_ptr;
-    g_ws_bytes = device_ptr ? bytes : 0;
+    g_ws_ptr[dev] = device_ptr;
+    g_ws_bytes[dev] = device_ptr ? bytes : 0;
     return LSS_OK;
 }
 
@@ -222,7 +248,7 @@ int lss_segment_attn_fwd(const void *q_seg, const void *k, const void *v, int64_
                          int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, void *out, float *lse,
                          void *stream)
 {
-    return fwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, out, lse, stream);
+    return fwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, 0u, nullptr, 0, out, lse, stream);
 }
 
 int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
@@ -230,7 +256,7 @@ int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v, int64_
                          const float *lse, const void *dO, void *dq, float *dk_partial, float *dv_partial,
                          void *stream)
 {
-    return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, out, lse, dO, dq,
+    return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, 0u, nullptr, 0, out, lse, dO, dq,
                                  dk_partial, dv_partial, stream);
 }
 
@@ -238,7 +264,7 @@ int lss_segment_attn_fwd_f32(const void *q_seg, const void *k, const void *v, in
                              int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, void *out, float *lse,
                              void *stream)
 {
-    return fwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, out, lse, stream);
+    return fwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, 0u, nullptr, 0, out, lse, stream);
 }
 
 int lss_segment_attn_bwd_f32(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
@@ -246,19 +272,43 @@ int lss_segment_attn_bwd_f32(const void *q_seg, const void *k, const void *v, in
                              const float *lse, const void *dO, void *dq, float *dk_partial, float *dv_partial,
                              void *stream)
 {
-    return bwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, out, lse, dO, dq, dk_partial,
+    return bwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, 0u, nullptr, 0, out, lse, dO, dq, dk_partial,
                            dv_partial, stream);
+}
+
+int lss_segment_attn_fwd_ex(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s, int64_t l_x,
+                            int64_t B, int64_t H, int64_t d, int causal, double p_drop, uint64_t seed, int elem_bytes,
+                            unsigned flags, void *workspace, size_t workspace_bytes, void *out, float *lse, void *stream)
+{
+    if (elem_bytes == 2)
+        return fwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, flags, workspace,
+                                     workspace_bytes, out, lse, stream);
+    if (elem_bytes == 4)
+        return fwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, flags, workspace,
+                               workspace_bytes, out, lse, stream);
+    return fail(LSS_ERR_SHAPE, "elem_bytes = %d: 2 (bf16) or 4 (float)", elem_bytes);
+}
+
+int lss_segment_attn_bwd_ex(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s, int64_t l_x,
+                            int64_t B, int64_t H, int64_t d, int causal, double p_drop, uint64_t seed, int elem_bytes,
+                            unsigned flags, void *workspace, size_t workspace_bytes, const void *out, const float *lse,
+                            const void *dO, void *dq, float *dk_partial, float *dv_partial, void *stream)
+{
+    if (elem_bytes == 2)
+        return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, flags, workspace,
+                                     workspace_bytes, out, lse, dO, dq, dk_partial, dv_partial, stream);
+    if (elem_bytes == 4)
+        return bwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, flags, workspace,
+                               workspace_bytes, out, lse, dO, dq, dk_partial, dv_partial, stream);
+    return fail(LSS_ERR_SHAPE, "elem_bytes = %d: 2 (bf16) or 4 (float)", elem_bytes);
 }
 
 int lss_segment_attn_fwd_dropout(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
                                  int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, double p_drop,
                                  uint64_t seed, int elem_bytes, void *out, float *lse, void *stream)
 {
-    if (elem_bytes == 2)
-        return fwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, out, lse, stream);
-    if (elem_bytes == 4)
-        return fwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, out, lse, stream);
-    return fail(LSS_ERR_SHAPE, "elem_bytes = %d: 2 (bf16) or 4 (float)", elem_bytes);
+    return lss_segment_attn_fwd_ex(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, elem_bytes, 0u, nullptr,
+                                   0, out, lse, stream);
 }
 
 int lss_segment_attn_bwd_dropout(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
@@ -266,13 +316,8 @@ int lss_segment_attn_bwd_dropout(const void *q_seg, const void *k, const void *v
                                  uint64_t seed, int elem_bytes, const void *out, const float *lse, const void *dO,
                                  void *dq, float *dk_partial, float *dv_partial, void *stream)
 {
-    if (elem_bytes == 2)
-        return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, out, lse, dO,
-                                     dq, dk_partial, dv_partial, stream);
-    if (elem_bytes == 4)
-        return bwd_impl<float>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, out, lse, dO, dq,
-                               dk_partial, dv_partial, stream);
-    return fail(LSS_ERR_SHAPE, "elem_bytes = %d: 2 (bf16) or 4 (float)", elem_bytes);
+    return lss_segment_attn_bwd_ex(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, p_drop, seed, elem_bytes, 0u, nullptr,
+                                   0, out, lse, dO, dq, dk_partial, dv_partial, stream);
 }
 
 int lss_project_qkv(const void *x, const void *w_q, const void *w_kv, int64_t seg_offset, int64_t l_s, int64_t l_x,
@@ -300,7 +345,15 @@ int lss_project_bwd(const void *dq, const float *dk_partial, const float *dv_par
                     int64_t l_s, int64_t l_x, int64_t rows_valid, int64_t B, int64_t H, int64_t d, float *dx_q,
                     float *dx_partial, void *stream)
 {
+    return lss_project_bwd_ex(dq, dk_partial, dv_partial, w_q, w_kv, l_s, l_x, rows_valid, B, H, d, 0u, dx_q, dx_partial, stream);
+}
+
+int lss_project_bwd_ex(const void *dq, const float *dk_partial, const float *dv_partial, const void *w_q, const void *w_kv,
+                       int64_t l_s, int64_t l_x, int64_t rows_valid, int64_t B, int64_t H, int64_t d, unsigned flags,
+                       float *dx_q, float *dx_partial, void *stream)
+{
     if (int rc = check_shape(0, l_s, l_x, B, H, d)) return rc;
+    if (int rc = check_flags(flags)) return rc;
     const int64_t E = H * d;
     if (E % 128 != 0 || E > 65536)
         return fail(LSS_ERR_SHAPE, "projections: E_m = H*d = %lld is not a multiple of 128 or exceeds 65536", (long long)E);
@@ -315,7 +368,7 @@ int lss_project_bwd(const void *dq, const float *dk_partial, const float *dv_par
     const hipError_t e = lss::launch_project_bwd(static_cast<const bf16_t *>(dq), dk_partial, dv_partial,
                                                  static_cast<const bf16_t *>(w_q), static_cast<const bf16_t *>(w_kv),
                                                  (int)l_s, (int)l_x, (int)rows_valid, (int)B, (int)E,
-                                                 g_skip_masked_tail.load(std::memory_order_relaxed), dx_q, dx_partial,
+                                                 (flags & LSS_FLAG_SKIP_MASKED_TAIL) ? 1 : 0, dx_q, dx_partial,
                                                  static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(LSS_ERR_LAUNCH, "project_bwd launch failed: %s", hipGetErrorString(e));
     return LSS_OK;

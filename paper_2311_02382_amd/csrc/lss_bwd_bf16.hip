@@ -921,7 +921,7 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const DropArgs &drop, con
     {
         const int64_t items = (int64_t)s.B * s.l_s * s.H * (D / 8);
         const dim3 grid((unsigned)((items + 255) / 256));
-        TimedLaunch tl(K_ROWDOT, st);
+        TimedLaunch tl(K_BWD_PREP_BF16, st);
         if (with_drop)
             hipLaunchKernelGGL((bwd_prep_bf16_kernel<D, true>), grid, dim3(256), 0, st, s, drop, out, dO, lse, ws.D, ws.Ls, ws.row_key);
         else
@@ -935,7 +935,7 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const DropArgs &drop, con
         if (skinny) n_key_tiles = (n_key_tiles + kSkinnyTilesPerWg - 1) / kSkinnyTilesPerWg;      // groups of key tiles
         const int n_dq = xcd_grid(s.B * s.H, n_q_tiles * n_splits), n_dkv = xcd_grid(s.B * s.H, n_key_tiles);
         const dim3 grid((unsigned)(n_dkv + n_dq));
-        TimedLaunch tl(K_BWD_MAIN, st);
+        TimedLaunch tl(K_BWD_MAIN_BF16, st);
         if (skinny)
             hipLaunchKernelGGL((bwd_main_bf16_kernel<D, false, true>), grid, dim3(256), 0, st, s, drop, q, k, v, out, dO, lse, ws.Ls,
                                ws.D, ws.row_key, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);

@@ -353,7 +353,7 @@ static hipError_t launch_fwd_main(const SegShape &s, const DropArgs &drop, const
     using C = FwdBf16Cfg<D>;
     const int n_q_tiles = (s.l_s + C::BR - 1) / C::BR;
     dim3 grid((unsigned)xcd_grid(s.B * s.H, n_q_tiles * n_splits));
-    TimedLaunch tl(K_FWD, st);
+    TimedLaunch tl(K_FWD_BF16, st);
     if (drop.thr != 0)
         hipLaunchKernelGGL((fwd_bf16_kernel<D, true>), grid, dim3(C::NT), 0, st, s, drop, q, k, v, out, lse, ws.o_part,
                            ws.lse_part, n_splits, n_q_tiles);

@@ -66,10 +66,12 @@ hipError_t launch_bwd_bf16_main(const SegShape &s, const DropArgs &drop, const b
                                 const bf16_t *v, const bf16_t *out, const float *lse, const bf16_t *dO, bf16_t *dq,
                                 float *dk_part, float *dv_part, const Workspace &ws, int n_splits, hipStream_t st);
 
-// Optional per-kernel timing for benchmarks: when enabled, every launch site brackets its
-// kernel with a pair of HIP events on the launch stream.
-enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_BWD_MAIN, K_PROJ_FWD, K_PROJ_BWD,
-                K_PE_FWD, K_PE_BWD, K_LN_FWD, K_LN_BWD, K_LN_PARAMS, K_GELU_FWD, K_GELU_BWD, K_LINEAR_FWD, K_LINEAR_BWD, K_RESIDUAL, K_LINEAR_WGRAD, K_COUNT };
+// Optional per-kernel timing for benchmarks (lss_timing.h): when enabled, every launch site
+// brackets its kernel with a pair of HIP events on the launch stream.  One id per __global__
+// function (per role where several entry points share one).
+enum KernelId { K_FWD = 0, K_FWD_MERGE, K_ROWDOT, K_DQ, K_DQ_MERGE, K_DKV, K_REDUCE, K_BWD_MAIN_BF16, K_PROJ_FWD, K_PROJ_BWD,
+                K_PE_FWD, K_PE_BWD, K_LN_FWD, K_LN_BWD, K_LN_PARAMS, K_GELU_FWD, K_GELU_BWD, K_LINEAR_FWD, K_LINEAR_BWD, K_RESIDUAL, K_LINEAR_WGRAD,
+                K_FWD_BF16, K_BWD_PREP_BF16, K_COUNT };
 void timing_begin(int id, hipStream_t st);
 void timing_end(int id, hipStream_t st);
 struct TimedLaunch {    // RAII bracket around one kernel launch

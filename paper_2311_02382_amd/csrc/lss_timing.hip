@@ -2,6 +2,7 @@
 // the library launches, summed per kernel.  Off by default; a benchmark turns it on.
 #include "lss_attn.h"
 #include "lss_kernels.h"
+#include "lss_timing.h"
 
 #include <atomic>
 #include <mutex>
@@ -12,7 +13,7 @@ namespace {
 
 struct Record { int id; hipEvent_t start, stop; };
 
-std::atomic<unsigned> g_mask{0};         // bit i set: kernel id i is timed
+std::atomic<uint64_t> g_mask{0};         // bit i set: kernel id i is timed
 std::mutex g_mu;
 std::vector<Record> g_open;             // recorded, not yet read back
 std::vector<hipEvent_t> g_free;         // events ready for reuse
@@ -20,13 +21,14 @@ thread_local hipEvent_t t_start = nullptr;
 double g_total_ms[K_COUNT] = {0};
 int64_t g_count[K_COUNT] = {0};
 
+// the __global__ function each id stands for; ":role" where entry points share one function
 const char *const kNames[K_COUNT] = {"fwd_kernel", "fwd_merge_kernel", "bwd_rowdot_kernel", "bwd_dq_kernel",
                                      "bwd_dq_merge_kernel", "bwd_dkv_kernel", "reduce_partials_kernel",
-                                     "bwd_main_kernel", "proj_fwd_kernel", "proj_bwd_kernel",
+                                     "bwd_main_bf16_kernel", "proj_gemm_kernel:project_qkv", "proj_gemm_kernel:project_bwd",
                                      "embed_pe_fwd_kernel", "embed_pe_bwd_kernel", "layernorm_fwd_kernel",
                                      "layernorm_bwd_kernel", "layernorm_bwd_params_kernel", "gelu_fwd_kernel",
-                                     "gelu_bwd_kernel", "linear_fwd_kernel", "linear_bwd_kernel", "residual_add_kernel",
-                                     "linear_wgrad_kernel"};
+                                     "gelu_bwd_kernel", "proj_gemm_kernel:linear_fwd", "proj_gemm_kernel:linear_bwd_input",
+                                     "residual_add_kernel", "wgrad_gemm_kernel", "fwd_bf16_kernel", "bwd_prep_bf16_kernel"};
 
 hipEvent_t get_event()
 {
@@ -91,11 +93,11 @@ extern "C" {
 
 int lss_timing_enable(int on)
 {
-    lss::g_mask.store(on != 0 ? ~0u : 0u);
+    lss::g_mask.store(on != 0 ? ~(uint64_t)0 : (uint64_t)0);
     return LSS_OK;
 }
 
-int lss_timing_select(unsigned kernel_mask)
+int lss_timing_select(uint64_t kernel_mask)
 {
     lss::g_mask.store(kernel_mask);
     return LSS_OK;

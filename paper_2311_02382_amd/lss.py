@@ -19,15 +19,17 @@ LSS_OK = 0
 STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_ERR_UNSUPPORTED_D",
                 -4: "LSS_ERR_ALIGN", -5: "LSS_ERR_RANGE", -6: "LSS_ERR_WORKSPACE", -7: "LSS_ERR_LAUNCH"}
 
-EXPORTS = ["lss_version", "lss_last_error", "lss_set_option", "lss_workspace_bytes", "lss_set_workspace",
+EXPORTS = ["lss_version", "lss_last_error", "lss_workspace_bytes", "lss_set_workspace",
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
-           "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd", "lss_project_bwd_weight_scratch_bytes", "lss_project_bwd_weight",
+           "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout",
+           "lss_segment_attn_fwd_ex", "lss_segment_attn_bwd_ex", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd",
+           "lss_project_bwd_ex", "lss_project_bwd_weight_scratch_bytes", "lss_project_bwd_weight",
            "lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_residual_dropout_add", "lss_layernorm_fwd", "lss_layernorm_bwd_scratch_bytes",
            "lss_layernorm_bwd", "lss_linear_fwd", "lss_linear_bwd_input", "lss_linear_bwd_weight_scratch_bytes", "lss_linear_bwd_weight",
            "lss_linear_gelu_fwd",
-           "lss_linear_bwd_input_gelu", "lss_gelu_fwd", "lss_gelu_bwd",
-           "lss_timing_enable", "lss_timing_select", "lss_timing_reset",
-           "lss_timing_read", "lss_timing_kernel_name"]
+           "lss_linear_bwd_input_gelu", "lss_gelu_fwd", "lss_gelu_bwd"]
+
+LSS_FLAG_SKIP_MASKED_TAIL = 1
 
 
 class LssError(RuntimeError):
@@ -47,8 +49,6 @@ def load():
     lib = ctypes.CDLL(str(LIB_PATH))
     i64, vp, ci, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
     lib.lss_version.restype = ci
-    lib.lss_set_option.restype = ci
-    lib.lss_set_option.argtypes = [ci, ci]
     lib.lss_last_error.restype = ctypes.c_char_p
     lib.lss_workspace_bytes.argtypes = [i64, i64, i64, i64, i64, ci]
     lib.lss_workspace_bytes.restype = sz
@@ -66,12 +66,20 @@ def load():
                                                  vp, vp, vp, vp, vp, vp, vp]
     lib.lss_segment_attn_fwd_dropout.restype = ci
     lib.lss_segment_attn_bwd_dropout.restype = ci
+    cu = ctypes.c_uint
+    lib.lss_segment_attn_fwd_ex.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, f64, u64, ci, cu, vp, sz, vp, vp, vp]
+    lib.lss_segment_attn_bwd_ex.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, f64, u64, ci, cu, vp, sz,
+                                            vp, vp, vp, vp, vp, vp, vp]
+    lib.lss_segment_attn_fwd_ex.restype = ci
+    lib.lss_segment_attn_bwd_ex.restype = ci
     lib.lss_reduce_partials.argtypes = [vp, ci, vp, i64, i64, i64, i64, vp, vp]
     lib.lss_reduce_partials.restype = ci
     lib.lss_project_qkv.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, vp, vp, vp]
     lib.lss_project_qkv.restype = ci
     lib.lss_project_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, vp, vp, vp]
     lib.lss_project_bwd.restype = ci
+    lib.lss_project_bwd_ex.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, cu, vp, vp, vp]
+    lib.lss_project_bwd_ex.restype = ci
     lib.lss_project_bwd_weight_scratch_bytes.argtypes = [i64, i64, i64, i64, i64]
     lib.lss_project_bwd_weight_scratch_bytes.restype = sz
     lib.lss_project_bwd_weight.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, vp, vp, vp, sz, vp]
@@ -96,13 +104,6 @@ def load():
     lib.lss_gelu_bwd.argtypes = [vp, vp, i64, vp, vp]
     for name in ("lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_residual_dropout_add", "lss_layernorm_fwd", "lss_layernorm_bwd", "lss_linear_fwd",
                  "lss_linear_bwd_input", "lss_linear_gelu_fwd", "lss_linear_bwd_input_gelu", "lss_gelu_fwd", "lss_gelu_bwd"):
-        getattr(lib, name).restype = ci
-    lib.lss_timing_enable.argtypes = [ci]
-    lib.lss_timing_select.argtypes = [ctypes.c_uint]
-    lib.lss_timing_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
-    lib.lss_timing_kernel_name.argtypes = [ci]
-    lib.lss_timing_kernel_name.restype = ctypes.c_char_p
-    for name in ("lss_timing_enable", "lss_timing_select", "lss_timing_reset", "lss_timing_read"):
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
@@ -176,10 +177,21 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr())
 
 
+def _own_workspace(workspace, need):
+    """(pointer, bytes) of a caller's scratch tensor for the *_ex entry points."""
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous device tensor")
+    nbytes = workspace.numel() * workspace.element_size()
+    if nbytes < need:
+        raise ValueError(f"workspace of {nbytes} bytes, need {need}")
+    return _ptr(workspace), nbytes
+
+
 def lss_segment_attn_fwd(q_seg, k, v, seg_offset, causal=True, out=None, lse=None, stream=None,
-                         p_drop=None, seed=0):
-    """Forward of one segment; dispatches on dtype (bf16 -> lss_segment_attn_fwd, f32 -> _f32), or calls
-    lss_segment_attn_fwd_dropout when p_drop is given.
+                         p_drop=None, seed=0, workspace=None):
+    """Forward of one segment; dispatches on dtype (bf16 -> lss_segment_attn_fwd, f32 -> _f32), calls
+    lss_segment_attn_fwd_dropout when p_drop is given, and lss_segment_attn_fwd_ex when `workspace` (a
+    device tensor of lss_workspace_bytes() bytes used by this call alone) is given.
 
     Returns (out [B,l_s,H,d] in the input dtype, lse [B,H,l_s] float32).
     """
@@ -189,6 +201,12 @@ def lss_segment_attn_fwd(q_seg, k, v, seg_offset, causal=True, out=None, lse=Non
     if lse is None:
         lse = torch.empty((B, H, l_s), dtype=torch.float32, device=q_seg.device)
     f32 = q_seg.dtype == torch.float32
+    if workspace is not None:
+        wp, wn = _own_workspace(workspace, lss_workspace_bytes(l_s, l_x, B, H, d, 4 if f32 else 2))
+        _check(load().lss_segment_attn_fwd_ex(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d,
+                                              int(bool(causal)), float(p_drop or 0.0), int(seed) & (2 ** 64 - 1),
+                                              4 if f32 else 2, 0, wp, wn, _ptr(out), _ptr(lse), _stream_ptr(stream)))
+        return out, lse
     _ensure_workspace(l_s, l_x, B, H, d, 4 if f32 else 2, q_seg.device)
     if p_drop is not None:
         _check(load().lss_segment_attn_fwd_dropout(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d,
@@ -202,8 +220,11 @@ def lss_segment_attn_fwd(q_seg, k, v, seg_offset, causal=True, out=None, lse=Non
 
 
 def lss_segment_attn_bwd(q_seg, k, v, seg_offset, out, lse, d_out, causal=True,
-                         dq=None, dk_partial=None, dv_partial=None, stream=None, p_drop=None, seed=0):
-    """Backward of one segment.  Returns (dq, dk_partial, dv_partial); partials are float32 [B,l_x,H,d]."""
+                         dq=None, dk_partial=None, dv_partial=None, stream=None, p_drop=None, seed=0,
+                         skip_masked_tail=False, workspace=None):
+    """Backward of one segment.  Returns (dq, dk_partial, dv_partial); partials are float32 [B,l_x,H,d].
+
+    skip_masked_tail (LSS_FLAG_SKIP_MASKED_TAIL) or `workspace` select lss_segment_attn_bwd_ex."""
     B, l_s, l_x, H, d = _dims(q_seg, k, v)
     for t in (out, d_out):
         if t.shape != q_seg.shape or t.dtype != q_seg.dtype or not t.is_contiguous():
@@ -217,7 +238,17 @@ def lss_segment_attn_bwd(q_seg, k, v, seg_offset, out, lse, d_out, causal=True,
     if dv_partial is None:
         dv_partial = torch.empty(k.shape, dtype=torch.float32, device=k.device)
     f32 = q_seg.dtype == torch.float32
-    _ensure_workspace(l_s, l_x, B, H, d, 4 if f32 else 2, q_seg.device)
+    if workspace is None:
+        _ensure_workspace(l_s, l_x, B, H, d, 4 if f32 else 2, q_seg.device)
+    if skip_masked_tail or workspace is not None:
+        wp, wn = (None, 0) if workspace is None else \
+            _own_workspace(workspace, lss_workspace_bytes(l_s, l_x, B, H, d, 4 if f32 else 2))
+        _check(load().lss_segment_attn_bwd_ex(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d,
+                                              int(bool(causal)), float(p_drop or 0.0), int(seed) & (2 ** 64 - 1),
+                                              4 if f32 else 2, LSS_FLAG_SKIP_MASKED_TAIL if skip_masked_tail else 0,
+                                              wp, wn, _ptr(out), _ptr(lse), _ptr(d_out), _ptr(dq),
+                                              _ptr(dk_partial), _ptr(dv_partial), _stream_ptr(stream)))
+        return dq, dk_partial, dv_partial
     if p_drop is not None:
         _check(load().lss_segment_attn_bwd_dropout(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d,
                                                    int(bool(causal)), float(p_drop), int(seed) & (2 ** 64 - 1),
@@ -281,8 +312,11 @@ def lss_project_qkv(x, w_q, w_kv, seg_offset, l_s, H, q_seg=None, k=None, v=None
     return q_seg, k, v
 
 
-def lss_project_bwd(dq, dk_partial, dv_partial, w_q, w_kv, rows_valid=None, dx_q=None, dx_partial=None, stream=None):
-    """dx_q = dQ_i W_q^T [B,l_s,E] and dx_partial = dK_part W_k^T + dV_part W_v^T [B,l_x,E], both float32."""
+def lss_project_bwd(dq, dk_partial, dv_partial, w_q, w_kv, rows_valid=None, dx_q=None, dx_partial=None, stream=None,
+                    skip_masked_tail=False):
+    """dx_q = dQ_i W_q^T [B,l_s,E] and dx_partial = dK_part W_k^T + dV_part W_v^T [B,l_x,E], both float32.
+
+    skip_masked_tail selects lss_project_bwd_ex with LSS_FLAG_SKIP_MASKED_TAIL."""
     if dq.dim() != 4 or dk_partial.dim() != 4 or dk_partial.shape != dv_partial.shape:
         raise ValueError("dq must be [B,l_s,H,d]; partials [B,l_x,H,d]")
     B, l_s, H, d = dq.shape
@@ -301,6 +335,11 @@ def lss_project_bwd(dq, dk_partial, dv_partial, w_q, w_kv, rows_valid=None, dx_q
                   (dv_partial, torch.float32), (dx_q, torch.float32), (dx_partial, torch.float32)):
         if not t.is_cuda or not t.is_contiguous() or t.dtype != dt:
             raise ValueError("tensors must be contiguous device tensors of the documented types")
+    if skip_masked_tail:
+        _check(load().lss_project_bwd_ex(_ptr(dq), _ptr(dk_partial), _ptr(dv_partial), _ptr(w_q), _ptr(w_kv), l_s, l_x,
+                                         int(rows_valid), B, H, d, LSS_FLAG_SKIP_MASKED_TAIL, _ptr(dx_q), _ptr(dx_partial),
+                                         _stream_ptr(stream)))
+        return dx_q, dx_partial
     _check(load().lss_project_bwd(_ptr(dq), _ptr(dk_partial), _ptr(dv_partial), _ptr(w_q), _ptr(w_kv), l_s, l_x,
                                   int(rows_valid), B, H, d, _ptr(dx_q), _ptr(dx_partial), _stream_ptr(stream)))
     return dx_q, dx_partial
@@ -521,39 +560,3 @@ def lss_gelu_bwd(u, dg, du=None, stream=None):
     du = _out(du, u.shape, torch.bfloat16, u)
     _check(load().lss_gelu_bwd(_ptr(u), _ptr(dg), u.numel(), _ptr(du), _stream_ptr(stream)))
     return du
-
-
-def lss_timing_enable(on: bool) -> None:
-    _check(load().lss_timing_enable(int(bool(on))))
-
-
-LSS_OPT_SKIP_MASKED_TAIL = 1
-
-
-def lss_set_option(option: int, value: int) -> None:
-    """Process-wide option, see include/lss_attn.h."""
-    _check(load().lss_set_option(int(option), int(value)))
-
-
-def lss_timing_select(kernel_ids) -> None:
-    """Record only the kernels whose ids are listed (an empty list records nothing)."""
-    mask = 0
-    for k in kernel_ids:
-        mask |= 1 << int(k)
-    _check(load().lss_timing_select(mask))
-
-
-def lss_timing_reset() -> None:
-    _check(load().lss_timing_reset())
-
-
-def lss_timing_kernel_name(kernel_id: int):
-    name = load().lss_timing_kernel_name(kernel_id)
-    return name.decode() if name else None
-
-
-def lss_timing_read(kernel_id: int):
-    """(total milliseconds, launches) of kernel `kernel_id` since the last reset."""
-    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
-    _check(load().lss_timing_read(kernel_id, ctypes.byref(ms), ctypes.byref(n)))
-    return ms.value, n.value

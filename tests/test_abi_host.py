@@ -95,12 +95,30 @@ def test_backward_and_reduce_argument_checks(lib):
     assert red(nul, 2, None, 256, 1, 1, 64, 0x3000, None) == -1
 
 
-def test_options(lib):
-    lib.lss_set_option.restype = ctypes.c_int
-    assert lib.lss_set_option(1, 1) == 0        # LSS_OPT_SKIP_MASKED_TAIL on
-    assert lib.lss_set_option(1, 0) == 0        # ... and off again (process-wide state)
-    assert lib.lss_set_option(77, 1) == -5      # unknown option
-    assert b"option" in lib.lss_last_error()
+def test_per_call_flags_and_workspace(lib):
+    # the general forms: unknown flag bits, a caller's own workspace (size, alignment) -- all host checks
+    need = lib.lss_workspace_bytes(128, 256, 1, 1, 64, 2)
+    f = lib.lss_segment_attn_fwd_ex
+    g = lib.lss_segment_attn_bwd_ex
+
+    def fwd(flags=0, ws=0x10000, nbytes=need, eb=2):
+        return f(0x1000, 0x2000, 0x3000, 0, 128, 256, 1, 1, 64, 1, 0.0, 0, eb, flags, ws, nbytes, 0x4000, 0x5000, None)
+
+    def bwd(flags=1, ws=0x10000, nbytes=need, eb=2, p=0.0):
+        return g(0x1000, 0x2000, 0x3000, 0, 128, 256, 1, 1, 64, 1, p, 0, eb, flags, ws, nbytes, 0x4000, 0x5000, 0x6000,
+                 0x7000, 0x8000, 0x9000, None)
+
+    assert fwd(flags=2) == -5 and b"flag" in lib.lss_last_error()
+    assert bwd(flags=6) == -5
+    assert fwd(nbytes=need - 1) == -6 and b"passed" in lib.lss_last_error()
+    assert bwd(nbytes=need - 1) == -6
+    assert fwd(ws=0x10004) == -4
+    assert fwd(eb=3) == -2
+    assert bwd(p=1.0) == -5
+    assert lib.lss_set_workspace(None, 0) == 0
+    assert fwd(ws=None, nbytes=0) == -6 and b"registered" in lib.lss_last_error()
+    pb = lib.lss_project_bwd_ex
+    assert pb(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 128, 256, 256, 1, 2, 64, 8, 0x6000, 0x7000, None) == -5
 
 
 def test_projection_weight_gradient_argument_checks(lib):

@@ -170,39 +170,43 @@ def test_lx50k_full_sweep_segment_sum_is_exact_and_reproducible():
     assert rel_err(to_np(dK1[b, j_lo:, h]), rdk[0, j_lo:, 0]) <= T["t"]
 
 
-def test_lx8k_in_the_benchmark_configuration():
-    # exactly the calls of one bench.py step: preallocated outputs, LSS_OPT_SKIP_MASKED_TAIL on (key
-    # tiles past a segment's last query stay unwritten -- here they hold a canary), then the segment
-    # sum with rows_valid.  Checked: the sums against the oracle's full-sequence gradient on one
-    # slice, the canary where nothing may be written, sampled rows of out and dq.
-    W = Workload("lx8k")
+@pytest.mark.parametrize("name,slice_bh", [("lx8k", (1, 2)), ("lx24k", (2, 7)), ("lx32k_d128", (0, 9)), ("lx50k", (0, 5))])
+def test_benchmark_configuration_sums_to_the_full_sequence_gradient(name, slice_bh):
+    # Exactly the calls of one bench.py step, for every configuration it times: preallocated outputs, all N
+    # segments forward and backward with LSS_FLAG_SKIP_MASKED_TAIL (key tiles past a causal segment's last
+    # query stay unwritten -- here they hold a canary), then the segment sum with rows_valid.  Checked
+    # against ONE call of the oracle on the unsegmented sequence (Section 3, Principle 3: the segments'
+    # outputs concatenate to the sequential result; Principle 4 / Fig. 2(v): the partials add up to the
+    # full gradient), for one (batch, head) slice: all l_x rows of dK and dV, the concatenated dQ and out.
+    W = Workload(name)
     w = W.w
     qd, kd, vd, dod = W.dev
     canary = 12345.0
     dks = [torch.full(kd.shape, canary, dtype=torch.float32, device="cuda") for _ in range(w.N)]
     dvs = [torch.full(kd.shape, canary, dtype=torch.float32, device="cuda") for _ in range(w.N)]
-    outs, dqs = [], []
-    lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, 1)
-    try:
-        for i, s0 in enumerate(w.offsets()):
-            q_seg, do_seg = qd[:, s0:s0 + w.l_s].contiguous(), dod[:, s0:s0 + w.l_s].contiguous()
-            out, lse = lss.lss_segment_attn_fwd(q_seg, kd, vd, s0, True)
-            dq, _, _ = lss.lss_segment_attn_bwd(q_seg, kd, vd, s0, out, lse, do_seg, True,
-                                                dk_partial=dks[i], dv_partial=dvs[i])
-            outs.append(out); dqs.append(dq)
-    finally:
-        lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, 0)
-    rows_valid = [s0 + w.l_s for s0 in w.offsets()]
+    outs, dqs, lses = [], [], []
+    for i, s0 in enumerate(w.offsets()):
+        q_seg, do_seg = qd[:, s0:s0 + w.l_s].contiguous(), dod[:, s0:s0 + w.l_s].contiguous()
+        out, lse = lss.lss_segment_attn_fwd(q_seg, kd, vd, s0, w.causal)
+        dq, _, _ = lss.lss_segment_attn_bwd(q_seg, kd, vd, s0, out, lse, do_seg, w.causal,
+                                            dk_partial=dks[i], dv_partial=dvs[i], skip_masked_tail=True)
+        outs.append(out); dqs.append(dq); lses.append(lse)
+    rows_valid = [s0 + w.l_s if w.causal else w.l_x for s0 in w.offsets()]
     for i, rv in enumerate(rows_valid):
         hidden = -(-rv // 128) * 128                       # first key tile no query of segment i sees
         assert bool((dks[i][:, hidden:] == canary).all()) and bool((dvs[i][:, hidden:] == canary).all())
-        assert torch.count_nonzero(dks[i][:, rv:hidden]) == 0
+        assert torch.count_nonzero(dks[i][:, rv:hidden]) == 0 and torch.count_nonzero(dvs[i][:, rv:hidden]) == 0
     dK = lss.lss_reduce_partials(dks, rows_valid)
     dV = lss.lss_reduce_partials(dvs, rows_valid)
-    b, h = 1, 2
-    fdq, fdk, fdv = oracle.segment_bwd(W.host(0, b, h), W.host(1, b, h), W.host(2, b, h), W.host(3, b, h), 0, True)
-    assert rel_err(to_np(dK[b, :, h]), fdk[0, :, 0]) <= T["t"]
-    assert rel_err(to_np(dV[b, :, h]), fdv[0, :, 0]) <= T["t"]
-    assert rel_err(to_np(torch.cat(dqs, dim=1)[b, :, h]), fdq[0, :, 0]) <= T["t"]
-    fo, _ = oracle.segment_fwd(W.host(0, b, h), W.host(1, b, h), W.host(2, b, h), 0, True)
-    assert rel_err(to_np(torch.cat(outs, dim=1)[b, :, h]), fo[0, :, 0]) <= T["t"]
+    del dks, dvs
+    b, h = slice_bh
+    qh, kh, vh, doh = (W.host(t, b, h) for t in range(4))
+    fdq, fdk, fdv = oracle.segment_bwd(qh, kh, vh, doh, 0, w.causal)
+    fo, fl = oracle.segment_fwd(qh, kh, vh, 0, w.causal)
+    errs = {"dK": rel_err(to_np(dK[b, :, h]), fdk[0, :, 0]), "dV": rel_err(to_np(dV[b, :, h]), fdv[0, :, 0]),
+            "dQ": rel_err(to_np(torch.cat(dqs, dim=1)[b, :, h]), fdq[0, :, 0]),
+            "out": rel_err(to_np(torch.cat(outs, dim=1)[b, :, h]), fo[0, :, 0])}
+    e_lse = lse_err(to_np(torch.cat(lses, dim=2)[b, h]), fl[0, 0])
+    print(f"{name} slice {slice_bh}: {errs} lse {e_lse:.2e}")
+    assert max(errs.values()) <= T["t"], errs
+    assert e_lse <= T["lse"]

@@ -185,18 +185,15 @@ def test_skip_masked_tail_option(kind):
     fwd, bwd = lss.lss_segment_attn_fwd, lss.lss_segment_attn_bwd       # dispatch on the tensors' dtype
     segs = [(0, 58), (58, 300), (358, 642)]
     parts = {0: [], 1: []}
-    try:
-        for opt in (0, 1):
-            lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, opt)
-            for s0, l_s in segs:
-                q = Q.dev[:, s0:s0 + l_s].contiguous()
-                out, lse = fwd(q, K.dev, V.dev, s0, True)
-                dk = torch.full((B, l_x, H, d), 7.0, dtype=torch.float32, device="cuda")
-                dv = torch.full((B, l_x, H, d), 7.0, dtype=torch.float32, device="cuda")
-                bwd(q, K.dev, V.dev, s0, out, lse, DO.dev[:, s0:s0 + l_s].contiguous(), True, dk_partial=dk, dv_partial=dv)
-                parts[opt].append((dk, dv))
-    finally:
-        lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, 0)
+    for opt in (0, 1):      # the flag is an argument of the call (lss_segment_attn_bwd_ex), not a state of the library
+        for s0, l_s in segs:
+            q = Q.dev[:, s0:s0 + l_s].contiguous()
+            out, lse = fwd(q, K.dev, V.dev, s0, True)
+            dk = torch.full((B, l_x, H, d), 7.0, dtype=torch.float32, device="cuda")
+            dv = torch.full((B, l_x, H, d), 7.0, dtype=torch.float32, device="cuda")
+            bwd(q, K.dev, V.dev, s0, out, lse, DO.dev[:, s0:s0 + l_s].contiguous(), True, dk_partial=dk, dv_partial=dv,
+                skip_masked_tail=bool(opt))
+            parts[opt].append((dk, dv))
     rows_valid = [s0 + l_s for s0, l_s in segs]
     for (s0, l_s), (dk0, dv0), (dk1, dv1) in zip(segs, parts[0], parts[1]):
         hi = s0 + l_s

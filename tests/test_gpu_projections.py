@@ -63,11 +63,8 @@ def test_project_bwd_matches_oracle(B, l_x, H, d, s0, l_s, skip_tail):
     dv_dev[:, rows_valid:] = float("nan")
     canary = -7.25
     dxp = torch.full((B, l_x, E), canary, dtype=torch.float32, device="cuda")
-    lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, int(skip_tail))
-    try:
-        dxq, dxp = lss.lss_project_bwd(DQ.dev, dk_dev, dv_dev, WQ.dev, WKV.dev, rows_valid, dx_partial=dxp)
-    finally:
-        lss.lss_set_option(lss.LSS_OPT_SKIP_MASKED_TAIL, 0)
+    dxq, dxp = lss.lss_project_bwd(DQ.dev, dk_dev, dv_dev, WQ.dev, WKV.dev, rows_valid, dx_partial=dxp,
+                                   skip_masked_tail=skip_tail)
     assert rel_err(to_np(dxq), rdxq) <= TOL["bf16"]["t"]
     got = to_np(dxp)
     assert rel_err(got[:, :rows_valid], rdxp[:, :rows_valid]) <= TOL["bf16"]["t"]
