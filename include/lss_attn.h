@@ -116,6 +116,27 @@ int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v,
                          void *dq, float *dk_partial, float *dv_partial, void *stream);
 
 /*
+ * lss_segment_attn_bwd for callers that cannot allocate or register memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels, same results bit for bit; the scratch (the rows' start
+ * values -D and -lse*sqrt(d), split partial dQ) lives in a buffer of
+ * LSS_NOALLOC_SCRATCH_BYTES bytes that is part of the library's device image: every GPU
+ * the library runs on holds one until the process ends.  The call allocates and frees
+ * nothing and ignores lss_set_workspace().  Shapes for which lss_workspace_bytes(l_s,
+ * l_x, B, H, d, 2) exceeds the buffer are rejected with LSS_ERR_WORKSPACE.  Nothing in
+ * the buffer has to be cleared between calls (every value is written before it is read),
+ * but all calls on one GPU share it: calls that overlap in time on one GPU (different
+ * streams, different threads) race.  The first call on a GPU looks the buffer's address up
+ * (hipGetSymbolAddress), so make it before a capture begins.
+ */
+#define LSS_NOALLOC_SCRATCH_BYTES (64u << 20)
+int lss_segment_attn_bwd_noalloc(const void *q_seg, const void *k, const void *v,
+                                 int64_t seg_offset, int64_t l_s, int64_t l_x,
+                                 int64_t B, int64_t H, int64_t d, int causal,
+                                 const void *out, const float *lse, const void *dO,
+                                 void *dq, float *dk_partial, float *dv_partial, void *stream);
+
+/*
  * Single-precision twins (the paper's runs are single precision, Section 5.2):
  * q_seg, k, v, out, dO, dq are float; products run on fp32 matrix cores.
  */

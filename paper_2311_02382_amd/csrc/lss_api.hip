@@ -148,6 +148,35 @@ int get_workspace(int l_s, int l_x, int B, int H, int d, int elem_bytes, void *o
     return LSS_OK;
 }
 
+// ---- built-in scratch of lss_segment_attn_bwd_noalloc
+// Device memory that exists from the moment the library's code object is loaded on a GPU until the
+// process ends; each GPU holds its own copy at its own address.  In host code the array's name is only
+// a handle for hipGetSymbolAddress: kernels are always given the address that call returned.
+static __device__ __align__(256) unsigned char scratch[LSS_NOALLOC_SCRATCH_BYTES];
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+int builtin_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return fail(LSS_ERR_WORKSPACE, "built-in scratch: no current GPU (or its device id is not below %d)", kMaxDevices);
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {        // first call on this GPU, which is current
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return fail(LSS_ERR_WORKSPACE, "built-in scratch: hipGetSymbolAddress failed on device %d: %s", dev, hipGetErrorString(e));
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return LSS_OK;
+}
+
 int check_flags(unsigned flags)
 {
     if (flags & ~LSS_FLAG_SKIP_MASKED_TAIL) return fail(LSS_ERR_RANGE, "unknown flag bits 0x%x", flags & ~LSS_FLAG_SKIP_MASKED_TAIL);
@@ -258,6 +287,23 @@ int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v, int64_
 {
     return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, 0u, nullptr, 0, out, lse, dO, dq,
                                  dk_partial, dv_partial, stream);
+}
+
+int lss_segment_attn_bwd_noalloc(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,
+                                 int64_t l_x, int64_t B, int64_t H, int64_t d, int causal, const void *out,
+                                 const float *lse, const void *dO, void *dq, float *dk_partial, float *dv_partial,
+                                 void *stream)
+{
+    if (int rc = check_shape(seg_offset, l_s, l_x, B, H, d)) return rc;
+    const size_t need = (l_s > 0 && B > 0) ? lss::workspace_bytes((int)l_s, (int)l_x, (int)B, (int)H, (int)d, 2) : 0;
+    if (need > (size_t)LSS_NOALLOC_SCRATCH_BYTES)
+        return fail(LSS_ERR_WORKSPACE, "this shape needs %zu bytes of scratch, the built-in buffer holds %zu: use lss_segment_attn_bwd",
+                    need, (size_t)LSS_NOALLOC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    if (need > 0)
+        if (int rc = builtin_scratch(&ws)) return rc;
+    return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, 0u, ws,
+                                 ws ? (size_t)LSS_NOALLOC_SCRATCH_BYTES : 0, out, lse, dO, dq, dk_partial, dv_partial, stream);
 }
 
 int lss_segment_attn_fwd_f32(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,

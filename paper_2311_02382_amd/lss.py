@@ -22,7 +22,7 @@ STATUS_NAMES = {0: "LSS_OK", -1: "LSS_ERR_NULL", -2: "LSS_ERR_SHAPE", -3: "LSS_E
 EXPORTS = ["lss_version", "lss_last_error", "lss_workspace_bytes", "lss_set_workspace",
            "lss_segment_attn_fwd", "lss_segment_attn_bwd", "lss_segment_attn_fwd_f32",
            "lss_segment_attn_bwd_f32", "lss_segment_attn_fwd_dropout", "lss_segment_attn_bwd_dropout",
-           "lss_segment_attn_fwd_ex", "lss_segment_attn_bwd_ex", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd",
+           "lss_segment_attn_fwd_ex", "lss_segment_attn_bwd_ex", "lss_segment_attn_bwd_noalloc", "lss_reduce_partials", "lss_project_qkv", "lss_project_bwd",
            "lss_project_bwd_ex", "lss_project_bwd_weight_scratch_bytes", "lss_project_bwd_weight",
            "lss_embed_pe_fwd", "lss_embed_pe_bwd", "lss_residual_dropout_add", "lss_layernorm_fwd", "lss_layernorm_bwd_scratch_bytes",
            "lss_layernorm_bwd", "lss_linear_fwd", "lss_linear_bwd_input", "lss_linear_bwd_weight_scratch_bytes", "lss_linear_bwd_weight",
@@ -57,7 +57,8 @@ def load():
     fwd = [vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, vp, vp, vp]
     bwd = [vp, vp, vp, i64, i64, i64, i64, i64, i64, ci, vp, vp, vp, vp, vp, vp, vp]
     for name, args in (("lss_segment_attn_fwd", fwd), ("lss_segment_attn_fwd_f32", fwd),
-                       ("lss_segment_attn_bwd", bwd), ("lss_segment_attn_bwd_f32", bwd)):
+                       ("lss_segment_attn_bwd", bwd), ("lss_segment_attn_bwd_f32", bwd),
+                       ("lss_segment_attn_bwd_noalloc", bwd)):
         getattr(lib, name).argtypes = args
         getattr(lib, name).restype = ci
     f64, u64 = ctypes.c_double, ctypes.c_uint64
@@ -259,6 +260,29 @@ def lss_segment_attn_bwd(q_seg, k, v, seg_offset, out, lse, d_out, causal=True,
     _check(fn(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d, int(bool(causal)),
               _ptr(out), _ptr(lse), _ptr(d_out), _ptr(dq), _ptr(dk_partial), _ptr(dv_partial),
               _stream_ptr(stream)))
+    return dq, dk_partial, dv_partial
+
+
+LSS_NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def lss_segment_attn_bwd_noalloc(q_seg, k, v, seg_offset, out, lse, d_out, causal, dq, dk_partial, dv_partial, stream=None):
+    """lss_segment_attn_bwd with the library's built-in scratch buffer (bf16 only): the call itself allocates
+    nothing, so every output must be passed in."""
+    B, l_s, l_x, H, d = _dims(q_seg, k, v)
+    if q_seg.dtype != torch.bfloat16:
+        raise ValueError("bf16 only")
+    for t in (out, d_out, dq):
+        if t.shape != q_seg.shape or t.dtype != q_seg.dtype or not t.is_contiguous():
+            raise ValueError("out, d_out and dq must match q_seg in shape and dtype and be contiguous")
+    if lse.shape != (B, H, l_s) or lse.dtype != torch.float32 or not lse.is_contiguous():
+        raise ValueError("lse must be contiguous float32 [B, H, l_s]")
+    for t in (dk_partial, dv_partial):
+        if t.shape != k.shape or t.dtype != torch.float32 or not t.is_contiguous():
+            raise ValueError("partials must be contiguous float32 [B, l_x, H, d]")
+    _check(load().lss_segment_attn_bwd_noalloc(_ptr(q_seg), _ptr(k), _ptr(v), int(seg_offset), l_s, l_x, B, H, d,
+                                               int(bool(causal)), _ptr(out), _ptr(lse), _ptr(d_out), _ptr(dq),
+                                               _ptr(dk_partial), _ptr(dv_partial), _stream_ptr(stream)))
     return dq, dk_partial, dv_partial
 
 
