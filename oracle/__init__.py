@@ -38,6 +38,22 @@ def build(force: bool = False) -> Path:
     return _LIB
 
 
+def build_sanitized() -> Path:
+    """Compile lss_oracle.c together with san_check.c under AddressSanitizer and UndefinedBehaviorSanitizer
+    (host code only; the sanitizer runtimes are linked statically, so the program needs no preloading)
+    into a stand-alone checker.  Returns the program's path; run it, exit status 0 means clean."""
+    exe = _SRC.with_name("san_check")
+    tmp = exe.with_suffix(f".tmp{os.getpid()}")
+    subprocess.run(
+        ["gcc", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+         "-static-libasan", "-static-libubsan", "-fopenmp", "-Wall", "-Wextra",
+         "-o", str(tmp), str(_SRC.with_name("san_check.c")), str(_SRC), "-lm"],
+        check=True,
+    )
+    os.replace(tmp, exe)
+    return exe
+
+
 def _load():
     global _lib
     if _lib is None:
@@ -180,7 +196,7 @@ def reduce_partials(parts):
 
 
 # ---- the linear maps either side of the segment attention (fused-communication form) ----------
-# Section 2.2 says only that x is "linearly transformed" into Q, K and V, each the size of x; the
+# Section 2.2 gives Q, K and V only as linear maps of x with the shape of x; the
 # reading taken here is Q = x W_q, K = x W_k, V = x W_v with square E_m x E_m weights and no bias.
 # Section 3, Principle 3 and Fig. 2(ii): a segment projects its query from its own rows x_i, and
 # the key and value from the gathered sequence x.  W_kv holds [W_k | W_v] side by side (E_m x 2E_m).

@@ -222,26 +222,29 @@ int lss_oracle_reduce_partials(const double *const *parts, int n, int64_t n_elem
 }
 
 /* ------------------------------------------------------------------------
- * Dropout on the attention weights.  Section 2.2 says the scores are
- * "normalized by a dropout and a SoftMax"; the reading taken here is the
- * usual one of the framework the paper was written in: the softmax row A_w
- * is computed first, then each weight is kept with probability 1 - p and the
- * kept ones are divided by 1 - p, and E = dropout(A_w) V.  lse stays the
+ * Dropout on the attention weights.  Section 2.2 names a dropout next to
+ * the softmax in the normalisation of the scores; the reading taken here is
+ * the usual one of the framework the paper was written in: the softmax row
+ * A_w is computed first, then each weight is kept with probability 1 - p and
+ * the kept ones are divided by 1 - p, and E = dropout(A_w) V.  lse stays the
  * logsumexp of the scores.
  *
  * The keep decision of a weight is a function of (seed, b*H + h, GLOBAL query
  * position, key position) alone, so that a segment drops exactly what the
  * sequential computation would drop at those positions and the segments'
  * outputs still concatenate to the full-sequence result (Section 3,
- * Principle 3).  It is a counter-based generator built from a published
- * 32-bit integer mixing function (two multiply-xorshift rounds), not a
- * stream: nothing depends on the order of evaluation.  The random number of
- * a weight is mix(row key + column key): the row key mixes the low half of
- * the seed, the batch*head index and the row; the column key mixes the high
- * half of the seed and the column.  (Separable on purpose: a kernel in which
- * a lane owns a row keeps the row key in a register, one in which a lane owns
- * a key keeps the column key.)  The HIP library implements the same function
- * on its side.
+ * Principle 3).  The paper does not say how the random numbers are drawn.
+ * DEFINITION used here: a counter-based generator, not a stream (nothing
+ * depends on the order of evaluation), built from a published 32-bit integer
+ * mixing function mix32 (two multiply-xorshift rounds):
+ *     row_key(seed, bh, row) = mix32(mix32(lo32(seed) + 0x9e3779b9 (bh + 1)) ^ row)
+ *     col_key(seed, col)     = mix32(mix32(hi32(seed) + 0x85ebca6b) ^ col)
+ *     u(seed, bh, row, col)  = mix32(row_key + col_key)            (mod 2^32)
+ *     keep                   = u >= round(p 2^32)
+ * The argument of the last mix is a sum of a row term and a column term; the
+ * pins check that the mix removes that structure (the parity of the keep bits
+ * at the four corners of any rectangle of rows and columns behaves like that
+ * of four independent coin flips).
  * ------------------------------------------------------------------------ */
 static uint32_t mix32(uint32_t x)
 {

@@ -1,5 +1,5 @@
-"""Pins for the oracle's dropout on the attention weights (Section 2.2: the scores are "normalized
-by a dropout and a SoftMax"; read as softmax, then inverted dropout on the weights).
+"""Pins for the oracle's dropout on the attention weights (Section 2.2 names a dropout beside the softmax
+in the normalisation of the scores; read as softmax, then inverted dropout on the weights).
 
 What fixes the right answer: p = 0 is the pinned no-dropout oracle; the keep decision depends on
 positions in the whole sequence, so segments still concatenate to the sequential result (Section
@@ -49,6 +49,29 @@ def test_mask_has_the_statistics_of_independent_coin_flips(p):
         assert abs((a * b).mean() / var) < 5 / np.sqrt(a.size)
     # transposing the roles of row and column gives another mask
     assert abs((c * c.transpose(0, 1, 3, 2)).mean() / var) < 0.02
+
+
+@pytest.mark.parametrize("p", [0.1, 0.5, 0.75])
+def test_rectangles_of_the_mask_are_not_tied_together(p):
+    # The random number of a weight is a mix of (row key + column key): a SEPARABLE input.  If the
+    # final mix were weak, the four corners of a rectangle (r1, c1), (r1, c2), (r2, c1), (r2, c2) would
+    # be tied -- e.g. keep = f(row) xor g(col) gives parity 0 for every rectangle.  For independent coin
+    # flips that keep with probability s = 1 - p, the parity of four of them is odd with probability
+    # (1 - (2s - 1)^4) / 2.  Checked over all rectangles built from neighbouring and from distant rows
+    # and columns, per (batch, head).
+    B, H, l_x = 2, 2, 384
+    m = oracle.dropout_mask(p, 0x0BAD_5EED_0000_0042, 0, l_x, l_x, B, H).astype(np.int64)
+    s_keep = 1.0 - p
+    expect = (1.0 - (2.0 * s_keep - 1.0) ** 4) / 2.0
+    for dr, dc in ((1, 1), (1, 7), (5, 1), (64, 64), (191, 3), (2, 190)):
+        par = (m[:, :, :-dr, :-dc] + m[:, :, dr:, :-dc] + m[:, :, :-dr, dc:] + m[:, :, dr:, dc:]) & 1
+        n = par.size
+        # overlapping rectangles share corners, so their parities are only pairwise weakly dependent:
+        # allow 8 standard deviations of the independent case
+        assert abs(par.mean() - expect) < 8 * np.sqrt(expect * (1 - expect) / n), (dr, dc, par.mean(), expect)
+    # and the same for rectangles that span two heads (same rows and columns, other batch*head key)
+    par = (m[0, 0, :-1, :-1] + m[0, 0, 1:, 1:] + m[1, 1, :-1, :-1] + m[1, 1, 1:, 1:]) & 1
+    assert abs(par.mean() - expect) < 8 * np.sqrt(expect * (1 - expect) / par.size)
 
 
 def test_mask_depends_on_every_part_of_its_key():
