@@ -30,12 +30,27 @@ __device__ __forceinline__ void lds_dma(const void *g_uniform, uint32_t voff, co
                      : "=&s"(saved) : "s"(lds_addr), "v"(voff), "s"(g_uniform) : "memory");
 }
 
+// Chunk permutation of a row-major LDS tile with D bf16 columns (D / 8 chunks of 16 bytes per row): chunk c
+// of row r sits at chunk position c ^ tile_swizzle<D>(r).  The LDS has 64 banks of 4 bytes, i.e. 16
+// chunk-wide bank groups.  D = 64 (rows of 128 bytes, two rows per pass over the banks): r & 7 -- the 16
+// rows of one plain fragment read and the 8 rows x 4 chunks of one transposing read each spread evenly.
+// D = 128 (a row covers all banks once): with r & 7 the 8 rows x 4 chunks of a transposing read fall on 4
+// bank groups per half of the rows (4-way conflicts: 6.4 cycles per instruction measured against 3.2);
+// ((r & 3) << 2) | ((r >> 2) & 3) is a bijection on 16 consecutive rows (plain reads) whose upper two
+// bits take every value twice on 8 consecutive rows (transposing reads).
+template <int D>
+__device__ __forceinline__ int tile_swizzle(int r)
+{
+    static_assert(D == 64 || D == 128, "");
+    return D == 64 ? (r & 7) : (((r & 3) << 2) | ((r >> 2) & 3));
+}
+
 // [ROWS][D] bf16 tile loaded global -> LDS directly (no registers in between), by WAVES wavefronts.
 // One such load instruction moves 16 bytes per lane and writes the wavefront's 64 chunks back to
 // back (1 KB), so rows cannot be padded; instead the 16-byte chunk c of row r sits at chunk
-// position c ^ (r & 7) of its row, which spreads a column of chunks over the LDS banks as padding
-// would.  The permutation is applied on the global side: the lane that fills position p of row r
-// fetches chunk p ^ (r & 7).
+// position c ^ tile_swizzle<D>(r) of its row, which spreads a column of chunks over the LDS banks as
+// padding would.  The permutation is applied on the global side: the lane that fills position p of
+// row r fetches chunk p ^ tile_swizzle<D>(r).
 template <int D, int ROWS, int WAVES = 4>
 struct DirectTile {
     static constexpr int CPR = D / 8;                 // 16-byte chunks per row
@@ -54,7 +69,7 @@ struct DirectTile {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
             const int row = (i * WAVES + wave) * RPI + lane / CPR, pos = lane % CPR;
-            const int chunk = min((pos & ~7) | ((pos ^ row) & 7), chunks_ok - 1);
+            const int chunk = min(pos ^ tile_swizzle<D>(row), chunks_ok - 1);
             off[i] = ((uint32_t)min(row, rows_ok - 1) * (uint32_t)row_stride + (uint32_t)chunk * 8u) * 2u;
         }
     }
@@ -95,7 +110,7 @@ struct DirectTile {
         }
     }
     // byte offset inside the tile of the 16-byte chunk c of row r
-    static __device__ __forceinline__ int chunk_offset(int r, int c) { return r * (D * 2) + (((c & ~7) | ((c ^ r) & 7)) * 16); }
+    static __device__ __forceinline__ int chunk_offset(int r, int c) { return r * (D * 2) + ((c ^ tile_swizzle<D>(r)) * 16); }
 };
 
 // DS_READ_B64_TR_B16: within each group of 16 lanes, lane i receives element (i % 4) of the
@@ -111,18 +126,20 @@ struct DirectTile {
 template <int D>
 __device__ __forceinline__ Frag<bf16_t> load_frag_tr_sw(const char *tile, int row0, int lane_off)
 {
+    // the second read's rows lie 8 further down: the same permutation for D = 64, chunk position ^ 2 for D = 128
     const char *p = tile + row0 * (D * 2) + lane_off;
+    const char *p8 = tile + row0 * (D * 2) + (D == 64 ? lane_off : (lane_off ^ 32)) + 8 * (D * 2);
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 8 * (D * 2)));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p8));
     const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     Frag<bf16_t> f;
     f.v = __builtin_bit_cast(bf16x8, both);
     return f;
 }
 // Byte offset for load_frag_tr_sw, columns [32 db, 32 db + 32): within its group of 16 lanes, lane
-// s addresses row 4*hh + s/4 (+ 8, + row0: neither changes row & 7) and the 8-byte piece (s % 4)
-// of the 32-byte column group nh (hh, nh: bits 1 and 0 of the group index), at the position the
-// chunk permutation of DirectTile gives it.
+// s addresses row 4*hh + s/4 (+ row0, a multiple of 16, which does not change the permutation; + 8 for the
+// second read, see load_frag_tr_sw) and the 8-byte piece (s % 4) of the 32-byte column group nh (hh,
+// nh: bits 1 and 0 of the group index), at the position the chunk permutation of DirectTile gives it.
 template <int D>
 __device__ __forceinline__ int tr_lane_offset_sw(int lane, int db)
 {
@@ -145,6 +162,14 @@ __device__ __forceinline__ bool xcd_item(int id, int bhs, int n_inner, int &bh, 
     inner = rest % n_inner;
     bh = x + kXcds * (rest / n_inner);
     return bh < bhs;
+}
+
+// Address of tile `tile` of a tensor whose tiles lie `tile_bytes` apart (below 2^32: 64 rows of at most 2^23
+// elements): one 32 x 32 -> 64-bit scalar multiply and a 64-bit add, wavefront-uniform.
+template <typename T>
+__device__ __forceinline__ const T *tile_ptr(const T *base, int tile, uint32_t tile_bytes)
+{
+    return reinterpret_cast<const T *>(reinterpret_cast<const char *>(base) + (uint64_t)(uint32_t)tile * tile_bytes);
 }
 
 // Wait until every outstanding vector-memory load of this wave has returned, the direct

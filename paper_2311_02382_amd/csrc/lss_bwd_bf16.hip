@@ -36,14 +36,14 @@ struct DqBf16Cfg {
 // As in the dK/dV kernel below the stages are software-pipelined, step g issuing the matrix
 // instructions of A(g+1) and C(g-1) with the vector work of B(g) spread between them, over a ring
 // of three K/V tiles that are loaded global -> LDS directly, a full loop iteration ahead.
-// D = rowsum(dO * out) of the wavefront's own rows is computed here.
+// -D = -rowsum(dO * out) of the wavefront's rows comes from the preprocess kernel (`Dn`).
 // DROP: dropout on the weights (mask M = keep / (1 - p), decided by drop_keep() of (seed,
 // batch*head, global row, key)): dS = P * (M dP - D).
 template <int D, bool DROP>
 __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const DropArgs &dr, const bf16_t *__restrict__ q,
                                             const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-                                            const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO,
-                                            const float *__restrict__ lse, bf16_t *__restrict__ dq,
+                                            const bf16_t *__restrict__ dO, const float *__restrict__ lse,
+                                            const float *__restrict__ Dn, bf16_t *__restrict__ dq,
                                             float *__restrict__ dq_part, int n_splits, int q_tile, int n_q_tiles, int bh,
                                             int split)
 {
@@ -76,17 +76,12 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
     {
         const int rc = min(r, s.l_s - 1);
         const int64_t off = ((int64_t)b * s.l_s + rc) * ld + (int64_t)h * D + hh * 8;
-        float dsum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < NU; ++kb) {
             qf[kb] = load_frag<bf16_t>(q + off + kb * 16);
             gf[kb] = load_frag<bf16_t>(dO + off + kb * 16);
-            const Frag<bf16_t> of = load_frag<bf16_t>(out + off + kb * 16);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) dsum += (float)gf[kb].v[e] * (float)of.v[e];
         }
-        dsum += __shfl_xor(dsum, 32);
-        Dr = dsum;
+        Dr = -Dn[(int64_t)bh * s.l_s + rc];
         const float lv = lse[(int64_t)bh * s.l_s + rc];
         L2 = row_ok ? lv * kLog2e : INFINITY;
     }
@@ -112,20 +107,32 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
         if (DROP) { drop_rk = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)(s.s0 + r)); drop_cs = drop_col_seed(dr.seed_hi); }
         char *const ck_ring = smem + C::RING * C::SLOT;
 
-        // ---- tile loads, by all four wavefronts
-        uint32_t offF[Tile::NI];                        // this lane's global offsets within a full tile
-        Tile::offsets(offF, ld, C::BC, wave, lane);
+        // ---- tile loads, by all four wavefronts.  Branch-free on purpose: a branch inside a pipeline step
+        // splits it into basic blocks, and the vector work that was meant to sit between the step's
+        // matrix instructions is then moved behind the branch in one lump.
+        uint32_t offF[Tile::NI], offD[Tile::NI];        // this lane's global offsets within a full tile; and what
+        Tile::offsets(offF, ld, C::BC, wave, lane);     // must be added to them in the sequence's last, partial tile
+        const int t_part = s.l_x % C::BC ? s.l_x / C::BC : -1;     // (rows past the end re-read the last row)
+        {
+            uint32_t offL[Tile::NI];
+            Tile::offsets(offL, ld, t_part >= 0 ? s.l_x % C::BC : C::BC, wave, lane);
+#pragma unroll
+            for (int i = 0; i < Tile::NI; ++i) offD[i] = offL[i] - offF[i];
+        }
+        const uint32_t tile_bytes = (uint32_t)(C::BC * ld * 2);
         auto issue_tile = [&](int t, int slot) {
-            const int j0 = t * C::BC, rows_ok = s.l_x - j0;
+            const int j0 = t * C::BC;
+            const uint32_t part = t == t_part ? ~0u : 0u;
             uint32_t off[Tile::NI];
 #pragma unroll
-            for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i];
-            if (rows_ok < C::BC) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
+            for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i] + (offD[i] & part);
             static_assert(C::OFF_V == Tile::BYTES, "V tile follows K tile");
-            Tile::issue_pair(kbase + (int64_t)j0 * ld, vbase + (int64_t)j0 * ld, off, smem + slot * C::SLOT, wave);
+            Tile::issue_pair(tile_ptr(kbase, t, tile_bytes), tile_ptr(vbase, t, tile_bytes), off, smem + slot * C::SLOT, wave);
             if (DROP && wave == 0)
                 reinterpret_cast<uint32_t *>(ck_ring)[(t & 3) * C::BC + lane] = drop_col_key(drop_cs, (uint32_t)(j0 + lane));
         };
+        // the loop's prefetch: tile t + 2, or once more the last tile into a slot nobody reads any more
+        auto issue_ahead = [&](int t, int slot) { issue_tile(t_begin + min(t + 2, T - 1), slot); };
 
         // ---- per-lane LDS offsets (bytes, within a tile)
         int a_off[NU];                                  // A-operand chunk of row lq for operand step kb
@@ -166,10 +173,11 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
         // into P = dS = 0: keys after the lane's row, and keys past the sequence (whose loads
         // re-read its last row).  C-tile element e of this lane is key 8*(e/4) + 4*hh + e%4 of the block.
         auto mask_s = [&](int jb, f32x16 &sc) __attribute__((always_inline)) {
-            const bool diag = s.causal && (jb + 31 > s.s0 + rw0);
+            // (positions are below 2^30, checked on the host: 32-bit scalar compares, no vector work per step)
+            const bool diag = s.causal && (jb + 31 > (int)s.s0 + rw0);
             if (diag || jb + 32 > s.l_x) {
-                const int64_t last = s.causal ? min<int64_t>(s.s0 + r, s.l_x - 1) : (int64_t)s.l_x - 1;
-                const int rel = (int)max<int64_t>(min<int64_t>(last - jb - 4 * hh, 64), -1);
+                const int last = s.causal ? min((int)s.s0 + r, s.l_x - 1) : s.l_x - 1;
+                const int rel = max(min(last - jb - 4 * hh, 64), -1);
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
                     if (8 * (e >> 2) + (e & 3) > rel) sc[e] = -INFINITY;
@@ -253,9 +261,10 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
                 const int prv = cur == 0 ? C::RING - 1 : cur - 1;
                 wait_vmem_all();
                 __syncthreads();
-                if (t + 2 < T) issue_tile(t_begin + t + 2, prv);
+                issue_ahead(t, prv);
                 cur = cur == C::RING - 1 ? 0 : cur + 1;
             }
+            wait_vmem_all();                            // the last, redundant prefetches must land before the workgroup's LDS is given away
             return;
         }
 
@@ -285,7 +294,7 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
                  t_a2, 0, t_cur, 0, [&] {
                      wait_vmem_all();
                      __syncthreads();
-                     if (t + 2 < T) issue_tile(t_begin + t + 2, prv);
+                     issue_ahead(t, prv);
                  });
             // odd step g = 2t+1: A(2t+2) [tile t+1, first half; past the end result unused], B(2t+1),
             // C(2t) [tile t, first half]
@@ -299,6 +308,7 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
             step(false_type{}, false_type{}, true_type{}, smem, 0, sc0, dp0, sc0, dp0, 0, df0, t_last, 1, df1, smem, 0, t_last,
                  1, nothing);
         }
+        wait_vmem_all();                                // the last, redundant prefetches must land before the workgroup's LDS is given away
     }
 
     if (!row_ok) return;
@@ -454,24 +464,34 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
     const uint32_t *rbase = DROP ? row_key + (int64_t)bh * s.l_s : nullptr;
     const uint32_t drop_ck = DROP ? drop_col_key(drop_col_seed(dr.seed_hi), (uint32_t)j) : 0u;  // this lane's key
 
-    // ---- tile loads: all four wavefronts move Q and dO; wavefronts 0 and 1 also the 64 start values
-    uint32_t offF[Tile::NI];                            // this lane's global offsets within a full tile
-    Tile::offsets(offF, ld, C::BQ, wave, lane);
-    auto issue_tile = [&](int rq0, int slot) {
-        const int rows_ok = s.l_s - rq0;
+    // ---- tile loads: all four wavefronts move Q and dO, and the 64 start values of either kind (even
+    // wavefronts -lse*sqrt(d), odd ones -D; each twice, which is cheaper than a branch inside a pipeline
+    // step: a branch splits the step into basic blocks, and the vector work meant to sit between its
+    // matrix instructions is then moved behind the branch in one lump)
+    uint32_t offF[Tile::NI], offD[Tile::NI];            // this lane's global offsets within a full tile; and what
+    Tile::offsets(offF, ld, C::BQ, wave, lane);         // must be added to them in the segment's last, partial tile
+    const int tq_part = s.l_s % C::BQ ? s.l_s / C::BQ : -1;        // (rows past the end re-read the last row)
+    {
+        uint32_t offL[Tile::NI];
+        Tile::offsets(offL, ld, tq_part >= 0 ? s.l_s % C::BQ : C::BQ, wave, lane);
+#pragma unroll
+        for (int i = 0; i < Tile::NI; ++i) offD[i] = offL[i] - offF[i];
+    }
+    const uint32_t tile_bytes = (uint32_t)(C::BQ * ld * 2);
+    const float *const sv_base = (wave & 1) ? dbase : lbase;
+    const int sv_off = (wave & 1) ? C::OFF_D : C::OFF_L;
+    auto issue_tile = [&](int tq, int slot) {           // tile tq = query rows [64 tq, 64 tq + 64) of the segment
+        const int rq0 = tq * C::BQ;
+        const uint32_t part = tq == tq_part ? ~0u : 0u;
         uint32_t off[Tile::NI];
 #pragma unroll
-        for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i];
-        if (rows_ok < C::BQ) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
+        for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i] + (offD[i] & part);
         static_assert(C::OFF_G == Tile::BYTES, "dO tile follows Q tile");
         char *dst = smem + slot * C::SLOT;
-        Tile::issue_pair(qbase + (int64_t)rq0 * ld, gbase + (int64_t)rq0 * ld, off, dst, wave);
-        if (wave < 2) {
-            const float *src = (wave == 0 ? lbase : dbase) + rq0;
-            const uint32_t ro = (uint32_t)min(lane, rows_ok - 1) * 4u;
-            lds_dma<4>(src, ro, dst + (wave == 0 ? C::OFF_L : C::OFF_D));
-        }
-        if (DROP && wave == 2) lds_dma<4>(rbase + rq0, (uint32_t)min(lane, rows_ok - 1) * 4u, dst + C::OFF_R);
+        Tile::issue_pair(tile_ptr(qbase, tq, tile_bytes), tile_ptr(gbase, tq, tile_bytes), off, dst, wave);
+        const uint32_t ro = (uint32_t)min(lane, s.l_s - rq0 - 1) * 4u;
+        lds_dma<4>(sv_base + rq0, ro, dst + sv_off);
+        if (DROP && wave == 2) lds_dma<4>(rbase + rq0, ro, dst + C::OFF_R);
     };
 
     // ---- per-lane LDS offsets (bytes, within a tile)
@@ -509,9 +529,9 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
     // r0), the masked elements start at -inf instead, which B turns into P = dS = 0: rows before
     // the lane's key, and rows past the segment (whose loads re-read its last row).
     auto init_mask = [&](int r0, f32x16 &sc) __attribute__((always_inline)) {
-        const bool diag = s.causal && ((int64_t)jw0 + C::KW - 1 > s.s0 + r0);
+        const bool diag = s.causal && (jw0 + C::KW - 1 > (int)s.s0 + r0);      // positions are below 2^30: 32-bit scalar compare
         if (diag || r0 + 32 > s.l_s) {
-            const int first = diag ? (int)max<int64_t>(min<int64_t>((int64_t)j - s.s0 - r0 - 4 * hh, 64), 0) : 0;
+            const int first = diag ? max(min(j - (int)s.s0 - r0 - 4 * hh, 64), 0) : 0;
             const int end = min(s.l_s - r0, 32) - 4 * hh;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
@@ -625,9 +645,11 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
     using std::false_type;
 
     // ---- pipeline.  Block g of this workgroup = rows rq_begin + 32 g ..; tile t = blocks 2t, 2t+1.
-    const int T = (s.l_s - rq_begin + C::BQ - 1) / C::BQ;
-    issue_tile(rq_begin, 0);
-    if (T > 1) issue_tile(rq_begin + C::BQ, 1);
+    const int T = (s.l_s - rq_begin + C::BQ - 1) / C::BQ, tq_begin = rq_begin / C::BQ;
+    // the loop's prefetch: tile t + 2, or once more the last tile into a slot nobody reads any more
+    auto issue_ahead = [&](int t, int slot) { issue_tile(tq_begin + min(t + 2, T - 1), slot); };
+    issue_tile(tq_begin, 0);
+    if (T > 1) issue_tile(tq_begin + 1, 1);
     wait_vmem_all();
     __syncthreads();
 
@@ -658,7 +680,7 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
              t > 0 ? t_prv : t_cur, 1, pf1, df1, t_a2, 0, t_cur, 0, [&] {
                  wait_vmem_all();
                  __syncthreads();
-                 if (t + 2 < T) issue_tile(rq_begin + (t + 2) * C::BQ, prv);
+                 issue_ahead(t, prv);
              });
         // odd step g = 2t+1: A(2t+2) [tile t+1, first half; past the end result unused], B(2t+1),
         // C(2t) [tile t, first half]
@@ -673,7 +695,8 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
              df1, smem, 0, t_last, 1, nothing);
     }
 
-    // the ring is free once every wavefront has made its last reads
+    // the ring is free once every wavefront has made its last reads and the last, redundant prefetches have landed
+    wait_vmem_all();
     __syncthreads();
     {
         char *buf = smem + wave * (32 * D * 4);
@@ -788,9 +811,9 @@ __device__ __forceinline__ void bwd_dkv_skinny_body(char *smem, const SegShape &
                     for (int i = 0; i < 4; ++i) { sc[4 * e4 + i] = l4[i]; dp[4 * e4 + i] = d4[i]; }
                 }
                 {
-                    const bool diag = s.causal && ((int64_t)jw0 + C::KW - 1 > s.s0 + r0);
+                    const bool diag = s.causal && (jw0 + C::KW - 1 > (int)s.s0 + r0);
                     if (diag || r0 + 32 > s.l_s) {
-                        const int first = diag ? (int)max<int64_t>(min<int64_t>((int64_t)j - s.s0 - r0 - 4 * hh, 64), 0) : 0;
+                        const int first = diag ? max(min(j - (int)s.s0 - r0 - 4 * hh, 64), 0) : 0;
                         const int end = min(s.l_s - r0, 32) - 4 * hh;
 #pragma unroll
                         for (int e = 0; e < 16; ++e) {
@@ -905,7 +928,7 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
         else bwd_dkv_body<D, DROP>(smem, s, dr, q, k, v, dO, Ls, Dn, row_key, dk_part, dv_part, bh, inner);
     } else {
         if (!xcd_item(id, bhs, n_q_tiles * n_splits, bh, inner)) return;
-        bwd_dq_body<D, DROP>(smem, s, dr, q, k, v, out, dO, lse, dq, dq_part, n_splits, inner % n_q_tiles, n_q_tiles, bh,
+        bwd_dq_body<D, DROP>(smem, s, dr, q, k, v, dO, lse, Dn, dq, dq_part, n_splits, inner % n_q_tiles, n_q_tiles, bh,
                              inner / n_q_tiles);
     }
 }

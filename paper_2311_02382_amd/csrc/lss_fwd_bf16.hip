@@ -104,20 +104,32 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
         if (DROP) { drop_rk = drop_row_key(dr.seed_lo, (uint32_t)bh, (uint32_t)(s.s0 + r)); drop_cs = drop_col_seed(dr.seed_hi); }
         char *const ck_ring = smem + C::RING * C::SLOT;
 
-        // ---- tile loads, by all four wavefronts
-        uint32_t offF[Tile::NI];                        // this lane's global offsets within a full tile
-        Tile::offsets(offF, ld, C::BC, wave, lane);
+        // ---- tile loads, by all four wavefronts.  Branch-free on purpose: a branch inside a pipeline step
+        // splits it into basic blocks, and the vector work that was meant to sit between the step's
+        // matrix instructions is then moved behind the branch in one lump.
+        uint32_t offF[Tile::NI], offD[Tile::NI];        // this lane's global offsets within a full tile; and what
+        Tile::offsets(offF, ld, C::BC, wave, lane);     // must be added to them in the sequence's last, partial tile
+        const int t_part = s.l_x % C::BC ? s.l_x / C::BC : -1;     // (rows past the end re-read the last row)
+        {
+            uint32_t offL[Tile::NI];
+            Tile::offsets(offL, ld, t_part >= 0 ? s.l_x % C::BC : C::BC, wave, lane);
+#pragma unroll
+            for (int i = 0; i < Tile::NI; ++i) offD[i] = offL[i] - offF[i];
+        }
+        const uint32_t tile_bytes = (uint32_t)(C::BC * ld * 2);
         auto issue_tile = [&](int t, int slot) {
-            const int j0 = t * C::BC, rows_ok = s.l_x - j0;
+            const int j0 = t * C::BC;
+            const uint32_t part = t == t_part ? ~0u : 0u;
             uint32_t off[Tile::NI];
 #pragma unroll
-            for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i];
-            if (rows_ok < C::BC) Tile::offsets(off, ld, rows_ok, wave, lane);   // last, partial tile: clamp rows
+            for (int i = 0; i < Tile::NI; ++i) off[i] = offF[i] + (offD[i] & part);
             static_assert(C::OFF_V == Tile::BYTES, "V tile follows K tile");
-            Tile::issue_pair(kbase + (int64_t)j0 * ld, vbase + (int64_t)j0 * ld, off, smem + slot * C::SLOT, wave);
+            Tile::issue_pair(tile_ptr(kbase, t, tile_bytes), tile_ptr(vbase, t, tile_bytes), off, smem + slot * C::SLOT, wave);
             if (DROP && wave == 0)
                 reinterpret_cast<uint32_t *>(ck_ring)[(t & 3) * C::BC + lane] = drop_col_key(drop_cs, (uint32_t)(j0 + lane));
         };
+        // the loop's prefetch: tile t + 2, or once more the last tile into a slot nobody reads any more
+        auto issue_ahead = [&](int t, int slot) { issue_tile(t_begin + min(t + 2, T - 1), slot); };
 
         // ---- per-lane LDS offsets (bytes, within a tile)
         int a_off[NU];                                  // A-operand chunk of row lq for operand step kb
@@ -140,10 +152,11 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
         // 0: keys after the lane's row, and keys past the sequence (whose loads re-read its last
         // row).  C-tile element e of this lane is key 8*(e/4) + 4*hh + e%4 of the block.
         auto mask_s = [&](int jb, f32x16 &sc) __attribute__((always_inline)) {
-            const bool diag = s.causal && (jb + 31 > s.s0 + rw0);
+            // (positions are below 2^30, checked on the host: 32-bit scalar compares, no vector work per step)
+            const bool diag = s.causal && (jb + 31 > (int)s.s0 + rw0);
             if (diag || jb + 32 > s.l_x) {
-                const int64_t last = s.causal ? min<int64_t>(s.s0 + r, s.l_x - 1) : (int64_t)s.l_x - 1;
-                const int rel = (int)max<int64_t>(min<int64_t>(last - jb - 4 * hh, 64), -1);
+                const int last = s.causal ? min((int)s.s0 + r, s.l_x - 1) : s.l_x - 1;
+                const int rel = max(min(last - jb - 4 * hh, 64), -1);
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
                     if (8 * (e >> 2) + (e & 3) > rel) sc[e] = -INFINITY;
@@ -268,9 +281,10 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
                 const int prv = cur == 0 ? C::RING - 1 : cur - 1;
                 wait_vmem_all();
                 __syncthreads();
-                if (t + 2 < T) issue_tile(t_begin + t + 2, prv);
+                issue_ahead(t, prv);
                 cur = cur == C::RING - 1 ? 0 : cur + 1;
             }
+            wait_vmem_all();                            // the last, redundant prefetches must land before the workgroup's LDS is given away
             return;
         }
 
@@ -300,7 +314,7 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
                  t_cur, 0, [&] {
                      wait_vmem_all();
                      __syncthreads();
-                     if (t + 2 < T) issue_tile(t_begin + t + 2, prv);
+                     issue_ahead(t, prv);
                  });
             // odd step g = 2t+1: A(2t+2) [tile t+1, first half; past the end result unused], B(2t+1),
             // C(2t) [tile t, first half]
@@ -313,6 +327,7 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
             const char *t_last = smem + (cur == 0 ? C::RING - 1 : cur - 1) * C::SLOT;
             step(false_type{}, false_type{}, true_type{}, smem, 0, sc0, sc0, 0, pf0, t_last, 1, pf1, smem, 0, t_last, 1, nothing);
         }
+        wait_vmem_all();                                // the last, redundant prefetches must land before the workgroup's LDS is given away
     }
 
     const float l_tot = l + __shfl_xor(l, 32);
