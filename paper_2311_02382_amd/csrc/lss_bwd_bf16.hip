@@ -154,18 +154,25 @@ __device__ __forceinline__ void bwd_dq_body(char *smem, const SegShape &s, const
         };
         // B for elements [e0, e1): P = 2^(c * S - lse * log2 e), dS = P * (dP - D); finished pairs are
         // rounded to bf16 into the operand fragments of C
+        // An element's exponential and the multiply that consumes it are issued one element apart (the
+        // multiply of element e - 1 follows the exponential of element e): a transcendental's result may not
+        // be read by the very next instruction, and the slot that would otherwise idle is not free.
         u32x4 ck4;      // dropout: the column keys of four consecutive elements, read when the first is due
         auto b_elems = [&](f32x16 &sc, f32x16 &dp, int jb, int e0, int e1, Frag<bf16_t> (&df)[2]) __attribute__((always_inline)) {
+            auto finish = [&](int i) __attribute__((always_inline)) {       // sc[i] holds P by now
+                if (DROP) {     // dp holds dP - D; element i of this lane is key jb + 8 (i / 4) + 4 hh + i % 4
+                    if ((i & 3) == 0)
+                        ck4 = *reinterpret_cast<const u32x4 *>(ck_ring + (((jb >> 6) & 3) * C::BC + (jb & 63) + 8 * (i >> 2) + 4 * hh) * 4);
+                    dp[i] = drop_keep(drop_rk, ck4[i & 3], dr.thr) ? (dp[i] + Dr) * dr.scale - Dr : -Dr;
+                }
+                dp[i] = sc[i] * dp[i];
+                if (i & 1) { df[i >> 3].v[(i & 7) - 1] = (bf16_t)dp[i - 1]; df[i >> 3].v[i & 7] = (bf16_t)dp[i]; }
+            };
 #pragma unroll
             for (int e = e0; e < e1; ++e) {
-                const float p = fast_exp2(sc[e] * c - L2);
-                if (DROP) {     // dp holds dP - D; element e of this lane is key jb + 8 (e / 4) + 4 hh + e % 4
-                    if ((e & 3) == 0)
-                        ck4 = *reinterpret_cast<const u32x4 *>(ck_ring + (((jb >> 6) & 3) * C::BC + (jb & 63) + 8 * (e >> 2) + 4 * hh) * 4);
-                    dp[e] = drop_keep(drop_rk, ck4[e & 3], dr.thr) ? (dp[e] + Dr) * dr.scale - Dr : -Dr;
-                }
-                dp[e] = p * dp[e];
-                if (e & 1) { df[e >> 3].v[(e & 7) - 1] = (bf16_t)dp[e - 1]; df[e >> 3].v[e & 7] = (bf16_t)dp[e]; }
+                sc[e] = fast_exp2(sc[e] * c - L2);
+                if (e > 0) finish(e - 1);
+                if (e == 15) finish(15);
             }
         };
         // Where the causal diagonal or the end of the sequence crosses a block (first key jb), the
@@ -544,29 +551,35 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
     // rounded to bf16 into the operand fragments of C
     // (dropout: `tile_b`, `qb_b` name B's block; the row keys and -D of four elements are read when
     // the first of them is due)
+    // (An element's exponential and the multiplies that consume it are issued one element apart, as in the dQ
+    // workgroups: a transcendental's result may not be read by the very next instruction.)
     u32x4 rk4;
     f32x4 nd4;
     auto b_elems = [&](const char *tile_b, int qb_b, f32x16 &sc, f32x16 &dp, int e0, int e1, Frag<bf16_t> (&pf)[2],
                        Frag<bf16_t> (&df)[2]) __attribute__((always_inline)) {
+        auto finish = [&](int i) __attribute__((always_inline)) {           // sc[i] holds P by now
+            if constexpr (DROP) {
+                if ((i & 3) == 0) {
+                    rk4 = *reinterpret_cast<const u32x4 *>(tile_b + C::OFF_R + (qb_b * 32 + 8 * (i >> 2) + 4 * hh) * 4);
+                    nd4 = *reinterpret_cast<const f32x4 *>(tile_b + C::OFF_D + (qb_b * 32 + 8 * (i >> 2) + 4 * hh) * 4);
+                }
+                const float p = sc[i];
+                const float a = drop_keep(rk4[i & 3], drop_ck, dr.thr) ? p * dr.scale : 0.f;
+                sc[i] = a;
+                dp[i] = a * dp[i] + (p - a) * nd4[i & 3];
+            } else {
+                dp[i] = sc[i] * dp[i];
+            }
+            if (i & 1) {
+                pf[i >> 3].v[(i & 7) - 1] = (bf16_t)sc[i - 1]; pf[i >> 3].v[i & 7] = (bf16_t)sc[i];
+                df[i >> 3].v[(i & 7) - 1] = (bf16_t)dp[i - 1]; df[i >> 3].v[i & 7] = (bf16_t)dp[i];
+            }
+        };
 #pragma unroll
         for (int e = e0; e < e1; ++e) {
-            const float p = fast_exp2(sc[e] * c);
-            if constexpr (DROP) {
-                if ((e & 3) == 0) {
-                    rk4 = *reinterpret_cast<const u32x4 *>(tile_b + C::OFF_R + (qb_b * 32 + 8 * (e >> 2) + 4 * hh) * 4);
-                    nd4 = *reinterpret_cast<const f32x4 *>(tile_b + C::OFF_D + (qb_b * 32 + 8 * (e >> 2) + 4 * hh) * 4);
-                }
-                const float a = drop_keep(rk4[e & 3], drop_ck, dr.thr) ? p * dr.scale : 0.f;
-                sc[e] = a;
-                dp[e] = a * dp[e] + (p - a) * nd4[e & 3];
-            } else {
-                sc[e] = p;
-                dp[e] = p * dp[e];
-            }
-            if (e & 1) {
-                pf[e >> 3].v[(e & 7) - 1] = (bf16_t)sc[e - 1]; pf[e >> 3].v[e & 7] = (bf16_t)sc[e];
-                df[e >> 3].v[(e & 7) - 1] = (bf16_t)dp[e - 1]; df[e >> 3].v[e & 7] = (bf16_t)dp[e];
-            }
+            sc[e] = fast_exp2(sc[e] * c);
+            if (e > 0) finish(e - 1);
+            if (e == 15) finish(15);
         }
     };
     // One pipeline step.  A: block (tile_a, qb_a), first row r0_a, into (sc_a, dp_a).  B: (sc_b, dp_b),
