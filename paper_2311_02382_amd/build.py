@@ -1,6 +1,7 @@
 """Builds liblss_attn.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
 
-    python -m paper_2311_02382_amd.build
+    python -m paper_2311_02382_amd.build                # the library
+    python -m paper_2311_02382_amd.build --microbench   # also lss_microbench (issue-rate microbenchmarks, a stand-alone program)
 
 hipcc cross-compiles without a GPU.  The library lands next to this file so that it
 travels with the source tree; nothing is installed.
@@ -62,6 +63,23 @@ def build_library(verbose: bool = True) -> Path:
     return LIB
 
 
+MICROBENCH = PKG / "lss_microbench"
+
+
+def build_microbench(verbose: bool = True) -> Path:
+    """Compile csrc/lss_microbench.hip into the stand-alone program lss_microbench."""
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-mllvm", "-amdgpu-mfma-vgpr-form", str(CSRC / "lss_microbench.hip"), "-o", str(MICROBENCH)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on lss_microbench.hip:\n{r.stderr}")
+    if verbose:
+        print(f"built {MICROBENCH}")
+    return MICROBENCH
+
+
 if __name__ == "__main__":
     build_library()
+    if "--microbench" in sys.argv[1:]:
+        build_microbench()
     sys.exit(0)
