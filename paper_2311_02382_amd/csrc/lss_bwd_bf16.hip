@@ -922,7 +922,7 @@ __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(SegShape s, DropArgs
 template <int D, bool DROP, bool SKINNY = false>
 __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_main_bf16_kernel(
     SegShape s, DropArgs dr, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const bf16_t *__restrict__ out, const bf16_t *__restrict__ dO, const float *__restrict__ lse,
+    const bf16_t *__restrict__ dO, const float *__restrict__ lse,
     const float *__restrict__ Ls, const float *__restrict__ Dn, const uint32_t *__restrict__ row_key, bf16_t *__restrict__ dq,
     float *__restrict__ dq_part, float *__restrict__ dk_part, float *__restrict__ dv_part, int n_splits, int n_dq, int n_q_tiles,
     int n_key_tiles)
@@ -973,13 +973,13 @@ static hipError_t launch_bwd_bf16_d(const SegShape &s, const DropArgs &drop, con
         const dim3 grid((unsigned)(n_dkv + n_dq));
         TimedLaunch tl(K_BWD_MAIN_BF16, st);
         if (skinny)
-            hipLaunchKernelGGL((bwd_main_bf16_kernel<D, false, true>), grid, dim3(256), 0, st, s, drop, q, k, v, out, dO, lse, ws.Ls,
+            hipLaunchKernelGGL((bwd_main_bf16_kernel<D, false, true>), grid, dim3(256), 0, st, s, drop, q, k, v, dO, lse, ws.Ls,
                                ws.D, ws.row_key, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);
         else if (with_drop)
-            hipLaunchKernelGGL((bwd_main_bf16_kernel<D, true>), grid, dim3(256), 0, st, s, drop, q, k, v, out, dO, lse, ws.Ls, ws.D,
+            hipLaunchKernelGGL((bwd_main_bf16_kernel<D, true>), grid, dim3(256), 0, st, s, drop, q, k, v, dO, lse, ws.Ls, ws.D,
                                ws.row_key, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);
         else
-            hipLaunchKernelGGL((bwd_main_bf16_kernel<D, false>), grid, dim3(256), 0, st, s, drop, q, k, v, out, dO, lse, ws.Ls, ws.D,
+            hipLaunchKernelGGL((bwd_main_bf16_kernel<D, false>), grid, dim3(256), 0, st, s, drop, q, k, v, dO, lse, ws.Ls, ws.D,
                                ws.row_key, dq, ws.dq_part, dk_part, dv_part, n_splits, n_dq, n_q_tiles, n_key_tiles);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
