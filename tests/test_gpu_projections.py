@@ -103,8 +103,13 @@ def test_whole_chain_matches_oracle(causal):
     total = lss.lss_reduce_partials([p.view(B, l_x, 1, E) for p in parts], rows_valid).view(B, l_x, E)
     dx += total
     ref_dx += oracle.reduce_partials(ref_parts)
-    assert rel_err(to_np(total), oracle.reduce_partials(ref_parts)) <= 2 * TOL["bf16"]["t"]
-    assert rel_err(to_np(dx), ref_dx) <= 2 * TOL["bf16"]["t"]
+    # The 2e-2 that the benchmark spec states is for the attention's own tensors (O, dQ, dK, dV against bf16 inputs).  This
+    # chain rounds to bf16 at every stage on the way (Q, K, V, E, dQ, the partials as operands): its bound is twice
+    # the single-stage one.  The measured errors are printed so that the margin is on record.
+    e_total, e_dx = rel_err(to_np(total), oracle.reduce_partials(ref_parts)), rel_err(to_np(dx), ref_dx)
+    print(f"whole chain causal={causal}: sum of dx partials err {e_total:.2e}, dx err {e_dx:.2e} (bound {2 * TOL['bf16']['t']:.0e})")
+    assert e_total <= 2 * TOL["bf16"]["t"]
+    assert e_dx <= 2 * TOL["bf16"]["t"]
 
 
 def test_projections_bitwise_reproducible_and_empty_segment():
