@@ -12,6 +12,10 @@
 //   5. co-issue with LDS reads: per matrix instruction 3 fma + 1 exp2 and NL DS_READ_B128 whose data feeds the matrix
 //      instructions of the NEXT iteration (two register sets, explicit waits), so only their issue and the LDS
 //      pipeline count, not their latency;
+//   6. the matrix pipe's sustained rate against the DATA and the instruction mix: the same loop of matrix instructions
+//      on constant operands (all ones) and on random ones, then on random ones with the vector work of a softmax
+//      beside each matrix instruction; every launch is long enough (10 ms) for the chip's power management to settle
+//      the clock, and the figure is wall time, so it includes that clock;
 //   4. LDS fragment reads: DS_READ_B128 by rows and DS_READ_B64_TR_B16 (transposing) on tiles with 128- and
 //      256-byte rows under the chunk permutations of lss_bf16.h (tile_swizzle) and under the plain r & 7 one.
 // Every kernel touches only registers and its own LDS; cycle counts come from clock64() of one wavefront.
@@ -175,6 +179,58 @@ static void run_lds_issue(float *d, long long *dc, const char *name)
     printf("\n");
 }
 
+// ---- section 6: data dependence of the sustained matrix rate
+__device__ uint32_t mix_u32(uint32_t x) { x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; return x ^ (x >> 16); }
+template <int RANDOM, int NV, int NT>
+__global__ __launch_bounds__(256) void data_kernel(float *out, int iters)
+{
+    bf16x8 a[8], b[8];      // eight fragments each; every instruction pairs another two
+    for (int j = 0; j < 8; ++j)
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t h = mix_u32(threadIdx.x * 977u + blockIdx.x * 131u + j * 17u + i);
+            a[j][i] = (__bf16)(RANDOM ? ((int)(h & 0xffff) - 32768) * (1.0f / 16384.f) : 1.0f);
+            b[j][i] = (__bf16)(RANDOM ? ((int)(h >> 16) - 32768) * (1.0f / 16384.f) : 1.0f);
+        }
+    f32x16 c[4];
+    for (int j = 0; j < 4; ++j) for (int i = 0; i < 16; ++i) c[j][i] = 0.f;
+    float x[16], y[16];     // independent chains of fma and of exp2 (kept bounded)
+    for (int i = 0; i < 16; ++i) { x[i] = threadIdx.x * 1e-3f + i; y[i] = threadIdx.x * 1e-4f + i * 0.01f; }
+    const float fa = 1.0001f, fb = 1e-4f;
+    for (int it = 0; it < iters; it += 8) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            int vi = 0, ti = 0;
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                c[m & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[(m + r) & 7], c[m & 3], 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < NV; ++j) { x[vi & 15] = __builtin_fmaf(x[vi & 15], fa, fb); ++vi; }
+#pragma unroll
+                for (int j = 0; j < NT; ++j) { y[ti & 15] = __builtin_amdgcn_exp2f(y[ti & 15] * 0.5f - 1.0f); ++ti; }
+            }
+        }
+    }
+    float s = 0.f;
+    for (int j = 0; j < 4; ++j) for (int i = 0; i < 16; ++i) s += c[j][i];
+    for (int i = 0; i < 16; ++i) s += x[i] + y[i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+template <int RANDOM, int NV = 0, int NT = 0>
+static void run_data(float *d, const char *name)
+{
+    const int iters = 40000;        // x 8 instructions x 32 cycles x 2 wavefronts per SIMD: about 10 ms
+    data_kernel<RANDOM, NV, NT><<<512, 256>>>(d, 1000);
+    CHECK(hipDeviceSynchronize());
+    const auto w0 = std::chrono::steady_clock::now();
+    data_kernel<RANDOM, NV, NT><<<512, 256>>>(d, iters);
+    CHECK(hipDeviceSynchronize());
+    const double us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - w0).count();
+    const double flops = 512.0 * 4 * iters * 8 * 32768.0;
+    printf("%-44s  %6.2f ms  %5.0f TFLOP/s  (= %4.2f GHz at 32 cycles per instruction)\n", name, us / 1e3, flops / (us * 1e-6) / 1e12,
+           flops / (us * 1e-6) / (256.0 * 4 * 1024.0) / 1e9);
+}
+
 // ---- section 4: LDS fragment reads
 template <int MODE, int D>
 __device__ int chunk_off(int r, int c)
@@ -269,6 +325,15 @@ int main()
     printf("# 5. as 3., operands of the matrix instructions read from LDS one iteration ahead (ds_read_b128 per matrix instruction)\n");
     run_lds_issue<0>(d, dc, "mfma + 3 fma + 1 exp2, no LDS read");
     run_lds_issue<1>(d, dc, "mfma + 3 fma + 1 exp2 + 1 ds_read_b128");
+    printf("# 6. a loop of matrix instructions, two wavefronts per SIMD, wall time of a 10 ms launch (clock included)\n");
+    run_data<0>(d, "constant operands (all ones)");
+    run_data<1>(d, "random operands in [-2, 2)");
+    run_data<1, 3, 1>(d, "random, + 3 fma + 1 exp2 per instruction");
+    run_data<1, 6, 2>(d, "random, + 6 fma + 2 exp2 per instruction");
+    run_data<0>(d, "constant operands (all ones), again");
+    run_data<1>(d, "random operands in [-2, 2), again");
+    run_data<1, 3, 1>(d, "random, + 3 fma + 1 exp2, again");
+    run_data<1, 6, 2>(d, "random, + 6 fma + 2 exp2, again");
     printf("# 4. LDS fragment reads, [rows][D] bf16 tiles, time per wave-instruction per compute unit\n");
     run_lds<0, 64, 0>(d, "ds_read_b128 by rows, D=64, r&7");
     run_lds<0, 128, 0>(d, "ds_read_b128 by rows, D=128, r&7");
