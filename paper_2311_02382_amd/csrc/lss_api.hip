@@ -29,23 +29,60 @@ int choose_splits(int l_s, int l_x, int B, int H, int rows_per_wg)
     return (int)want;
 }
 
+int max_fwd_splits(int l_s, int l_x, int B, int H, int rows_per_wg)
+{
+    // up to four workgroups per compute unit; a split needs >= 4 key tiles
+    const int64_t wgs = (int64_t)((l_s + rows_per_wg - 1) / rows_per_wg) * B * H;
+    if (wgs <= 0) return 1;
+    int64_t most = (1024 + wgs - 1) / wgs;
+    const int64_t tiles = (l_x + 63) / 64;
+    if (most > tiles / 4) most = tiles / 4;
+    if (most > 16) most = 16;
+    return most < 1 ? 1 : (int)most;
+}
+
+int fwd_wgs_per_cu(int elem_bytes, int d) { return elem_bytes == 2 ? (d == 64 ? 3 : 1) : 2; }
+
+int pick_fwd_splits(int l_s, int B, int H, int rows_per_wg, int64_t kv_tiles, int max_splits, int resident)
+{
+    // Measured on the bf16 forward kernels (8..2048 query tiles, 1..16 splits), in units of the time a
+    // lone workgroup takes per 64-key tile (0.77 us at d = 64): a launch takes about
+    //   (key tiles per workgroup + 8) x g(n) + 6 if split,   n = workgroups per compute unit, rounded up,
+    // 8 for a workgroup's start and results, 6 for the merge launch, g(1) = 1 and g(n) = 0.17 + 0.65 n
+    // where several workgroups share a compute unit (a second co-resident workgroup adds about a
+    // third of a workgroup's throughput), g(n) = n where only one fits.  What matters most is
+    // that the workgroup count lands just below a multiple of the 256 compute units.  The smallest
+    // count within 3 % of the best estimate is taken.
+    const int64_t wgs = (int64_t)((l_s + rows_per_wg - 1) / rows_per_wg) * B * H;
+    if (wgs <= 0 || max_splits <= 1) return 1;
+    double best = 0.0;
+    int best_s = 1;
+    for (int sp = 1; sp <= max_splits; ++sp) {
+        if (sp > 1 && kv_tiles / sp < 8) break;        // shorter splits cost more than they gain
+        const int64_t per_cu = (wgs * sp + 255) / 256;
+        const double g = per_cu <= 1 ? 1.0 : resident <= 1 ? (double)per_cu : 0.17 + 0.65 * (double)per_cu;
+        const double t = ((double)((kv_tiles + sp - 1) / sp) + 8.0) * g + (sp > 1 ? 6.0 : 0.0);
+        if (sp == 1 || t < 0.97 * best) { best = t; best_s = sp; }
+    }
+    return best_s;
+}
+
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout { size_t o_part, lse_part, D, Ls, dq_part, row_key, total; };
 static WsLayout ws_layout(int l_s, int l_x, int B, int H, int d, int elem_bytes)
 {
     // forward and dQ kernels may use different tile heights, hence different split counts
-    const size_t sp_f = (size_t)choose_splits(l_s, l_x, B, H, fwd_rows_per_wg(elem_bytes, d));
+    const size_t sp_f = (size_t)max_fwd_splits(l_s, l_x, B, H, fwd_rows_per_wg(elem_bytes, d));
     const size_t sp_q = (size_t)choose_splits(l_s, l_x, B, H, dq_rows_per_wg(elem_bytes, d));
-    const size_t sp = sp_f > sp_q ? sp_f : sp_q;
     const size_t rows = (size_t)B * H * l_s;
     WsLayout w;
     size_t off = 0;
-    w.o_part = off;   off += align256(sp > 1 ? sp * rows * d * sizeof(float) : 0);
-    w.lse_part = off; off += align256(sp > 1 ? sp * rows * sizeof(float) : 0);
+    w.o_part = off;   off += align256(sp_f > 1 ? sp_f * rows * d * sizeof(float) : 0);
+    w.lse_part = off; off += align256(sp_f > 1 ? sp_f * rows * sizeof(float) : 0);
     w.D = off;        off += align256(rows * sizeof(float));
     w.Ls = off;       off += align256(rows * sizeof(float));
-    w.dq_part = off;  off += align256(sp > 1 ? sp * rows * d * sizeof(float) : 0);
+    w.dq_part = off;  off += align256(sp_q > 1 ? sp_q * rows * d * sizeof(float) : 0);
     w.row_key = off;  off += align256(rows * sizeof(uint32_t));
     w.total = off;
     return w;

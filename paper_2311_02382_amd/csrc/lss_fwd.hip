@@ -222,15 +222,12 @@ static hipError_t launch_fwd_d(const SegShape &s, const DropArgs &drop, const T 
                                float *lse, const Workspace &ws, hipStream_t st)
 {
     using C = FwdCfg<T, D>;
-    int n_splits = choose_splits(s.l_s, s.l_x, s.B, s.H, fwd_rows_per_wg((int)sizeof(T), D));
-    {
-        // the split count above only knows the shape; under the causal mask a segment near the start of
-        // the sequence sees few keys, and a split of fewer than 8 key tiles costs more (partial
-        // outputs, merge) than it gains
-        const int64_t kv_extent = s.causal ? (s.s0 + s.l_s < s.l_x ? s.s0 + s.l_s : (int64_t)s.l_x) : (int64_t)s.l_x;
-        const int cap = (int)((kv_extent + 63) / 64 / 8);
-        if (cap < n_splits) n_splits = cap < 1 ? 1 : cap;
-    }
+    // Under the causal mask a segment near the start of the sequence sees few keys: the split count
+    // follows the keys this segment's query tiles see, within what the workspace was sized for.
+    const int rows_per_wg = fwd_rows_per_wg((int)sizeof(T), D);
+    const int64_t kv_extent = s.causal ? (s.s0 + s.l_s < s.l_x ? s.s0 + s.l_s : (int64_t)s.l_x) : (int64_t)s.l_x;
+    const int n_splits = pick_fwd_splits(s.l_s, s.B, s.H, rows_per_wg, (kv_extent + 63) / 64,
+                                         max_fwd_splits(s.l_s, s.l_x, s.B, s.H, rows_per_wg), fwd_wgs_per_cu((int)sizeof(T), D));
     hipError_t e;
     const dim3 grid((s.l_s + C::BR - 1) / C::BR, s.B * s.H, n_splits);
     if constexpr (sizeof(T) == 2) {

@@ -30,6 +30,11 @@ struct DropArgs {
 // skinny segment (l_s << l_x) still fills the chip.  Shape-only, deterministic.
 // `rows_per_wg` is the query-tile height of the kernel that will run (it differs per dtype).
 int choose_splits(int l_s, int l_x, int B, int H, int rows_per_wg);
+// Forward: the largest split count the workspace is sized for (shape-only), and the count a launch
+// uses for the `kv_tiles` 64-key tiles its query tiles actually see (never above the former).
+int max_fwd_splits(int l_s, int l_x, int B, int H, int rows_per_wg);
+int pick_fwd_splits(int l_s, int B, int H, int rows_per_wg, int64_t kv_tiles, int max_splits, int resident);
+int fwd_wgs_per_cu(int elem_bytes, int d);      // forward workgroups a compute unit holds at once ("resident")
 int fwd_rows_per_wg(int elem_bytes, int d);     // query rows per workgroup of the forward kernel
 int dq_rows_per_wg(int elem_bytes, int d);      // ... and of the dQ kernel
 
