@@ -383,6 +383,34 @@ def attention(args, w, steps, warmup, with_cpu_baseline):
     step_stats = {"median_ms": round(per_step[len(per_step) // 2], 4), "min_ms": round(per_step[0], 4),
                   "max_ms": round(per_step[-1], 4), "note": "GPU time between step boundaries inside the timed region"}
 
+    # 1b. the same steps recorded once into a HIP graph and replayed (the library allocates nothing, records no
+    # memset nodes and never synchronises, so a caller may do this): what a launch-bound configuration gains
+    # from it.  Reported beside `value`, never as `value`.
+    graph_replay = None
+    if not args.no_graph:
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                step()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step()
+            graph.replay()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(steps):
+                graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            graph_replay = {"ms_per_step": round(e0.elapsed_time(e1) / steps, 4)}
+            del graph
+        except Exception as exc:       # reported, not fatal: the eager figures above stand on their own
+            graph_replay = {"error": str(exc)[:200]}
+
     # 2. survey pass: every kernel bracketed by events, to find the one with the largest share of a step and to
     # report the others.  3. the timed region again, with that one kernel bracketed: its average launch duration
     # under the same back-to-back conditions, for the roofline.
@@ -549,6 +577,9 @@ def attention(args, w, steps, warmup, with_cpu_baseline):
         ("frac_of_f32_peak" if f32 else "frac_of_bf16_peak"): round(value / peak, 4),
         "tflops_with_recompute_count_14Pd": round(flops_fa / (ms_per_step * 1e-3) / 1e12, 2),
         "gpu_ms_per_step_events": round(gpu_ms_per_step, 4), "step_stats": step_stats,
+        "graph_replay": (None if graph_replay is None else graph_replay if "error" in graph_replay else
+                         dict(graph_replay, value=round((flops_strict + flops_proj) / (graph_replay["ms_per_step"] * 1e-3) / 1e12, 2),
+                              note="the same steps replayed from one HIP graph; not `value`")),
         "roofline": roofline, "cpu_baseline": cpu_baseline, "rates": rates, "kernels": kernels,
     }
 
@@ -578,6 +609,7 @@ def main() -> int:
                          "fit in memory at once, e.g. lx50k_skinny); the segment sum then adds these segments' partials")
     ap.add_argument("--skip-masked-tail", action="store_true",
                     help="backward calls pass LSS_FLAG_SKIP_MASKED_TAIL: key tiles no query of a causal segment sees stay unwritten")
+    ap.add_argument("--no-graph", action="store_true", help="skip the HIP-graph replay of the step (`graph_replay`)")
     ap.add_argument("--no-extra", action="store_true", help="leave out the other configurations' figures")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
@@ -622,7 +654,7 @@ def main() -> int:
             torch.cuda.empty_cache()
             e = attention(args, synth.WORKLOADS[name], min(args.steps, 5), min(args.warmup, 2), False)
             extra.append({"workload": name, "value": e["value"], "unit": e["unit"], "ms_per_step": e["ms_per_step"],
-                          "steps": e["steps"], "frac_of_bf16_peak": e["frac_of_bf16_peak"],
+                          "graph_replay": e["graph_replay"], "steps": e["steps"], "frac_of_bf16_peak": e["frac_of_bf16_peak"],
                           "config": {k_: e["config"][k_] for k_ in ("B", "l_x", "N", "l_s", "H", "d", "causal")},
                           "roofline": e["roofline"], "rates": e["rates"]})
         line["extra"] = extra
