@@ -122,8 +122,11 @@ int lss_segment_attn_bwd(const void *q_seg, const void *k, const void *v,
  * values -D and -lse*sqrt(d), split partial dQ) lives in a buffer of
  * LSS_NOALLOC_SCRATCH_BYTES bytes that is part of the library's device image: every GPU
  * the library runs on holds one until the process ends.  The call allocates and frees
- * nothing and ignores lss_set_workspace().  Shapes for which lss_workspace_bytes(l_s,
- * l_x, B, H, d, 2) exceeds the buffer are rejected with LSS_ERR_WORKSPACE.  Nothing in
+ * nothing and ignores lss_set_workspace().  Shapes whose backward scratch exceeds the
+ * buffer are rejected with LSS_ERR_WORKSPACE: that scratch is the part of
+ * lss_workspace_bytes(l_s, l_x, B, H, d, 2) that is not the forward's split partial
+ * results -- 12 bytes per query row and head, plus 4 B l_s H d bytes per key split of dQ
+ * (at most 16; none once B H l_s / 128 reaches 512) -- and lss_last_error() names it.  Nothing in
  * the buffer has to be cleared between calls (every value is written before it is read),
  * but all calls on one GPU share it: calls that overlap in time on one GPU (different
  * streams, different threads) race.  The first call on a GPU looks the buffer's address up

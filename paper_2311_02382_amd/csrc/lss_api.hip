@@ -69,7 +69,8 @@ int pick_fwd_splits(int l_s, int B, int H, int rows_per_wg, int64_t kv_tiles, in
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-struct WsLayout { size_t o_part, lse_part, D, Ls, dq_part, row_key, total; };
+// The backward's regions come first: a backward call needs only the first `bwd_total` bytes.
+struct WsLayout { size_t D, Ls, dq_part, row_key, bwd_total, o_part, lse_part, total; };
 static WsLayout ws_layout(int l_s, int l_x, int B, int H, int d, int elem_bytes)
 {
     // forward and dQ kernels may use different tile heights, hence different split counts
@@ -78,18 +79,23 @@ static WsLayout ws_layout(int l_s, int l_x, int B, int H, int d, int elem_bytes)
     const size_t rows = (size_t)B * H * l_s;
     WsLayout w;
     size_t off = 0;
-    w.o_part = off;   off += align256(sp_f > 1 ? sp_f * rows * d * sizeof(float) : 0);
-    w.lse_part = off; off += align256(sp_f > 1 ? sp_f * rows * sizeof(float) : 0);
     w.D = off;        off += align256(rows * sizeof(float));
     w.Ls = off;       off += align256(rows * sizeof(float));
     w.dq_part = off;  off += align256(sp_q > 1 ? sp_q * rows * d * sizeof(float) : 0);
     w.row_key = off;  off += align256(rows * sizeof(uint32_t));
+    w.bwd_total = off;
+    w.o_part = off;   off += align256(sp_f > 1 ? sp_f * rows * d * sizeof(float) : 0);
+    w.lse_part = off; off += align256(sp_f > 1 ? sp_f * rows * sizeof(float) : 0);
     w.total = off;
     return w;
 }
 size_t workspace_bytes(int l_s, int l_x, int B, int H, int d, int elem_bytes)
 {
     return ws_layout(l_s, l_x, B, H, d, elem_bytes).total;
+}
+size_t bwd_workspace_bytes(int l_s, int l_x, int B, int H, int d, int elem_bytes)
+{
+    return ws_layout(l_s, l_x, B, H, d, elem_bytes).bwd_total;
 }
 Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d, int elem_bytes)
 {
@@ -166,9 +172,13 @@ int current_device(int *dev)
 
 // The scratch of one call: the caller's own buffer (`own`, `own_bytes`) if given, else the one
 // registered for the current GPU.
-int get_workspace(int l_s, int l_x, int B, int H, int d, int elem_bytes, void *own, size_t own_bytes, lss::Workspace *ws)
+// `bwd_only`: the buffer need only hold the backward's regions (the built-in scratch of
+// lss_segment_attn_bwd_noalloc); the forward's pointers then lie outside it and are never used.
+int get_workspace(int l_s, int l_x, int B, int H, int d, int elem_bytes, void *own, size_t own_bytes, lss::Workspace *ws,
+                  bool bwd_only = false)
 {
-    const size_t need = lss::workspace_bytes(l_s, l_x, B, H, d, elem_bytes);
+    const size_t need = bwd_only ? lss::bwd_workspace_bytes(l_s, l_x, B, H, d, elem_bytes)
+                                 : lss::workspace_bytes(l_s, l_x, B, H, d, elem_bytes);
     void *base = own;
     size_t have = own_bytes;
     if (own == nullptr) {
@@ -182,6 +192,7 @@ int get_workspace(int l_s, int l_x, int B, int H, int d, int elem_bytes, void *o
         return fail(LSS_ERR_WORKSPACE, "workspace of %zu bytes needed, %zu %s", need, base ? have : (size_t)0,
                     own ? "passed" : "registered for this GPU (lss_set_workspace)");
     *ws = lss::carve_workspace(base, l_s, l_x, B, H, d, elem_bytes);
+    if (bwd_only) ws->o_part = ws->lse_part = nullptr;
     return LSS_OK;
 }
 
@@ -247,7 +258,8 @@ int fwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
 template <typename T>
 int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_s, int64_t l_x, int64_t B,
              int64_t H, int64_t d, int causal, double p_drop, uint64_t seed, unsigned flags, void *wsp, size_t wsp_bytes,
-             const void *out, const float *lse, const void *dO, void *dq, float *dk_part, float *dv_part, void *stream)
+             const void *out, const float *lse, const void *dO, void *dq, float *dk_part, float *dv_part, void *stream,
+             bool bwd_only_scratch = false)
 {
     if (int rc = check_shape(s0, l_s, l_x, B, H, d)) return rc;
     if (int rc = check_dropout(p_drop)) return rc;
@@ -272,7 +284,8 @@ int bwd_impl(const void *q, const void *k, const void *v, int64_t s0, int64_t l_
         return LSS_OK;
     }
     lss::Workspace ws;
-    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), wsp, wsp_bytes, &ws)) return rc;
+    if (int rc = get_workspace((int)l_s, (int)l_x, (int)B, (int)H, (int)d, (int)sizeof(T), wsp, wsp_bytes, &ws, bwd_only_scratch))
+        return rc;
     const lss::SegShape s{s0, (int)l_s, (int)l_x, (int)B, (int)H, (int)d, causal ? 1 : 0,
                           (flags & LSS_FLAG_SKIP_MASKED_TAIL) ? 1 : 0};
     const lss::DropArgs drop = dropout_args(p_drop, seed);
@@ -332,15 +345,16 @@ int lss_segment_attn_bwd_noalloc(const void *q_seg, const void *k, const void *v
                                  void *stream)
 {
     if (int rc = check_shape(seg_offset, l_s, l_x, B, H, d)) return rc;
-    const size_t need = (l_s > 0 && B > 0) ? lss::workspace_bytes((int)l_s, (int)l_x, (int)B, (int)H, (int)d, 2) : 0;
+    const size_t need = (l_s > 0 && B > 0) ? lss::bwd_workspace_bytes((int)l_s, (int)l_x, (int)B, (int)H, (int)d, 2) : 0;
     if (need > (size_t)LSS_NOALLOC_SCRATCH_BYTES)
-        return fail(LSS_ERR_WORKSPACE, "this shape needs %zu bytes of scratch, the built-in buffer holds %zu: use lss_segment_attn_bwd",
+        return fail(LSS_ERR_WORKSPACE, "the backward of this shape needs %zu bytes of scratch, the built-in buffer holds %zu: use lss_segment_attn_bwd",
                     need, (size_t)LSS_NOALLOC_SCRATCH_BYTES);
     void *ws = nullptr;
     if (need > 0)
         if (int rc = builtin_scratch(&ws)) return rc;
     return bwd_impl<lss::bf16_t>(q_seg, k, v, seg_offset, l_s, l_x, B, H, d, causal, 0.0, 0, 0u, ws,
-                                 ws ? (size_t)LSS_NOALLOC_SCRATCH_BYTES : 0, out, lse, dO, dq, dk_partial, dv_partial, stream);
+                                 ws ? (size_t)LSS_NOALLOC_SCRATCH_BYTES : 0, out, lse, dO, dq, dk_partial, dv_partial, stream,
+                                 /*bwd_only_scratch=*/true);
 }
 
 int lss_segment_attn_fwd_f32(const void *q_seg, const void *k, const void *v, int64_t seg_offset, int64_t l_s,

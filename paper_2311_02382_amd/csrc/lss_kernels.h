@@ -49,6 +49,7 @@ struct Workspace {
     uint32_t *row_key; // [B*H, l_s]      dropout in the bf16 dK/dV workgroups: the generator's key of every query row
 };
 size_t workspace_bytes(int l_s, int l_x, int B, int H, int d, int elem_bytes);
+size_t bwd_workspace_bytes(int l_s, int l_x, int B, int H, int d, int elem_bytes);    // the leading part a backward call uses
 Workspace carve_workspace(void *base, int l_s, int l_x, int B, int H, int d, int elem_bytes);
 
 template <typename T>

@@ -2,7 +2,8 @@
 
 Same kernels, scratch in the library's built-in device buffer instead of the caller's workspace: the results
 must be identical bit for bit.  Two calls in a row, the second on a smaller input (the buffer keeps the first
-call's contents), then a shape the buffer cannot hold."""
+call's contents), a shape whose forward scratch would not fit (the backward's does), then a shape the buffer
+cannot hold."""
 import pytest
 import torch
 
@@ -35,9 +36,17 @@ def test_noalloc_backward_equals_the_workspace_one_on_two_calls_in_a_row():
     _run(B=1, l_x=1024, H=4, d=64, s0=768, l_s=256, causal=True, seed=0)
 
 
-def test_noalloc_backward_rejects_what_the_buffer_cannot_hold():
-    B, l_s, l_x, H, d = 1, 2048, 65536, 8, 128      # few query tiles, long sequence: split partial results
+def test_noalloc_backward_needs_room_for_the_backward_scratch_only():
+    # few query tiles and a long sequence: the forward's split partial results alone exceed the buffer,
+    # the backward's scratch (start values and 4 partial dQ) does not
+    B, l_x, H, d, l_s = 1, 16384, 16, 128, 1024
     assert lss.lss_workspace_bytes(l_s, l_x, B, H, d, 2) > lss.LSS_NOALLOC_SCRATCH_BYTES
+    _run(B=B, l_x=l_x, H=H, d=d, s0=l_x - l_s, l_s=l_s, causal=True, seed=43)
+
+
+def test_noalloc_backward_rejects_what_the_buffer_cannot_hold():
+    B, l_s, l_x, H, d = 8, 32768, 32768, 32, 64     # 12 bytes of backward scratch per query row and head: 96 MiB
+    assert 12 * B * H * l_s > lss.LSS_NOALLOC_SCRATCH_BYTES
     lib = lss.load()
     rc = lib.lss_segment_attn_bwd_noalloc(0x1000, 0x2000, 0x3000, 0, l_s, l_x, B, H, d, 1, 0x4000, 0x5000, 0x6000,
                                           0x7000, 0x8000, 0x9000, None)
