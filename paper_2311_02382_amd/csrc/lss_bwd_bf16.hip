@@ -456,6 +456,17 @@ __device__ __forceinline__ void bwd_dkv_body(char *smem, const SegShape &s, cons
             vf[kb] = load_frag<bf16_t>(v + off + kb * 16);
         }
     }
+    if constexpr (D == 128) {
+        // At d = 128 the kernel needs more than 256 registers and the allocator parks these 64 in the
+        // accumulation half of the register file -- then copies each into a vector register before
+        // every use (54 to 68 copies per 32 matrix instructions).  A matrix instruction can read its
+        // B operand from that half directly: naming the class here makes it do so.
+#pragma unroll
+        for (int kb = 0; kb < NU; ++kb) {
+            asm volatile("" : "+a"(kf[kb].v));
+            asm volatile("" : "+a"(vf[kb].v));
+        }
+    }
 
     f32x16 dk[D / 32], dv[D / 32];
 #pragma unroll
