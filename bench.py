@@ -10,7 +10,8 @@ reduce-scatter of Fig. 2(v)).  Inputs are resident in HBM before the timed regio
 
 The default workload is lx24k (B=4, l_x=24576, 6 segments of 4096 rows, 16 heads of width 64, causal): the
 largest configuration with d = 64 and l_s >= 1024.  Run without --workload, the line also carries `extra`: the
-other four configurations (tiny, lx8k, lx32k_d128, lx50k), each timed the same way over a few steps.
+other four configurations (tiny, lx8k, lx32k_d128, lx50k), each timed the same way over at least 5 steps and
+50 ms, after at least 30 ms of warm-up (the chip's clock needs that long under load to settle).
 
 With --projections every segment also runs the linear maps either side of the attention in
 the fused-communication form (Q_i, K, V from x before the forward; dx_q and dx_partial after
@@ -245,8 +246,13 @@ def layer_ops(args, w) -> int:
     return 0
 
 
-def attention(args, w, steps, warmup, with_cpu_baseline):
-    """Times `steps` steps of workload `w` and returns the JSON line as a dict."""
+def attention(args, w, steps, warmup, with_cpu_baseline, min_warm_ms=0.0, min_timed_ms=0.0):
+    """Times `steps` steps of workload `w` and returns the JSON line as a dict.
+
+    min_warm_ms / min_timed_ms (the `extra` configurations): warm up for at least that much GPU time and time at
+    least that much, whatever `steps` and `warmup` say -- the chip takes some ten milliseconds under load to reach
+    the clock it then holds, and five 1 ms steps after two would be timed on the way there (lx8k: 373 against
+    413 TFLOP/s)."""
     import numpy as np
     import torch
 
@@ -340,6 +346,19 @@ def attention(args, w, steps, warmup, with_cpu_baseline):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    if min_timed_ms > 0:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        step()
+        e1.record()
+        torch.cuda.synchronize()
+        est_ms = max(e0.elapsed_time(e1), 1e-3)
+        more = int(min_warm_ms / est_ms)
+        for _ in range(more):
+            step()
+        torch.cuda.synchronize()
+        warmup += 1 + more
+        steps = max(steps, int(min_timed_ms / est_ms) + 1)
     if args.calib_copy_mib > 0:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -652,9 +671,10 @@ def main() -> int:
         extra = []
         for name in ("tiny", "lx8k", "lx32k_d128", "lx50k"):
             torch.cuda.empty_cache()
-            e = attention(args, synth.WORKLOADS[name], min(args.steps, 5), min(args.warmup, 2), False)
+            e = attention(args, synth.WORKLOADS[name], min(args.steps, 5), min(args.warmup, 2), False,
+                          min_warm_ms=30.0, min_timed_ms=50.0)
             extra.append({"workload": name, "value": e["value"], "unit": e["unit"], "ms_per_step": e["ms_per_step"],
-                          "graph_replay": e["graph_replay"], "steps": e["steps"], "frac_of_bf16_peak": e["frac_of_bf16_peak"],
+                          "graph_replay": e["graph_replay"], "steps": e["steps"], "warmup": e["warmup"], "frac_of_bf16_peak": e["frac_of_bf16_peak"],
                           "config": {k_: e["config"][k_] for k_ in ("B", "l_x", "N", "l_s", "H", "d", "causal")},
                           "roofline": e["roofline"], "rates": e["rates"]})
         line["extra"] = extra
