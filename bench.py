@@ -11,7 +11,7 @@ reduce-scatter of Fig. 2(v)).  Inputs are resident in HBM before the timed regio
 The default workload is lx24k (B=4, l_x=24576, 6 segments of 4096 rows, 16 heads of width 64, causal): the
 largest configuration with d = 64 and l_s >= 1024.  Run without --workload, the line also carries `extra`: the
 other four configurations (tiny, lx8k, lx32k_d128, lx50k), each timed the same way over at least 5 steps and
-50 ms, after at least 30 ms of warm-up (the chip's clock needs that long under load to settle).
+50 ms, after at least 30 ms of warm-up (a run needs that long under load to reach its steady state).
 
 With --projections every segment also runs the linear maps either side of the attention in
 the fused-communication form (Q_i, K, V from x before the forward; dx_q and dx_partial after
@@ -250,9 +250,9 @@ def attention(args, w, steps, warmup, with_cpu_baseline, min_warm_ms=0.0, min_ti
     """Times `steps` steps of workload `w` and returns the JSON line as a dict.
 
     min_warm_ms / min_timed_ms (the `extra` configurations): warm up for at least that much GPU time and time at
-    least that much, whatever `steps` and `warmup` say -- the chip takes some ten milliseconds under load to reach
-    the clock it then holds, and five 1 ms steps after two would be timed on the way there (lx8k: 373 against
-    413 TFLOP/s)."""
+    least that much, whatever `steps` and `warmup` say -- a run takes some ten milliseconds under load to reach
+    its steady state (clock, launch queue), and five 1 ms steps after two would be timed on the way there (lx8k:
+    373 against 413 TFLOP/s)."""
     import numpy as np
     import torch
 
