@@ -268,3 +268,12 @@ def test_product_package_does_not_touch_the_oracle():
         assert "import oracle" not in text and "from oracle" not in text, path
     for path in (pkg / "csrc").iterdir():
         assert "oracle" not in path.read_text().lower(), path
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU's share of the path: no collectives, no second GPU -- said before anything touches a device
+    import subprocess
+    import sys
+    root = Path(__file__).resolve().parents[1]
+    r = subprocess.run([sys.executable, str(root / "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "--gpus 2 is not supported" in r.stderr and r.stdout == ""
