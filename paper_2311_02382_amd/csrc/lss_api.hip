@@ -84,7 +84,7 @@ static WsLayout ws_layout(int l_s, int l_x, int B, int H, int d, int elem_bytes)
     w.dq_part = off;  off += align256(sp_q > 1 ? sp_q * rows * d * sizeof(float) : 0);
     w.row_key = off;  off += align256(rows * sizeof(uint32_t));
     w.bwd_total = off;
-    w.o_part = off;   off += align256(sp_f > 1 ? sp_f * rows * d * sizeof(float) : 0);
+    w.o_part = off;   off += align256(sp_f > 1 ? sp_f * rows * d * (size_t)elem_bytes : 0);     // in the storage type
     w.lse_part = off; off += align256(sp_f > 1 ? sp_f * rows * sizeof(float) : 0);
     w.total = off;
     return w;

@@ -193,7 +193,14 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(SegShape s, const float 
     for (int sp = 0; sp < MAXS; ++sp) {
         const int spc = sp < n_splits ? sp : n_splits - 1;
         l[sp] = __builtin_nontemporal_load(lse_part + spc * rows + row);
-        part[sp] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(o_part + (spc * rows + row) * D + c4));
+        if constexpr (sizeof(T) == 2) {     // the bf16 kernel writes its partial outputs in bf16
+            const bf16x4 pv = __builtin_nontemporal_load(
+                reinterpret_cast<const bf16x4 *>(reinterpret_cast<const bf16_t *>(o_part) + (spc * rows + row) * D + c4));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) part[sp][i] = (float)pv[i];
+        } else {
+            part[sp] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(o_part + (spc * rows + row) * D + c4));
+        }
     }
     float mx = -INFINITY;
 #pragma unroll

@@ -344,17 +344,16 @@ __global__ __launch_bounds__(FwdBf16Cfg<D>::NT, D == 64 ? 2 : 1) void fwd_bf16_k
                     pack4(o[db][4 * e4] * inv, o[db][4 * e4 + 1] * inv, o[db][4 * e4 + 2] * inv, o[db][4 * e4 + 3] * inv);
         if (hh == 0) lse[(int64_t)bh * s.l_s + r] = lse_nat;
     } else {
+        // a split's normalised output travels to the merge kernel in bf16 (half the bytes; the merged
+        // row is rounded to bf16 anyway), its lse in fp32
         const int64_t row = ((int64_t)split * bhs + bh) * s.l_s + r;
-        float *op = o_part + row * D;
+        bf16_t *op = reinterpret_cast<bf16_t *>(o_part) + row * D;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                f32x4 val;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) val[i] = o[db][4 * e4 + i] * inv;
-                *reinterpret_cast<f32x4 *>(op + db * 32 + 8 * e4 + 4 * hh) = val;
-            }
+            for (int e4 = 0; e4 < 4; ++e4)
+                *reinterpret_cast<bf16x4 *>(op + db * 32 + 8 * e4 + 4 * hh) =
+                    pack4(o[db][4 * e4] * inv, o[db][4 * e4 + 1] * inv, o[db][4 * e4 + 2] * inv, o[db][4 * e4 + 3] * inv);
         if (hh == 0) lse_part[row] = lse_nat;
     }
 }

@@ -40,7 +40,7 @@ int dq_rows_per_wg(int elem_bytes, int d);      // ... and of the dQ kernel
 
 struct Workspace {
     // forward
-    float *o_part;    // [splits, B*H, l_s, d]
+    float *o_part;    // [splits, B*H, l_s, d] in the storage type (bf16 kernels write bf16 here)
     float *lse_part;  // [splits, B*H, l_s]
     // backward
     float *D;         // [B*H, l_s]      rowsum(dO * out)   (bf16 kernels: its negative)
